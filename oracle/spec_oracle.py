@@ -1,0 +1,290 @@
+"""CPU oracle for tree-based parallel decoding (SpecInfer, arxiv 2305.09781).
+
+TEST INFRASTRUCTURE ONLY. This file is the plain, slow, float64 statement of what the hot path
+computes. It is imported by tests, by the smoke check and by the benchmark's CPU-baseline leg, and
+by nothing else; it shares no code with the GPU library and never calls it.
+
+What each function follows:
+  ancestor_matrix        Definition 3.1 (S_u = S_parent(u) ++ {t_u}) and Section 4.2 (topology-aware
+                         causal mask: a tree token may see its ancestors and itself, nothing else)
+  kv_append              Section 4.2, "depth-first search to update key-value cache": one cache
+                         region holds the whole tree, token i at row prefix_len + i
+  tree_attention         Definition 4.1 with the attention equations of Section 4.1 (scores scaled by
+                         1/sqrt(d), masked entries -inf, softmax, times V)
+  verify_greedy          Algorithm 2, VerifyGreedy
+  verify_stochastic      Algorithm 2, VerifyStochastic (multi-step speculative sampling)
+  kv_commit              Algorithm 2 main loop (verified tokens are appended to the sequence), so the
+                         K/V rows of the accepted path must become the contiguous prefix
+
+Parity pins (tests/test_oracle_*.py): per-path brute-force causal attention, chain/star/N=1 special
+cases against a library routine, constant-V and non-interference invariants (attention); exhaustive
+path enumeration and incremental decoding on a bigram model (greedy); exact cell-by-cell enumeration
+against a closed-form law, Theorem 4.2 and 4.3 in closed form, chi-square over many seeds
+(stochastic); round trips and overlapping-path cases (append / commit). No function is unpinned.
+
+Readings taken where the paper is silent are listed next to each function.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# status bits reported per request for data-dependent faults
+ST_BAD_TREE = 1        # parent[0] != -1, or parent[i] not in [0, i), or depth[i] != depth[parent[i]] + 1
+ST_CAPACITY = 2        # prefix_len + N > S_cap, or prefix_len < 0
+ST_BAD_PATH = 4        # accepted path: len out of range, path[0] != 0, not strictly increasing, or out of range
+ST_ZERO_RESIDUAL = 8   # residual distribution had no mass left (kept previous distribution)
+
+
+# ---------------------------------------------------------------------------------------------
+# token tree helpers (Definition 3.1)
+# ---------------------------------------------------------------------------------------------
+
+def tree_status(parent, depth=None):
+    """0 if `parent` (and `depth`, if given) describe a valid linearised token tree, else ST_BAD_TREE."""
+    parent = np.asarray(parent)
+    n = len(parent)
+    if n == 0 or parent[0] != -1:
+        return ST_BAD_TREE
+    for i in range(1, n):
+        if not (0 <= parent[i] < i):
+            return ST_BAD_TREE
+    if depth is not None:
+        depth = np.asarray(depth)
+        if depth[0] != 0:
+            return ST_BAD_TREE
+        for i in range(1, n):
+            if depth[i] != depth[parent[i]] + 1:
+                return ST_BAD_TREE
+    return 0
+
+
+def ancestor_matrix(parent):
+    """anc[i, a] = True iff a is i itself or an ancestor of i (the tokens of S_i inside the tree)."""
+    parent = np.asarray(parent)
+    n = len(parent)
+    anc = np.zeros((n, n), dtype=bool)
+    for i in range(n):
+        u = i
+        while u >= 0:
+            anc[i, u] = True
+            u = int(parent[u])
+    return anc
+
+
+def children(parent, u):
+    return [v for v in range(len(parent)) if parent[v] == u]
+
+
+# ---------------------------------------------------------------------------------------------
+# KV append  (Section 4.2)
+# ---------------------------------------------------------------------------------------------
+
+def kv_append(k_cache, v_cache, k_new, v_new, prefix_len):
+    """cache[b, h, prefix_len[b] + i, :] = new[b, i, h, :] for every tree token i. In place.
+
+    k_cache, v_cache: [B,H,S_cap,D]; k_new, v_new: [B,N,H,D]. Returns status [B]; a request whose
+    tree does not fit (prefix_len + N > S_cap) is left untouched and flagged ST_CAPACITY."""
+    B, N = k_new.shape[0], k_new.shape[1]
+    S_cap = k_cache.shape[2]
+    status = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        p = int(prefix_len[b])
+        if p < 0 or p + N > S_cap:
+            status[b] |= ST_CAPACITY
+            continue
+        for i in range(N):
+            k_cache[b, :, p + i, :] = k_new[b, i, :, :]
+            v_cache[b, :, p + i, :] = v_new[b, i, :, :]
+    return status
+
+
+# ---------------------------------------------------------------------------------------------
+# tree attention  (Definition 4.1, Section 4.1 equations, Section 4.2 mask)
+# ---------------------------------------------------------------------------------------------
+
+def tree_attention(q, k_cache, v_cache, tree_parent, prefix_len, softmax_scale=None):
+    """Attention output of every tree node over (cached prefix) ++ (its own root-to-node path).
+
+    q: [B,N,H,D]; caches [B,H,S_cap,D] already holding the tree rows at prefix_len[b] + i.
+    Returns float64 [B,N,H,D]. A = Q K^T / sqrt(d); mask(A) puts -inf wherever key j is a tree token
+    that is neither node i nor one of its ancestors; H = softmax(mask(A)) V.
+    Readings: d is the head dimension; a row is never fully masked (a node sees itself)."""
+    q = np.asarray(q, dtype=np.float64)
+    B, N, H, D = q.shape
+    scale = 1.0 / np.sqrt(D) if softmax_scale is None else float(softmax_scale)
+    out = np.zeros((B, N, H, D), dtype=np.float64)
+    for b in range(B):
+        p = int(prefix_len[b])
+        L = p + N
+        visible = np.concatenate([np.ones((N, p), dtype=bool), ancestor_matrix(tree_parent[b])], axis=1)
+        for h in range(H):
+            K = np.asarray(k_cache[b, h, :L, :], dtype=np.float64)
+            V = np.asarray(v_cache[b, h, :L, :], dtype=np.float64)
+            A = (q[b, :, h, :] @ K.T) * scale
+            A = np.where(visible, A, -np.inf)
+            W = np.exp(A - A.max(axis=1, keepdims=True))
+            W = W / W.sum(axis=1, keepdims=True)
+            out[b, :, h, :] = W @ V
+    return out
+
+
+# ---------------------------------------------------------------------------------------------
+# greedy verification  (Algorithm 2, VerifyGreedy)
+# ---------------------------------------------------------------------------------------------
+
+def verify_greedy(logits, tree_token, tree_parent):
+    """O(u) = argmax of the LLM's logits at node u (lowest token id on ties). Starting at the root,
+    move to a child whose token equals O(u) while one exists (lowest node index if several);
+    finally append O(u) of the last node reached.
+
+    logits [B,N,V]; returns accepted_path [B,N] (node indices, root first, padded -1),
+    accepted_len [B], out_tokens [B,N] (tokens of the accepted children, then the bonus token,
+    padded -1; same count as path nodes), node_argmax [B,N]."""
+    logits = np.asarray(logits)
+    B, N, V = logits.shape
+    path = np.full((B, N), -1, dtype=np.int32)
+    toks = np.full((B, N), -1, dtype=np.int32)
+    ln = np.zeros(B, dtype=np.int32)
+    node_argmax = np.zeros((B, N), dtype=np.int32)
+    for b in range(B):
+        for u in range(N):
+            node_argmax[b, u] = int(np.argmax(logits[b, u]))   # first occurrence = lowest id
+        u = 0
+        k = 0
+        path[b, 0] = 0
+        while True:
+            nxt = -1
+            for v in children(tree_parent[b], u):
+                if int(tree_token[b, v]) == int(node_argmax[b, u]):
+                    nxt = v
+                    break
+            if nxt < 0:
+                break
+            toks[b, k] = tree_token[b, nxt]
+            k += 1
+            path[b, k] = nxt
+            u = nxt
+        toks[b, k] = node_argmax[b, u]
+        ln[b] = k + 1
+    return path, ln, toks, node_argmax
+
+
+# ---------------------------------------------------------------------------------------------
+# stochastic verification  (Algorithm 2, VerifyStochastic: multi-step speculative sampling)
+# ---------------------------------------------------------------------------------------------
+
+def verify_stochastic(logits, probs_ssm, ssm_row, tree_token, tree_parent, u_accept, u_order, u_final,
+                      temperature=1.0, return_margins=False):
+    """Multi-step speculative sampling over a token tree.
+
+    At node u: P = softmax(logits[u] / temperature). The children of u are tried in ascending order of
+    (u_order[v], v) -- a uniformly random order without replacement. Child s with token x and draft
+    distribution Q = probs_ssm[ssm_row[s]] passes iff r <= P(x)/Q(x), r = u_accept[s], evaluated as
+    r * Q(x) <= P(x) on float32-rounded values (no division; Q(x) = 0 passes). If it passes, x is
+    emitted and the walk moves to s. Otherwise P := norm(max(0, P - Q)) and s is dropped. When no child
+    is left (or u is a leaf) the final token is drawn from the current P by inverse CDF over
+    ascending token id: the first k with cumsum(P)[k] > u_final * sum(P).
+
+    Readings: the residual persists only across the siblings of one node; an all-zero residual keeps
+    the previous P and sets ST_ZERO_RESIDUAL; uniforms are float32 in [0,1) supplied by the caller.
+
+    Returns accepted_path [B,N], accepted_len [B], out_tokens [B,N], status [B] and, if asked,
+    margins [B,2]: [:,0] the smallest relative gap |r Q(x) - P(x)| / max(...) over the ratio tests
+    taken, [:,1] the distance of the final draw's target from the nearest CDF step as a fraction of
+    the total mass. They tell how far each decision is from flipping under rounding noise."""
+    logits = np.asarray(logits, dtype=np.float64)
+    probs_ssm = np.asarray(probs_ssm, dtype=np.float64)
+    B, N, V = logits.shape
+    path = np.full((B, N), -1, dtype=np.int32)
+    toks = np.full((B, N), -1, dtype=np.int32)
+    ln = np.zeros(B, dtype=np.int32)
+    status = np.zeros(B, dtype=np.int32)
+    margins = np.full((B, 2), np.inf)
+    for b in range(B):
+        u = 0
+        k = 0
+        path[b, 0] = 0
+        while True:
+            z = logits[b, u] / float(temperature)
+            P = np.exp(z - z.max())
+            P = P / P.sum()
+            H = sorted(children(tree_parent[b], u), key=lambda v: (float(u_order[b, v]), v))
+            accepted = False
+            for s in H:
+                x = int(tree_token[b, s])
+                Q = probs_ssm[int(ssm_row[b, s])]
+                r = np.float32(u_accept[b, s])
+                lhs = np.float32(r * np.float32(Q[x]))
+                rhs = np.float32(P[x])
+                denom = max(float(rhs), float(lhs), 1e-300)
+                margins[b, 0] = min(margins[b, 0], abs(float(lhs) - float(rhs)) / denom)
+                if lhs <= rhs:
+                    toks[b, k] = x
+                    k += 1
+                    path[b, k] = s
+                    u = s
+                    accepted = True
+                    break
+                R = np.maximum(0.0, P - Q)
+                Z = R.sum()
+                if Z > 0.0:
+                    P = R / Z
+                else:
+                    status[b] |= ST_ZERO_RESIDUAL
+            if not accepted:
+                break
+        cdf = np.cumsum(P)
+        target = float(np.float32(u_final[b])) * cdf[-1]
+        x_next = int(np.searchsorted(cdf, target, side="right"))   # first k with cdf[k] > target
+        x_next = min(x_next, V - 1)
+        lo = cdf[x_next - 1] if x_next > 0 else -np.inf
+        margins[b, 1] = min((target - lo) / cdf[-1], (cdf[x_next] - target) / cdf[-1])
+        toks[b, k] = x_next
+        ln[b] = k + 1
+    if return_margins:
+        return path, ln, toks, status, margins
+    return path, ln, toks, status
+
+
+# ---------------------------------------------------------------------------------------------
+# KV commit  (Algorithm 2 main loop: S.append(t) for every verified token)
+# ---------------------------------------------------------------------------------------------
+
+def path_status(path_b, len_b, parent_b):
+    """0 if path_b[:len_b] is a root-to-node chain of the tree, else ST_BAD_PATH."""
+    n = len(parent_b)
+    if not (1 <= len_b <= n) or len_b > len(path_b) or path_b[0] != 0:
+        return ST_BAD_PATH
+    for k in range(1, len_b):
+        if not (0 < path_b[k] < n) or parent_b[path_b[k]] != path_b[k - 1]:
+            return ST_BAD_PATH
+    return 0
+
+
+def kv_commit(k_caches, v_caches, accepted_path, accepted_len, prefix_len, N=None):
+    """For every layer's cache and every request: row prefix_len + k <- row prefix_len + path[k],
+    k = 0..len-1 (K and V), so the accepted tokens' K/V become the contiguous continuation of the
+    prefix. Returns (prefix_len_out = prefix_len + len, status [B]). In place; rows at and beyond
+    the new prefix length are unspecified afterwards.
+
+    Only the structure a copy needs is checked here (path[0] = 0, strictly increasing, inside the
+    tree's N rows); requests failing it are left untouched with prefix_len_out = prefix_len."""
+    B = len(prefix_len)
+    out_len = np.array(prefix_len, dtype=np.int32).copy()
+    status = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        p = int(prefix_len[b])
+        n = int(accepted_len[b])
+        pb = [int(x) for x in accepted_path[b][:max(n, 0)]]
+        limit = (k_caches[0].shape[2] - p) if N is None else N
+        ok = 1 <= n <= len(accepted_path[b]) and pb[0] == 0 and all(pb[k] > pb[k - 1] for k in range(1, n)) \
+            and pb[-1] < limit
+        if not ok:
+            status[b] |= ST_BAD_PATH
+            continue
+        for kc, vc in zip(k_caches, v_caches):
+            for k in range(n):           # increasing k is safe: destination row <= source row
+                kc[b, :, p + k, :] = kc[b, :, p + pb[k], :]
+                vc[b, :, p + k, :] = vc[b, :, p + pb[k], :]
+        out_len[b] = p + n
+    return out_len, status

@@ -1,0 +1,252 @@
+"""Pins for the oracle's tree attention, append and ancestor mask (CPU only).
+
+Each test checks the oracle against something fixed by the paper or by mathematics, written with
+separate code: Definition 4.1 by brute force per root-to-node path, special trees that reduce to a
+library attention routine, invariants of softmax-weighted averages, and a hand-derived fixture.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import spec_oracle as orc
+from paper_2305_09781_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _tiny(seed, B=2, H=2, D=8, P=(3, 6), N=7, tree="random"):
+    rng = np.random.default_rng(seed)
+    S_cap = max(P) + N + 2
+    prefix_len = np.array([P[b % len(P)] for b in range(B)], dtype=np.int32)
+    if tree == "random":
+        parent = np.stack([wl.tree_random_parent(rng, N) for _ in range(B)])
+    elif tree == "chain":
+        parent = np.stack([np.arange(-1, N - 1, dtype=np.int32) for _ in range(B)])
+    elif tree == "star":
+        parent = np.stack([np.array([-1] + [0] * (N - 1), dtype=np.int32) for _ in range(B)])
+    q = rng.standard_normal((B, N, H, D))
+    k_new = rng.standard_normal((B, N, H, D))
+    v_new = rng.standard_normal((B, N, H, D))
+    k_cache = rng.standard_normal((B, H, S_cap, D)) * 50
+    v_cache = rng.standard_normal((B, H, S_cap, D)) * 50
+    for b in range(B):
+        k_cache[b, :, :prefix_len[b]] = rng.standard_normal((H, prefix_len[b], D))
+        v_cache[b, :, :prefix_len[b]] = rng.standard_normal((H, prefix_len[b], D))
+    return dict(q=q, k_new=k_new, v_new=v_new, k_cache=k_cache, v_cache=v_cache, parent=parent,
+                prefix_len=prefix_len)
+
+
+def _textbook_causal_attention_last_row(qs, ks, vs):
+    """Plain causal self-attention over a sequence (Section 4.1 equations, lower-triangular mask),
+    written with scalar loops; returns the output of the last position only."""
+    l, d = len(ks), len(ks[0])
+    A = [[-math.inf] * l for _ in range(l)]
+    for j in range(l):
+        for k in range(l):
+            if j >= k:
+                A[j][k] = sum(qs[j][t] * ks[k][t] for t in range(d)) / math.sqrt(d)
+    j = l - 1
+    m = max(A[j])
+    w = [math.exp(a - m) if a != -math.inf else 0.0 for a in A[j]]
+    z = sum(w)
+    return [sum(w[k] * vs[k][t] for k in range(l)) / z for t in range(d)]
+
+
+def _path_to(parent, u):
+    chain = []
+    while u >= 0:
+        chain.append(u)
+        u = int(parent[u])
+    return chain[::-1]
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_definition_4_1_bruteforce_per_path(seed):
+    """TreeAttention(u) == Attention(S_u): decode every node as the last token of prefix ++ path(u)."""
+    t = _tiny(seed)
+    st = orc.kv_append(t["k_cache"], t["v_cache"], t["k_new"], t["v_new"], t["prefix_len"])
+    assert (st == 0).all()
+    out = orc.tree_attention(t["q"], t["k_cache"], t["v_cache"], t["parent"], t["prefix_len"])
+    B, N, H, D = t["q"].shape
+    rng = np.random.default_rng(99)
+    for b in range(B):
+        p = int(t["prefix_len"][b])
+        for h in range(H):
+            for u in range(N):
+                path = _path_to(t["parent"][b], u)
+                # the sequence's K/V: original prefix rows, then the path's *new* rows (not via the cache)
+                ks = [list(t["k_cache"][b, h, j]) for j in range(p)] + [list(t["k_new"][b, a, h]) for a in path]
+                vs = [list(t["v_cache"][b, h, j]) for j in range(p)] + [list(t["v_new"][b, a, h]) for a in path]
+                qs = [list(rng.standard_normal(D)) for _ in range(p)] + [list(t["q"][b, a, h]) for a in path]
+                ref = _textbook_causal_attention_last_row(qs, ks, vs)
+                assert np.allclose(out[b, u, h], ref, rtol=0, atol=1e-12)
+
+
+def test_chain_tree_equals_library_causal_attention():
+    """parent[i] = i-1 makes the tree a sequence: rows P..P+N-1 of ordinary causal attention."""
+    t = _tiny(5, B=2, H=3, D=16, P=(4, 9), N=6, tree="chain")
+    orc.kv_append(t["k_cache"], t["v_cache"], t["k_new"], t["v_new"], t["prefix_len"])
+    out = orc.tree_attention(t["q"], t["k_cache"], t["v_cache"], t["parent"], t["prefix_len"])
+    B, N, H, D = t["q"].shape
+    for b in range(B):
+        p = int(t["prefix_len"][b])
+        L = p + N
+        K = torch.from_numpy(t["k_cache"][b, :, :L])          # [H,L,D]
+        V = torch.from_numpy(t["v_cache"][b, :, :L])
+        Q = torch.zeros(H, L, D, dtype=torch.float64)
+        Q[:, p:] = torch.from_numpy(t["q"][b]).permute(1, 0, 2)
+        ref = torch.nn.functional.scaled_dot_product_attention(Q, K, V, is_causal=True)
+        assert torch.allclose(torch.from_numpy(out[b]).permute(1, 0, 2), ref[:, p:], rtol=0, atol=1e-12)
+
+
+def test_single_node_is_decode_attention():
+    """N = 1: one query over prefix + itself (ordinary incremental decoding step)."""
+    t = _tiny(6, B=2, H=2, D=8, P=(5, 7), N=1)
+    orc.kv_append(t["k_cache"], t["v_cache"], t["k_new"], t["v_new"], t["prefix_len"])
+    out = orc.tree_attention(t["q"], t["k_cache"], t["v_cache"], t["parent"], t["prefix_len"])
+    for b in range(2):
+        p = int(t["prefix_len"][b])
+        for h in range(2):
+            K = np.concatenate([t["k_cache"][b, h, :p], t["k_new"][b, 0:1, h]])
+            V = np.concatenate([t["v_cache"][b, h, :p], t["v_new"][b, 0:1, h]])
+            s = K @ t["q"][b, 0, h] / math.sqrt(8)
+            w = torch.softmax(torch.from_numpy(s), 0).numpy()
+            assert np.allclose(out[b, 0, h], w @ V, atol=1e-12)
+
+
+def test_star_tree_sees_prefix_root_self_only():
+    t = _tiny(7, B=1, H=2, D=8, P=(4,), N=5, tree="star")
+    orc.kv_append(t["k_cache"], t["v_cache"], t["k_new"], t["v_new"], t["prefix_len"])
+    out = orc.tree_attention(t["q"], t["k_cache"], t["v_cache"], t["parent"], t["prefix_len"])
+    p = 4
+    for h in range(2):
+        for u in range(1, 5):
+            idx = list(range(p)) + [p, p + u]
+            K = t["k_cache"][0, h, idx]
+            V = t["v_cache"][0, h, idx]
+            s = K @ t["q"][0, u, h] / math.sqrt(8)
+            w = np.exp(s - s.max())
+            w /= w.sum()
+            assert np.allclose(out[0, u, h], w @ V, atol=1e-12)
+
+
+def test_non_ancestor_rows_do_not_interfere():
+    """Changing K/V of a tree token that is not on node i's path leaves node i's output bitwise equal."""
+    t = _tiny(8, B=1, H=2, D=8, P=(5,), N=9)
+    orc.kv_append(t["k_cache"], t["v_cache"], t["k_new"], t["v_new"], t["prefix_len"])
+    base = orc.tree_attention(t["q"], t["k_cache"], t["v_cache"], t["parent"], t["prefix_len"])
+    anc = orc.ancestor_matrix(t["parent"][0])
+    p = 5
+    for a in range(9):
+        kc, vc = t["k_cache"].copy(), t["v_cache"].copy()
+        kc[0, :, p + a] += 3.0
+        vc[0, :, p + a] -= 7.0
+        pert = orc.tree_attention(t["q"], kc, vc, t["parent"], t["prefix_len"])
+        for i in range(9):
+            same = np.array_equal(pert[0, i], base[0, i])
+            assert same == (not anc[i, a]), (i, a)
+    # rows beyond prefix+N (stale garbage) are never read
+    kc = t["k_cache"].copy()
+    kc[0, :, p + 9:] = np.nan
+    assert np.array_equal(orc.tree_attention(t["q"], kc, t["v_cache"], t["parent"], t["prefix_len"]), base)
+
+
+def test_constant_values_give_constant_output():
+    """Softmax weights sum to one: V == c  =>  output == c."""
+    t = _tiny(9)
+    orc.kv_append(t["k_cache"], t["v_cache"], t["k_new"], t["v_new"], t["prefix_len"])
+    t["v_cache"][:] = 0.375
+    out = orc.tree_attention(t["q"], t["k_cache"], t["v_cache"], t["parent"], t["prefix_len"])
+    assert np.allclose(out, 0.375, atol=1e-15)
+
+
+def test_relabelling_nodes_permutes_outputs():
+    """Another valid topological numbering of the same tree permutes the outputs and nothing else."""
+    t = _tiny(10, B=1, H=2, D=8, P=(4,), N=8)
+    parent = t["parent"][0]
+    new_parent = wl.dfs_relabel(parent)
+    # recover the permutation old -> new used by dfs_relabel
+    ch = wl.children_of(parent)
+    order, stack = [], [0]
+    while stack:
+        u = stack.pop()
+        order.append(u)
+        stack.extend(reversed(ch[u]))
+    kc1, vc1 = t["k_cache"].copy(), t["v_cache"].copy()
+    orc.kv_append(kc1, vc1, t["k_new"], t["v_new"], t["prefix_len"])
+    out1 = orc.tree_attention(t["q"], kc1, vc1, t["parent"], t["prefix_len"])
+    perm = np.array(order)
+    kc2, vc2 = t["k_cache"].copy(), t["v_cache"].copy()
+    orc.kv_append(kc2, vc2, t["k_new"][:, perm], t["v_new"][:, perm], t["prefix_len"])
+    out2 = orc.tree_attention(t["q"][:, perm], kc2, vc2, new_parent[None], t["prefix_len"])
+    assert np.allclose(out2, out1[:, perm], atol=1e-13)
+
+
+def test_softmax_scale_and_mask_sign():
+    """A dropped 1/sqrt(d) or an inverted mask would change this closed-form two-key case."""
+    D = 4
+    q = np.zeros((1, 2, 1, D))
+    q[0, :, 0, 0] = 2.0
+    kc = np.zeros((1, 1, 3, D))
+    vc = np.zeros((1, 1, 3, D))
+    kc[0, 0, 0, 0] = 1.0   # prefix key: score 2*1/2 = 1
+    kc[0, 0, 1, 0] = 3.0   # root key:   score 3
+    kc[0, 0, 2, 0] = -1.0  # child key:  score -1
+    vc[0, 0, 0, 0], vc[0, 0, 1, 0], vc[0, 0, 2, 0] = 1.0, 10.0, 100.0
+    out = orc.tree_attention(q, kc, vc, np.array([[-1, 0]]), np.array([1]))
+    e = math.exp
+    root = (e(1) * 1 + e(3) * 10) / (e(1) + e(3))
+    child = (e(1) * 1 + e(3) * 10 + e(-1) * 100) / (e(1) + e(3) + e(-1))
+    assert abs(out[0, 0, 0, 0] - root) < 1e-12 and abs(out[0, 1, 0, 0] - child) < 1e-12
+
+
+def test_fig4_consistent_fixture():
+    with open(os.path.join(GOLDEN, "fig4_consistent_tree.txt")) as f:
+        lines = [ln.strip() for ln in f if ln.strip() and not ln.startswith("#")]
+    parent = np.array([int(x) for x in lines[0].split()])
+    anc = orc.ancestor_matrix(parent)
+    for ln in lines[1:]:
+        node, rest = ln.split(":")
+        want = {int(x) for x in rest.split()}
+        assert set(np.nonzero(anc[int(node)])[0]) == want
+    assert orc.tree_status(parent, wl.depth_of(parent)) == 0
+    assert not anc[5, 3]          # t5 is not visible to t7
+    assert np.array_equal(wl.dfs_relabel(parent), parent)   # already in depth-first order
+
+
+def test_append_places_rows_and_flags_capacity():
+    t = _tiny(11, B=2, H=2, D=8, P=(3, 6), N=4)
+    k0 = t["k_cache"].copy()
+    S_cap = t["k_cache"].shape[2]
+    pl = np.array([3, S_cap - 3], dtype=np.int32)     # second request does not fit
+    st = orc.kv_append(t["k_cache"], t["v_cache"], t["k_new"], t["v_new"], pl)
+    assert st[0] == 0 and st[1] == orc.ST_CAPACITY
+    assert np.array_equal(t["k_cache"][1], k0[1])
+    for i in range(4):
+        assert np.array_equal(t["k_cache"][0, :, 3 + i], t["k_new"][0, i])
+    assert np.array_equal(t["k_cache"][0, :, :3], k0[0, :, :3]) and np.array_equal(t["k_cache"][0, :, 7:], k0[0, :, 7:])
+
+
+def test_tree_status_rejects_bad_trees():
+    assert orc.tree_status([-1, 0, 1], [0, 1, 2]) == 0
+    assert orc.tree_status([0, 0, 1]) == orc.ST_BAD_TREE
+    assert orc.tree_status([-1, 1, 0]) == orc.ST_BAD_TREE
+    assert orc.tree_status([-1, 0, 2]) == orc.ST_BAD_TREE
+    assert orc.tree_status([-1, 0, 1], [0, 1, 1]) == orc.ST_BAD_TREE
+
+
+def test_config_tree_shapes():
+    """The expansion trees named by the configs (definitions, checked against hand-derived arrays)."""
+    p2 = wl.tree_expansion(wl.EXPANSION_EVAL, 16)
+    assert list(p2) == [-1, 0, 1, 2, 3, 4, 5, 6, 2, 8, 9, 10, 2, 12, 13, 14]
+    assert list(wl.depth_of(p2)) == [0, 1, 2, 3, 4, 5, 6, 7, 3, 4, 5, 6, 3, 4, 5, 6]
+    for cfg in wl.CONFIGS.values():
+        par = wl.make_trees(cfg, np.random.default_rng(cfg.seed))
+        for b in range(cfg.B):
+            assert orc.tree_status(par[b], wl.depth_of(par[b])) == 0
+        if cfg.cfg == 3:
+            assert max(wl.depth_of(par[b]).max() for b in range(cfg.B)) <= 16
+            assert max(len(c) for b in range(cfg.B) for c in wl.children_of(par[b])) <= 4
