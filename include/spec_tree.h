@@ -1,0 +1,169 @@
+/*
+ * spec_tree.h - C ABI of the tree-based parallel decoding library for AMD MI355X (gfx950).
+ *
+ * One decoding iteration of a speculative-inference server verifies, for every request, a whole
+ * speculated token tree in a single pass of the LLM (SpecInfer, arxiv 2305.09781, Section 4 and
+ * Algorithm 2). The calls below are the per-layer and per-pass steps of that iteration:
+ *
+ *   for each layer:  spec_kv_append  ->  spec_tree_attention
+ *   once per pass:   spec_verify_greedy | spec_verify_stochastic  ->  spec_kv_commit (all layers)
+ *
+ * Conventions common to every call
+ *   - Every data pointer is a DEVICE pointer unless its comment says "host". The caller owns all
+ *     buffers; the library allocates nothing and keeps no state between calls. Scratch memory comes
+ *     from a caller-supplied workspace whose size is returned by the matching *_workspace_bytes call.
+ *   - Every call only enqueues work on `hip_stream` (a hipStream_t passed as void*, NULL = the null
+ *     stream) and returns without synchronising. Outputs are valid once the stream reaches that point.
+ *   - Return value: SPEC_OK (0) or a negative SPEC_ERR_* code for anything the host can check
+ *     (null pointers, unsupported shapes, misaligned pointers or strides, workspace too small). When an
+ *     error is returned nothing has been enqueued.
+ *   - Data-dependent faults (a malformed tree, a request that does not fit its cache, a malformed
+ *     accepted path) are detected on the device: the request's outputs become a defined no-op and the
+ *     SPEC_ST_* bit is OR-ed into status[b]. `status` ([B] int32, device) may be NULL; the caller
+ *     clears it. No such input can cause an out-of-bounds access.
+ *   - Token tree (Definition 3.1): N nodes per request in a topological order, node 0 is the root (the
+ *     last verified token, whose K/V is not cached yet), tree_parent[b][0] = -1 and
+ *     0 <= tree_parent[b][i] < i. Depth-first order (Section 4.2) is one such order.
+ *     tree_depth[b][i] = tree_depth[b][parent] + 1, tree_depth[b][0] = 0. N <= SPEC_MAX_TREE_NODES.
+ *   - Layouts. q / out / k_new / v_new: [B, N, H, D] addressed with (q_stride_b, q_stride_n,
+ *     q_stride_h), D contiguous. KV cache of one layer: [B, H_kv, S_cap, D] addressed with
+ *     (kv_stride_b, kv_stride_h, kv_stride_s), D contiguous; row s of request b holds token s of the
+ *     request's sequence, rows [0, prefix_len[b]) are the verified prefix and rows
+ *     [prefix_len[b], prefix_len[b] + N) hold the tree in node order after spec_kv_append.
+ *     All strides are in ELEMENTS and must be multiples of 16 bytes; base pointers 16-byte aligned.
+ */
+#ifndef SPEC_TREE_H
+#define SPEC_TREE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPEC_MAX_TREE_NODES 128
+#define SPEC_MAX_COMMIT_LAYERS 128
+
+/* return codes */
+#define SPEC_OK 0
+#define SPEC_ERR_INVALID_ARG (-1) /* null pointer, non-positive size, bad stride or alignment        */
+#define SPEC_ERR_UNSUPPORTED (-2) /* D not in {64,128}, N > SPEC_MAX_TREE_NODES, H_kv != H, dtype    */
+#define SPEC_ERR_CAPACITY (-3)    /* N > S_cap, max_prefix_len + N > S_cap                           */
+#define SPEC_ERR_HIP (-4)         /* a HIP runtime call failed (launch error)                        */
+#define SPEC_ERR_WORKSPACE (-5)   /* workspace NULL or smaller than *_workspace_bytes reports        */
+
+/* per-request status bits (device side) */
+#define SPEC_ST_BAD_TREE 1      /* tree_parent / tree_depth violate the token-tree contract          */
+#define SPEC_ST_CAPACITY 2      /* prefix_len[b] < 0 or prefix_len[b] + N > S_cap                    */
+#define SPEC_ST_BAD_PATH 4      /* accepted path: len out of range, path[0] != 0, not increasing     */
+#define SPEC_ST_ZERO_RESIDUAL 8 /* stochastic verify: residual distribution had no mass left         */
+
+typedef enum { SPEC_F32 = 0, SPEC_BF16 = 1 } spec_dtype_t;
+
+/* Shape of one attention layer call; passed by pointer (host memory), read during the call only. */
+typedef struct spec_attn_desc {
+  int32_t B;              /* requests in the batch                                                   */
+  int32_t H;              /* query heads                                                             */
+  int32_t H_kv;           /* key/value heads; must equal H (the paper's models are multi-head)       */
+  int32_t D;              /* head dimension: 64 or 128                                               */
+  int32_t N;              /* tree nodes per request, 1..SPEC_MAX_TREE_NODES                          */
+  int32_t S_cap;          /* rows per (request, head) in the cache                                   */
+  int32_t dtype;          /* spec_dtype_t of q, out, k_new, v_new and the caches                     */
+  int32_t max_prefix_len; /* upper bound of prefix_len[b], sizes grid and workspace; 0 = S_cap - N   */
+  int64_t q_stride_b, q_stride_n, q_stride_h;
+  int64_t kv_stride_b, kv_stride_h, kv_stride_s;
+  float softmax_scale;    /* 0 = 1/sqrt(D)                                                           */
+  int32_t reserved;       /* must be 0                                                               */
+} spec_attn_desc_t;
+
+/*
+ * KV append (Section 4.2, "depth-first search to update key-value cache"): one cache region is shared
+ * by every sequence of the tree; tree token i of request b goes to cache row prefix_len[b] + i:
+ *     cache[b, h, prefix_len[b] + i, :] = new[b, i, h, :]      (K and V, bit copy)
+ * A request with prefix_len[b] < 0 or prefix_len[b] + N > S_cap is skipped (SPEC_ST_CAPACITY).
+ */
+int spec_kv_append(const spec_attn_desc_t* desc, const void* k_new, const void* v_new, void* k_cache,
+                   void* v_cache, const int32_t* prefix_len /*[B]*/, int32_t* status /*[B] or NULL*/,
+                   void* hip_stream);
+
+/*
+ * Tree attention (Definition 4.1; attention equations of Section 4.1; topology-aware causal mask of
+ * Section 4.2). For every request b, head h and tree node i:
+ *     out[b,i,h,:] = softmax_j( q[b,i,h,:] . k[b,h,j,:] * scale ) . v[b,h,j,:]
+ * over j in [0, prefix_len[b])  union  { prefix_len[b] + a : a is node i or an ancestor of i },
+ * i.e. exactly the sequence attention of the node's root-to-node token sequence behind the prefix.
+ * The caches must already hold the tree rows (spec_kv_append). Scores, softmax and accumulation are
+ * float32; `out` has the input dtype. A request with a malformed tree (SPEC_ST_BAD_TREE) or that
+ * does not fit (SPEC_ST_CAPACITY) gets out = 0. tree_depth is only validated here.
+ * workspace: spec_tree_attention_workspace_bytes(desc) bytes, 256-byte aligned; contents are scratch.
+ */
+int spec_tree_attention(const spec_attn_desc_t* desc, const void* q, const void* k_cache,
+                        const void* v_cache, const int32_t* tree_parent /*[B,N]*/,
+                        const int32_t* tree_depth /*[B,N]*/, const int32_t* prefix_len /*[B]*/,
+                        void* out, void* workspace, size_t workspace_bytes,
+                        int32_t* status /*[B] or NULL*/, void* hip_stream);
+size_t spec_tree_attention_workspace_bytes(const spec_attn_desc_t* desc);
+
+/*
+ * Greedy verification (Algorithm 2, VerifyGreedy). O(u) = argmax_x logits_llm[b,u,x] (lowest token id
+ * on ties). Starting at the root, while some child v of u has tree_token[b,v] == O(u) (lowest node
+ * index if several) accept v and continue from it; finally emit the bonus token O(u).
+ * Outputs: accepted_path[b, 0..len) node indices, root first; out_tokens[b, 0..len) = tokens of the
+ * accepted children followed by the bonus token (same count as path nodes); both padded with -1 up to
+ * Lmax; accepted_len[b] = len >= 1; node_argmax[b,u] = O(u) (may be NULL, then `workspace` must hold
+ * B*N*4 bytes). Lmax >= max depth + 1 (N always suffices). A malformed tree gives accepted_len = 0.
+ * logits_dtype: SPEC_F32 or SPEC_BF16, [B,N,V] contiguous.
+ */
+int spec_verify_greedy(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, const void* logits_llm,
+                       const int32_t* tree_token /*[B,N]*/, const int32_t* tree_parent /*[B,N]*/,
+                       int32_t Lmax, int32_t* accepted_path /*[B,Lmax]*/, int32_t* accepted_len /*[B]*/,
+                       int32_t* out_tokens /*[B,Lmax]*/, int32_t* node_argmax /*[B,N] or NULL*/,
+                       void* workspace, size_t workspace_bytes, int32_t* status, void* hip_stream);
+
+/*
+ * Stochastic verification (Algorithm 2, VerifyStochastic: multi-step speculative sampling, Section
+ * 4.3). At node u: P = softmax(logits_llm[b,u,:] / temperature). The children of u are tried in
+ * ascending order of (u_order[b,v], v). Child s with token x = tree_token[b,s] and draft distribution
+ * Q = probs_ssm[ssm_row[b,s], :] passes iff u_accept[b,s] * Q[x] <= P[x] (float32); then x is emitted
+ * and the walk continues from s. Otherwise P := normalise(max(0, P - Q)) for the remaining siblings.
+ * When no child is left (or u is a leaf) the last token is drawn from the current P by inverse CDF
+ * over ascending token id: the first k with cumsum(P)[k] > u_final[b] * sum(P).
+ * The uniforms are supplied by the caller (float32 in [0,1)); the library draws no random numbers.
+ * Outputs as for spec_verify_greedy. SPEC_ST_ZERO_RESIDUAL: a residual had no mass; the previous P
+ * was kept. workspace: spec_verify_stochastic_workspace_bytes(B, N, V) bytes.
+ */
+int spec_verify_stochastic(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, const void* logits_llm,
+                           const float* probs_ssm /*[R,V]*/, int32_t R, const int32_t* ssm_row /*[B,N]*/,
+                           const int32_t* tree_token, const int32_t* tree_parent,
+                           const float* u_accept /*[B,N]*/, const float* u_order /*[B,N]*/,
+                           const float* u_final /*[B]*/, float temperature, int32_t Lmax,
+                           int32_t* accepted_path, int32_t* accepted_len, int32_t* out_tokens,
+                           void* workspace, size_t workspace_bytes, int32_t* status, void* hip_stream);
+size_t spec_verify_stochastic_workspace_bytes(int32_t B, int32_t N, int32_t V);
+
+/*
+ * KV commit (Algorithm 2 main loop: every verified token is appended to the sequence, so the accepted
+ * path's K/V must become the contiguous continuation of the prefix). For every layer l, request b,
+ * head h and k in [0, accepted_len[b]):
+ *     cache_l[b, h, prefix_len[b] + k, :] = cache_l[b, h, prefix_len[b] + accepted_path[b,k], :]
+ * (K and V, bit copy), and prefix_len_out[b] = prefix_len[b] + accepted_len[b]. Source rows are read
+ * before any destination row that could alias them is written. Rows at and beyond the new prefix
+ * length are unspecified afterwards. A malformed path (SPEC_ST_BAD_PATH) leaves the request's caches
+ * untouched and prefix_len_out[b] = prefix_len[b].
+ * k_caches / v_caches: HOST arrays of n_layers device pointers (n_layers <= SPEC_MAX_COMMIT_LAYERS),
+ * read during the call. prefix_len_out must not alias prefix_len.
+ */
+int spec_kv_commit(const spec_attn_desc_t* desc, int32_t n_layers, void* const* k_caches /*host*/,
+                   void* const* v_caches /*host*/, const int32_t* accepted_path /*[B,Lmax]*/,
+                   int32_t Lmax, const int32_t* accepted_len /*[B]*/, const int32_t* prefix_len /*[B]*/,
+                   int32_t* prefix_len_out /*[B]*/, int32_t* status, void* hip_stream);
+
+/* Text for a SPEC_ERR_* code (static storage). Library version as major*10000 + minor*100 + patch. */
+const char* spec_strerror(int code);
+int spec_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPEC_TREE_H */

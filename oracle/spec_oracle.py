@@ -277,6 +277,9 @@ def kv_commit(k_caches, v_caches, accepted_path, accepted_len, prefix_len, N=Non
         n = int(accepted_len[b])
         pb = [int(x) for x in accepted_path[b][:max(n, 0)]]
         limit = (k_caches[0].shape[2] - p) if N is None else N
+        if p < 0 or p + limit > k_caches[0].shape[2]:      # the tree region does not fit: skipped
+            status[b] |= ST_CAPACITY
+            continue
         ok = 1 <= n <= len(accepted_path[b]) and pb[0] == 0 and all(pb[k] > pb[k - 1] for k in range(1, n)) \
             and pb[-1] < limit
         if not ok:

@@ -1,0 +1,226 @@
+"""ctypes binding of libspectree (include/spec_tree.h): argument marshalling only.
+
+Each function has the name of the C entry point it calls and passes device pointers of torch tensors
+(torch is used for device memory and streams, nothing else). Every step of the hot path runs in the
+HIP kernels of the library; there is no fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libspectree.so")
+_lib = None
+
+SPEC_F32, SPEC_BF16 = 0, 1
+SPEC_MAX_TREE_NODES = 128
+ST_BAD_TREE, ST_CAPACITY, ST_BAD_PATH, ST_ZERO_RESIDUAL = 1, 2, 4, 8
+ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_CAPACITY, ERR_HIP, ERR_WORKSPACE = -1, -2, -3, -4, -5
+
+EXPORTED = [
+    "spec_kv_append", "spec_tree_attention", "spec_tree_attention_workspace_bytes", "spec_verify_greedy",
+    "spec_verify_stochastic", "spec_verify_stochastic_workspace_bytes", "spec_kv_commit", "spec_strerror",
+    "spec_version",
+]
+
+
+class SpecError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = load().spec_strerror(code).decode()
+        super().__init__(f"{where}: {msg} (code {code})")
+
+
+class AttnDesc(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("H_kv", ctypes.c_int32), ("D", ctypes.c_int32),
+        ("N", ctypes.c_int32), ("S_cap", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("max_prefix_len", ctypes.c_int32),
+        ("q_stride_b", ctypes.c_int64), ("q_stride_n", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
+        ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64), ("kv_stride_s", ctypes.c_int64),
+        ("softmax_scale", ctypes.c_float), ("reserved", ctypes.c_int32),
+    ]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Loads libspectree.so built in-tree; raises if it is missing (there is no other code path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} not found: build it with `python -m paper_2305_09781_amd.build` "
+                           "(the HIP library is the only implementation of the hot path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+    dp = ctypes.POINTER(AttnDesc)
+    lib.spec_kv_append.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
+    lib.spec_kv_append.restype = ctypes.c_int
+    lib.spec_tree_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
+    lib.spec_tree_attention.restype = ctypes.c_int
+    lib.spec_tree_attention_workspace_bytes.argtypes = [dp]
+    lib.spec_tree_attention_workspace_bytes.restype = sz
+    lib.spec_verify_greedy.argtypes = [i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp, vp]
+    lib.spec_verify_greedy.restype = ctypes.c_int
+    lib.spec_verify_stochastic.argtypes = [i32, i32, i32, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp, f32, i32,
+                                           vp, vp, vp, vp, sz, vp, vp]
+    lib.spec_verify_stochastic.restype = ctypes.c_int
+    lib.spec_verify_stochastic_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.spec_verify_stochastic_workspace_bytes.restype = sz
+    lib.spec_kv_commit.argtypes = [dp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i32, vp, vp, vp, vp, vp]
+    lib.spec_kv_commit.restype = ctypes.c_int
+    lib.spec_strerror.argtypes = [ctypes.c_int]
+    lib.spec_strerror.restype = ctypes.c_char_p
+    lib.spec_version.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+# ------------------------------------------------------------------------------------------------
+# marshalling helpers
+# ------------------------------------------------------------------------------------------------
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dtype_code(dt: torch.dtype) -> int:
+    if dt == torch.float32:
+        return SPEC_F32
+    if dt == torch.bfloat16:
+        return SPEC_BF16
+    raise TypeError(f"unsupported dtype {dt}")
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise SpecError(rc, where)
+
+
+def make_desc(q_like: torch.Tensor, k_cache: torch.Tensor, max_prefix_len: int = 0,
+              softmax_scale: float = 0.0) -> AttnDesc:
+    """Descriptor from a [B,N,H,D] tensor (q / out / k_new / v_new) and a [B,H,S_cap,D] cache."""
+    B, N, H, D = q_like.shape
+    Bc, Hkv, S_cap, Dc = k_cache.shape
+    if (Bc, Dc) != (B, D) or q_like.stride(3) != 1 or k_cache.stride(3) != 1:
+        raise ValueError("q must be [B,N,H,D], cache [B,H_kv,S_cap,D], D contiguous")
+    return AttnDesc(B, H, Hkv, D, N, S_cap, _dtype_code(q_like.dtype), int(max_prefix_len),
+                    q_like.stride(0), q_like.stride(1), q_like.stride(2),
+                    k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), float(softmax_scale), 0)
+
+
+def _same_layout(a: torch.Tensor, b: torch.Tensor, what: str):
+    if a.shape != b.shape or a.stride() != b.stride() or a.dtype != b.dtype:
+        raise ValueError(f"{what} must share shape, strides and dtype")
+
+
+# ------------------------------------------------------------------------------------------------
+# entry points
+# ------------------------------------------------------------------------------------------------
+
+def spec_kv_append(k_new, v_new, k_cache, v_cache, prefix_len, status=None, stream=None, desc=None):
+    _same_layout(k_new, v_new, "k_new and v_new")
+    _same_layout(k_cache, v_cache, "k_cache and v_cache")
+    d = desc if desc is not None else make_desc(k_new, k_cache)
+    _check(load().spec_kv_append(ctypes.byref(d), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                 _ptr(prefix_len), _ptr(status), _stream(stream)), "spec_kv_append")
+
+
+def spec_tree_attention_workspace_bytes(desc: AttnDesc) -> int:
+    return int(load().spec_tree_attention_workspace_bytes(ctypes.byref(desc)))
+
+
+def spec_tree_attention(q, k_cache, v_cache, tree_parent, tree_depth, prefix_len, out=None, workspace=None,
+                        status=None, max_prefix_len: int = 0, softmax_scale: float = 0.0, stream=None, desc=None):
+    _same_layout(k_cache, v_cache, "k_cache and v_cache")
+    if out is None:
+        out = torch.empty_like(q)
+    _same_layout(q, out, "q and out")
+    d = desc if desc is not None else make_desc(q, k_cache, max_prefix_len, softmax_scale)
+    need = spec_tree_attention_workspace_bytes(d)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().spec_tree_attention(ctypes.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(tree_parent),
+                                      _ptr(tree_depth), _ptr(prefix_len), _ptr(out), _ptr(workspace), ws_bytes,
+                                      _ptr(status), _stream(stream)), "spec_tree_attention")
+    return out
+
+
+def spec_verify_greedy(logits, tree_token, tree_parent, Lmax: Optional[int] = None, status=None, stream=None,
+                       out: Optional[Tuple[torch.Tensor, ...]] = None):
+    """Returns (accepted_path [B,Lmax], accepted_len [B], out_tokens [B,Lmax], node_argmax [B,N])."""
+    B, N, V = logits.shape
+    Lmax = N if Lmax is None else Lmax
+    dev = logits.device
+    if out is None:
+        out = (torch.empty((B, Lmax), dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+               torch.empty((B, Lmax), dtype=torch.int32, device=dev), torch.empty((B, N), dtype=torch.int32, device=dev))
+    path, ln, toks, amax = out
+    _check(load().spec_verify_greedy(B, N, V, _dtype_code(logits.dtype), _ptr(logits), _ptr(tree_token),
+                                     _ptr(tree_parent), Lmax, _ptr(path), _ptr(ln), _ptr(toks), _ptr(amax), None, 0,
+                                     _ptr(status), _stream(stream)), "spec_verify_greedy")
+    return path, ln, toks, amax
+
+
+def spec_verify_stochastic_workspace_bytes(B: int, N: int, V: int) -> int:
+    return int(load().spec_verify_stochastic_workspace_bytes(B, N, V))
+
+
+def spec_verify_stochastic(logits, probs_ssm, ssm_row, tree_token, tree_parent, u_accept, u_order, u_final,
+                           temperature: float = 1.0, Lmax: Optional[int] = None, workspace=None, status=None,
+                           stream=None, out: Optional[Tuple[torch.Tensor, ...]] = None):
+    """Returns (accepted_path [B,Lmax], accepted_len [B], out_tokens [B,Lmax])."""
+    B, N, V = logits.shape
+    Lmax = N if Lmax is None else Lmax
+    dev = logits.device
+    if probs_ssm.dtype != torch.float32 or (probs_ssm.numel() and probs_ssm.shape[1] != V) or not probs_ssm.is_contiguous():
+        raise ValueError("probs_ssm must be contiguous float32 [R,V]")
+    need = spec_verify_stochastic_workspace_bytes(B, N, V)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    if out is None:
+        out = (torch.empty((B, Lmax), dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+               torch.empty((B, Lmax), dtype=torch.int32, device=dev))
+    path, ln, toks = out
+    _check(load().spec_verify_stochastic(B, N, V, _dtype_code(logits.dtype), _ptr(logits), _ptr(probs_ssm),
+                                         probs_ssm.shape[0], _ptr(ssm_row), _ptr(tree_token), _ptr(tree_parent),
+                                         _ptr(u_accept), _ptr(u_order), _ptr(u_final), float(temperature), Lmax,
+                                         _ptr(path), _ptr(ln), _ptr(toks), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _ptr(status), _stream(stream)),
+           "spec_verify_stochastic")
+    return path, ln, toks
+
+
+def spec_kv_commit(k_caches: Sequence[torch.Tensor], v_caches: Sequence[torch.Tensor], accepted_path, accepted_len,
+                   prefix_len, N: int, prefix_len_out=None, status=None, stream=None):
+    """Commits the accepted path in every layer's cache; returns prefix_len_out [B]."""
+    L = len(k_caches)
+    k0 = k_caches[0]
+    for kc, vc in zip(k_caches, v_caches):
+        _same_layout(kc, k0, "all layer caches")
+        _same_layout(vc, k0, "all layer caches")
+    B, H, S_cap, D = k0.shape
+    d = AttnDesc(B, H, H, D, N, S_cap, _dtype_code(k0.dtype), 0, N * H * D, H * D, D,
+                 k0.stride(0), k0.stride(1), k0.stride(2), 0.0, 0)
+    if prefix_len_out is None:
+        prefix_len_out = torch.empty_like(prefix_len)
+    arr_t = ctypes.c_void_p * L
+    ks = arr_t(*[kc.data_ptr() for kc in k_caches])
+    vs = arr_t(*[vc.data_ptr() for vc in v_caches])
+    _check(load().spec_kv_commit(ctypes.byref(d), L, ks, vs, _ptr(accepted_path), accepted_path.shape[1],
+                                 _ptr(accepted_len), _ptr(prefix_len), _ptr(prefix_len_out), _ptr(status),
+                                 _stream(stream)), "spec_kv_commit")
+    return prefix_len_out

@@ -1,0 +1,138 @@
+// KV-cache update kernels: append of the tree tokens' K/V in node order (Section 4.2, one shared
+// cache region for the whole tree) and commit of the accepted path (Algorithm 2 main loop: the
+// verified tokens join the sequence, so their rows become the contiguous continuation of the prefix).
+// Both are pure 16-byte-vector copies; they are bound by HBM traffic that is tiny next to attention.
+#include "spec_internal.h"
+
+namespace spec {
+
+// One thread moves 16 bytes of K and 16 bytes of V of one (request, node, head) row.
+__global__ void __launch_bounds__(256) kv_append_kernel(const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
+                                                        uint4* __restrict__ k_cache, uint4* __restrict__ v_cache,
+                                                        const int32_t* __restrict__ prefix_len, int32_t* status,
+                                                        int B, int N, int H, int S_cap, int vec_per_row,
+                                                        long q_sb, long q_sn, long q_sh,     // in uint4 units
+                                                        long kv_sb, long kv_sh, long kv_ss) {
+  const long total = (long)B * N * H * vec_per_row;
+  long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int c = (int)(idx % vec_per_row);
+  idx /= vec_per_row;
+  const int h = (int)(idx % H);
+  idx /= H;
+  const int i = (int)(idx % N);
+  const int b = (int)(idx / N);
+  const int p = prefix_len[b];
+  if (p < 0 || p > S_cap - N) {
+    if (i == 0 && h == 0 && c == 0) set_status(status, b, SPEC_ST_CAPACITY);
+    return;
+  }
+  const long src = b * q_sb + i * q_sn + h * q_sh + c;
+  const long dst = b * kv_sb + h * kv_sh + (long)(p + i) * kv_ss + c;
+  k_cache[dst] = k_new[src];
+  v_cache[dst] = v_new[src];
+}
+
+struct LayerPtrs {
+  uint4* k[SPEC_MAX_COMMIT_LAYERS];
+  uint4* v[SPEC_MAX_COMMIT_LAYERS];
+};
+
+// grid = (ceil(H * vec_per_row / 256), n_layers, B). A thread owns one 16-byte column of one head and
+// walks the path in order. Row prefix+k is written only after rows prefix+path[j], j <= k, were read
+// by the same thread (batches of 8: all loads, then all stores), and path[j] > k for j > k, so no
+// source is overwritten before it is read.
+__global__ void __launch_bounds__(256) kv_commit_kernel(LayerPtrs ptrs, const int32_t* __restrict__ path,
+                                                        const int32_t* __restrict__ len,
+                                                        const int32_t* __restrict__ prefix_len,
+                                                        int32_t* __restrict__ prefix_len_out, int32_t* status, int N,
+                                                        int H, int S_cap, int Lmax, int vec_per_row, long kv_sb,
+                                                        long kv_sh, long kv_ss) {
+  __shared__ int s_path[SPEC_MAX_TREE_NODES];
+  __shared__ int s_bad;
+  const int b = blockIdx.z;
+  const int layer = blockIdx.y;
+  const int t = threadIdx.x;
+  const int n = len[b];
+  const int p = prefix_len[b];
+  if (t == 0) s_bad = 0;
+  __syncthreads();
+  const bool cap_ok = (p >= 0) && (p <= S_cap - N);
+  const bool head_ok = cap_ok && (n >= 1) && (n <= Lmax) && (n <= N);
+  if (head_ok) {
+    for (int k = t; k < n; k += blockDim.x) {
+      const int v = path[(long)b * Lmax + k];
+      s_path[k] = v;
+      bool ok = (k == 0) ? (v == 0) : (v > path[(long)b * Lmax + k - 1] && v < N);
+      if (!ok) atomicOr(&s_bad, 1);
+    }
+  }
+  __syncthreads();
+  const bool ok = head_ok && s_bad == 0;
+  if (blockIdx.x == 0 && layer == 0 && t == 0) {
+    prefix_len_out[b] = ok ? p + n : p;
+    if (!ok) set_status(status, b, cap_ok ? SPEC_ST_BAD_PATH : SPEC_ST_CAPACITY);
+  }
+  if (!ok) return;
+  const int col = blockIdx.x * blockDim.x + t;
+  if (col >= H * vec_per_row) return;
+  const int h = col / vec_per_row, c = col % vec_per_row;
+  uint4* kc = ptrs.k[layer] + b * kv_sb + h * kv_sh + c;
+  uint4* vc = ptrs.v[layer] + b * kv_sb + h * kv_sh + c;
+  for (int k0 = 0; k0 < n; k0 += 8) {
+    uint4 kr[8], vr[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int k = k0 + j;
+      if (k < n && s_path[k] != k) {
+        kr[j] = kc[(long)(p + s_path[k]) * kv_ss];
+        vr[j] = vc[(long)(p + s_path[k]) * kv_ss];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int k = k0 + j;
+      if (k < n && s_path[k] != k) {
+        kc[(long)(p + k) * kv_ss] = kr[j];
+        vc[(long)(p + k) * kv_ss] = vr[j];
+      }
+    }
+  }
+}
+
+static inline int elem_bytes(int dtype) { return dtype == SPEC_F32 ? 4 : 2; }
+
+hipError_t launch_kv_append(const spec_attn_desc_t& d, const void* k_new, const void* v_new, void* k_cache,
+                            void* v_cache, const int32_t* prefix_len, int32_t* status, hipStream_t s) {
+  const int e = elem_bytes(d.dtype);
+  const int per16 = 16 / e;
+  const int vec_per_row = d.D / per16;
+  const long total = (long)d.B * d.N * d.H * vec_per_row;
+  const int grid = (int)((total + 255) / 256);
+  hipLaunchKernelGGL(kv_append_kernel, dim3(grid), dim3(256), 0, s, (const uint4*)k_new, (const uint4*)v_new,
+                     (uint4*)k_cache, (uint4*)v_cache, prefix_len, status, d.B, d.N, d.H, d.S_cap, vec_per_row,
+                     d.q_stride_b / per16, d.q_stride_n / per16, d.q_stride_h / per16, d.kv_stride_b / per16,
+                     d.kv_stride_h / per16, d.kv_stride_s / per16);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_commit(const spec_attn_desc_t& d, int n_layers, void* const* k_caches, void* const* v_caches,
+                            const int32_t* path, int Lmax, const int32_t* len, const int32_t* prefix_len,
+                            int32_t* prefix_len_out, int32_t* status, hipStream_t s) {
+  const int e = elem_bytes(d.dtype);
+  const int per16 = 16 / e;
+  const int vec_per_row = d.D / per16;
+  LayerPtrs ptrs;
+  for (int l = 0; l < SPEC_MAX_COMMIT_LAYERS; ++l) {
+    ptrs.k[l] = (uint4*)(l < n_layers ? k_caches[l] : nullptr);
+    ptrs.v[l] = (uint4*)(l < n_layers ? v_caches[l] : nullptr);
+  }
+  const int cols = d.H * vec_per_row;
+  dim3 grid((cols + 255) / 256, n_layers, d.B);
+  hipLaunchKernelGGL(kv_commit_kernel, grid, dim3(256), 0, s, ptrs, path, len, prefix_len, prefix_len_out, status, d.N,
+                     d.H, d.S_cap, Lmax, vec_per_row, d.kv_stride_b / per16, d.kv_stride_h / per16,
+                     d.kv_stride_s / per16);
+  return hipGetLastError();
+}
+
+}  // namespace spec

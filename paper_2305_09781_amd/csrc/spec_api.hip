@@ -1,0 +1,221 @@
+// C ABI of libspectree: host-side argument checks and kernel launches. Every entry point validates
+// what the host can see, enqueues its kernels on the caller's stream and returns; nothing here
+// allocates or synchronises.
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+
+#include "spec_internal.h"
+
+namespace spec {
+
+static inline int elem_bytes(int dtype) { return dtype == SPEC_F32 ? 4 : 2; }
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static int env_int(const char* name, int dflt) {
+  const char* v = std::getenv(name);
+  if (v == nullptr || *v == 0) return dflt;
+  return std::atoi(v);
+}
+
+// Host-checkable part of the attention descriptor. Returns SPEC_OK or an error code.
+static int check_desc(const spec_attn_desc_t* d) {
+  if (d == nullptr) return SPEC_ERR_INVALID_ARG;
+  if (d->B <= 0 || d->H <= 0 || d->H_kv <= 0 || d->N <= 0 || d->S_cap <= 0 || d->D <= 0) return SPEC_ERR_INVALID_ARG;
+  if (d->reserved != 0) return SPEC_ERR_INVALID_ARG;
+  if (d->dtype != SPEC_F32 && d->dtype != SPEC_BF16) return SPEC_ERR_UNSUPPORTED;
+  if (d->D != 64 && d->D != 128) return SPEC_ERR_UNSUPPORTED;
+  if (d->N > SPEC_MAX_TREE_NODES) return SPEC_ERR_UNSUPPORTED;
+  if (d->H_kv != d->H) return SPEC_ERR_UNSUPPORTED;
+  if (d->N > d->S_cap) return SPEC_ERR_CAPACITY;
+  if (d->max_prefix_len < 0 || (long)d->max_prefix_len + d->N > d->S_cap) return SPEC_ERR_CAPACITY;
+  if (!(d->softmax_scale >= 0.f) || std::isinf(d->softmax_scale)) return SPEC_ERR_INVALID_ARG;
+  const int per16 = 16 / elem_bytes(d->dtype);
+  const int64_t strides[6] = {d->q_stride_b, d->q_stride_n, d->q_stride_h, d->kv_stride_b, d->kv_stride_h, d->kv_stride_s};
+  for (int64_t s : strides)
+    if (s <= 0 || s % per16 != 0) return SPEC_ERR_INVALID_ARG;
+  if (d->q_stride_h < d->D || d->kv_stride_s < d->D) return SPEC_ERR_INVALID_ARG;
+  return SPEC_OK;
+}
+
+AttnPlan make_attn_plan(const spec_attn_desc_t& d) {
+  AttnPlan p;
+  const int max_prefix = d.max_prefix_len > 0 ? d.max_prefix_len : d.S_cap - d.N;
+  const int max_len = max_prefix + d.N;
+  int chunk = env_int("SPEC_TREE_CHUNK_KEYS", 0);
+  if (chunk <= 0) {
+    // aim at a few workgroups per compute unit while keeping chunks long enough to amortise the
+    // per-workgroup prologue and merge
+    const int nq = d.dtype == SPEC_BF16 ? (d.N <= 16 ? 16 : 32) : SPEC_MAX_TREE_NODES;
+    const long groups = (long)d.B * d.H * ((d.N + nq - 1) / nq);
+    const long target_wgs = 256L * 4;
+    long splits = (target_wgs + groups - 1) / groups;
+    if (splits < 1) splits = 1;
+    chunk = (int)((max_len + splits - 1) / splits);
+    if (chunk < 128) chunk = 128;
+  }
+  chunk = (int)round_up((size_t)chunk, 32);
+  p.chunk_keys = chunk;
+  p.n_splits = (max_len + chunk - 1) / chunk;
+  if (p.n_splits <= 1) {
+    p.n_splits = 1;
+    p.ws_o_off = p.ws_ml_off = 0;
+    p.ws_bytes = 0;
+  } else {
+    const size_t rows = (size_t)d.B * d.H * p.n_splits * d.N;
+    p.ws_o_off = 0;
+    p.ws_ml_off = round_up(rows * d.D * sizeof(float), 256);
+    p.ws_bytes = p.ws_ml_off + round_up(rows * 2 * sizeof(float), 256);
+  }
+  return p;
+}
+
+}  // namespace spec
+
+using namespace spec;
+
+extern "C" {
+
+int spec_version(void) { return 100; }
+
+const char* spec_strerror(int code) {
+  switch (code) {
+    case SPEC_OK: return "ok";
+    case SPEC_ERR_INVALID_ARG: return "invalid argument (null pointer, non-positive size, bad stride or alignment)";
+    case SPEC_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+    case SPEC_ERR_CAPACITY: return "tree does not fit the cache capacity";
+    case SPEC_ERR_HIP: return "HIP runtime error";
+    case SPEC_ERR_WORKSPACE: return "workspace missing or too small";
+    default: return "unknown error code";
+  }
+}
+
+int spec_kv_append(const spec_attn_desc_t* desc, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                   const int32_t* prefix_len, int32_t* status, void* hip_stream) {
+  const int rc = check_desc(desc);
+  if (rc != SPEC_OK) return rc;
+  if (!k_new || !v_new || !k_cache || !v_cache || !prefix_len) return SPEC_ERR_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache)) return SPEC_ERR_INVALID_ARG;
+  return launch_kv_append(*desc, k_new, v_new, k_cache, v_cache, prefix_len, status, (hipStream_t)hip_stream) == hipSuccess
+             ? SPEC_OK
+             : SPEC_ERR_HIP;
+}
+
+size_t spec_tree_attention_workspace_bytes(const spec_attn_desc_t* desc) {
+  if (check_desc(desc) != SPEC_OK) return 0;
+  return make_attn_plan(*desc).ws_bytes;
+}
+
+int spec_tree_attention(const spec_attn_desc_t* desc, const void* q, const void* k_cache, const void* v_cache,
+                        const int32_t* tree_parent, const int32_t* tree_depth, const int32_t* prefix_len, void* out,
+                        void* workspace, size_t workspace_bytes, int32_t* status, void* hip_stream) {
+  const int rc = check_desc(desc);
+  if (rc != SPEC_OK) return rc;
+  if (!q || !k_cache || !v_cache || !tree_parent || !tree_depth || !prefix_len || !out) return SPEC_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out)) return SPEC_ERR_INVALID_ARG;
+  const AttnPlan plan = make_attn_plan(*desc);
+  if (plan.ws_bytes > 0) {
+    if (workspace == nullptr || workspace_bytes < plan.ws_bytes) return SPEC_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return SPEC_ERR_INVALID_ARG;
+  }
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipError_t e;
+  if (desc->dtype == SPEC_BF16)
+    e = launch_tree_attention_bf16(*desc, plan, q, k_cache, v_cache, tree_parent, tree_depth, prefix_len, out, workspace,
+                                   status, s);
+  else
+    e = launch_tree_attention_f32(*desc, plan, (const float*)q, (const float*)k_cache, (const float*)v_cache, tree_parent,
+                                  tree_depth, prefix_len, (float*)out, workspace, status, s);
+  if (e != hipSuccess) return SPEC_ERR_HIP;
+  if (plan.n_splits > 1) {
+    e = launch_attn_combine(*desc, plan, tree_parent, tree_depth, prefix_len, workspace, out, status, s);
+    if (e != hipSuccess) return SPEC_ERR_HIP;
+  }
+  return SPEC_OK;
+}
+
+static int check_verify_common(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, const void* logits,
+                               const int32_t* tree_token, const int32_t* tree_parent, int32_t Lmax,
+                               const int32_t* accepted_path, const int32_t* accepted_len, const int32_t* out_tokens) {
+  if (B <= 0 || N <= 0 || V <= 0 || Lmax <= 0) return SPEC_ERR_INVALID_ARG;
+  if (N > SPEC_MAX_TREE_NODES) return SPEC_ERR_UNSUPPORTED;
+  if (logits_dtype != SPEC_F32 && logits_dtype != SPEC_BF16) return SPEC_ERR_UNSUPPORTED;
+  if (!logits || !tree_token || !tree_parent || !accepted_path || !accepted_len || !out_tokens) return SPEC_ERR_INVALID_ARG;
+  if (!aligned16(logits)) return SPEC_ERR_INVALID_ARG;
+  return SPEC_OK;
+}
+
+int spec_verify_greedy(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, const void* logits_llm,
+                       const int32_t* tree_token, const int32_t* tree_parent, int32_t Lmax, int32_t* accepted_path,
+                       int32_t* accepted_len, int32_t* out_tokens, int32_t* node_argmax, void* workspace,
+                       size_t workspace_bytes, int32_t* status, void* hip_stream) {
+  const int rc = check_verify_common(B, N, V, logits_dtype, logits_llm, tree_token, tree_parent, Lmax, accepted_path,
+                                     accepted_len, out_tokens);
+  if (rc != SPEC_OK) return rc;
+  if (node_argmax == nullptr) {
+    if (workspace == nullptr || workspace_bytes < (size_t)B * N * sizeof(int32_t)) return SPEC_ERR_WORKSPACE;
+    node_argmax = (int32_t*)workspace;
+  }
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (launch_node_stats(B, N, V, logits_dtype, logits_llm, 1.0f, node_argmax, nullptr, nullptr, s) != hipSuccess)
+    return SPEC_ERR_HIP;
+  if (launch_greedy_walk(B, N, node_argmax, tree_token, tree_parent, Lmax, accepted_path, accepted_len, out_tokens,
+                         status, s) != hipSuccess)
+    return SPEC_ERR_HIP;
+  return SPEC_OK;
+}
+
+size_t spec_verify_stochastic_workspace_bytes(int32_t B, int32_t N, int32_t V) {
+  if (B <= 0 || N <= 0 || V <= 0) return 0;
+  // node max + node sum-exp, then two residual buffers of V floats per request
+  return round_up((size_t)B * N * 2 * sizeof(float), 256) + round_up((size_t)2 * B * V * sizeof(float), 256);
+}
+
+int spec_verify_stochastic(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, const void* logits_llm,
+                           const float* probs_ssm, int32_t R, const int32_t* ssm_row, const int32_t* tree_token,
+                           const int32_t* tree_parent, const float* u_accept, const float* u_order,
+                           const float* u_final, float temperature, int32_t Lmax, int32_t* accepted_path,
+                           int32_t* accepted_len, int32_t* out_tokens, void* workspace, size_t workspace_bytes,
+                           int32_t* status, void* hip_stream) {
+  const int rc = check_verify_common(B, N, V, logits_dtype, logits_llm, tree_token, tree_parent, Lmax, accepted_path,
+                                     accepted_len, out_tokens);
+  if (rc != SPEC_OK) return rc;
+  if (!ssm_row || !u_accept || !u_order || !u_final) return SPEC_ERR_INVALID_ARG;
+  if (R < 0 || (R > 0 && probs_ssm == nullptr)) return SPEC_ERR_INVALID_ARG;
+  if (!(temperature > 0.f) || std::isinf(temperature)) return SPEC_ERR_INVALID_ARG;
+  const size_t need = spec_verify_stochastic_workspace_bytes(B, N, V);
+  if (workspace == nullptr || workspace_bytes < need) return SPEC_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return SPEC_ERR_INVALID_ARG;
+  float* node_max = (float*)workspace;
+  float* node_sumexp = node_max + (size_t)B * N;
+  float* resid = (float*)((char*)workspace + round_up((size_t)B * N * 2 * sizeof(float), 256));
+  const float inv_temp = 1.0f / temperature;
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (launch_node_stats(B, N, V, logits_dtype, logits_llm, inv_temp, nullptr, node_max, node_sumexp, s) != hipSuccess)
+    return SPEC_ERR_HIP;
+  if (launch_stochastic_walk(B, N, V, logits_dtype, logits_llm, probs_ssm, R, ssm_row, tree_token, tree_parent, u_accept,
+                             u_order, u_final, inv_temp, node_max, node_sumexp, resid, Lmax, accepted_path, accepted_len,
+                             out_tokens, status, s) != hipSuccess)
+    return SPEC_ERR_HIP;
+  return SPEC_OK;
+}
+
+int spec_kv_commit(const spec_attn_desc_t* desc, int32_t n_layers, void* const* k_caches, void* const* v_caches,
+                   const int32_t* accepted_path, int32_t Lmax, const int32_t* accepted_len, const int32_t* prefix_len,
+                   int32_t* prefix_len_out, int32_t* status, void* hip_stream) {
+  const int rc = check_desc(desc);
+  if (rc != SPEC_OK) return rc;
+  if (n_layers <= 0 || Lmax <= 0) return SPEC_ERR_INVALID_ARG;
+  if (n_layers > SPEC_MAX_COMMIT_LAYERS) return SPEC_ERR_UNSUPPORTED;
+  if (!k_caches || !v_caches || !accepted_path || !accepted_len || !prefix_len || !prefix_len_out) return SPEC_ERR_INVALID_ARG;
+  if (prefix_len_out == prefix_len) return SPEC_ERR_INVALID_ARG;
+  for (int l = 0; l < n_layers; ++l)
+    if (!k_caches[l] || !v_caches[l] || !aligned16(k_caches[l]) || !aligned16(v_caches[l])) return SPEC_ERR_INVALID_ARG;
+  return launch_kv_commit(*desc, n_layers, k_caches, v_caches, accepted_path, Lmax, accepted_len, prefix_len,
+                          prefix_len_out, status, (hipStream_t)hip_stream) == hipSuccess
+             ? SPEC_OK
+             : SPEC_ERR_HIP;
+}
+
+}  // extern "C"

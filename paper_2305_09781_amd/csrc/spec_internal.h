@@ -1,0 +1,87 @@
+// Internal declarations shared by the translation units of libspectree (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "spec_tree.h"
+
+namespace spec {
+
+// ---------------------------------------------------------------------------------------------
+// Launch plan of one tree-attention call: how the key range [0, prefix_len + N) of every
+// (request, head) is cut into chunks (one workgroup each) and where the partial results live.
+// ---------------------------------------------------------------------------------------------
+struct AttnPlan {
+  int chunk_keys;   // keys per workgroup (multiple of 32)
+  int n_splits;     // chunks covering max_prefix_len + N
+  size_t ws_o_off;  // float [B][H][n_splits][N][D]   un-normalised partial outputs
+  size_t ws_ml_off; // float [B][H][n_splits][N][2]   running max (log2 domain) and partial sum
+  size_t ws_bytes;
+};
+
+AttnPlan make_attn_plan(const spec_attn_desc_t& d);
+
+// Kernel launchers (defined in the .hip files). All return hipError_t of the launch.
+hipError_t launch_kv_append(const spec_attn_desc_t& d, const void* k_new, const void* v_new, void* k_cache,
+                            void* v_cache, const int32_t* prefix_len, int32_t* status, hipStream_t s);
+hipError_t launch_kv_commit(const spec_attn_desc_t& d, int n_layers, void* const* k_caches, void* const* v_caches,
+                            const int32_t* path, int Lmax, const int32_t* len, const int32_t* prefix_len,
+                            int32_t* prefix_len_out, int32_t* status, hipStream_t s);
+hipError_t launch_tree_attention_f32(const spec_attn_desc_t& d, const AttnPlan& plan, const float* q,
+                                     const float* k_cache, const float* v_cache, const int32_t* parent,
+                                     const int32_t* depth, const int32_t* prefix_len, float* out, void* ws,
+                                     int32_t* status, hipStream_t s);
+hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan& plan, const void* q,
+                                      const void* k_cache, const void* v_cache, const int32_t* parent,
+                                      const int32_t* depth, const int32_t* prefix_len, void* out, void* ws,
+                                      int32_t* status, hipStream_t s);
+hipError_t launch_attn_combine(const spec_attn_desc_t& d, const AttnPlan& plan, const int32_t* parent,
+                               const int32_t* depth, const int32_t* prefix_len, const void* ws, void* out,
+                               int32_t* status, hipStream_t s);
+hipError_t launch_node_stats(int B, int N, int V, int logits_dtype, const void* logits, float inv_temp,
+                             int32_t* node_argmax, float* node_max, float* node_sumexp, hipStream_t s);
+hipError_t launch_greedy_walk(int B, int N, const int32_t* node_argmax, const int32_t* token, const int32_t* parent,
+                              int Lmax, int32_t* path, int32_t* len, int32_t* out_tokens, int32_t* status,
+                              hipStream_t s);
+hipError_t launch_stochastic_walk(int B, int N, int V, int logits_dtype, const void* logits, const float* probs_ssm,
+                                  int R, const int32_t* ssm_row, const int32_t* token, const int32_t* parent,
+                                  const float* u_accept, const float* u_order, const float* u_final, float inv_temp,
+                                  const float* node_max, const float* node_sumexp, float* resid, int Lmax,
+                                  int32_t* path, int32_t* len, int32_t* out_tokens, int32_t* status, hipStream_t s);
+
+// ---------------------------------------------------------------------------------------------
+// Device helpers
+// ---------------------------------------------------------------------------------------------
+#ifdef __HIPCC__
+
+// Validates one request's tree with the threads of a workgroup (blockDim.x >= N).
+// Returns true for every thread iff parent[0] == -1, 0 <= parent[i] < i and depth[i] == depth[parent[i]] + 1.
+// `flag` is one int of LDS. Contains two __syncthreads().
+__device__ inline bool tree_is_valid(const int32_t* __restrict__ parent, const int32_t* __restrict__ depth, int N,
+                                     int* flag) {
+  const int t = threadIdx.x;
+  if (t == 0) *flag = 0;
+  __syncthreads();
+  if (t < N) {
+    const int p = parent[t];
+    bool ok;
+    if (t == 0) {
+      ok = (p == -1) && (depth == nullptr || depth[0] == 0);
+    } else {
+      ok = (p >= 0) && (p < t);
+      if (ok && depth != nullptr) ok = depth[t] == depth[p] + 1;
+    }
+    if (!ok) atomicOr(flag, 1);
+  }
+  __syncthreads();
+  return *flag == 0;
+}
+
+__device__ inline void set_status(int32_t* status, int b, int bit) {
+  if (status != nullptr) atomicOr(&status[b], bit);
+}
+
+#endif  // __HIPCC__
+
+}  // namespace spec

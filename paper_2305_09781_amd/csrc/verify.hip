@@ -1,0 +1,366 @@
+// Token-tree verification on the GPU (Algorithm 2: VerifyGreedy and VerifyStochastic, Section 4.3).
+//
+// The paper runs verification on the host after copying the LLM's per-node outputs back; here it
+// stays on the device so an iteration needs no host round trip. Three kernels:
+//   node_stats_kernel      one workgroup per (request, node) row of logits: argmax (lowest token id on
+//                          ties), max, and sum of exp((x - max)/T). All nodes in parallel, so the
+//                          sequential tree walk that follows needs P(x) at a node in O(1).
+//   greedy_walk_kernel     one workgroup per request: follow children whose token equals the node's
+//                          argmax; emit the bonus token.
+//   stochastic_walk_kernel one workgroup per request: multi-step speculative sampling. The first ratio
+//                          test at a node uses the precomputed softmax statistics; only a rejection
+//                          materialises the residual distribution norm(max(0, P - Q)) (one pass over
+//                          the vocabulary per rejection, kept un-normalised with its mass Z). The last
+//                          token is drawn by inverse CDF with a float64 block scan in token-id order.
+#include <hip/hip_bf16.h>
+
+#include "spec_internal.h"
+
+namespace spec {
+
+template <bool BF16>
+__device__ inline float load_logit(const void* base, long idx) {
+  if (BF16) return __bfloat162float(((const __hip_bfloat16*)base)[idx]);
+  return ((const float*)base)[idx];
+}
+
+// ---------------------------------------------------------------------------------------------
+// block-wide reductions (blockDim.x multiple of 64, <= 1024); `scratch` holds >= 16 + 1 entries
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__device__ inline T block_sum(T v, T* scratch) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) scratch[w] = v;
+  __syncthreads();
+  T tot = 0;
+  for (int i = 0; i < nw; ++i) tot += scratch[i];
+  return tot;
+}
+
+// ---------------------------------------------------------------------------------------------
+// per-node statistics
+// ---------------------------------------------------------------------------------------------
+template <bool BF16>
+__global__ void __launch_bounds__(256) node_stats_kernel(const void* __restrict__ logits, int V, float inv_temp,
+                                                         int32_t* __restrict__ node_argmax,
+                                                         float* __restrict__ node_max,
+                                                         float* __restrict__ node_sumexp) {
+  __shared__ float s_val[4];
+  __shared__ int s_idx[4];
+  __shared__ float s_sum[17];
+  const long row = blockIdx.x;
+  const int t = threadIdx.x;
+  const long base = row * V;
+  float best = -INFINITY;
+  int best_i = 0x7fffffff;
+  const bool vec = !BF16 && (V % 4 == 0);
+  if (vec) {
+    const float4* p = (const float4*)((const float*)logits + base);
+    for (int i = t; i < V / 4; i += 256) {
+      const float4 x = p[i];
+      if (x.x > best) { best = x.x; best_i = 4 * i; }
+      if (x.y > best) { best = x.y; best_i = 4 * i + 1; }
+      if (x.z > best) { best = x.z; best_i = 4 * i + 2; }
+      if (x.w > best) { best = x.w; best_i = 4 * i + 3; }
+    }
+  } else {
+    for (int i = t; i < V; i += 256) {
+      const float x = load_logit<BF16>(logits, base + i);
+      if (x > best) { best = x; best_i = i; }
+    }
+  }
+  // reduce (value desc, index asc)
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(best, o);
+    const int oi = __shfl_xor(best_i, o);
+    if (ov > best || (ov == best && oi < best_i)) { best = ov; best_i = oi; }
+  }
+  if ((t & 63) == 0) { s_val[t >> 6] = best; s_idx[t >> 6] = best_i; }
+  __syncthreads();
+  best = s_val[0]; best_i = s_idx[0];
+  for (int w = 1; w < 4; ++w)
+    if (s_val[w] > best || (s_val[w] == best && s_idx[w] < best_i)) { best = s_val[w]; best_i = s_idx[w]; }
+  if (best_i == 0x7fffffff) best_i = 0;   // all -inf / NaN row
+  float sum = 0.f;
+  if (node_sumexp != nullptr) {
+    if (vec) {
+      const float4* p = (const float4*)((const float*)logits + base);
+      for (int i = t; i < V / 4; i += 256) {
+        const float4 x = p[i];
+        sum += expf((x.x - best) * inv_temp) + expf((x.y - best) * inv_temp) + expf((x.z - best) * inv_temp) +
+               expf((x.w - best) * inv_temp);
+      }
+    } else {
+      for (int i = t; i < V; i += 256) sum += expf((load_logit<BF16>(logits, base + i) - best) * inv_temp);
+    }
+    sum = block_sum(sum, s_sum);
+  }
+  if (t == 0) {
+    if (node_argmax != nullptr) node_argmax[row] = best_i;
+    if (node_max != nullptr) node_max[row] = best;
+    if (node_sumexp != nullptr) node_sumexp[row] = sum;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// greedy walk: blockDim = 128, thread v <-> node v
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(128) greedy_walk_kernel(int N, const int32_t* __restrict__ node_argmax,
+                                                          const int32_t* __restrict__ token,
+                                                          const int32_t* __restrict__ parent, int Lmax,
+                                                          int32_t* __restrict__ path, int32_t* __restrict__ len,
+                                                          int32_t* __restrict__ out_tokens, int32_t* status) {
+  __shared__ int s_next;
+  __shared__ int s_flag;
+  const int b = blockIdx.x, v = threadIdx.x;
+  const bool valid = tree_is_valid(parent + (long)b * N, nullptr, N, &s_flag);
+  for (int k = v; k < Lmax; k += 128) {
+    path[(long)b * Lmax + k] = -1;
+    out_tokens[(long)b * Lmax + k] = -1;
+  }
+  if (!valid) {
+    if (v == 0) { len[b] = 0; set_status(status, b, SPEC_ST_BAD_TREE); }
+    return;
+  }
+  const int my_parent = v < N ? parent[(long)b * N + v] : -2;
+  const int my_token = v < N ? token[(long)b * N + v] : -1;
+  __syncthreads();   // padding writes above are ordered before the walk's writes (same block)
+  int u = 0, k = 0;
+  if (v == 0) path[(long)b * Lmax] = 0;
+  while (k + 1 < Lmax) {
+    if (v == 0) s_next = 0x7fffffff;
+    __syncthreads();
+    const int want = node_argmax[(long)b * N + u];
+    if (my_parent == u && my_token == want) atomicMin(&s_next, v);
+    __syncthreads();
+    const int nxt = s_next;
+    __syncthreads();
+    if (nxt == 0x7fffffff) break;
+    if (v == 0) {
+      out_tokens[(long)b * Lmax + k] = token[(long)b * N + nxt];
+      path[(long)b * Lmax + k + 1] = nxt;
+    }
+    ++k;
+    u = nxt;
+  }
+  if (v == 0) {
+    out_tokens[(long)b * Lmax + k] = node_argmax[(long)b * N + u];
+    len[b] = k + 1;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// stochastic walk: blockDim = 1024
+// ---------------------------------------------------------------------------------------------
+constexpr int SW_THREADS = 1024;
+
+template <bool BF16>
+__global__ void __launch_bounds__(SW_THREADS) stochastic_walk_kernel(
+    int N, int V, const void* __restrict__ logits, const float* __restrict__ probs_ssm, int R,
+    const int32_t* __restrict__ ssm_row, const int32_t* __restrict__ token, const int32_t* __restrict__ parent,
+    const float* __restrict__ u_accept, const float* __restrict__ u_order, const float* __restrict__ u_final,
+    float inv_temp, const float* __restrict__ node_max, const float* __restrict__ node_sumexp,
+    float* __restrict__ resid_all, int Lmax, int32_t* __restrict__ path, int32_t* __restrict__ len,
+    int32_t* __restrict__ out_tokens, int32_t* status) {
+  __shared__ int s_flag;
+  __shared__ int s_child[SPEC_MAX_TREE_NODES];
+  __shared__ int s_sorted[SPEC_MAX_TREE_NODES];
+  __shared__ int s_nchild;
+  __shared__ float s_fsum[17];
+  __shared__ double s_dsum[17];
+  __shared__ double s_scan[SW_THREADS / 64];
+  __shared__ int s_pick;
+
+  const int b = blockIdx.x, t = threadIdx.x;
+  float* resid0 = resid_all + (long)b * V;
+  float* resid1 = resid_all + ((long)gridDim.x + b) * V;
+  float* resid = resid0;
+  int cur = 0;   // resid == (cur ? resid1 : resid0)
+  const int32_t* par = parent + (long)b * N;
+  const int32_t* tok = token + (long)b * N;
+
+  bool valid = tree_is_valid(par, nullptr, N, &s_flag);
+  __syncthreads();
+  if (t == 0) s_flag = 0;
+  __syncthreads();
+  if (valid && t >= 1 && t < N) {
+    const int x = tok[t], r = ssm_row[(long)b * N + t];
+    if (x < 0 || x >= V || r < 0 || r >= R) atomicOr(&s_flag, 1);
+  }
+  __syncthreads();
+  valid = valid && (s_flag == 0);
+  for (int k = t; k < Lmax; k += SW_THREADS) {
+    path[(long)b * Lmax + k] = -1;
+    out_tokens[(long)b * Lmax + k] = -1;
+  }
+  if (!valid) {
+    if (t == 0) { len[b] = 0; set_status(status, b, SPEC_ST_BAD_TREE); }
+    return;
+  }
+  __syncthreads();
+  if (t == 0) path[(long)b * Lmax] = 0;
+
+  int u = 0, k = 0;
+  bool implicit = true;   // current P is softmax(logits[u]) given by (node_max, node_sumexp); else resid / Z
+  float Z = 1.f;
+  float mx = node_max[(long)b * N], se = node_sumexp[(long)b * N];
+  while (true) {
+    // children of u in ascending (u_order, index)
+    if (t == 0) s_nchild = 0;
+    __syncthreads();
+    if (t < N && par[t] == u) s_child[atomicAdd(&s_nchild, 1)] = t;
+    __syncthreads();
+    const int nchild = (k + 1 < Lmax) ? s_nchild : 0;
+    if (nchild == 0) break;
+    if (t < nchild) {
+      const int me = s_child[t];
+      const float mk = u_order[(long)b * N + me];
+      int rank = 0;
+      for (int j = 0; j < nchild; ++j) {
+        const int o = s_child[j];
+        const float ok = u_order[(long)b * N + o];
+        rank += (ok < mk) || (ok == mk && o < me);
+      }
+      s_sorted[rank] = me;
+    }
+    __syncthreads();
+    bool accepted = false;
+    int next_u = -1;
+    for (int j = 0; j < nchild; ++j) {
+      const int s = s_sorted[j];
+      const int x = tok[s];
+      const float* Q = probs_ssm + (long)ssm_row[(long)b * N + s] * V;
+      const float r = u_accept[(long)b * N + s];
+      float px;
+      if (implicit) px = expf((load_logit<BF16>(logits, ((long)b * N + u) * V + x) - mx) * inv_temp) / se;
+      else px = resid[x] / Z;
+      if (r * Q[x] <= px) {
+        accepted = true;
+        next_u = s;
+        if (t == 0) {
+          out_tokens[(long)b * Lmax + k] = x;
+          path[(long)b * Lmax + k + 1] = s;
+        }
+        break;
+      }
+      // rejected: P := norm(max(0, P - Q)), kept as un-normalised values plus their sum Z. The new
+      // residual goes to the other buffer, so an empty residual simply keeps the previous P.
+      float* dst = cur ? resid0 : resid1;
+      float part = 0.f;
+      const float invZ = 1.f / Z, inv_se = 1.f / se;
+      for (int i = t; i < V; i += SW_THREADS) {
+        float p;
+        if (implicit) p = expf((load_logit<BF16>(logits, ((long)b * N + u) * V + i) - mx) * inv_temp) * inv_se;
+        else p = resid[i] * invZ;
+        const float d = fmaxf(0.f, p - Q[i]);
+        part += d;
+        dst[i] = d;
+      }
+      const float Znew = block_sum(part, s_fsum);
+      if (Znew > 0.f) {
+        Z = Znew;
+        implicit = false;
+        resid = dst;
+        cur ^= 1;
+      } else if (t == 0) {
+        set_status(status, b, SPEC_ST_ZERO_RESIDUAL);
+      }
+      __syncthreads();   // the new residual is visible to every thread before the next test reads it
+    }
+    if (!accepted) break;
+    u = next_u;
+    ++k;
+    implicit = true;
+    resid = resid0;
+    cur = 0;
+    mx = node_max[(long)b * N + u];
+    se = node_sumexp[(long)b * N + u];
+    __syncthreads();
+  }
+
+  // final token: inverse CDF in ascending token id, float64 running sum over contiguous per-thread chunks
+  const int chunk = (V + SW_THREADS - 1) / SW_THREADS;
+  const int i0 = min(t * chunk, V), i1 = min(i0 + chunk, V);
+  double mine = 0.0;
+  for (int i = i0; i < i1; ++i) {
+    const float w = implicit ? expf((load_logit<BF16>(logits, ((long)b * N + u) * V + i) - mx) * inv_temp) : resid[i];
+    mine += (double)w;
+  }
+  // inclusive scan over threads: wave-level shuffles, then wave totals
+  double incl = mine;
+  const int lane = t & 63, wv = t >> 6;
+  for (int o = 1; o < 64; o <<= 1) {
+    const double up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
+  }
+  if (lane == 63) s_scan[wv] = incl;
+  if (t == 0) s_pick = 0x7fffffff;
+  __syncthreads();
+  double before = 0.0, total = 0.0;
+  for (int w = 0; w < SW_THREADS / 64; ++w) {
+    if (w < wv) before += s_scan[w];
+    total += s_scan[w];
+  }
+  incl += before;
+  const double excl = incl - mine;
+  const double target = (double)u_final[b] * total;
+  // the first thread whose inclusive sum exceeds the target holds the answer
+  if (incl > target && excl <= target && i1 > i0) atomicMin(&s_pick, t);
+  __syncthreads();
+  const int pick = s_pick;
+  if (pick == 0x7fffffff) {
+    if (t == 0) { out_tokens[(long)b * Lmax + k] = V - 1; len[b] = k + 1; }
+    return;
+  }
+  if (t == pick) {
+    double run = excl;
+    int ans = i1 - 1;
+    for (int i = i0; i < i1; ++i) {
+      const float w = implicit ? expf((load_logit<BF16>(logits, ((long)b * N + u) * V + i) - mx) * inv_temp) : resid[i];
+      run += (double)w;
+      if (run > target) { ans = i; break; }
+    }
+    out_tokens[(long)b * Lmax + k] = ans;
+    len[b] = k + 1;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+hipError_t launch_node_stats(int B, int N, int V, int logits_dtype, const void* logits, float inv_temp,
+                             int32_t* node_argmax, float* node_max, float* node_sumexp, hipStream_t s) {
+  if (logits_dtype == SPEC_BF16)
+    hipLaunchKernelGGL(node_stats_kernel<true>, dim3(B * N), dim3(256), 0, s, logits, V, inv_temp, node_argmax, node_max,
+                       node_sumexp);
+  else
+    hipLaunchKernelGGL(node_stats_kernel<false>, dim3(B * N), dim3(256), 0, s, logits, V, inv_temp, node_argmax,
+                       node_max, node_sumexp);
+  return hipGetLastError();
+}
+
+hipError_t launch_greedy_walk(int B, int N, const int32_t* node_argmax, const int32_t* token, const int32_t* parent,
+                              int Lmax, int32_t* path, int32_t* len, int32_t* out_tokens, int32_t* status,
+                              hipStream_t s) {
+  hipLaunchKernelGGL(greedy_walk_kernel, dim3(B), dim3(128), 0, s, N, node_argmax, token, parent, Lmax, path, len,
+                     out_tokens, status);
+  return hipGetLastError();
+}
+
+hipError_t launch_stochastic_walk(int B, int N, int V, int logits_dtype, const void* logits, const float* probs_ssm,
+                                  int R, const int32_t* ssm_row, const int32_t* token, const int32_t* parent,
+                                  const float* u_accept, const float* u_order, const float* u_final, float inv_temp,
+                                  const float* node_max, const float* node_sumexp, float* resid, int Lmax,
+                                  int32_t* path, int32_t* len, int32_t* out_tokens, int32_t* status, hipStream_t s) {
+  if (logits_dtype == SPEC_BF16)
+    hipLaunchKernelGGL(stochastic_walk_kernel<true>, dim3(B), dim3(SW_THREADS), 0, s, N, V, logits, probs_ssm, R, ssm_row,
+                       token, parent, u_accept, u_order, u_final, inv_temp, node_max, node_sumexp, resid, Lmax, path,
+                       len, out_tokens, status);
+  else
+    hipLaunchKernelGGL(stochastic_walk_kernel<false>, dim3(B), dim3(SW_THREADS), 0, s, N, V, logits, probs_ssm, R,
+                       ssm_row, token, parent, u_accept, u_order, u_final, inv_temp, node_max, node_sumexp, resid, Lmax,
+                       path, len, out_tokens, status);
+  return hipGetLastError();
+}
+
+}  // namespace spec

@@ -15,6 +15,7 @@ bytes.
 """
 from __future__ import annotations
 
+import concurrent.futures
 import dataclasses
 from typing import Dict, List, Optional, Sequence, Tuple
 
@@ -178,8 +179,27 @@ def make_trees(cfg: Config, rng: np.random.Generator) -> np.ndarray:
 # attention-side tensors
 # --------------------------------------------------------------------------------------------------
 
+_BIG = 1 << 22     # elements per independently seeded block of a large array
+
+
 def _normal(rng: np.random.Generator, shape, dtype: torch.dtype, scale: float = 1.0) -> torch.Tensor:
-    x = rng.standard_normal(shape, dtype=np.float32)
+    """N(0, scale) values of `shape` in `dtype`. Large arrays are filled block-wise by child generators
+    whose seeds are drawn from `rng`, on a few threads; the result does not depend on the threading."""
+    n = int(np.prod(shape))
+    if n <= _BIG:
+        x = rng.standard_normal(shape, dtype=np.float32)
+    else:
+        x = np.empty(n, dtype=np.float32)
+        nblk = (n + _BIG - 1) // _BIG
+        seeds = rng.integers(0, 2 ** 63 - 1, size=nblk)
+
+        def fill(i):
+            lo, hi = i * _BIG, min((i + 1) * _BIG, n)
+            np.random.Generator(np.random.PCG64(int(seeds[i]))).standard_normal(out=x[lo:hi], dtype=np.float32)
+
+        with concurrent.futures.ThreadPoolExecutor(max_workers=8) as ex:
+            list(ex.map(fill, range(nblk)))
+        x = x.reshape(shape)
     if scale != 1.0:
         x *= np.float32(scale)
     return torch.from_numpy(x).to(dtype)
@@ -240,7 +260,8 @@ def make_logits(cfg: Config, rng: np.random.Generator, dtype: torch.dtype = torc
 
 def plant_greedy_tokens(rng: np.random.Generator, logits: torch.Tensor, parent: np.ndarray) -> np.ndarray:
     """tree_token [B,N]: for a node with c children, with probability GREEDY_MATCH_RATE[c] one child
-    (uniformly chosen) carries the position of the node's largest logit; all siblings distinct."""
+    (uniformly chosen) carries the position of the node's largest logit; siblings are distinct unless
+    the vocabulary is too small for that."""
     B, N, V = logits.shape
     top = torch.argmax(logits.float(), dim=-1).numpy()   # only used to place a matching token
     tok = rng.integers(0, V, size=(B, N)).astype(np.int32)
@@ -259,7 +280,9 @@ def plant_greedy_tokens(rng: np.random.Generator, logits: torch.Tensor, parent: 
                     t = int(top[b, u])
                 else:
                     t = int(rng.integers(0, V))
-                    while t in used or t == int(top[b, u]):
+                    for _ in range(32):      # distinct non-matching siblings when the vocabulary allows it
+                        if t not in used and t != int(top[b, u]):
+                            break
                         t = int(rng.integers(0, V))
                 used.add(t)
                 tok[b, v] = t

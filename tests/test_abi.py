@@ -1,0 +1,99 @@
+"""The C-ABI library loads without a GPU, exports every function include/spec_tree.h declares, and
+rejects on the host what the host can check (no kernel is launched by these calls)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2305_09781_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "spec_tree.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spec_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load()
+    names = _declared_functions()
+    assert set(names) == set(binding.EXPORTED)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert lib.spec_version() >= 100
+    assert b"workspace" in lib.spec_strerror(binding.ERR_WORKSPACE)
+
+
+def _desc(**kw):
+    base = dict(B=1, H=4, H_kv=4, D=64, N=8, S_cap=136, dtype=binding.SPEC_F32, max_prefix_len=0,
+                q_stride_b=8 * 4 * 64, q_stride_n=4 * 64, q_stride_h=64,
+                kv_stride_b=4 * 136 * 64, kv_stride_h=136 * 64, kv_stride_s=64, softmax_scale=0.0, reserved=0)
+    base.update(kw)
+    return binding.AttnDesc(**base)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(), binding.ERR_INVALID_ARG),                       # null data pointers
+    (dict(D=96), binding.ERR_UNSUPPORTED),
+    (dict(N=129, S_cap=400), binding.ERR_UNSUPPORTED),
+    (dict(H_kv=2), binding.ERR_UNSUPPORTED),
+    (dict(dtype=5), binding.ERR_UNSUPPORTED),
+    (dict(N=8, S_cap=4), binding.ERR_CAPACITY),
+    (dict(max_prefix_len=130), binding.ERR_CAPACITY),
+    (dict(q_stride_h=66), binding.ERR_INVALID_ARG),
+    (dict(kv_stride_s=32), binding.ERR_INVALID_ARG),
+    (dict(B=0), binding.ERR_INVALID_ARG),
+    (dict(reserved=1), binding.ERR_INVALID_ARG),
+    (dict(softmax_scale=-1.0), binding.ERR_INVALID_ARG),
+])
+def test_attention_and_append_reject_bad_descriptors(kw, code):
+    lib = binding.load()
+    d = _desc(**kw)
+    assert lib.spec_tree_attention(ctypes.byref(d), None, None, None, None, None, None, None, None, 0, None, None) == code
+    assert lib.spec_kv_append(ctypes.byref(d), None, None, None, None, None, None, None) == code
+    if kw:
+        assert lib.spec_tree_attention_workspace_bytes(ctypes.byref(d)) == 0
+
+
+def test_misaligned_pointers_and_workspace_are_rejected():
+    lib = binding.load()
+    d = _desc()
+    buf = ctypes.create_string_buffer(4096)
+    base = ctypes.addressof(buf)
+    a = ctypes.c_void_p((base + 255) // 256 * 256)
+    mis = ctypes.c_void_p(a.value + 4)
+    assert lib.spec_tree_attention(ctypes.byref(d), mis, a, a, a, a, a, a, None, 0, None, None) == binding.ERR_INVALID_ARG
+    need = lib.spec_tree_attention_workspace_bytes(ctypes.byref(d))
+    assert need > 0
+    assert lib.spec_tree_attention(ctypes.byref(d), a, a, a, a, a, a, a, None, 0, None, None) == binding.ERR_WORKSPACE
+    assert lib.spec_tree_attention(ctypes.byref(d), a, a, a, a, a, a, a, a, need - 1, None, None) == binding.ERR_WORKSPACE
+
+
+def test_verify_and_commit_reject_bad_arguments():
+    lib = binding.load()
+    assert lib.spec_verify_greedy(0, 8, 64, 0, None, None, None, 8, None, None, None, None, None, 0, None, None) == binding.ERR_INVALID_ARG
+    assert lib.spec_verify_greedy(1, 200, 64, 0, None, None, None, 8, None, None, None, None, None, 0, None, None) == binding.ERR_UNSUPPORTED
+    assert lib.spec_verify_greedy(1, 8, 64, 3, None, None, None, 8, None, None, None, None, None, 0, None, None) == binding.ERR_UNSUPPORTED
+    assert lib.spec_verify_greedy(1, 8, 64, 0, None, None, None, 8, None, None, None, None, None, 0, None, None) == binding.ERR_INVALID_ARG
+    assert lib.spec_verify_stochastic_workspace_bytes(2, 8, 64) >= 2 * 8 * 2 * 4 + 2 * 2 * 64 * 4
+    assert lib.spec_verify_stochastic_workspace_bytes(0, 8, 64) == 0
+    buf = ctypes.create_string_buffer(4096)
+    a = ctypes.c_void_p((ctypes.addressof(buf) + 255) // 256 * 256)
+    # temperature must be positive; workspace must be present
+    assert lib.spec_verify_stochastic(1, 8, 64, 0, a, a, 1, a, a, a, a, a, a, 0.0, 8, a, a, a, a, 1 << 20, None, None) == binding.ERR_INVALID_ARG
+    assert lib.spec_verify_stochastic(1, 8, 64, 0, a, a, 1, a, a, a, a, a, a, 1.0, 8, a, a, a, None, 0, None, None) == binding.ERR_WORKSPACE
+    d = _desc()
+    assert lib.spec_kv_commit(ctypes.byref(d), 0, None, None, None, 8, None, None, None, None, None) == binding.ERR_INVALID_ARG
+    assert lib.spec_kv_commit(ctypes.byref(d), 200, None, None, None, 8, None, None, None, None, None) == binding.ERR_UNSUPPORTED
+    arr = (ctypes.c_void_p * 1)(a.value)
+    assert lib.spec_kv_commit(ctypes.byref(d), 1, arr, arr, a, 8, a, a, a, None, None) == binding.ERR_INVALID_ARG  # out aliases in
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libspectree.so")
+    with pytest.raises(RuntimeError, match="not found"):
+        binding.load()

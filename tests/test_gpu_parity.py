@@ -1,0 +1,441 @@
+"""GPU-vs-oracle parity through the C ABI (needs an MI355X: `pytest -m gpu`).
+
+Bars: attention max-abs 1e-5 for float32 inputs, |g-o| <= 2e-2 + 1e-2*|o| for bf16 inputs (oracle in
+float64, not rounded); append, commit, verification decisions, paths and tokens bit-exact.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import spec_oracle as orc
+from oracle import vetting
+from paper_2305_09781_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _dev(x):
+    if isinstance(x, np.ndarray):
+        x = torch.from_numpy(np.ascontiguousarray(x))
+    return x.to(DEV)
+
+
+def _f64(t):
+    return t.double().numpy()
+
+
+def _bits(t):
+    """Raw element bits as integers (bit-exact comparison of copies)."""
+    t = t.cpu().contiguous()
+    return t.view(torch.int16 if t.element_size() == 2 else torch.int32).numpy()
+
+
+def _check_attention(out_gpu, ref64, dtype):
+    g = out_gpu.double().cpu().numpy()
+    err = np.abs(g - ref64)
+    if dtype == torch.float32:
+        assert err.max() <= 1e-5, f"max abs err {err.max():.3e}"
+    else:
+        bound = 2e-2 + 1e-2 * np.abs(ref64)
+        worst = (err - bound).max()
+        assert worst <= 0, f"bf16 tolerance exceeded by {worst:.3e} (max abs err {err.max():.3e})"
+    return float(err.max())
+
+
+class _chunk_keys:
+    """Forces the number of keys per workgroup so that small inputs span several chunks."""
+
+    def __init__(self, n):
+        self.n = n
+
+    def __enter__(self):
+        self.old = os.environ.get("SPEC_TREE_CHUNK_KEYS")
+        if self.n:
+            os.environ["SPEC_TREE_CHUNK_KEYS"] = str(self.n)
+        else:
+            os.environ.pop("SPEC_TREE_CHUNK_KEYS", None)
+
+    def __exit__(self, *a):
+        if self.old is None:
+            os.environ.pop("SPEC_TREE_CHUNK_KEYS", None)
+        else:
+            os.environ["SPEC_TREE_CHUNK_KEYS"] = self.old
+
+
+def _run_append_attention(spec, inp, layer=0, status=None):
+    """append + attention on the GPU for one layer of `inp`; returns (out, k_cache, v_cache) device tensors."""
+    kc, vc = _dev(inp["k_cache"][layer]), _dev(inp["v_cache"][layer])
+    pl = _dev(inp["prefix_len"])
+    spec.spec_kv_append(_dev(inp["k_new"][layer]), _dev(inp["v_new"][layer]), kc, vc, pl, status=status)
+    out = spec.spec_tree_attention(_dev(inp["q"][layer]), kc, vc, _dev(inp["tree_parent"]), _dev(inp["tree_depth"]), pl,
+                                   status=status,
+                                   max_prefix_len=min(int(inp["prefix_len"].max()), kc.shape[2] - inp["q"][layer].shape[1]))
+    torch.cuda.synchronize()
+    return out, kc, vc
+
+
+def _oracle_append_attention(inp, layer=0, bsel=None, hsel=None):
+    """Oracle on a (request, head) subset; caches are converted to float64 for the subset only."""
+    bsel = list(range(inp["q"][layer].shape[0])) if bsel is None else bsel
+    hsel = list(range(inp["q"][layer].shape[2])) if hsel is None else hsel
+    ix = np.ix_(bsel, hsel)
+    kc = _f64(inp["k_cache"][layer][bsel][:, hsel])
+    vc = _f64(inp["v_cache"][layer][bsel][:, hsel])
+    q = _f64(inp["q"][layer][bsel][:, :, hsel])
+    kn = _f64(inp["k_new"][layer][bsel][:, :, hsel])
+    vn = _f64(inp["v_new"][layer][bsel][:, :, hsel])
+    pl = inp["prefix_len"].numpy()[bsel]
+    st = orc.kv_append(kc, vc, kn, vn, pl)
+    assert (st == 0).all()
+    return orc.tree_attention(q, kc, vc, inp["tree_parent"].numpy()[bsel], pl), kc, vc
+
+
+# ------------------------------------------------------------------------------------------------
+# attention + append
+# ------------------------------------------------------------------------------------------------
+
+def test_config1_fp32_attention_and_append(spec):
+    cfg = wl.CONFIGS[1]
+    inp = wl.make_attention_inputs(cfg)
+    for chunk in (0, 32, 64):
+        with _chunk_keys(chunk):
+            out, kc, vc = _run_append_attention(spec, inp)
+        ref, kco, vco = _oracle_append_attention(inp)
+        _check_attention(out, ref, torch.float32)
+        assert np.array_equal(kc.cpu().numpy().astype(np.float64), kco)
+        assert np.array_equal(vc.cpu().numpy().astype(np.float64), vco)
+
+
+SMALL = [
+    # dtype, B, H, D, (P lo, hi), N, tree, forced chunk
+    ("bf16", 2, 3, 128, (70, 200), 16, "expansion", 64),
+    ("bf16", 2, 2, 128, (0, 5), 16, "random_parent", 0),
+    ("bf16", 3, 2, 128, (33, 97), 7, "random_parent", 32),
+    ("bf16", 2, 2, 128, (130, 300), 32, "random_branching", 96),
+    ("bf16", 2, 2, 128, (130, 300), 33, "random_branching", 128),
+    ("bf16", 1, 2, 128, (250, 250), 64, "random_branching", 64),
+    ("bf16", 2, 2, 128, (100, 260), 100, "random_branching", 160),
+    ("bf16", 1, 2, 128, (190, 190), 128, "random_branching", 0),
+    ("bf16", 2, 3, 64, (60, 220), 16, "random_parent", 64),
+    ("bf16", 2, 2, 64, (60, 220), 50, "random_branching", 96),
+    ("f32", 2, 2, 128, (40, 150), 16, "random_parent", 64),
+    ("f32", 1, 2, 64, (100, 100), 128, "random_branching", 96),
+    ("f32", 2, 2, 128, (0, 3), 1, "random_parent", 0),
+    ("bf16", 2, 2, 128, (0, 70), 1, "random_parent", 32),
+]
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[f"{c[0]}-B{c[1]}H{c[2]}D{c[3]}P{c[4][0]}-{c[4][1]}N{c[5]}-{c[6]}-ck{c[7]}" for c in SMALL])
+def test_small_shapes_attention_and_append(spec, case):
+    dtype, B, H, D, P, N, tree, chunk = case
+    cfg = wl.Config(90, "small", dtype, B=B, H=H, D=D, P=P if P[0] != P[1] else P[0], N=N, tree=tree,
+                    widths=wl.EXPANSION_EVAL * 2)
+    inp = wl.make_attention_inputs(cfg, seed=1000 + N + D + B, S_cap=P[1] + N + 5)
+    with _chunk_keys(chunk):
+        out, kc, vc = _run_append_attention(spec, inp)
+    ref, kco, vco = _oracle_append_attention(inp)
+    _check_attention(out, ref, cfg.torch_dtype)
+    # append is a bit copy: compare the whole cache (float64 conversion of either dtype is exact)
+    assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco)
+
+
+def test_config2_bf16_full(spec):
+    cfg = wl.CONFIGS[2]
+    inp = wl.make_attention_inputs(cfg)
+    out, kc, vc = _run_append_attention(spec, inp)
+    ref, kco, vco = _oracle_append_attention(inp)
+    _check_attention(out, ref, torch.bfloat16)
+    assert np.array_equal(kc.double().cpu().numpy(), kco)
+
+
+@pytest.mark.parametrize("c", [3, 4, 5])
+def test_large_configs_sampled_heads(spec, c):
+    """Full-size launch (the configuration the benchmark times); the oracle checks sampled
+    (request, head) pairs completely, every node and channel."""
+    cfg = wl.CONFIGS[c]
+    inp = wl.make_attention_inputs(cfg)
+    out, kc, vc = _run_append_attention(spec, inp)
+    assert torch.isfinite(out.float()).all()
+    rng = np.random.default_rng(c)
+    bsel = sorted(set(int(x) for x in rng.integers(0, cfg.B, size=3)) | {cfg.B - 1})
+    hsel = sorted(set(int(x) for x in rng.integers(0, cfg.H, size=3)) | {0})
+    ref, kco, _ = _oracle_append_attention(inp, bsel=bsel, hsel=hsel)
+    sub = out[bsel][:, :, hsel]
+    _check_attention(sub, ref, torch.bfloat16)
+    assert np.array_equal(kc[bsel][:, hsel].double().cpu().numpy(), kco)
+
+
+def test_attention_status_bits_and_noop(spec):
+    """Malformed trees and requests that do not fit are flagged and produce zeros; others unaffected."""
+    cfg = wl.Config(91, "bad", "bf16", B=4, H=2, D=128, P=(40, 90), N=16, tree="random_parent")
+    for chunk in (0, 64):
+        inp = wl.make_attention_inputs(cfg, seed=5, S_cap=90 + 16)
+        inp["tree_parent"][1, 5] = 9            # parent after child
+        inp["tree_depth"][2, 7] += 1            # depth inconsistent with parent
+        inp["prefix_len"][3] = 90 + 1           # prefix + N > S_cap
+        status = torch.zeros(cfg.B, dtype=torch.int32, device=DEV)
+        with _chunk_keys(chunk):
+            out, kc, vc = _run_append_attention(spec, inp, status=status)
+        st = status.cpu().numpy()
+        assert st[0] == 0 and st[1] == orc.ST_BAD_TREE and st[2] == orc.ST_BAD_TREE and st[3] == orc.ST_CAPACITY
+        assert (out[1:].float() == 0).all()
+        ref, _, _ = _oracle_append_attention(inp, bsel=[0])
+        _check_attention(out[:1], ref, torch.bfloat16)
+        assert orc.tree_status(inp["tree_parent"][1].numpy()) == orc.ST_BAD_TREE
+        assert orc.tree_status(inp["tree_parent"][2].numpy(), inp["tree_depth"][2].numpy()) == orc.ST_BAD_TREE
+        # the request that does not fit was not appended
+        assert np.array_equal(_bits(kc[3]), _bits(inp["k_cache"][0][3]))
+
+
+def test_host_side_errors(spec):
+    cfg = wl.Config(92, "err", "bf16", B=1, H=2, D=128, P=20, N=16, tree="random_parent")
+    inp = wl.make_attention_inputs(cfg, seed=1)
+    q, kc, vc = _dev(inp["q"][0]), _dev(inp["k_cache"][0]), _dev(inp["v_cache"][0])
+    par, dep, pl = _dev(inp["tree_parent"]), _dev(inp["tree_depth"]), _dev(inp["prefix_len"])
+    d = spec.make_desc(q, kc)
+    for field, val, code in (("D", 96, spec.ERR_UNSUPPORTED), ("N", 129, spec.ERR_UNSUPPORTED),
+                             ("H_kv", 1, spec.ERR_UNSUPPORTED), ("max_prefix_len", 30, spec.ERR_CAPACITY),
+                             ("q_stride_h", 100, spec.ERR_INVALID_ARG), ("dtype", 7, spec.ERR_UNSUPPORTED)):
+        bad = spec.make_desc(q, kc)
+        setattr(bad, field, val)
+        with pytest.raises(spec.SpecError) as e:
+            spec.spec_tree_attention(q, kc, vc, par, dep, pl, desc=bad)
+        assert e.value.code == code, field
+    with _chunk_keys(32):
+        with pytest.raises(spec.SpecError) as e:
+            spec.spec_tree_attention(q, kc, vc, par, dep, pl, workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
+        assert e.value.code == spec.ERR_WORKSPACE
+
+
+# ------------------------------------------------------------------------------------------------
+# verification
+# ------------------------------------------------------------------------------------------------
+
+def _greedy_case(spec, cfg, seed=None, logits_dtype=torch.float32):
+    inp = wl.make_verify_inputs(cfg, seed=seed, mode="greedy", logits_dtype=logits_dtype)
+    path, ln, toks, am = spec.spec_verify_greedy(_dev(inp["logits"]), _dev(inp["tree_token"]), _dev(inp["tree_parent"]))
+    torch.cuda.synchronize()
+    lg = inp["logits"].float().numpy()
+    rp, rl, rt, ra = orc.verify_greedy(lg, inp["tree_token"].numpy(), inp["tree_parent"].numpy())
+    assert np.array_equal(am.cpu().numpy(), ra)
+    assert np.array_equal(ln.cpu().numpy(), rl)
+    assert np.array_equal(path.cpu().numpy(), rp) and np.array_equal(toks.cpu().numpy(), rt)
+    return rl
+
+
+@pytest.mark.parametrize("c", [1, 2, 3, 5])
+def test_greedy_configs(spec, c):
+    rl = _greedy_case(spec, wl.CONFIGS[c])
+    assert rl.min() >= 1
+
+
+def test_greedy_bf16_logits_ties_and_odd_vocab(spec):
+    # bf16 logits tie often near the top (spacing 2^-4 at |x| ~ 8): lowest token id must win
+    _greedy_case(spec, wl.CONFIGS[2], seed=77, logits_dtype=torch.bfloat16)
+    for V in (1, 3, 63, 1001):
+        cfg = wl.Config(93, "oddV", "f32", B=3, H=1, D=64, P=1, N=9, tree="random_parent", V=V)
+        _greedy_case(spec, cfg, seed=V)
+
+
+def test_greedy_bad_tree(spec):
+    cfg = wl.Config(94, "badg", "f32", B=2, H=1, D=64, P=1, N=8, tree="random_parent", V=50)
+    inp = wl.make_verify_inputs(cfg, mode="greedy")
+    inp["tree_parent"][1, 3] = 3
+    status = torch.zeros(2, dtype=torch.int32, device=DEV)
+    path, ln, toks, am = spec.spec_verify_greedy(_dev(inp["logits"]), _dev(inp["tree_token"]), _dev(inp["tree_parent"]),
+                                                 status=status)
+    torch.cuda.synchronize()
+    assert list(status.cpu().numpy()) == [0, orc.ST_BAD_TREE] and ln[1].item() == 0 and ln[0].item() >= 1
+    assert (path[1] == -1).all()
+
+
+def _stochastic_case(spec, cfg, seed=None, tau=1.2, temperature=1.0, logits_dtype=torch.float32):
+    inp = wl.make_verify_inputs(cfg, seed=seed, mode="stochastic", tau=tau, logits_dtype=logits_dtype)
+    lg = inp["logits"].float().numpy()
+    args = (lg, inp["probs_ssm"].numpy(), inp["ssm_row"].numpy(), inp["tree_token"].numpy(), inp["tree_parent"].numpy())
+    ua, uf, redraws = vetting.vet_uniforms(*args, inp["u_accept"].numpy(), inp["u_order"].numpy(), inp["u_final"].numpy(),
+                                           inp["rng"], temperature=temperature)
+    rp, rl, rt, rs = orc.verify_stochastic(*args, ua, inp["u_order"].numpy(), uf, temperature=temperature)
+    status = torch.zeros(cfg.B, dtype=torch.int32, device=DEV)
+    path, ln, toks = spec.spec_verify_stochastic(_dev(inp["logits"]), _dev(inp["probs_ssm"]), _dev(inp["ssm_row"]),
+                                                 _dev(inp["tree_token"]), _dev(inp["tree_parent"]), _dev(ua),
+                                                 _dev(inp["u_order"]), _dev(uf), temperature=temperature, status=status)
+    torch.cuda.synchronize()
+    assert np.array_equal(ln.cpu().numpy(), rl), (ln.cpu().numpy(), rl)
+    assert np.array_equal(path.cpu().numpy(), rp) and np.array_equal(toks.cpu().numpy(), rt)
+    assert np.array_equal(status.cpu().numpy(), rs)
+    return rl, redraws
+
+
+@pytest.mark.parametrize("c", [1, 2, 3])
+def test_stochastic_configs(spec, c):
+    rl, redraws = _stochastic_case(spec, wl.CONFIGS[c], tau=None if c == 1 else 1.2)
+    print(f"config {c}: accepted lengths {rl.tolist()}, re-drawn requests {redraws}")
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_stochastic_many_rejections_and_temperature(spec, seed):
+    """Drafts far from the LLM (many residual updates per node), wide trees, temperature != 1."""
+    cfg = wl.Config(95, "rej", "f32", B=6, H=1, D=64, P=1, N=40, tree="random_branching", V=777, n_ssm=3)
+    _stochastic_case(spec, cfg, seed=seed, tau=4.0, temperature=[1.0, 0.7, 1.5, 1.0][seed])
+    cfg = wl.Config(96, "rej2", "f32", B=4, H=1, D=64, P=1, N=12, tree="random_parent", V=5, n_ssm=2)
+    _stochastic_case(spec, cfg, seed=seed, tau=None)
+
+
+def test_stochastic_bf16_logits(spec):
+    _stochastic_case(spec, wl.CONFIGS[2], seed=31, logits_dtype=torch.bfloat16)
+
+
+# ------------------------------------------------------------------------------------------------
+# commit
+# ------------------------------------------------------------------------------------------------
+
+def _commit_case(spec, cfg, n_layers, paths=None, seed=None):
+    inp = wl.make_attention_inputs(cfg, seed=seed, n_layers=n_layers)
+    rng = np.random.default_rng(cfg.seed + 7)
+    par = inp["tree_parent"].numpy()
+    if paths is None:
+        ap, al = wl.random_accepted_paths(rng, par)
+    else:
+        ap, al = paths
+    pl = _dev(inp["prefix_len"])
+    kcs, vcs = [_dev(c) for c in inp["k_cache"]], [_dev(c) for c in inp["v_cache"]]
+    for l in range(n_layers):
+        spec.spec_kv_append(_dev(inp["k_new"][l]), _dev(inp["v_new"][l]), kcs[l], vcs[l], pl)
+    status = torch.zeros(cfg.B, dtype=torch.int32, device=DEV)
+    new_len = spec.spec_kv_commit(kcs, vcs, _dev(ap), _dev(al), pl, cfg.N, status=status)
+    torch.cuda.synchronize()
+    # oracle on raw bits
+    okc = [_bits(c).copy() for c in inp["k_cache"]]
+    ovc = [_bits(c).copy() for c in inp["v_cache"]]
+    for l in range(n_layers):
+        orc.kv_append(okc[l], ovc[l], _bits(inp["k_new"][l]), _bits(inp["v_new"][l]), inp["prefix_len"].numpy())
+    ref_len, ref_st = orc.kv_commit(okc, ovc, ap, al, inp["prefix_len"].numpy(), N=cfg.N)
+    assert np.array_equal(new_len.cpu().numpy(), ref_len) and np.array_equal(status.cpu().numpy(), ref_st)
+    for l in range(n_layers):
+        gk, gv = _bits(kcs[l]), _bits(vcs[l])
+        for b in range(cfg.B):
+            n = int(ref_len[b])      # rows beyond the new prefix are unspecified
+            assert np.array_equal(gk[b, :, :n], okc[l][b, :, :n]) and np.array_equal(gv[b, :, :n], ovc[l][b, :, :n])
+    return ap, al
+
+
+def test_commit_config4_layer_sample(spec):
+    """LLaMA-65B-shaped caches, accepted paths of random length 1..9, four of the layers."""
+    _commit_case(spec, wl.CONFIGS[4], n_layers=4)
+
+
+def test_commit_small_all_layers_and_overlap(spec):
+    cfg = wl.Config(97, "commit", "bf16", B=5, H=3, D=128, P=(10, 60), N=16, tree="expansion", widths=wl.EXPANSION_EVAL)
+    par = wl.tree_expansion(wl.EXPANSION_EVAL, 16)
+    # hand-made paths on parent = [-1,0,1,2,3,4,5,6,2,8,9,10,2,12,13,14]: overlapping src/dst, identity, root only
+    raw = [[0, 1, 2, 8, 9], [0, 1, 2, 12, 13, 14, 15], [0, 1, 2, 3, 4, 5, 6, 7], [0], [0, 1, 2, 8, 9, 10, 11]]
+    ap = np.full((5, 16), -1, dtype=np.int32)
+    al = np.zeros(5, dtype=np.int32)
+    for b, p in enumerate(raw):
+        assert orc.path_status(p, len(p), par) == 0
+        ap[b, :len(p)] = p
+        al[b] = len(p)
+    _commit_case(spec, cfg, n_layers=32, paths=(ap, al))
+    cfg32 = wl.Config(98, "commit32", "f32", B=5, H=2, D=64, P=(10, 60), N=16, tree="expansion", widths=wl.EXPANSION_EVAL)
+    _commit_case(spec, cfg32, n_layers=3, paths=(ap, al))
+
+
+def test_commit_bad_paths_are_noops(spec):
+    cfg = wl.Config(99, "commitbad", "bf16", B=4, H=2, D=128, P=(10, 30), N=16, tree="expansion", widths=wl.EXPANSION_EVAL)
+    ap = np.full((4, 16), -1, dtype=np.int32)
+    al = np.array([3, 3, 0, 2], dtype=np.int32)
+    ap[0, :3] = [0, 1, 2]
+    ap[1, :3] = [0, 5, 3]     # not increasing
+    ap[3, :2] = [1, 2]        # does not start at the root
+    _commit_case(spec, cfg, n_layers=2, paths=(ap, al))
+
+
+def test_end_to_end_iteration_config5_two_layers(spec):
+    """append -> attention -> greedy verify -> commit with the GPU's own accepted path, long ragged prefix."""
+    cfg = wl.CONFIGS[5]
+    small = wl.Config(5, cfg.name, cfg.dtype, B=2, H=4, D=128, P=(3000, 5000), N=32, tree="expansion", widths=cfg.widths,
+                      V=cfg.V)
+    inp = wl.make_attention_inputs(small, n_layers=2)
+    ver = wl.make_verify_inputs(small, mode="greedy", parent=inp["tree_parent"].numpy())
+    pl = _dev(inp["prefix_len"])
+    kcs, vcs = [_dev(c) for c in inp["k_cache"]], [_dev(c) for c in inp["v_cache"]]
+    par, dep = _dev(inp["tree_parent"]), _dev(inp["tree_depth"])
+    outs = []
+    for l in range(2):
+        spec.spec_kv_append(_dev(inp["k_new"][l]), _dev(inp["v_new"][l]), kcs[l], vcs[l], pl)
+        outs.append(spec.spec_tree_attention(_dev(inp["q"][l]), kcs[l], vcs[l], par, dep, pl,
+                                             max_prefix_len=int(inp["prefix_len"].max())))
+    path, ln, toks, _ = spec.spec_verify_greedy(_dev(ver["logits"]), _dev(ver["tree_token"]), par)
+    new_len = spec.spec_kv_commit(kcs, vcs, path, ln, pl, small.N)
+    torch.cuda.synchronize()
+    rp, rl, rt, _ = orc.verify_greedy(ver["logits"].numpy(), ver["tree_token"].numpy(), inp["tree_parent"].numpy())
+    assert np.array_equal(path.cpu().numpy(), rp) and np.array_equal(toks.cpu().numpy(), rt)
+    for l in range(2):
+        ref, kco, vco = _oracle_append_attention(inp, layer=l)
+        _check_attention(outs[l], ref, torch.bfloat16)
+        orc.kv_commit([kco], [vco], rp, rl, inp["prefix_len"].numpy(), N=small.N)
+        for b in range(small.B):
+            n = int(inp["prefix_len"][b]) + int(rl[b])
+            assert new_len[b].item() == n
+            assert np.array_equal(kcs[l][b, :, :n].double().cpu().numpy(), kco[b, :, :n])
+            assert np.array_equal(vcs[l][b, :, :n].double().cpu().numpy(), vco[b, :, :n])
+
+
+def test_hip_graph_replays_match_eager(spec):
+    """The benchmark replays a captured pass; every replay must reproduce the eager results, with
+    eager launches and synchronisations in between."""
+    cfg = wl.Config(2, "graph", "bf16", B=2, H=4, D=128, P=(300, 500), N=16, tree="expansion", widths=wl.EXPANSION_EVAL,
+                    V=3000)
+    L = 3
+    inp = wl.make_attention_inputs(cfg, n_layers=L)
+    ver = wl.make_verify_inputs(cfg, mode="greedy", parent=inp["tree_parent"].numpy())
+    pl, par, dep = _dev(inp["prefix_len"]), _dev(inp["tree_parent"]), _dev(inp["tree_depth"])
+    q, kn, vn = [_dev(x) for x in inp["q"]], [_dev(x) for x in inp["k_new"]], [_dev(x) for x in inp["v_new"]]
+    k0, v0 = [_dev(x) for x in inp["k_cache"]], [_dev(x) for x in inp["v_cache"]]
+    kcs, vcs = [x.clone() for x in k0], [x.clone() for x in v0]
+    outs = [torch.empty_like(x) for x in q]
+    logits, tok = _dev(ver["logits"]), _dev(ver["tree_token"])
+    desc = spec.make_desc(q[0], kcs[0], max_prefix_len=int(inp["prefix_len"].max()))
+    ws = torch.empty(max(spec.spec_tree_attention_workspace_bytes(desc), 256), dtype=torch.uint8, device=DEV)
+    vout = (torch.empty((2, 16), dtype=torch.int32, device=DEV), torch.empty(2, dtype=torch.int32, device=DEV),
+            torch.empty((2, 16), dtype=torch.int32, device=DEV), torch.empty((2, 16), dtype=torch.int32, device=DEV))
+    pl_out = torch.empty_like(pl)
+
+    def one_pass():
+        for l in range(L):
+            spec.spec_kv_append(kn[l], vn[l], kcs[l], vcs[l], pl, desc=desc)
+            spec.spec_tree_attention(q[l], kcs[l], vcs[l], par, dep, pl, out=outs[l], workspace=ws, desc=desc)
+        spec.spec_verify_greedy(logits, tok, par, out=vout)
+        spec.spec_kv_commit(kcs, vcs, vout[0], vout[1], pl, cfg.N, prefix_len_out=pl_out)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [o.clone() for o in outs] + [c.clone() for c in kcs] + [x.clone() for x in vout] + [pl_out.clone()]
+
+    def reset():
+        for l in range(L):
+            kcs[l].copy_(k0[l])
+            vcs[l].copy_(v0[l])
+            outs[l].zero_()
+        for x in vout:
+            x.fill_(-7)
+        pl_out.zero_()
+
+    one_pass()
+    want = snapshot()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        one_pass()
+    for rep in range(4):
+        reset()
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(want, got):
+            assert torch.equal(a, b), f"replay {rep} differs from the eager pass"
+        one_pass()                      # eager work between replays
+        torch.cuda.synchronize()
