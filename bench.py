@@ -2,7 +2,8 @@
 """Benchmark of the tree-based parallel decoding hot path on one MI355X.
 
 One step = one verification pass of a whole model over one batch of token trees:
-    for each of the L layers: spec_kv_append + spec_tree_attention   (distinct per-layer caches)
+    for each of the L layers: spec_tree_attention_append (KV append fused into tree attention; distinct
+                              per-layer caches)
     spec_verify_greedy, spec_verify_stochastic                        (once per pass)
     spec_kv_commit of the greedy path over all L layers
 Inputs are resident in HBM before the timed region. Prints ONE JSON line.
@@ -115,14 +116,13 @@ def main():
 
     def attention_layers():
         for l in range(L):
-            spec.spec_tree_attention(W["q"][l], W["k_cache"][l], W["v_cache"][l], par, dep, pl, out=W["out"][l],
-                                     workspace=ws, status=status, desc=desc)
+            spec.spec_tree_attention_append(W["q"][l], W["k_new"][l], W["v_new"][l], W["k_cache"][l], W["v_cache"][l], par,
+                                            dep, pl, out=W["out"][l], workspace=ws, status=status, desc=desc)
 
     def one_pass():
         for l in range(L):
-            spec.spec_kv_append(W["k_new"][l], W["v_new"][l], W["k_cache"][l], W["v_cache"][l], pl, status=status, desc=desc)
-            spec.spec_tree_attention(W["q"][l], W["k_cache"][l], W["v_cache"][l], par, dep, pl, out=W["out"][l],
-                                     workspace=ws, status=status, desc=desc)
+            spec.spec_tree_attention_append(W["q"][l], W["k_new"][l], W["v_new"][l], W["k_cache"][l], W["v_cache"][l], par,
+                                            dep, pl, out=W["out"][l], workspace=ws, status=status, desc=desc)
         spec.spec_verify_greedy(g_logits, g_tok, par, Lmax=Lmax, status=status, out=g_out)
         spec.spec_verify_stochastic(s_dev["logits"], s_dev["probs_ssm"], s_dev["ssm_row"], s_dev["tree_token"], par,
                                     s_dev["u_accept"], s_dev["u_order"], s_dev["u_final"], Lmax=Lmax, workspace=s_ws,
@@ -167,9 +167,10 @@ def main():
     torch.cuda.synchronize()
     attn_us = ev0.elapsed_time(ev1) * 1e3 / (reps * L)
     sum_p = int(W["host"]["prefix_len"].sum())
-    attn_bytes = e * H * D * (2 * (sum_p + B * N) + 2 * B * N)     # K,V rows of prefix+tree, Q in, O out
+    # fused append + attention: prefix K,V read (2P), new K,V read (2N) and written to the cache (2N), Q in, O out
+    attn_bytes = e * H * D * (2 * sum_p + 6 * B * N)
     achieved = attn_bytes / (attn_us * 1e-6) / 1e9
-    layer_bytes = e * H * D * (2 * sum_p + 6 * B * N)              # append + attention, per layer
+    layer_bytes = attn_bytes
 
     result = {
         "metric": "verified tree tokens/sec (whole verification pass: L layers of KV append + tree attention, "
@@ -184,7 +185,7 @@ def main():
                    "attention_us_per_layer": attn_us, "layer_algorithmic_bytes": layer_bytes},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "tree_attention_bf16_kernel (+ attn_combine_kernel)", "bytes_per_launch": attn_bytes,
+                     "kernel": "tree_attention_bf16_kernel (KV append fused; + attn_combine_kernel when the key range is split)", "bytes_per_launch": attn_bytes,
                      "us_per_launch": attn_us},
     }
 

@@ -5,7 +5,7 @@
  * speculated token tree in a single pass of the LLM (SpecInfer, arxiv 2305.09781, Section 4 and
  * Algorithm 2). The calls below are the per-layer and per-pass steps of that iteration:
  *
- *   for each layer:  spec_kv_append  ->  spec_tree_attention
+ *   for each layer:  spec_kv_append  ->  spec_tree_attention      (or the fused spec_tree_attention_append)
  *   once per pass:   spec_verify_greedy | spec_verify_stochastic  ->  spec_kv_commit (all layers)
  *
  * Conventions common to every call
@@ -104,6 +104,20 @@ int spec_tree_attention(const spec_attn_desc_t* desc, const void* q, const void*
                         void* out, void* workspace, size_t workspace_bytes,
                         int32_t* status /*[B] or NULL*/, void* hip_stream);
 size_t spec_tree_attention_workspace_bytes(const spec_attn_desc_t* desc);
+
+/*
+ * Fused form of spec_kv_append followed by spec_tree_attention (same sections of the paper): the tree
+ * rows are read from k_new / v_new, used by the attention and written to the caches in the same
+ * pass, which saves one launch and re-reading the 2N new rows per (request, head). Results, status
+ * bits and workspace are those of the two calls made one after the other, except that for a request
+ * flagged SPEC_ST_BAD_TREE (out = 0) it is unspecified whether its tree rows were written to the cache.
+ * A request flagged SPEC_ST_CAPACITY is neither appended nor attended.
+ */
+int spec_tree_attention_append(const spec_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,
+                               void* k_cache, void* v_cache, const int32_t* tree_parent /*[B,N]*/,
+                               const int32_t* tree_depth /*[B,N]*/, const int32_t* prefix_len /*[B]*/, void* out,
+                               void* workspace, size_t workspace_bytes, int32_t* status /*[B] or NULL*/,
+                               void* hip_stream);
 
 /*
  * Greedy verification (Algorithm 2, VerifyGreedy). O(u) = argmax_x logits_llm[b,u,x] (lowest token id

@@ -21,7 +21,8 @@ ST_BAD_TREE, ST_CAPACITY, ST_BAD_PATH, ST_ZERO_RESIDUAL = 1, 2, 4, 8
 ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_CAPACITY, ERR_HIP, ERR_WORKSPACE = -1, -2, -3, -4, -5
 
 EXPORTED = [
-    "spec_kv_append", "spec_tree_attention", "spec_tree_attention_workspace_bytes", "spec_verify_greedy",
+    "spec_kv_append", "spec_tree_attention", "spec_tree_attention_append", "spec_tree_attention_workspace_bytes",
+    "spec_verify_greedy",
     "spec_verify_stochastic", "spec_verify_stochastic_workspace_bytes", "spec_kv_commit", "spec_strerror",
     "spec_version",
 ]
@@ -64,6 +65,8 @@ def load():
     lib.spec_kv_append.restype = ctypes.c_int
     lib.spec_tree_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
     lib.spec_tree_attention.restype = ctypes.c_int
+    lib.spec_tree_attention_append.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
+    lib.spec_tree_attention_append.restype = ctypes.c_int
     lib.spec_tree_attention_workspace_bytes.argtypes = [dp]
     lib.spec_tree_attention_workspace_bytes.restype = sz
     lib.spec_verify_greedy.argtypes = [i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp, vp]
@@ -156,6 +159,28 @@ def spec_tree_attention(q, k_cache, v_cache, tree_parent, tree_depth, prefix_len
     _check(load().spec_tree_attention(ctypes.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(tree_parent),
                                       _ptr(tree_depth), _ptr(prefix_len), _ptr(out), _ptr(workspace), ws_bytes,
                                       _ptr(status), _stream(stream)), "spec_tree_attention")
+    return out
+
+
+def spec_tree_attention_append(q, k_new, v_new, k_cache, v_cache, tree_parent, tree_depth, prefix_len, out=None,
+                               workspace=None, status=None, max_prefix_len: int = 0, softmax_scale: float = 0.0,
+                               stream=None, desc=None):
+    """KV append of the tree rows fused with the tree attention over them."""
+    _same_layout(k_cache, v_cache, "k_cache and v_cache")
+    _same_layout(q, k_new, "q and k_new")
+    _same_layout(q, v_new, "q and v_new")
+    if out is None:
+        out = torch.empty_like(q)
+    _same_layout(q, out, "q and out")
+    d = desc if desc is not None else make_desc(q, k_cache, max_prefix_len, softmax_scale)
+    need = spec_tree_attention_workspace_bytes(d)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().spec_tree_attention_append(ctypes.byref(d), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache),
+                                             _ptr(v_cache), _ptr(tree_parent), _ptr(tree_depth), _ptr(prefix_len),
+                                             _ptr(out), _ptr(workspace), ws_bytes, _ptr(status), _stream(stream)),
+           "spec_tree_attention_append")
     return out
 
 

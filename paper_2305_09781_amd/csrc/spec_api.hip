@@ -45,13 +45,18 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d) {
   const int max_len = max_prefix + d.N;
   int chunk = env_int("SPEC_TREE_CHUNK_KEYS", 0);
   if (chunk <= 0) {
-    // aim at a few workgroups per compute unit while keeping chunks long enough to amortise the
-    // per-workgroup prologue and merge
+    // One workgroup per (request, head, query group) streams its whole key range when that already
+    // gives every compute unit a workgroup: a workgroup's fixed cost (first loads, tree set-up, final
+    // merge, and the extra combine launch) outweighs any gain from more parallel slack. Only batches
+    // with few (request, head) pairs are split, into chunks of at least 512 keys.
     const int nq = d.dtype == SPEC_BF16 ? (d.N <= 16 ? 16 : 32) : SPEC_MAX_TREE_NODES;
     const long groups = (long)d.B * d.H * ((d.N + nq - 1) / nq);
-    const long target_wgs = 256L * 4;
-    long splits = (target_wgs + groups - 1) / groups;
-    if (splits < 1) splits = 1;
+    long splits = 1;
+    if (groups < 256) {
+      splits = (768 + groups - 1) / groups;
+      const long max_splits = max_len / 512 > 0 ? max_len / 512 : 1;
+      if (splits > max_splits) splits = max_splits;
+    }
     chunk = (int)((max_len + splits - 1) / splits);
     if (chunk < 128) chunk = 128;
   }
@@ -107,13 +112,17 @@ size_t spec_tree_attention_workspace_bytes(const spec_attn_desc_t* desc) {
   return make_attn_plan(*desc).ws_bytes;
 }
 
-int spec_tree_attention(const spec_attn_desc_t* desc, const void* q, const void* k_cache, const void* v_cache,
-                        const int32_t* tree_parent, const int32_t* tree_depth, const int32_t* prefix_len, void* out,
-                        void* workspace, size_t workspace_bytes, int32_t* status, void* hip_stream) {
+// Shared body of spec_tree_attention (k_new == NULL) and spec_tree_attention_append.
+static int tree_attention_impl(const spec_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,
+                               void* k_cache, void* v_cache, const int32_t* tree_parent, const int32_t* tree_depth,
+                               const int32_t* prefix_len, void* out, void* workspace, size_t workspace_bytes,
+                               int32_t* status, void* hip_stream) {
   const int rc = check_desc(desc);
   if (rc != SPEC_OK) return rc;
   if (!q || !k_cache || !v_cache || !tree_parent || !tree_depth || !prefix_len || !out) return SPEC_ERR_INVALID_ARG;
   if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out)) return SPEC_ERR_INVALID_ARG;
+  const bool append = k_new != nullptr || v_new != nullptr;
+  if (append && (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new))) return SPEC_ERR_INVALID_ARG;
   const AttnPlan plan = make_attn_plan(*desc);
   if (plan.ws_bytes > 0) {
     if (workspace == nullptr || workspace_bytes < plan.ws_bytes) return SPEC_ERR_WORKSPACE;
@@ -121,18 +130,39 @@ int spec_tree_attention(const spec_attn_desc_t* desc, const void* q, const void*
   }
   hipStream_t s = (hipStream_t)hip_stream;
   hipError_t e;
-  if (desc->dtype == SPEC_BF16)
-    e = launch_tree_attention_bf16(*desc, plan, q, k_cache, v_cache, tree_parent, tree_depth, prefix_len, out, workspace,
-                                   status, s);
-  else
+  if (desc->dtype == SPEC_BF16) {
+    e = launch_tree_attention_bf16(*desc, plan, q, k_cache, v_cache, k_new, v_new, tree_parent, tree_depth, prefix_len,
+                                   out, workspace, status, s);
+  } else {
+    if (append) {
+      e = launch_kv_append(*desc, k_new, v_new, k_cache, v_cache, prefix_len, status, s);
+      if (e != hipSuccess) return SPEC_ERR_HIP;
+    }
     e = launch_tree_attention_f32(*desc, plan, (const float*)q, (const float*)k_cache, (const float*)v_cache, tree_parent,
                                   tree_depth, prefix_len, (float*)out, workspace, status, s);
+  }
   if (e != hipSuccess) return SPEC_ERR_HIP;
   if (plan.n_splits > 1) {
     e = launch_attn_combine(*desc, plan, tree_parent, tree_depth, prefix_len, workspace, out, status, s);
     if (e != hipSuccess) return SPEC_ERR_HIP;
   }
   return SPEC_OK;
+}
+
+int spec_tree_attention(const spec_attn_desc_t* desc, const void* q, const void* k_cache, const void* v_cache,
+                        const int32_t* tree_parent, const int32_t* tree_depth, const int32_t* prefix_len, void* out,
+                        void* workspace, size_t workspace_bytes, int32_t* status, void* hip_stream) {
+  return tree_attention_impl(desc, q, nullptr, nullptr, const_cast<void*>(k_cache), const_cast<void*>(v_cache),
+                             tree_parent, tree_depth, prefix_len, out, workspace, workspace_bytes, status, hip_stream);
+}
+
+int spec_tree_attention_append(const spec_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,
+                               void* k_cache, void* v_cache, const int32_t* tree_parent, const int32_t* tree_depth,
+                               const int32_t* prefix_len, void* out, void* workspace, size_t workspace_bytes,
+                               int32_t* status, void* hip_stream) {
+  if (!k_new || !v_new) return check_desc(desc) != SPEC_OK ? check_desc(desc) : SPEC_ERR_INVALID_ARG;
+  return tree_attention_impl(desc, q, k_new, v_new, k_cache, v_cache, tree_parent, tree_depth, prefix_len, out,
+                             workspace, workspace_bytes, status, hip_stream);
 }
 
 static int check_verify_common(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, const void* logits,

@@ -32,8 +32,9 @@ hipError_t launch_tree_attention_f32(const spec_attn_desc_t& d, const AttnPlan& 
                                      const float* k_cache, const float* v_cache, const int32_t* parent,
                                      const int32_t* depth, const int32_t* prefix_len, float* out, void* ws,
                                      int32_t* status, hipStream_t s);
-hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan& plan, const void* q,
-                                      const void* k_cache, const void* v_cache, const int32_t* parent,
+// k_new / v_new non-null: the kernel also appends the tree rows to the cache (fused KV append).
+hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan& plan, const void* q, void* k_cache,
+                                      void* v_cache, const void* k_new, const void* v_new, const int32_t* parent,
                                       const int32_t* depth, const int32_t* prefix_len, void* out, void* ws,
                                       int32_t* status, hipStream_t s);
 hipError_t launch_attn_combine(const spec_attn_desc_t& d, const AttnPlan& plan, const int32_t* parent,

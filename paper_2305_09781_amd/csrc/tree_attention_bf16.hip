@@ -5,8 +5,8 @@
 // Decomposition
 //   grid = (n_splits, H * n_qgroups, B). A workgroup (4 wavefronts) owns one chunk of the key range
 //   of one (request, head) and a group of NT*16 tree queries. The four wavefronts take the chunk's
-//   32-key tiles round-robin and are completely independent inside the main loop (no barrier): each
-//   keeps its own online-softmax state and merges with the others once, through LDS, at the end.
+//   32-key tiles round-robin and are independent inside the main loop (no barrier): each keeps its
+//   own online-softmax state and merges with the others once, through LDS, at the end.
 //
 // Per 32-key tile and wavefront
 //   S^T = K Q^T   v_mfma_f32_16x16x32_bf16, A = K rows read straight from global memory into the
@@ -22,28 +22,33 @@
 //                 loaded fully coalesced (four 256-byte rows per instruction), staged in a
 //                 wavefront-private LDS tile and read back with ds_read_b64_tr_b16.
 //
+// Latency structure. The fixed cost of a workgroup (first loads, tree set-up, final merge) is what
+// separates this kernel from a pure stream, so: the first tile's loads and Q are issued before
+// prefix_len is known (rows clamped to the cache capacity), every tile's loads are issued one tile
+// ahead, and the tree is validated and its ancestor masks are built only after the mask-free prefix
+// tiles, while the loads of the remaining tiles are in flight.
+//
+// With APPEND the kernel also performs the KV append of the tree tokens (Section 4.2): rows at and
+// beyond prefix_len are taken from k_new / v_new and written to the cache by query group 0.
+//
 // Results are written as the final bf16 output when one chunk covers the whole key range, else as
 // float32 partials (m, l, O) merged by attn_combine_kernel.
 #include <hip/hip_bf16.h>
+
+#include <type_traits>
 
 #include "spec_internal.h"
 
 namespace spec {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;   // 16-byte load/store unit (plain vector: stays in registers)
 
 constexpr float kLog2eB = 1.4426950408889634f;
 constexpr int TILE = 32;          // keys per wavefront tile
 constexpr int WAVES = 4;
-
-template <int D>
-struct VTile {
-  static constexpr int ROW_BYTES = D * 2 + 16;        // +16 B pad: 4 consecutive rows fall in distinct banks
-  static constexpr int BYTES = TILE * ROW_BYTES;
-};
 
 __device__ inline float wave_max_over_lane_groups(float v) {
   // lanes l, l^16, l^32, l^48 hold the same query: reduce over the four 16-lane groups
@@ -58,25 +63,78 @@ __device__ inline float wave_sum_over_lane_groups(float v) {
 }
 
 template <int D, int NT>
-__global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
-    const __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ k_cache,
-    const __hip_bfloat16* __restrict__ v_cache, const int32_t* __restrict__ parent, const int32_t* __restrict__ depth,
-    const int32_t* __restrict__ prefix_len, __hip_bfloat16* __restrict__ out, float* __restrict__ ws_o,
-    float* __restrict__ ws_ml, int32_t* status, int N, int H, int S_cap, int n_qgroups, int chunk_keys, int n_splits,
-    long q_sb, long q_sn, long q_sh, long kv_sb, long kv_sh, long kv_ss, float scale_log2) {
-  constexpr int KS = D / 32;            // k-steps of the QK^T product
-  constexpr int DB = D / 16;            // 16-wide d blocks of the output
-  constexpr int LPR = D * 2 / 16;       // lanes (16-byte pieces) per K/V row
-  constexpr int RPI = 64 / LPR;         // rows covered by one wave-wide 16-byte load
-  constexpr int NVL = TILE / RPI;       // V loads per lane per tile
-  constexpr int VROW = VTile<D>::ROW_BYTES;
-  constexpr int NQ = NT * 16;           // queries per workgroup
-  constexpr int MROW = D + 4;           // floats per merge row: O[D], m, l, 2 pad (keeps rows 16-byte aligned)
-  constexpr int MERGE_BYTES = WAVES * NQ * MROW * 4;
-  constexpr int STAGE_BYTES = WAVES * VTile<D>::BYTES;
-  constexpr int LDS_BYTES = MERGE_BYTES > STAGE_BYTES ? MERGE_BYTES : STAGE_BYTES;
+struct AttnTraits {
+  static constexpr int KS = D / 32;            // k-steps of the QK^T product
+  static constexpr int DB = D / 16;            // 16-wide d blocks of the output
+  static constexpr int LPR = D * 2 / 16;       // lanes (16-byte pieces) per K/V row
+  static constexpr int RPI = 64 / LPR;         // rows covered by one wave-wide 16-byte load
+  static constexpr int NVL = TILE / RPI;       // V loads per lane per tile
+  static constexpr int VROW = D * 2 + 16;      // LDS bytes per staged V row (+16 B pad)
+  static constexpr int VTILE_BYTES = TILE * VROW;
+  static constexpr int NQ = NT * 16;           // queries per workgroup
+  static constexpr int MROW = D + 4;           // floats per merge row: O[D], m, l, 2 pad (16-byte aligned rows)
+  static constexpr int MERGE_BYTES = WAVES * NQ * MROW * 4;
+  static constexpr int STAGE_BYTES = WAVES * VTILE_BYTES;
+  static constexpr int LDS_BYTES = MERGE_BYTES > STAGE_BYTES ? MERGE_BYTES : STAGE_BYTES;
+};
 
-  __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
+// Pointers and strides one lane needs to fetch its pieces of a tile.
+struct TileSrc {
+  const unsigned char* kc;   // cache K of this (request, head), byte pointer at the lane's column
+  const unsigned char* vc;
+  const unsigned char* kn;   // new K of this (request, head) at node 0, lane's column (APPEND only)
+  const unsigned char* vn;
+  unsigned cache_row_bytes;
+  unsigned new_row_bytes;
+};
+
+// Loads of one tile. CLEAN: every row lies inside the cached prefix (no clamp, no source select).
+// Otherwise rows are clamped to `last_row`; with APPEND rows >= P come from the new K/V.
+template <int D, int NT, bool APPEND, bool CLEAN>
+__device__ __forceinline__ void issue_tile_loads(const TileSrc& s, int k0, int P, int last_row, int r16, int lane,
+                                                 u32x4 (&Kn)[2][AttnTraits<D, NT>::KS],
+                                                 u32x4 (&Vn)[AttnTraits<D, NT>::NVL]) {
+  using T = AttnTraits<D, NT>;
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf) {
+    int row = k0 + hf * 16 + r16;
+    const unsigned char* p;
+    if (CLEAN) {
+      p = s.kc + (unsigned)row * s.cache_row_bytes;
+    } else {
+      row = min(row, last_row);
+      p = (APPEND && row >= P) ? s.kn + (unsigned)(row - P) * s.new_row_bytes : s.kc + (unsigned)row * s.cache_row_bytes;
+    }
+#pragma unroll
+    for (int ks = 0; ks < T::KS; ++ks) Kn[hf][ks] = *(const u32x4*)(p + ks * 64);
+  }
+#pragma unroll
+  for (int j = 0; j < T::NVL; ++j) {
+    int row = k0 + j * T::RPI + lane / T::LPR;
+    const unsigned char* p;
+    if (CLEAN) {
+      p = s.vc + (unsigned)row * s.cache_row_bytes;
+    } else {
+      row = min(row, last_row);
+      p = (APPEND && row >= P) ? s.vn + (unsigned)(row - P) * s.new_row_bytes : s.vc + (unsigned)row * s.cache_row_bytes;
+    }
+    Vn[j] = *(const u32x4*)p;
+  }
+}
+
+template <int D, int NT, bool APPEND>
+__global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
+    const __hip_bfloat16* __restrict__ q, __hip_bfloat16* k_cache, __hip_bfloat16* v_cache,
+    const __hip_bfloat16* __restrict__ k_new, const __hip_bfloat16* __restrict__ v_new,
+    const int32_t* __restrict__ parent, const int32_t* __restrict__ depth, const int32_t* __restrict__ prefix_len,
+    __hip_bfloat16* __restrict__ out, float* __restrict__ ws_o, float* __restrict__ ws_ml, int32_t* status, int N, int H,
+    int S_cap, int n_qgroups, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long kv_sb, long kv_sh,
+    long kv_ss, float scale_log2) {
+  using T = AttnTraits<D, NT>;
+  constexpr int KS = T::KS, DB = T::DB, LPR = T::LPR, RPI = T::RPI, NVL = T::NVL, VROW = T::VROW, NQ = T::NQ,
+                MROW = T::MROW;
+
+  __shared__ __attribute__((aligned(16))) unsigned char lds[T::LDS_BYTES];
   __shared__ unsigned long long s_anc[SPEC_MAX_TREE_NODES][2];
   __shared__ int s_parent[SPEC_MAX_TREE_NODES];
   __shared__ int s_depth[SPEC_MAX_TREE_NODES];
@@ -88,11 +146,42 @@ __global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
   const int h = blockIdx.y / n_qgroups, qg = blockIdx.y % n_qgroups;
   const int b = blockIdx.z;
   const int q0 = qg * NQ;
+  const int c0 = split * chunk_keys;
+
+  TileSrc src;
+  src.cache_row_bytes = (unsigned)kv_ss * 2u;
+  src.new_row_bytes = (unsigned)q_sn * 2u;
+  src.kc = (const unsigned char*)(k_cache + b * kv_sb + h * kv_sh) + g * 16;
+  src.vc = (const unsigned char*)(v_cache + b * kv_sb + h * kv_sh) + (lane % LPR) * 16;
+  src.kn = APPEND ? (const unsigned char*)(k_new + b * q_sb + h * q_sh) + g * 16 : nullptr;
+  src.vn = APPEND ? (const unsigned char*)(v_new + b * q_sb + h * q_sh) + (lane % LPR) * 16 : nullptr;
+
+  // ---- everything that does not depend on prefix_len is requested first: the first tile (rows
+  // clamped to the cache capacity, so the addresses are valid whatever prefix_len turns out to be),
+  // Q, and this thread's node of the tree.
+  u32x4 Kn[2][KS], Vn[NVL];
+  issue_tile_loads<D, NT, false, false>(src, c0 + wave * TILE, 0, S_cap - 1, r16, lane, Kn, Vn);
+
+  bf16x8 qB[NT][KS];   // Q^T as the B operand: lane (r16, g) holds Q[n = r16][d = ks*32 + g*8 .. +8]
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int n = q0 + nt * 16 + r16;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      u32x4 raw = {0u, 0u, 0u, 0u};
+      if (n < N) raw = *(const u32x4*)(q + b * q_sb + n * q_sn + h * q_sh + ks * 32 + g * 8);
+      qB[nt][ks] = __builtin_bit_cast(bf16x8, raw);
+    }
+  }
+  int my_parent = 0, my_depth = 0;
+  if (t < N) {
+    my_parent = parent[(long)b * N + t];
+    my_depth = depth[(long)b * N + t];
+  }
 
   const int P = prefix_len[b];
   const bool cap_ok = (P >= 0) && (P <= S_cap - N);
   const int len = P + N;
-  const int c0 = split * chunk_keys;
   if (!cap_ok) {
     if (n_splits == 1) {
       for (int i = t; i < NQ * D; i += 256) {
@@ -106,113 +195,66 @@ __global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
   if (c0 >= len) return;
   const int c1 = min(c0 + chunk_keys, len);
   const bool touches_tree = c1 > P;
+  const int n_tiles = (c1 - c0 + TILE - 1) / TILE;
+  const int n_clean = max(0, min(P, c1) - c0) / TILE;     // tiles entirely inside the prefix and the chunk
+  const int last_row = len - 1;
 
-  unsigned long long anc_lo[NT], anc_hi[NT];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) anc_lo[nt] = anc_hi[nt] = 0ull;
-
-  if (touches_tree) {
-    // stage the tree, validate it, build ancestor-or-self masks by walking up the parent chain
-    if (t == 0) s_flag = 0;
-    if (t < N) {
-      s_parent[t] = parent[(long)b * N + t];
-      s_depth[t] = depth[(long)b * N + t];
-    }
-    __syncthreads();
-    if (t < N) {
-      const int p = s_parent[t];
-      bool ok = (t == 0) ? (p == -1 && s_depth[0] == 0) : (p >= 0 && p < t);
-      if (ok && t > 0) ok = s_depth[t] == s_depth[p] + 1;
-      if (!ok) atomicOr(&s_flag, 1);
-    }
-    __syncthreads();
-    if (s_flag != 0) {
-      if (n_splits == 1) {
-        for (int i = t; i < NQ * D; i += 256) {
-          const int n = q0 + i / D;
-          if (n < N) out[b * q_sb + n * q_sn + h * q_sh + (i % D)] = __float2bfloat16(0.f);
-        }
-        if (h == 0 && qg == 0 && t == 0) set_status(status, b, SPEC_ST_BAD_TREE);
-      }
-      return;
-    }
-    if (t < N) {
-      unsigned long long lo = 0, hi = 0;
-      int u = t;
-      for (int step = 0; step < N && u >= 0; ++step) {
-        if (u < 64) lo |= 1ull << u; else hi |= 1ull << (u - 64);
-        u = s_parent[u];
-      }
-      s_anc[t][0] = lo;
-      s_anc[t][1] = hi;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const int n = q0 + nt * 16 + r16;
-      if (n < N) { anc_lo[nt] = s_anc[n][0]; anc_hi[nt] = s_anc[n][1]; }
-    }
-  }
-
-  // ---- Q^T as the B operand: lane (r16, g) holds Q[n = r16][d = ks*32 + g*8 .. +8]
-  bf16x8 qB[NT][KS];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    const int n = q0 + nt * 16 + r16;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      uint4 raw = make_uint4(0, 0, 0, 0);
-      if (n < N) raw = *(const uint4*)(q + b * q_sb + n * q_sn + h * q_sh + ks * 32 + g * 8);
-      qB[nt][ks] = __builtin_bit_cast(bf16x8, raw);
-    }
-  }
+  if (APPEND && wave >= n_clean)   // the speculative first tile reaches the tree: fetch it from the right sources
+    issue_tile_loads<D, NT, true, false>(src, c0 + wave * TILE, P, last_row, r16, lane, Kn, Vn);
 
   f32x4 O[NT][DB];
   float m_run[NT], l_run[NT];
+  unsigned long long anc_lo[NT], anc_hi[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     m_run[nt] = -INFINITY;
     l_run[nt] = 0.f;
+    anc_lo[nt] = anc_hi[nt] = 0ull;
 #pragma unroll
     for (int db = 0; db < DB; ++db) O[nt][db] = (f32x4){0.f, 0.f, 0.f, 0.f};
   }
+  unsigned char* vst = lds + wave * T::VTILE_BYTES;
 
-  const __hip_bfloat16* kb = k_cache + b * kv_sb + h * kv_sh;
-  const __hip_bfloat16* vb = v_cache + b * kv_sb + h * kv_sh;
-  unsigned char* vst = lds + wave * VTile<D>::BYTES;
-  const int n_tiles = (c1 - c0 + TILE - 1) / TILE;
-  const int last_row = len - 1;
-
-  uint4 Kn[2][KS], Vn[NVL];
-  auto issue_loads = [&](int ti) {
+  // One tile: consume the loads issued one step earlier, issue the next tile's, S^T, softmax, O^T.
+  auto tile_step = [&](const int ti, auto masked_tag) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
     const int k0 = c0 + ti * TILE;
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf) {
-      const int row = min(k0 + hf * 16 + r16, last_row);
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) Kn[hf][ks] = *(const uint4*)(kb + (long)row * kv_ss + ks * 32 + g * 8);
-    }
-#pragma unroll
-    for (int j = 0; j < NVL; ++j) {
-      const int row = min(k0 + j * RPI + lane / LPR, last_row);
-      Vn[j] = *(const uint4*)(vb + (long)row * kv_ss + (lane % LPR) * 8);
-    }
-  };
-
-  int ti = wave;
-  if (ti < n_tiles) issue_loads(ti);
-  for (; ti < n_tiles; ti += WAVES) {
-    const int k0 = c0 + ti * TILE;
-    // current tile: K operands to their own registers, V to the wavefront's LDS tile
     bf16x8 Kc[2][KS];
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) Kc[hf][ks] = __builtin_bit_cast(bf16x8, Kn[hf][ks]);
+    if (MASKED) {
+      // rows at and beyond the end of the chunk hold stale data: their V must not reach the product
 #pragma unroll
-    for (int j = 0; j < NVL; ++j)
-      *(uint4*)(vst + (j * RPI + lane / LPR) * VROW + (lane % LPR) * 16) = Vn[j];
-    if (ti + WAVES < n_tiles) issue_loads(ti + WAVES);
+      for (int j = 0; j < NVL; ++j)
+        if (k0 + j * RPI + lane / LPR >= c1) Vn[j] = (u32x4){0u, 0u, 0u, 0u};
+      if (APPEND && qg == 0) {   // this tile carries tree rows taken from k_new / v_new: put them in the cache
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+          const int row = k0 + hf * 16 + r16;
+          if (row >= P && row < c1) {
+            unsigned char* dst = (unsigned char*)(k_cache + b * kv_sb + h * kv_sh) + (unsigned)row * src.cache_row_bytes + g * 16;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) *(u32x4*)(dst + ks * 64) = Kn[hf][ks];
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < NVL; ++j) {
+          const int row = k0 + j * RPI + lane / LPR;
+          if (row >= P && row < c1)
+            *(u32x4*)((unsigned char*)(v_cache + b * kv_sb + h * kv_sh) + (unsigned)row * src.cache_row_bytes +
+                      (lane % LPR) * 16) = Vn[j];
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < NVL; ++j) *(u32x4*)(vst + (j * RPI + lane / LPR) * VROW + (lane % LPR) * 16) = Vn[j];
+    {
+      const int kn0 = k0 + WAVES * TILE;   // next tile of this wavefront (harmless if past the chunk)
+      if (kn0 + TILE <= P) issue_tile_loads<D, NT, APPEND, true>(src, kn0, P, last_row, r16, lane, Kn, Vn);
+      else issue_tile_loads<D, NT, APPEND, false>(src, kn0, P, last_row, r16, lane, Kn, Vn);
+    }
 
     // ---- S^T = K Q^T : sc[nt][hf][v] = score of query nt*16+r16 and key k0 + hf*16 + 4g + v
     f32x4 sc[NT][2];
@@ -227,7 +269,6 @@ __global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
         sc[nt][hf] = acc;
       }
 
-    const bool need_mask = (k0 + TILE > P) || (k0 + TILE > c1);
     bf16x8 pB[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
@@ -236,7 +277,7 @@ __global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
       for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
         for (int v = 0; v < 4; ++v) s[hf * 4 + v] = sc[nt][hf][v] * scale_log2;
-      if (need_mask) {
+      if (MASKED) {
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
@@ -289,7 +330,54 @@ __global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     __builtin_amdgcn_wave_barrier();
+  };
+
+  // ---- phase A: tiles inside the prefix need no mask and no tree
+  int ti = wave;
+  for (; ti < n_clean; ti += WAVES) tile_step(ti, std::false_type{});
+
+  // ---- tree set-up (only workgroups whose chunk reaches the tree), then phase B: the remaining tiles
+  if (touches_tree) {
+    if (t == 0) s_flag = 0;
+    if (t < N) {
+      s_parent[t] = my_parent;
+      s_depth[t] = my_depth;
+    }
+    __syncthreads();
+    if (t < N) {
+      bool ok = (t == 0) ? (my_parent == -1 && my_depth == 0) : (my_parent >= 0 && my_parent < t);
+      if (ok && t > 0) ok = my_depth == s_depth[my_parent] + 1;
+      if (!ok) atomicOr(&s_flag, 1);
+    }
+    __syncthreads();
+    if (s_flag != 0) {
+      if (n_splits == 1) {
+        for (int i = t; i < NQ * D; i += 256) {
+          const int n = q0 + i / D;
+          if (n < N) out[b * q_sb + n * q_sn + h * q_sh + (i % D)] = __float2bfloat16(0.f);
+        }
+        if (h == 0 && qg == 0 && t == 0) set_status(status, b, SPEC_ST_BAD_TREE);
+      }
+      return;
+    }
+    if (t < N) {
+      unsigned long long lo = 0, hi = 0;
+      int u = t;
+      for (int step = 0; step < N && u >= 0; ++step) {
+        if (u < 64) lo |= 1ull << u; else hi |= 1ull << (u - 64);
+        u = s_parent[u];
+      }
+      s_anc[t][0] = lo;
+      s_anc[t][1] = hi;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int n = q0 + nt * 16 + r16;
+      if (n < N) { anc_lo[nt] = s_anc[n][0]; anc_hi[nt] = s_anc[n][1]; }
+    }
   }
+  for (; ti < n_tiles; ti += WAVES) tile_step(ti, std::true_type{});
 
   // ---- merge the four wavefronts through LDS: layout [wave][n][MROW] floats (O row, m, l)
   __syncthreads();
@@ -341,8 +429,8 @@ __global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
   }
 }
 
-hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan& plan, const void* q,
-                                      const void* k_cache, const void* v_cache, const int32_t* parent,
+hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan& plan, const void* q, void* k_cache,
+                                      void* v_cache, const void* k_new, const void* v_new, const int32_t* parent,
                                       const int32_t* depth, const int32_t* prefix_len, void* out, void* ws,
                                       int32_t* status, hipStream_t s) {
   const float scale = (d.softmax_scale != 0.f ? d.softmax_scale : 1.0f / sqrtf((float)d.D)) * kLog2eB;
@@ -351,17 +439,22 @@ hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan&
   const int nt = d.N <= 16 ? 1 : 2;
   const int nq = nt * 16;
   const int n_qgroups = (d.N + nq - 1) / nq;
+  const bool append = k_new != nullptr;
   dim3 grid(plan.n_splits, d.H * n_qgroups, d.B);
-#define SPEC_LAUNCH(DD, NTT)                                                                                          \
-  hipLaunchKernelGGL((tree_attention_bf16_kernel<DD, NTT>), grid, dim3(256), 0, s, (const __hip_bfloat16*)q,          \
-                     (const __hip_bfloat16*)k_cache, (const __hip_bfloat16*)v_cache, parent, depth, prefix_len,       \
-                     (__hip_bfloat16*)out, ws_o, ws_ml, status, d.N, d.H, d.S_cap, n_qgroups, plan.chunk_keys,        \
-                     plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h, (long)d.kv_stride_b,  \
-                     (long)d.kv_stride_h, (long)d.kv_stride_s, scale)
-  if (d.D == 128 && nt == 1) SPEC_LAUNCH(128, 1);
-  else if (d.D == 128) SPEC_LAUNCH(128, 2);
-  else if (nt == 1) SPEC_LAUNCH(64, 1);
-  else SPEC_LAUNCH(64, 2);
+#define SPEC_LAUNCH(DD, NTT, APP)                                                                                     \
+  hipLaunchKernelGGL((tree_attention_bf16_kernel<DD, NTT, APP>), grid, dim3(256), 0, s, (const __hip_bfloat16*)q,     \
+                     (__hip_bfloat16*)k_cache, (__hip_bfloat16*)v_cache, (const __hip_bfloat16*)k_new,                \
+                     (const __hip_bfloat16*)v_new, parent, depth, prefix_len, (__hip_bfloat16*)out, ws_o, ws_ml,      \
+                     status, d.N, d.H, d.S_cap, n_qgroups, plan.chunk_keys, plan.n_splits, (long)d.q_stride_b,        \
+                     (long)d.q_stride_n, (long)d.q_stride_h, (long)d.kv_stride_b, (long)d.kv_stride_h,                \
+                     (long)d.kv_stride_s, scale)
+#define SPEC_DISPATCH(APP)                          \
+  if (d.D == 128 && nt == 1) SPEC_LAUNCH(128, 1, APP); \
+  else if (d.D == 128) SPEC_LAUNCH(128, 2, APP);       \
+  else if (nt == 1) SPEC_LAUNCH(64, 1, APP);           \
+  else SPEC_LAUNCH(64, 2, APP)
+  if (append) { SPEC_DISPATCH(true); } else { SPEC_DISPATCH(false); }
+#undef SPEC_DISPATCH
 #undef SPEC_LAUNCH
   return hipGetLastError();
 }

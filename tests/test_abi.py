@@ -60,7 +60,7 @@ def test_attention_and_append_reject_bad_descriptors(kw, code):
 
 def test_misaligned_pointers_and_workspace_are_rejected():
     lib = binding.load()
-    d = _desc()
+    d = _desc(S_cap=4104, kv_stride_h=4104 * 64, kv_stride_b=4 * 4104 * 64)   # long enough to be split
     buf = ctypes.create_string_buffer(4096)
     base = ctypes.addressof(buf)
     a = ctypes.c_void_p((base + 255) // 256 * 256)

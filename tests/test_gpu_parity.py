@@ -65,14 +65,20 @@ class _chunk_keys:
             os.environ["SPEC_TREE_CHUNK_KEYS"] = self.old
 
 
-def _run_append_attention(spec, inp, layer=0, status=None):
-    """append + attention on the GPU for one layer of `inp`; returns (out, k_cache, v_cache) device tensors."""
+def _run_append_attention(spec, inp, layer=0, status=None, fused=False):
+    """append + attention on the GPU for one layer of `inp` (two calls, or the fused entry point);
+    returns (out, k_cache, v_cache) device tensors."""
     kc, vc = _dev(inp["k_cache"][layer]), _dev(inp["v_cache"][layer])
     pl = _dev(inp["prefix_len"])
-    spec.spec_kv_append(_dev(inp["k_new"][layer]), _dev(inp["v_new"][layer]), kc, vc, pl, status=status)
-    out = spec.spec_tree_attention(_dev(inp["q"][layer]), kc, vc, _dev(inp["tree_parent"]), _dev(inp["tree_depth"]), pl,
-                                   status=status,
-                                   max_prefix_len=min(int(inp["prefix_len"].max()), kc.shape[2] - inp["q"][layer].shape[1]))
+    mp = min(int(inp["prefix_len"].max()), kc.shape[2] - inp["q"][layer].shape[1])
+    kn, vn = _dev(inp["k_new"][layer]), _dev(inp["v_new"][layer])
+    if fused:
+        out = spec.spec_tree_attention_append(_dev(inp["q"][layer]), kn, vn, kc, vc, _dev(inp["tree_parent"]),
+                                              _dev(inp["tree_depth"]), pl, status=status, max_prefix_len=mp)
+    else:
+        spec.spec_kv_append(kn, vn, kc, vc, pl, status=status)
+        out = spec.spec_tree_attention(_dev(inp["q"][layer]), kc, vc, _dev(inp["tree_parent"]), _dev(inp["tree_depth"]),
+                                       pl, status=status, max_prefix_len=mp)
     torch.cuda.synchronize()
     return out, kc, vc
 
@@ -102,7 +108,7 @@ def test_config1_fp32_attention_and_append(spec):
     inp = wl.make_attention_inputs(cfg)
     for chunk in (0, 32, 64):
         with _chunk_keys(chunk):
-            out, kc, vc = _run_append_attention(spec, inp)
+            out, kc, vc = _run_append_attention(spec, inp, fused=(chunk == 32))
         ref, kco, vco = _oracle_append_attention(inp)
         _check_attention(out, ref, torch.float32)
         assert np.array_equal(kc.cpu().numpy().astype(np.float64), kco)
@@ -134,21 +140,23 @@ def test_small_shapes_attention_and_append(spec, case):
     cfg = wl.Config(90, "small", dtype, B=B, H=H, D=D, P=P if P[0] != P[1] else P[0], N=N, tree=tree,
                     widths=wl.EXPANSION_EVAL * 2)
     inp = wl.make_attention_inputs(cfg, seed=1000 + N + D + B, S_cap=P[1] + N + 5)
-    with _chunk_keys(chunk):
-        out, kc, vc = _run_append_attention(spec, inp)
     ref, kco, vco = _oracle_append_attention(inp)
-    _check_attention(out, ref, cfg.torch_dtype)
-    # append is a bit copy: compare the whole cache (float64 conversion of either dtype is exact)
-    assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco)
+    for fused in (False, True):
+        with _chunk_keys(chunk):
+            out, kc, vc = _run_append_attention(spec, inp, fused=fused)
+        _check_attention(out, ref, cfg.torch_dtype)
+        # append is a bit copy: compare the whole cache (float64 conversion of either dtype is exact)
+        assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco), fused
 
 
-def test_config2_bf16_full(spec):
+@pytest.mark.parametrize("fused", [False, True])
+def test_config2_bf16_full(spec, fused):
     cfg = wl.CONFIGS[2]
     inp = wl.make_attention_inputs(cfg)
-    out, kc, vc = _run_append_attention(spec, inp)
+    out, kc, vc = _run_append_attention(spec, inp, fused=fused)
     ref, kco, vco = _oracle_append_attention(inp)
     _check_attention(out, ref, torch.bfloat16)
-    assert np.array_equal(kc.double().cpu().numpy(), kco)
+    assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco)
 
 
 @pytest.mark.parametrize("c", [3, 4, 5])
@@ -157,28 +165,29 @@ def test_large_configs_sampled_heads(spec, c):
     (request, head) pairs completely, every node and channel."""
     cfg = wl.CONFIGS[c]
     inp = wl.make_attention_inputs(cfg)
-    out, kc, vc = _run_append_attention(spec, inp)
+    out, kc, vc = _run_append_attention(spec, inp, fused=(c != 4))
     assert torch.isfinite(out.float()).all()
     rng = np.random.default_rng(c)
     bsel = sorted(set(int(x) for x in rng.integers(0, cfg.B, size=3)) | {cfg.B - 1})
     hsel = sorted(set(int(x) for x in rng.integers(0, cfg.H, size=3)) | {0})
-    ref, kco, _ = _oracle_append_attention(inp, bsel=bsel, hsel=hsel)
+    ref, kco, _vco = _oracle_append_attention(inp, bsel=bsel, hsel=hsel)
     sub = out[bsel][:, :, hsel]
     _check_attention(sub, ref, torch.bfloat16)
     assert np.array_equal(kc[bsel][:, hsel].double().cpu().numpy(), kco)
+    assert np.array_equal(vc[bsel][:, hsel].double().cpu().numpy(), _vco)
 
 
 def test_attention_status_bits_and_noop(spec):
     """Malformed trees and requests that do not fit are flagged and produce zeros; others unaffected."""
     cfg = wl.Config(91, "bad", "bf16", B=4, H=2, D=128, P=(40, 90), N=16, tree="random_parent")
-    for chunk in (0, 64):
+    for chunk, fused in ((0, False), (64, False), (0, True), (64, True)):
         inp = wl.make_attention_inputs(cfg, seed=5, S_cap=90 + 16)
         inp["tree_parent"][1, 5] = 9            # parent after child
         inp["tree_depth"][2, 7] += 1            # depth inconsistent with parent
         inp["prefix_len"][3] = 90 + 1           # prefix + N > S_cap
         status = torch.zeros(cfg.B, dtype=torch.int32, device=DEV)
         with _chunk_keys(chunk):
-            out, kc, vc = _run_append_attention(spec, inp, status=status)
+            out, kc, vc = _run_append_attention(spec, inp, status=status, fused=fused)
         st = status.cpu().numpy()
         assert st[0] == 0 and st[1] == orc.ST_BAD_TREE and st[2] == orc.ST_BAD_TREE and st[3] == orc.ST_CAPACITY
         assert (out[1:].float() == 0).all()
@@ -366,9 +375,9 @@ def test_end_to_end_iteration_config5_two_layers(spec):
     par, dep = _dev(inp["tree_parent"]), _dev(inp["tree_depth"])
     outs = []
     for l in range(2):
-        spec.spec_kv_append(_dev(inp["k_new"][l]), _dev(inp["v_new"][l]), kcs[l], vcs[l], pl)
-        outs.append(spec.spec_tree_attention(_dev(inp["q"][l]), kcs[l], vcs[l], par, dep, pl,
-                                             max_prefix_len=int(inp["prefix_len"].max())))
+        outs.append(spec.spec_tree_attention_append(_dev(inp["q"][l]), _dev(inp["k_new"][l]), _dev(inp["v_new"][l]),
+                                                    kcs[l], vcs[l], par, dep, pl,
+                                                    max_prefix_len=int(inp["prefix_len"].max())))
     path, ln, toks, _ = spec.spec_verify_greedy(_dev(ver["logits"]), _dev(ver["tree_token"]), par)
     new_len = spec.spec_kv_commit(kcs, vcs, path, ln, pl, small.N)
     torch.cuda.synchronize()
@@ -407,8 +416,12 @@ def test_hip_graph_replays_match_eager(spec):
 
     def one_pass():
         for l in range(L):
-            spec.spec_kv_append(kn[l], vn[l], kcs[l], vcs[l], pl, desc=desc)
-            spec.spec_tree_attention(q[l], kcs[l], vcs[l], par, dep, pl, out=outs[l], workspace=ws, desc=desc)
+            if l == 0:
+                spec.spec_kv_append(kn[l], vn[l], kcs[l], vcs[l], pl, desc=desc)
+                spec.spec_tree_attention(q[l], kcs[l], vcs[l], par, dep, pl, out=outs[l], workspace=ws, desc=desc)
+            else:
+                spec.spec_tree_attention_append(q[l], kn[l], vn[l], kcs[l], vcs[l], par, dep, pl, out=outs[l],
+                                                workspace=ws, desc=desc)
         spec.spec_verify_greedy(logits, tok, par, out=vout)
         spec.spec_kv_commit(kcs, vcs, vout[0], vout[1], pl, cfg.N, prefix_len_out=pl_out)
 
