@@ -3,10 +3,15 @@
 // cached prefix, so the kernel is bound by streaming K and V from HBM exactly once.
 //
 // Decomposition
-//   grid = (n_splits, H * n_qgroups, B). A workgroup (4 wavefronts) owns one chunk of the key range
-//   of one (request, head) and a group of NT*16 tree queries. The four wavefronts take the chunk's
-//   32-key tiles round-robin and are independent inside the main loop (no barrier): each keeps its
-//   own online-softmax state and merges with the others once, through LDS, at the end.
+//   grid = (n_splits, H * n_qgroups, B). A workgroup owns one chunk of the key range of one
+//   (request, head) and a group of NT*16 tree queries. It has five wavefronts:
+//     - four streaming wavefronts take the chunk's mask-free 32-key tiles (entirely inside the cached
+//       prefix) round-robin; they never need the tree, a mask, or a barrier inside their loop;
+//     - one tail wavefront owns the ragged end: the tiles that reach past prefix_len (the tree rows,
+//       the end of the sequence). It alone validates the tree, builds the ancestor masks, applies
+//       them, and (fused append) writes the new rows to the cache. Its few tiles run concurrently
+//       with the stream instead of forming a serial tail, and the stream stays evenly divided.
+//   Each wavefront keeps its own online-softmax state; the five are merged once, through LDS.
 //
 // Per 32-key tile and wavefront
 //   S^T = K Q^T   v_mfma_f32_16x16x32_bf16, A = K rows read straight from global memory into the
@@ -14,19 +19,18 @@
 //                 B = Q^T resident in registers. The transposed product leaves lane l with scores of
 //                 query l%16 for keys 4*(l/16)+v of each 16-key half: exactly the B-operand layout
 //                 P^T needs for the second product, so probabilities never leave registers.
-//   mask          only for tiles that reach past the prefix: bit (key - prefix_len) of the query's
-//                 128-bit ancestor-or-self mask (built once per workgroup from the parent array).
+//   mask          tail wavefront only: bit (key - prefix_len) of the query's 128-bit ancestor-or-self
+//                 mask (built from the parent array by walking up the parent chain in LDS).
 //   softmax       online, in the exp2 domain; row max over the tile = 8 in-lane values + 2 cross-lane
 //                 exchanges; the rescale factor of a query is lane-local for its O^T fragment.
 //   O^T += V^T P^T  A = V^T needs 8 keys x 1 d per lane, the transpose of how V lies in memory: V is
 //                 loaded fully coalesced (four 256-byte rows per instruction), staged in a
 //                 wavefront-private LDS tile and read back with ds_read_b64_tr_b16.
 //
-// Latency structure. The fixed cost of a workgroup (first loads, tree set-up, final merge) is what
-// separates this kernel from a pure stream, so: the first tile's loads and Q are issued before
-// prefix_len is known (rows clamped to the cache capacity), every tile's loads are issued one tile
-// ahead, and the tree is validated and its ancestor masks are built only after the mask-free prefix
-// tiles, while the loads of the remaining tiles are in flight.
+// Latency structure. A workgroup's fixed costs are what separate this kernel from a pure stream: the
+// first tile's loads are issued before prefix_len is known (rows clamped to the cache capacity), in
+// straight-line code so that all kernel arguments arrive in one batch; every tile's loads are issued
+// one tile ahead; nothing in the loop waits on more than its own tile.
 //
 // With APPEND the kernel also performs the KV append of the tree tokens (Section 4.2): rows at and
 // beyond prefix_len are taken from k_new / v_new and written to the cache by query group 0.
@@ -35,6 +39,7 @@
 // float32 partials (m, l, O) merged by attn_combine_kernel.
 #include <hip/hip_bf16.h>
 
+#include <cstdlib>
 #include <type_traits>
 
 #include "spec_internal.h"
@@ -46,9 +51,33 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;   // 16-byte load/store unit (plain vector: stays in registers)
 
+#ifdef SPEC_ATTN_TIMELINE
+// Development aid: per-wavefront timestamps (100 MHz wall clock) written to the workspace. The inline
+// asm keeps each reading where it is written in the program.
+#define SPEC_TS(slot)                                                                                         \
+  {                                                                                                           \
+    unsigned long long ts_;                                                                                   \
+    asm volatile("s_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(ts_)::"memory");                           \
+    if (lane == 0)                                                                                            \
+      ((unsigned long long*)ws_o)[((((long)b * gridDim.y + blockIdx.y) * n_splits + split) * WAVES + wave) * 8 + (slot)] = ts_; \
+  }
+#define SPEC_TS_DEP(slot, dep)                                                                                \
+  {                                                                                                           \
+    unsigned long long ts_;                                                                                   \
+    asm volatile("s_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(ts_) : "s"(dep) : "memory");               \
+    if (lane == 0)                                                                                            \
+      ((unsigned long long*)ws_o)[((((long)b * gridDim.y + blockIdx.y) * n_splits + split) * WAVES + wave) * 8 + (slot)] = ts_; \
+  }
+#else
+#define SPEC_TS(slot)
+#define SPEC_TS_DEP(slot, dep)
+#endif
+
 constexpr float kLog2eB = 1.4426950408889634f;
 constexpr int TILE = 32;          // keys per wavefront tile
-constexpr int WAVES = 4;
+constexpr int SWAVES = 4;         // streaming wavefronts
+constexpr int WAVES = SWAVES + 1; // plus the tail wavefront
+constexpr int TAIL = SWAVES;      // its index
 
 __device__ inline float wave_max_over_lane_groups(float v) {
   // lanes l, l^16, l^32, l^48 hold the same query: reduce over the four 16-lane groups
@@ -60,6 +89,19 @@ __device__ inline float wave_sum_over_lane_groups(float v) {
   v += __shfl_xor(v, 16);
   v += __shfl_xor(v, 32);
   return v;
+}
+// 16-byte store of an appended cache row. Marked non-temporal: the rows are not read again by this
+// kernel, and dirty lines left in the L2 lengthen the write-back at the end of the kernel.
+__device__ __forceinline__ void store_cache_row(void* p, u32x4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(p), "v"(v) : "memory");
+}
+
+// Orders LDS accesses of the lanes of one wavefront (they execute in lockstep; this stops the
+// compiler from moving LDS operations across the point).
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 template <int D, int NT>
@@ -75,7 +117,12 @@ struct AttnTraits {
   static constexpr int MROW = D + 4;           // floats per merge row: O[D], m, l, 2 pad (16-byte aligned rows)
   static constexpr int MERGE_BYTES = WAVES * NQ * MROW * 4;
   static constexpr int STAGE_BYTES = WAVES * VTILE_BYTES;
-  static constexpr int LDS_BYTES = MERGE_BYTES > STAGE_BYTES ? MERGE_BYTES : STAGE_BYTES;
+  // One query tile: the merge area lies behind the staging tiles, so a wavefront can publish its
+  // partial result as soon as it is done. Two query tiles: the merge area reuses the staging tiles.
+  static constexpr bool MERGE_SEPARATE = (NT == 1);
+  static constexpr int MERGE_OFF = MERGE_SEPARATE ? STAGE_BYTES : 0;
+  static constexpr int LDS_BYTES = MERGE_SEPARATE ? STAGE_BYTES + MERGE_BYTES
+                                                  : (MERGE_BYTES > STAGE_BYTES ? MERGE_BYTES : STAGE_BYTES);
 };
 
 // Pointers and strides one lane needs to fetch its pieces of a tile.
@@ -88,12 +135,29 @@ struct TileSrc {
   unsigned new_row_bytes;
 };
 
-// Loads of one tile. CLEAN: every row lies inside the cached prefix (no clamp, no source select).
-// Otherwise rows are clamped to `last_row`; with APPEND rows >= P come from the new K/V.
+// Loads of one tile, V rows and K rows separately (V is consumed first). CLEAN: every row lies inside
+// the cached prefix (no clamp, no source select). Otherwise rows are clamped to `last_row`; with
+// APPEND rows >= P come from the new K/V.
 template <int D, int NT, bool APPEND, bool CLEAN>
-__device__ __forceinline__ void issue_tile_loads(const TileSrc& s, int k0, int P, int last_row, int r16, int lane,
-                                                 u32x4 (&Kn)[2][AttnTraits<D, NT>::KS],
-                                                 u32x4 (&Vn)[AttnTraits<D, NT>::NVL]) {
+__device__ __forceinline__ void issue_v_loads(const TileSrc& s, int k0, int P, int last_row, int lane,
+                                              u32x4 (&Vn)[AttnTraits<D, NT>::NVL]) {
+  using T = AttnTraits<D, NT>;
+#pragma unroll
+  for (int j = 0; j < T::NVL; ++j) {
+    int row = k0 + j * T::RPI + lane / T::LPR;
+    const unsigned char* p;
+    if (CLEAN) {
+      p = s.vc + (unsigned)row * s.cache_row_bytes;
+    } else {
+      row = min(row, last_row);
+      p = (APPEND && row >= P) ? s.vn + (unsigned)(row - P) * s.new_row_bytes : s.vc + (unsigned)row * s.cache_row_bytes;
+    }
+    Vn[j] = *(const u32x4*)p;
+  }
+}
+template <int D, int NT, bool APPEND, bool CLEAN>
+__device__ __forceinline__ void issue_k_loads(const TileSrc& s, int k0, int P, int last_row, int r16,
+                                              u32x4 (&Kn)[2][AttnTraits<D, NT>::KS]) {
   using T = AttnTraits<D, NT>;
 #pragma unroll
   for (int hf = 0; hf < 2; ++hf) {
@@ -108,22 +172,17 @@ __device__ __forceinline__ void issue_tile_loads(const TileSrc& s, int k0, int P
 #pragma unroll
     for (int ks = 0; ks < T::KS; ++ks) Kn[hf][ks] = *(const u32x4*)(p + ks * 64);
   }
-#pragma unroll
-  for (int j = 0; j < T::NVL; ++j) {
-    int row = k0 + j * T::RPI + lane / T::LPR;
-    const unsigned char* p;
-    if (CLEAN) {
-      p = s.vc + (unsigned)row * s.cache_row_bytes;
-    } else {
-      row = min(row, last_row);
-      p = (APPEND && row >= P) ? s.vn + (unsigned)(row - P) * s.new_row_bytes : s.vc + (unsigned)row * s.cache_row_bytes;
-    }
-    Vn[j] = *(const u32x4*)p;
-  }
+}
+template <int D, int NT, bool APPEND, bool CLEAN>
+__device__ __forceinline__ void issue_tile_loads(const TileSrc& s, int k0, int P, int last_row, int r16, int lane,
+                                                 u32x4 (&Kn)[2][AttnTraits<D, NT>::KS],
+                                                 u32x4 (&Vn)[AttnTraits<D, NT>::NVL]) {
+  issue_v_loads<D, NT, APPEND, CLEAN>(s, k0, P, last_row, lane, Vn);
+  issue_k_loads<D, NT, APPEND, CLEAN>(s, k0, P, last_row, r16, Kn);
 }
 
 template <int D, int NT, bool APPEND>
-__global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
+__global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
     const __hip_bfloat16* __restrict__ q, __hip_bfloat16* k_cache, __hip_bfloat16* v_cache,
     const __hip_bfloat16* __restrict__ k_new, const __hip_bfloat16* __restrict__ v_new,
     const int32_t* __restrict__ parent, const int32_t* __restrict__ depth, const int32_t* __restrict__ prefix_len,
@@ -133,21 +192,29 @@ __global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
   using T = AttnTraits<D, NT>;
   constexpr int KS = T::KS, DB = T::DB, LPR = T::LPR, RPI = T::RPI, NVL = T::NVL, VROW = T::VROW, NQ = T::NQ,
                 MROW = T::MROW;
+  constexpr int NTHREADS = WAVES * 64;
 
   __shared__ __attribute__((aligned(16))) unsigned char lds[T::LDS_BYTES];
   __shared__ unsigned long long s_anc[SPEC_MAX_TREE_NODES][2];
   __shared__ int s_parent[SPEC_MAX_TREE_NODES];
   __shared__ int s_depth[SPEC_MAX_TREE_NODES];
-  __shared__ int s_flag;
+  __shared__ int s_bad_tree;
 
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int r16 = lane & 15, g = lane >> 4;
   const int split = blockIdx.x;
   const int h = blockIdx.y / n_qgroups, qg = blockIdx.y % n_qgroups;
   const int b = blockIdx.z;
   const int q0 = qg * NQ;
   const int c0 = split * chunk_keys;
+  SPEC_TS(0)
 
+  // ---- straight-line prologue (no branch before the first loads, so every kernel argument is
+  // fetched in one batch): the streaming wavefronts' first tile does not depend on prefix_len (rows
+  // clamped to the cache capacity keep the addresses valid; the tail wavefront's copy is discarded),
+  // Q, and two tree nodes per lane for the tail wavefront.
+  const int P = prefix_len[b];
   TileSrc src;
   src.cache_row_bytes = (unsigned)kv_ss * 2u;
   src.new_row_bytes = (unsigned)q_sn * 2u;
@@ -156,11 +223,9 @@ __global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
   src.kn = APPEND ? (const unsigned char*)(k_new + b * q_sb + h * q_sh) + g * 16 : nullptr;
   src.vn = APPEND ? (const unsigned char*)(v_new + b * q_sb + h * q_sh) + (lane % LPR) * 16 : nullptr;
 
-  // ---- everything that does not depend on prefix_len is requested first: the first tile (rows
-  // clamped to the cache capacity, so the addresses are valid whatever prefix_len turns out to be),
-  // Q, and this thread's node of the tree.
-  u32x4 Kn[2][KS], Vn[NVL];
-  issue_tile_loads<D, NT, false, false>(src, c0 + wave * TILE, 0, S_cap - 1, r16, lane, Kn, Vn);
+  u32x4 KA[2][KS], VA[NVL];   // tile buffer: loads land here one step ahead of use
+  issue_tile_loads<D, NT, false, false>(src, c0 + min(wave, SWAVES - 1) * TILE, 0, S_cap - 1, r16, lane, KA, VA);
+  SPEC_TS(1)
 
   bf16x8 qB[NT][KS];   // Q^T as the B operand: lane (r16, g) holds Q[n = r16][d = ks*32 + g*8 .. +8]
 #pragma unroll
@@ -168,23 +233,20 @@ __global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
     const int n = q0 + nt * 16 + r16;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      u32x4 raw = {0u, 0u, 0u, 0u};
-      if (n < N) raw = *(const u32x4*)(q + b * q_sb + n * q_sn + h * q_sh + ks * 32 + g * 8);
+      // rows past N repeat the last query (their results are never written): the load is unconditional
+      const u32x4 raw = *(const u32x4*)(q + b * q_sb + min(n, N - 1) * q_sn + h * q_sh + ks * 32 + g * 8);
       qB[nt][ks] = __builtin_bit_cast(bf16x8, raw);
     }
   }
-  int my_parent = 0, my_depth = 0;
-  if (t < N) {
-    my_parent = parent[(long)b * N + t];
-    my_depth = depth[(long)b * N + t];
-  }
+  const int node0 = min(lane, N - 1), node1 = min(lane + 64, N - 1);
+  const int par0 = parent[(long)b * N + node0], par1 = parent[(long)b * N + node1];
+  const int dep0 = depth[(long)b * N + node0], dep1 = depth[(long)b * N + node1];
 
-  const int P = prefix_len[b];
   const bool cap_ok = (P >= 0) && (P <= S_cap - N);
   const int len = P + N;
   if (!cap_ok) {
     if (n_splits == 1) {
-      for (int i = t; i < NQ * D; i += 256) {
+      for (int i = t; i < NQ * D; i += NTHREADS) {
         const int n = q0 + i / D;
         if (n < N) out[b * q_sb + n * q_sn + h * q_sh + (i % D)] = __float2bfloat16(0.f);
       }
@@ -198,9 +260,14 @@ __global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
   const int n_tiles = (c1 - c0 + TILE - 1) / TILE;
   const int n_clean = max(0, min(P, c1) - c0) / TILE;     // tiles entirely inside the prefix and the chunk
   const int last_row = len - 1;
+  const bool is_tail = wave == TAIL;
 
-  if (APPEND && wave >= n_clean)   // the speculative first tile reaches the tree: fetch it from the right sources
-    issue_tile_loads<D, NT, true, false>(src, c0 + wave * TILE, P, last_row, r16, lane, Kn, Vn);
+  // tiles of this wavefront: first, stride, count
+  const int ti_first = is_tail ? n_clean : wave;
+  const int ti_stride = is_tail ? 1 : SWAVES;
+  const int ti_end = is_tail ? n_tiles : n_clean;
+  if (is_tail && ti_first < ti_end)   // the tail wavefront's first tile (needs prefix_len: rows >= P have other sources)
+    issue_tile_loads<D, NT, APPEND, false>(src, c0 + ti_first * TILE, P, last_row, r16, lane, KA, VA);
 
   f32x4 O[NT][DB];
   float m_run[NT], l_run[NT];
@@ -213,48 +280,94 @@ __global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
 #pragma unroll
     for (int db = 0; db < DB; ++db) O[nt][db] = (f32x4){0.f, 0.f, 0.f, 0.f};
   }
+
+  // ---- tail wavefront: validate the tree and build the ancestor-or-self masks (LDS, this wavefront only)
+  bool bad_tree = false;
+  if (is_tail) {
+    if (lane == 0) s_bad_tree = 0;
+    if (touches_tree) {
+      if (lane < N) { s_parent[lane] = par0; s_depth[lane] = dep0; }
+      if (lane + 64 < N) { s_parent[lane + 64] = par1; s_depth[lane + 64] = dep1; }
+      wave_lds_sync();
+      bool ok = true;
+      if (lane < N) {
+        ok = (lane == 0) ? (par0 == -1 && dep0 == 0) : (par0 >= 0 && par0 < lane);
+        if (ok && lane > 0) ok = dep0 == s_depth[par0] + 1;
+      }
+      if (lane + 64 < N) {
+        bool ok1 = par1 >= 0 && par1 < lane + 64;
+        if (ok1) ok1 = dep1 == s_depth[par1] + 1;
+        ok = ok && ok1;
+      }
+      bad_tree = __any(!ok);
+      if (!bad_tree) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const int node = lane + 64 * half;
+          if (node < N) {
+            unsigned long long lo = 0, hi = 0;
+            int u = node;
+            for (int step = 0; step < N && u >= 0; ++step) {
+              if (u < 64) lo |= 1ull << u; else hi |= 1ull << (u - 64);
+              u = s_parent[u];
+            }
+            s_anc[node][0] = lo;
+            s_anc[node][1] = hi;
+          }
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          const int n = q0 + nt * 16 + r16;
+          if (n < N) { anc_lo[nt] = s_anc[n][0]; anc_hi[nt] = s_anc[n][1]; }
+        }
+      } else if (lane == 0) {
+        s_bad_tree = 1;
+      }
+    }
+  }
   unsigned char* vst = lds + wave * T::VTILE_BYTES;
 
-  // One tile: consume the loads issued one step earlier, issue the next tile's, S^T, softmax, O^T.
-  auto tile_step = [&](const int ti, auto masked_tag) {
+  // One tile: consume the buffer filled by earlier loads, refill it for the next step, S^T, softmax, O^T.
+  auto tile_step = [&](const int ti, const int ti_refill, auto masked_tag) {
     constexpr bool MASKED = decltype(masked_tag)::value;
     const int k0 = c0 + ti * TILE;
-    bf16x8 Kc[2][KS];
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) Kc[hf][ks] = __builtin_bit_cast(bf16x8, Kn[hf][ks]);
     if (MASKED) {
       // rows at and beyond the end of the chunk hold stale data: their V must not reach the product
 #pragma unroll
       for (int j = 0; j < NVL; ++j)
-        if (k0 + j * RPI + lane / LPR >= c1) Vn[j] = (u32x4){0u, 0u, 0u, 0u};
+        if (k0 + j * RPI + lane / LPR >= c1) VA[j] = (u32x4){0u, 0u, 0u, 0u};
       if (APPEND && qg == 0) {   // this tile carries tree rows taken from k_new / v_new: put them in the cache
+#pragma unroll
+        for (int j = 0; j < NVL; ++j) {
+          const int row = k0 + j * RPI + lane / LPR;
+          if (row >= P && row < c1)
+            store_cache_row((unsigned char*)(v_cache + b * kv_sb + h * kv_sh) + (unsigned)row * src.cache_row_bytes +
+                                (lane % LPR) * 16, VA[j]);
+        }
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf) {
           const int row = k0 + hf * 16 + r16;
           if (row >= P && row < c1) {
             unsigned char* dst = (unsigned char*)(k_cache + b * kv_sb + h * kv_sh) + (unsigned)row * src.cache_row_bytes + g * 16;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) *(u32x4*)(dst + ks * 64) = Kn[hf][ks];
+            for (int ks = 0; ks < KS; ++ks) store_cache_row(dst + ks * 64, KA[hf][ks]);
           }
-        }
-#pragma unroll
-        for (int j = 0; j < NVL; ++j) {
-          const int row = k0 + j * RPI + lane / LPR;
-          if (row >= P && row < c1)
-            *(u32x4*)((unsigned char*)(v_cache + b * kv_sb + h * kv_sh) + (unsigned)row * src.cache_row_bytes +
-                      (lane % LPR) * 16) = Vn[j];
         }
       }
     }
 #pragma unroll
-    for (int j = 0; j < NVL; ++j) *(u32x4*)(vst + (j * RPI + lane / LPR) * VROW + (lane % LPR) * 16) = Vn[j];
-    {
-      const int kn0 = k0 + WAVES * TILE;   // next tile of this wavefront (harmless if past the chunk)
-      if (kn0 + TILE <= P) issue_tile_loads<D, NT, APPEND, true>(src, kn0, P, last_row, r16, lane, Kn, Vn);
-      else issue_tile_loads<D, NT, APPEND, false>(src, kn0, P, last_row, r16, lane, Kn, Vn);
-    }
+    for (int j = 0; j < NVL; ++j) *(u32x4*)(vst + (j * RPI + lane / LPR) * VROW + (lane % LPR) * 16) = VA[j];
+    // Refill: V's registers are free once staged. K's are free after the S^T products; with one query
+    // tile there is room to copy K aside and request the next K at once, with two there is not.
+    const int kn0 = c0 + ti_refill * TILE;
+    if (ti_refill >= 0) issue_v_loads<D, NT, APPEND, !MASKED>(src, kn0, P, last_row, lane, VA);
+    bf16x8 Kc[2][KS];
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) Kc[hf][ks] = __builtin_bit_cast(bf16x8, KA[hf][ks]);
+    if (NT == 1 && ti_refill >= 0) issue_k_loads<D, NT, APPEND, !MASKED>(src, kn0, P, last_row, r16, KA);
 
     // ---- S^T = K Q^T : sc[nt][hf][v] = score of query nt*16+r16 and key k0 + hf*16 + 4g + v
     f32x4 sc[NT][2];
@@ -268,6 +381,11 @@ __global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Kc[hf][ks], qB[nt][ks], acc, 0, 0, 0);
         sc[nt][hf] = acc;
       }
+    if (NT != 1 && ti_refill >= 0) {
+      // the products above must have read K before the loads below overwrite it
+      asm volatile("" : "+v"(sc[0][0]), "+v"(sc[NT - 1][1]));
+      issue_k_loads<D, NT, APPEND, !MASKED>(src, kn0, P, last_row, r16, KA);
+    }
 
     bf16x8 pB[NT];
 #pragma unroll
@@ -332,56 +450,18 @@ __global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
     __builtin_amdgcn_wave_barrier();
   };
 
-  // ---- phase A: tiles inside the prefix need no mask and no tree
-  int ti = wave;
-  for (; ti < n_clean; ti += WAVES) tile_step(ti, std::false_type{});
-
-  // ---- tree set-up (only workgroups whose chunk reaches the tree), then phase B: the remaining tiles
-  if (touches_tree) {
-    if (t == 0) s_flag = 0;
-    if (t < N) {
-      s_parent[t] = my_parent;
-      s_depth[t] = my_depth;
-    }
-    __syncthreads();
-    if (t < N) {
-      bool ok = (t == 0) ? (my_parent == -1 && my_depth == 0) : (my_parent >= 0 && my_parent < t);
-      if (ok && t > 0) ok = my_depth == s_depth[my_parent] + 1;
-      if (!ok) atomicOr(&s_flag, 1);
-    }
-    __syncthreads();
-    if (s_flag != 0) {
-      if (n_splits == 1) {
-        for (int i = t; i < NQ * D; i += 256) {
-          const int n = q0 + i / D;
-          if (n < N) out[b * q_sb + n * q_sn + h * q_sh + (i % D)] = __float2bfloat16(0.f);
-        }
-        if (h == 0 && qg == 0 && t == 0) set_status(status, b, SPEC_ST_BAD_TREE);
-      }
-      return;
-    }
-    if (t < N) {
-      unsigned long long lo = 0, hi = 0;
-      int u = t;
-      for (int step = 0; step < N && u >= 0; ++step) {
-        if (u < 64) lo |= 1ull << u; else hi |= 1ull << (u - 64);
-        u = s_parent[u];
-      }
-      s_anc[t][0] = lo;
-      s_anc[t][1] = hi;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const int n = q0 + nt * 16 + r16;
-      if (n < N) { anc_lo[nt] = s_anc[n][0]; anc_hi[nt] = s_anc[n][1]; }
-    }
+  if (is_tail) {
+    if (!bad_tree)
+      for (int ti = ti_first; ti < ti_end; ++ti) tile_step(ti, ti + 1 < ti_end ? ti + 1 : -1, std::true_type{});
+  } else {
+    for (int ti = ti_first; ti < ti_end; ti += SWAVES)
+      tile_step(ti, ti + SWAVES < ti_end ? ti + SWAVES : -1, std::false_type{});
   }
-  for (; ti < n_tiles; ti += WAVES) tile_step(ti, std::true_type{});
+  SPEC_TS(5)
 
-  // ---- merge the four wavefronts through LDS: layout [wave][n][MROW] floats (O row, m, l)
-  __syncthreads();
-  float* mg = (float*)lds;
+  // ---- merge the five wavefronts through LDS: layout [wave][n][MROW] floats (O row, m, l)
+  if (!T::MERGE_SEPARATE) __syncthreads();   // the merge area overlays the staging tiles still being read
+  float* mg = (float*)(lds + T::MERGE_OFF);
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     const float l_tot = wave_sum_over_lane_groups(l_run[nt]);
@@ -394,8 +474,19 @@ __global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
     }
   }
   __syncthreads();
+  SPEC_TS(6)
+  if (s_bad_tree != 0) {   // malformed tree: defined result = zeros (written here when this workgroup owns the output)
+    if (n_splits == 1) {
+      for (int i = t; i < NQ * D; i += NTHREADS) {
+        const int n = q0 + i / D;
+        if (n < N) out[b * q_sb + n * q_sn + h * q_sh + (i % D)] = __float2bfloat16(0.f);
+      }
+      if (h == 0 && qg == 0 && t == 0) set_status(status, b, SPEC_ST_BAD_TREE);
+    }
+    return;
+  }
   constexpr int CG = D / 4;
-  for (int idx = t; idx < NQ * CG; idx += 256) {
+  for (int idx = t; idx < NQ * CG; idx += NTHREADS) {
     const int nl = idx / CG, cg = idx % CG;
     const int n = q0 + nl;
     if (n >= N) continue;
@@ -427,6 +518,7 @@ __global__ void __launch_bounds__(256, 2) tree_attention_bf16_kernel(
       }
     }
   }
+  SPEC_TS(7)
 }
 
 hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan& plan, const void* q, void* k_cache,
@@ -441,17 +533,18 @@ hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan&
   const int n_qgroups = (d.N + nq - 1) / nq;
   const bool append = k_new != nullptr;
   dim3 grid(plan.n_splits, d.H * n_qgroups, d.B);
-#define SPEC_LAUNCH(DD, NTT, APP)                                                                                     \
-  hipLaunchKernelGGL((tree_attention_bf16_kernel<DD, NTT, APP>), grid, dim3(256), 0, s, (const __hip_bfloat16*)q,     \
+#define SPEC_LAUNCH(DD, NTT, APP)                                                                                \
+  hipLaunchKernelGGL((tree_attention_bf16_kernel<DD, NTT, APP>), grid, dim3(WAVES * 64), 0, s,                   \
+                     (const __hip_bfloat16*)q,                                                                        \
                      (__hip_bfloat16*)k_cache, (__hip_bfloat16*)v_cache, (const __hip_bfloat16*)k_new,                \
                      (const __hip_bfloat16*)v_new, parent, depth, prefix_len, (__hip_bfloat16*)out, ws_o, ws_ml,      \
                      status, d.N, d.H, d.S_cap, n_qgroups, plan.chunk_keys, plan.n_splits, (long)d.q_stride_b,        \
                      (long)d.q_stride_n, (long)d.q_stride_h, (long)d.kv_stride_b, (long)d.kv_stride_h,                \
                      (long)d.kv_stride_s, scale)
-#define SPEC_DISPATCH(APP)                          \
-  if (d.D == 128 && nt == 1) SPEC_LAUNCH(128, 1, APP); \
-  else if (d.D == 128) SPEC_LAUNCH(128, 2, APP);       \
-  else if (nt == 1) SPEC_LAUNCH(64, 1, APP);           \
+#define SPEC_DISPATCH(APP)                             \
+  if (d.D == 128 && nt == 1) SPEC_LAUNCH(128, 1, APP);    \
+  else if (d.D == 128) SPEC_LAUNCH(128, 2, APP);          \
+  else if (nt == 1) SPEC_LAUNCH(64, 1, APP);              \
   else SPEC_LAUNCH(64, 2, APP)
   if (append) { SPEC_DISPATCH(true); } else { SPEC_DISPATCH(false); }
 #undef SPEC_DISPATCH
