@@ -22,6 +22,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
+# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy of
+# known size (profiles/tree_attention_bf16_config2_hbm_traffic.txt); only for the workload profiled.
+MEASURED_TRAFFIC_BYTES = {2: int((67172.4 * 2.000 + 3144.9) * 1024)}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -33,6 +37,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-only", action="store_true", help="time only the attention launches (profiling aid)")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run three plain 256 MiB device copies, the known-size reference for rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE readings")
     return ap.parse_args()
 
 
@@ -184,11 +191,18 @@ def main():
                    "layer_tree_tokens_per_s": B * N / (attn_us * 1e-6) if args.attn_only else None,
                    "attention_us_per_layer": attn_us, "layer_algorithmic_bytes": layer_bytes},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.cfg) if L == cfg.layers else None,
                      "kernel": "tree_attention_bf16_kernel (KV append fused; + attn_combine_kernel when the key range is split)", "bytes_per_launch": attn_bytes,
                      "us_per_launch": attn_us},
     }
 
+    if args.pmc_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, vcfg, W["host"], gi, si, L)
     print(json.dumps(result))

@@ -25,7 +25,47 @@ __device__ inline float load_logit(const void* base, long idx) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// block-wide reductions (blockDim.x multiple of 64, <= 1024); `scratch` holds >= 16 + 1 entries
+// Vocabulary sweeps. A row of V values is visited in groups of VEC consecutive elements (VEC = 4 when
+// V is a multiple of 4, so that every group is one aligned 16-byte (float) or 8-byte (bf16) access;
+// else 1). A block of NT threads takes U groups per thread at a time, all loads issued before any is
+// used: with V = 32000, NT = 1024, U = 8 a whole row is one round trip to memory.
+// ---------------------------------------------------------------------------------------------
+constexpr int SWEEP_U = 8;
+
+template <int VEC, bool BF16>
+__device__ __forceinline__ void load_logit_group(const void* base, long elem, float (&v)[VEC]) {
+  if (VEC == 4) {
+    if (BF16) {
+      const uint2 raw = *(const uint2*)((const __hip_bfloat16*)base + elem);
+      v[0] = __uint_as_float(raw.x << 16);
+      v[1] = __uint_as_float(raw.x & 0xffff0000u);
+      v[2] = __uint_as_float(raw.y << 16);
+      v[3] = __uint_as_float(raw.y & 0xffff0000u);
+    } else {
+      const float4 raw = *(const float4*)((const float*)base + elem);
+      v[0] = raw.x; v[1] = raw.y; v[2] = raw.z; v[3] = raw.w;
+    }
+  } else {
+    v[0] = load_logit<BF16>(base, elem);
+  }
+}
+template <int VEC>
+__device__ __forceinline__ void load_f32_group(const float* p, float (&v)[VEC]) {
+  if (VEC == 4) {
+    const float4 raw = *(const float4*)p;
+    v[0] = raw.x; v[1] = raw.y; v[2] = raw.z; v[3] = raw.w;
+  } else {
+    v[0] = *p;
+  }
+}
+template <int VEC>
+__device__ __forceinline__ void store_f32_group(float* p, const float (&v)[VEC]) {
+  if (VEC == 4) *(float4*)p = make_float4(v[0], v[1], v[2], v[3]);
+  else *p = v[0];
+}
+
+// ---------------------------------------------------------------------------------------------
+// block-wide reductions (blockDim.x multiple of 64, <= 1024); `scratch` holds >= 16 entries
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __device__ inline T block_sum(T v, T* scratch) {
@@ -40,38 +80,56 @@ __device__ inline T block_sum(T v, T* scratch) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// per-node statistics
+// per-node statistics: one block of 1024 threads per (request, node) row, one pass over the row.
+// Each thread keeps (max, lowest index of the max, sum of exp((x - max) / T)) of its elements; the
+// block combines the triples.
 // ---------------------------------------------------------------------------------------------
-template <bool BF16>
-__global__ void __launch_bounds__(256) node_stats_kernel(const void* __restrict__ logits, int V, float inv_temp,
-                                                         int32_t* __restrict__ node_argmax,
-                                                         float* __restrict__ node_max,
-                                                         float* __restrict__ node_sumexp) {
-  __shared__ float s_val[4];
-  __shared__ int s_idx[4];
-  __shared__ float s_sum[17];
+constexpr int NS_THREADS = 1024;
+
+template <bool BF16, int VEC>
+__global__ void __launch_bounds__(NS_THREADS) node_stats_kernel(const void* __restrict__ logits, int V, float inv_temp,
+                                                                int32_t* __restrict__ node_argmax,
+                                                                float* __restrict__ node_max,
+                                                                float* __restrict__ node_sumexp) {
+  __shared__ float s_val[NS_THREADS / 64];
+  __shared__ int s_idx[NS_THREADS / 64];
+  __shared__ float s_sum[NS_THREADS / 64];
   const long row = blockIdx.x;
   const int t = threadIdx.x;
   const long base = row * V;
-  float best = -INFINITY;
+  const int n_groups = V / VEC;
+  const bool want_sum = node_sumexp != nullptr;
+  float best = -INFINITY, sum = 0.f;
   int best_i = 0x7fffffff;
-  const bool vec = !BF16 && (V % 4 == 0);
-  if (vec) {
-    const float4* p = (const float4*)((const float*)logits + base);
-    for (int i = t; i < V / 4; i += 256) {
-      const float4 x = p[i];
-      if (x.x > best) { best = x.x; best_i = 4 * i; }
-      if (x.y > best) { best = x.y; best_i = 4 * i + 1; }
-      if (x.z > best) { best = x.z; best_i = 4 * i + 2; }
-      if (x.w > best) { best = x.w; best_i = 4 * i + 3; }
+  for (int g0 = 0; g0 < n_groups; g0 += NS_THREADS * SWEEP_U) {
+    float x[SWEEP_U][VEC];
+#pragma unroll
+    for (int j = 0; j < SWEEP_U; ++j) {
+      const int gi = g0 + j * NS_THREADS + t;
+      if (gi < n_groups) {
+        load_logit_group<VEC, BF16>(logits, base + (long)gi * VEC, x[j]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) x[j][e] = -INFINITY;
+      }
     }
-  } else {
-    for (int i = t; i < V; i += 256) {
-      const float x = load_logit<BF16>(logits, base + i);
-      if (x > best) { best = x; best_i = i; }
+    float m = best;
+#pragma unroll
+    for (int j = 0; j < SWEEP_U; ++j)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        if (x[j][e] > m) { m = x[j][e]; best_i = (g0 + j * NS_THREADS + t) * VEC + e; }   // ascending index: lowest wins ties
+    if (want_sum && m > -INFINITY) {
+      sum *= expf((best - m) * inv_temp);     // best = -inf gives 0
+#pragma unroll
+      for (int j = 0; j < SWEEP_U; ++j)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) sum += expf((x[j][e] - m) * inv_temp);   // padding: exp(-inf) = 0
     }
+    best = m;
   }
-  // reduce (value desc, index asc)
+  // combine (value desc, index asc); sums are rescaled to the common maximum
+  const float my_best = best;
   for (int o = 32; o > 0; o >>= 1) {
     const float ov = __shfl_xor(best, o);
     const int oi = __shfl_xor(best_i, o);
@@ -80,27 +138,17 @@ __global__ void __launch_bounds__(256) node_stats_kernel(const void* __restrict_
   if ((t & 63) == 0) { s_val[t >> 6] = best; s_idx[t >> 6] = best_i; }
   __syncthreads();
   best = s_val[0]; best_i = s_idx[0];
-  for (int w = 1; w < 4; ++w)
+  for (int w = 1; w < NS_THREADS / 64; ++w)
     if (s_val[w] > best || (s_val[w] == best && s_idx[w] < best_i)) { best = s_val[w]; best_i = s_idx[w]; }
   if (best_i == 0x7fffffff) best_i = 0;   // all -inf / NaN row
-  float sum = 0.f;
-  if (node_sumexp != nullptr) {
-    if (vec) {
-      const float4* p = (const float4*)((const float*)logits + base);
-      for (int i = t; i < V / 4; i += 256) {
-        const float4 x = p[i];
-        sum += expf((x.x - best) * inv_temp) + expf((x.y - best) * inv_temp) + expf((x.z - best) * inv_temp) +
-               expf((x.w - best) * inv_temp);
-      }
-    } else {
-      for (int i = t; i < V; i += 256) sum += expf((load_logit<BF16>(logits, base + i) - best) * inv_temp);
-    }
+  if (want_sum) {
+    if (my_best > -INFINITY) sum *= expf((my_best - best) * inv_temp); else sum = 0.f;
     sum = block_sum(sum, s_sum);
   }
   if (t == 0) {
     if (node_argmax != nullptr) node_argmax[row] = best_i;
     if (node_max != nullptr) node_max[row] = best;
-    if (node_sumexp != nullptr) node_sumexp[row] = sum;
+    if (want_sum) node_sumexp[row] = sum;
   }
 }
 
@@ -156,20 +204,18 @@ __global__ void __launch_bounds__(128) greedy_walk_kernel(int N, const int32_t* 
 // ---------------------------------------------------------------------------------------------
 constexpr int SW_THREADS = 1024;
 
-template <bool BF16>
+template <bool BF16, int VEC>
 __global__ void __launch_bounds__(SW_THREADS) stochastic_walk_kernel(
     int N, int V, const void* __restrict__ logits, const float* __restrict__ probs_ssm, int R,
     const int32_t* __restrict__ ssm_row, const int32_t* __restrict__ token, const int32_t* __restrict__ parent,
     const float* __restrict__ u_accept, const float* __restrict__ u_order, const float* __restrict__ u_final,
-    float inv_temp, const float* __restrict__ node_max, const float* __restrict__ node_sumexp,
-    float* __restrict__ resid_all, int Lmax, int32_t* __restrict__ path, int32_t* __restrict__ len,
-    int32_t* __restrict__ out_tokens, int32_t* status) {
+    float inv_temp, const float* __restrict__ node_max, const float* __restrict__ node_sumexp, float* resid_all, int Lmax,
+    int32_t* __restrict__ path, int32_t* __restrict__ len, int32_t* __restrict__ out_tokens, int32_t* status) {
   __shared__ int s_flag;
   __shared__ int s_child[SPEC_MAX_TREE_NODES];
   __shared__ int s_sorted[SPEC_MAX_TREE_NODES];
   __shared__ int s_nchild;
-  __shared__ float s_fsum[17];
-  __shared__ double s_dsum[17];
+  __shared__ float s_fsum[SW_THREADS / 64];
   __shared__ double s_scan[SW_THREADS / 64];
   __shared__ int s_pick;
 
@@ -180,6 +226,7 @@ __global__ void __launch_bounds__(SW_THREADS) stochastic_walk_kernel(
   int cur = 0;   // resid == (cur ? resid1 : resid0)
   const int32_t* par = parent + (long)b * N;
   const int32_t* tok = token + (long)b * N;
+  const int n_groups = V / VEC;
 
   bool valid = tree_is_valid(par, nullptr, N, &s_flag);
   __syncthreads();
@@ -228,13 +275,14 @@ __global__ void __launch_bounds__(SW_THREADS) stochastic_walk_kernel(
     __syncthreads();
     bool accepted = false;
     int next_u = -1;
+    const long lrow = ((long)b * N + u) * V;
     for (int j = 0; j < nchild; ++j) {
       const int s = s_sorted[j];
       const int x = tok[s];
       const float* Q = probs_ssm + (long)ssm_row[(long)b * N + s] * V;
       const float r = u_accept[(long)b * N + s];
       float px;
-      if (implicit) px = expf((load_logit<BF16>(logits, ((long)b * N + u) * V + x) - mx) * inv_temp) / se;
+      if (implicit) px = expf((load_logit<BF16>(logits, lrow + x) - mx) * inv_temp) / se;
       else px = resid[x] / Z;
       if (r * Q[x] <= px) {
         accepted = true;
@@ -250,13 +298,31 @@ __global__ void __launch_bounds__(SW_THREADS) stochastic_walk_kernel(
       float* dst = cur ? resid0 : resid1;
       float part = 0.f;
       const float invZ = 1.f / Z, inv_se = 1.f / se;
-      for (int i = t; i < V; i += SW_THREADS) {
-        float p;
-        if (implicit) p = expf((load_logit<BF16>(logits, ((long)b * N + u) * V + i) - mx) * inv_temp) * inv_se;
-        else p = resid[i] * invZ;
-        const float d = fmaxf(0.f, p - Q[i]);
-        part += d;
-        dst[i] = d;
+      for (int g0 = 0; g0 < n_groups; g0 += SW_THREADS * SWEEP_U) {
+        float pv[SWEEP_U][VEC], qv[SWEEP_U][VEC];
+#pragma unroll
+        for (int jj = 0; jj < SWEEP_U; ++jj) {
+          const int gi = g0 + jj * SW_THREADS + t;
+          if (gi < n_groups) {
+            if (implicit) load_logit_group<VEC, BF16>(logits, lrow + (long)gi * VEC, pv[jj]);
+            else load_f32_group<VEC>(resid + (long)gi * VEC, pv[jj]);
+            load_f32_group<VEC>(Q + (long)gi * VEC, qv[jj]);
+          }
+        }
+#pragma unroll
+        for (int jj = 0; jj < SWEEP_U; ++jj) {
+          const int gi = g0 + jj * SW_THREADS + t;
+          if (gi < n_groups) {
+            float d[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+              const float p = implicit ? expf((pv[jj][e] - mx) * inv_temp) * inv_se : pv[jj][e] * invZ;
+              d[e] = fmaxf(0.f, p - qv[jj][e]);
+              part += d[e];
+            }
+            store_f32_group<VEC>(dst + (long)gi * VEC, d);
+          }
+        }
       }
       const float Znew = block_sum(part, s_fsum);
       if (Znew > 0.f) {
@@ -280,13 +346,27 @@ __global__ void __launch_bounds__(SW_THREADS) stochastic_walk_kernel(
     __syncthreads();
   }
 
-  // final token: inverse CDF in ascending token id, float64 running sum over contiguous per-thread chunks
-  const int chunk = (V + SW_THREADS - 1) / SW_THREADS;
-  const int i0 = min(t * chunk, V), i1 = min(i0 + chunk, V);
+  // final token: inverse CDF in ascending token id. Every thread owns a contiguous range of the
+  // vocabulary and sums its weights in float64; a block scan finds the thread whose range holds the
+  // target, which then walks its range in order.
+  const long lrow = ((long)b * N + u) * V;
+  const int per_thread = ((V + SW_THREADS - 1) / SW_THREADS + VEC - 1) / VEC;    // groups per thread
+  const int g_lo = min(t * per_thread, n_groups), g_hi = min(g_lo + per_thread, n_groups);
   double mine = 0.0;
-  for (int i = i0; i < i1; ++i) {
-    const float w = implicit ? expf((load_logit<BF16>(logits, ((long)b * N + u) * V + i) - mx) * inv_temp) : resid[i];
-    mine += (double)w;
+  for (int g0 = g_lo; g0 < g_hi; g0 += SWEEP_U) {
+    float w[SWEEP_U][VEC];
+#pragma unroll
+    for (int jj = 0; jj < SWEEP_U; ++jj)
+      if (g0 + jj < g_hi) {
+        if (implicit) load_logit_group<VEC, BF16>(logits, lrow + (long)(g0 + jj) * VEC, w[jj]);
+        else load_f32_group<VEC>(resid + (long)(g0 + jj) * VEC, w[jj]);
+      }
+#pragma unroll
+    for (int jj = 0; jj < SWEEP_U; ++jj)
+      if (g0 + jj < g_hi) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) mine += (double)(implicit ? expf((w[jj][e] - mx) * inv_temp) : w[jj][e]);
+      }
   }
   // inclusive scan over threads: wave-level shuffles, then wave totals
   double incl = mine;
@@ -307,7 +387,7 @@ __global__ void __launch_bounds__(SW_THREADS) stochastic_walk_kernel(
   const double excl = incl - mine;
   const double target = (double)u_final[b] * total;
   // the first thread whose inclusive sum exceeds the target holds the answer
-  if (incl > target && excl <= target && i1 > i0) atomicMin(&s_pick, t);
+  if (incl > target && excl <= target && g_hi > g_lo) atomicMin(&s_pick, t);
   __syncthreads();
   const int pick = s_pick;
   if (pick == 0x7fffffff) {
@@ -316,9 +396,9 @@ __global__ void __launch_bounds__(SW_THREADS) stochastic_walk_kernel(
   }
   if (t == pick) {
     double run = excl;
-    int ans = i1 - 1;
-    for (int i = i0; i < i1; ++i) {
-      const float w = implicit ? expf((load_logit<BF16>(logits, ((long)b * N + u) * V + i) - mx) * inv_temp) : resid[i];
+    int ans = g_hi * VEC - 1;
+    for (int i = g_lo * VEC; i < g_hi * VEC; ++i) {
+      const float w = implicit ? expf((load_logit<BF16>(logits, lrow + i) - mx) * inv_temp) : resid[i];
       run += (double)w;
       if (run > target) { ans = i; break; }
     }
@@ -330,12 +410,15 @@ __global__ void __launch_bounds__(SW_THREADS) stochastic_walk_kernel(
 // ---------------------------------------------------------------------------------------------
 hipError_t launch_node_stats(int B, int N, int V, int logits_dtype, const void* logits, float inv_temp,
                              int32_t* node_argmax, float* node_max, float* node_sumexp, hipStream_t s) {
-  if (logits_dtype == SPEC_BF16)
-    hipLaunchKernelGGL(node_stats_kernel<true>, dim3(B * N), dim3(256), 0, s, logits, V, inv_temp, node_argmax, node_max,
-                       node_sumexp);
-  else
-    hipLaunchKernelGGL(node_stats_kernel<false>, dim3(B * N), dim3(256), 0, s, logits, V, inv_temp, node_argmax,
-                       node_max, node_sumexp);
+  const bool bf16 = logits_dtype == SPEC_BF16, vec = (V % 4 == 0);
+#define SPEC_NS(BF, VE)                                                                                           \
+  hipLaunchKernelGGL((node_stats_kernel<BF, VE>), dim3(B * N), dim3(NS_THREADS), 0, s, logits, V, inv_temp, node_argmax, \
+                     node_max, node_sumexp)
+  if (bf16 && vec) SPEC_NS(true, 4);
+  else if (bf16) SPEC_NS(true, 1);
+  else if (vec) SPEC_NS(false, 4);
+  else SPEC_NS(false, 1);
+#undef SPEC_NS
   return hipGetLastError();
 }
 
@@ -352,14 +435,16 @@ hipError_t launch_stochastic_walk(int B, int N, int V, int logits_dtype, const v
                                   const float* u_accept, const float* u_order, const float* u_final, float inv_temp,
                                   const float* node_max, const float* node_sumexp, float* resid, int Lmax,
                                   int32_t* path, int32_t* len, int32_t* out_tokens, int32_t* status, hipStream_t s) {
-  if (logits_dtype == SPEC_BF16)
-    hipLaunchKernelGGL(stochastic_walk_kernel<true>, dim3(B), dim3(SW_THREADS), 0, s, N, V, logits, probs_ssm, R, ssm_row,
-                       token, parent, u_accept, u_order, u_final, inv_temp, node_max, node_sumexp, resid, Lmax, path,
-                       len, out_tokens, status);
-  else
-    hipLaunchKernelGGL(stochastic_walk_kernel<false>, dim3(B), dim3(SW_THREADS), 0, s, N, V, logits, probs_ssm, R,
-                       ssm_row, token, parent, u_accept, u_order, u_final, inv_temp, node_max, node_sumexp, resid, Lmax,
-                       path, len, out_tokens, status);
+  const bool bf16 = logits_dtype == SPEC_BF16, vec = (V % 4 == 0);
+#define SPEC_SW(BF, VE)                                                                                              \
+  hipLaunchKernelGGL((stochastic_walk_kernel<BF, VE>), dim3(B), dim3(SW_THREADS), 0, s, N, V, logits, probs_ssm, R,    \
+                     ssm_row, token, parent, u_accept, u_order, u_final, inv_temp, node_max, node_sumexp, resid, Lmax, \
+                     path, len, out_tokens, status)
+  if (bf16 && vec) SPEC_SW(true, 4);
+  else if (bf16) SPEC_SW(true, 1);
+  else if (vec) SPEC_SW(false, 4);
+  else SPEC_SW(false, 1);
+#undef SPEC_SW
   return hipGetLastError();
 }
 
