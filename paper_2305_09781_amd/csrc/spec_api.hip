@@ -49,7 +49,7 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d) {
     // gives every compute unit a workgroup: a workgroup's fixed cost (first loads, tree set-up, final
     // merge, and the extra combine launch) outweighs any gain from more parallel slack. Only batches
     // with few (request, head) pairs are split, into chunks of at least 512 keys.
-    const int nq = d.dtype == SPEC_BF16 ? (d.N <= 16 ? 16 : 32) : SPEC_MAX_TREE_NODES;
+    const int nq = attn_queries_per_workgroup(d);
     const long groups = (long)d.B * d.H * ((d.N + nq - 1) / nq);
     long splits = 1;
     if (groups < 256) {

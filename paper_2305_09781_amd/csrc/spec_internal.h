@@ -22,6 +22,13 @@ struct AttnPlan {
 
 AttnPlan make_attn_plan(const spec_attn_desc_t& d);
 
+// Tree queries handled by one workgroup of the attention kernel chosen for this shape
+// (bf16: 16 / 32 in the few-query kernel, 64 / 128 in the wide-tree kernel; float32: all of them).
+inline int attn_queries_per_workgroup(const spec_attn_desc_t& d) {
+  if (d.dtype != SPEC_BF16) return SPEC_MAX_TREE_NODES;
+  return d.N <= 16 ? 16 : d.N <= 32 ? 32 : d.N <= 64 ? 64 : 128;
+}
+
 // Kernel launchers (defined in the .hip files). All return hipError_t of the launch.
 hipError_t launch_kv_append(const spec_attn_desc_t& d, const void* k_new, const void* v_new, void* k_cache,
                             void* v_cache, const int32_t* prefix_len, int32_t* status, hipStream_t s);
@@ -37,6 +44,11 @@ hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan&
                                       void* v_cache, const void* k_new, const void* v_new, const int32_t* parent,
                                       const int32_t* depth, const int32_t* prefix_len, void* out, void* ws,
                                       int32_t* status, hipStream_t s);
+// Wide trees (N > 32): the workgroup's wavefronts split the queries and share the K/V stream through LDS.
+hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const AttnPlan& plan, const void* q, void* k_cache,
+                                           void* v_cache, const void* k_new, const void* v_new, const int32_t* parent,
+                                           const int32_t* depth, const int32_t* prefix_len, void* out, void* ws,
+                                           int32_t* status, hipStream_t s);
 hipError_t launch_attn_combine(const spec_attn_desc_t& d, const AttnPlan& plan, const int32_t* parent,
                                const int32_t* depth, const int32_t* prefix_len, const void* ws, void* out,
                                int32_t* status, hipStream_t s);
