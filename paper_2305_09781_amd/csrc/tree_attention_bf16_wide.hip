@@ -384,8 +384,8 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_wide_kernel
     if (ti + 1 < n_tiles) step(ti + 1, Kr2, Vr2);
   }
   lds_barrier();
-
   WTS_L(4, true)
+
   // ---- every wavefront owns its queries: normalise and write (or emit the split partial)
 #pragma unroll
   for (int nt = 0; nt < NTW; ++nt) {
