@@ -1,6 +1,7 @@
 // C ABI of libspectree: host-side argument checks and kernel launches. Every entry point validates
 // what the host can see, enqueues its kernels on the caller's stream and returns; nothing here
 // allocates or synchronises.
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -39,31 +40,70 @@ static int check_desc(const spec_attn_desc_t* d) {
   return SPEC_OK;
 }
 
+// Compute units of the current device (256 when no device can be queried, e.g. sizing a workspace on a
+// machine without a GPU).
+static int compute_units() {
+  static int cached = 0;
+  if (cached == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cached = n;
+    else
+      cached = 256;
+  }
+  return cached;
+}
+
 AttnPlan make_attn_plan(const spec_attn_desc_t& d) {
   AttnPlan p;
+  p.balanced_wgs = 0;
+  p.balanced_tile = 0;
   const int max_prefix = d.max_prefix_len > 0 ? d.max_prefix_len : d.S_cap - d.N;
   const int max_len = max_prefix + d.N;
+  const int nq = attn_queries_per_workgroup(d);
+  const long groups = (long)d.B * d.H * ((d.N + nq - 1) / nq);
   int chunk = env_int("SPEC_TREE_CHUNK_KEYS", 0);
-  if (chunk <= 0) {
-    // One workgroup per (request, head, query group) streams its whole key range when that already
-    // gives every compute unit a workgroup: a workgroup's fixed cost (first loads, tree set-up, final
-    // merge, and the extra combine launch) outweighs any gain from more parallel slack. Only batches
-    // with few (request, head) pairs are split, into chunks of at least 512 keys.
-    const int nq = attn_queries_per_workgroup(d);
-    const long groups = (long)d.B * d.H * ((d.N + nq - 1) / nq);
-    long splits = 1;
-    if (groups < 256) {
-      splits = (768 + groups - 1) / groups;
-      const long max_splits = max_len / 512 > 0 ? max_len / 512 : 1;
-      if (splits > max_splits) splits = max_splits;
+  if (chunk <= 0 && d.dtype == SPEC_BF16) {
+    // Few (request, head) pairs with long key ranges (long-context serving, ragged lengths): the bf16
+    // kernels deal the key tiles of all pairs to as many workgroups as the device holds at once, in
+    // equal shares, so the stream is balanced whatever the individual lengths are. Used when it gives
+    // more workgroups than pairs, each with at least 512 keys at the stated maximum length.
+    const int tile = d.N <= 16 ? SPEC_SMALL_TILE_KEYS : SPEC_WIDE_TILE_KEYS;
+    const int resident_per_cu = (d.N > 16 && d.N <= 64) ? 2 : 1;   // four-wavefront workgroups: two per compute unit
+    int wgs = env_int("SPEC_TREE_BALANCED_WGS", -1);
+    if (wgs < 0) {
+      const long max_tiles = groups * ((max_len + tile - 1) / tile);
+      const long cand = std::min<long>((long)compute_units() * resident_per_cu, max_tiles / (512 / tile));
+      wgs = cand > groups ? (int)cand : 0;
     }
-    chunk = (int)((max_len + splits - 1) / splits);
-    if (chunk < 128) chunk = 128;
+    if (wgs > 0) {
+      p.balanced_wgs = wgs;
+      p.balanced_tile = tile;
+      p.chunk_keys = 0;
+      p.n_splits = (wgs + d.H - 1) / d.H + 1;   // a pair is overlapped by at most this many shares
+    }
   }
-  chunk = (int)round_up((size_t)chunk, 32);
-  p.chunk_keys = chunk;
-  p.n_splits = (max_len + chunk - 1) / chunk;
-  if (p.n_splits <= 1) {
+  if (p.balanced_wgs == 0) {
+    if (chunk <= 0) {
+      // One workgroup per (request, head, query group) streams its whole key range when that already
+      // gives every compute unit a workgroup: a workgroup's fixed cost (first loads, tree set-up, final
+      // merge, and the extra combine launch) outweighs any gain from more parallel slack. Only batches
+      // with few (request, head) pairs are split, into chunks of at least 512 keys.
+      long splits = 1;
+      if (groups < 256) {
+        splits = (768 + groups - 1) / groups;
+        const long max_splits = max_len / 512 > 0 ? max_len / 512 : 1;
+        if (splits > max_splits) splits = max_splits;
+      }
+      chunk = (int)((max_len + splits - 1) / splits);
+      if (chunk < 128) chunk = 128;
+    }
+    chunk = (int)round_up((size_t)chunk, 32);
+    p.chunk_keys = chunk;
+    p.n_splits = (max_len + chunk - 1) / chunk;
+  }
+  if (p.n_splits <= 1 && p.balanced_wgs == 0) {
     p.n_splits = 1;
     p.ws_o_off = p.ws_ml_off = 0;
     p.ws_bytes = 0;
@@ -142,7 +182,7 @@ static int tree_attention_impl(const spec_attn_desc_t* desc, const void* q, cons
                                   tree_depth, prefix_len, (float*)out, workspace, status, s);
   }
   if (e != hipSuccess) return SPEC_ERR_HIP;
-  if (plan.n_splits > 1) {
+  if (plan.n_splits > 1 || plan.balanced_wgs > 0) {
     e = launch_attn_combine(*desc, plan, tree_parent, tree_depth, prefix_len, workspace, out, status, s);
     if (e != hipSuccess) return SPEC_ERR_HIP;
   }

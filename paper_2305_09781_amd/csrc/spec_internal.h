@@ -14,7 +14,9 @@ namespace spec {
 // ---------------------------------------------------------------------------------------------
 struct AttnPlan {
   int chunk_keys;   // keys per workgroup (multiple of 32)
-  int n_splits;     // chunks covering max_prefix_len + N
+  int n_splits;     // chunks covering max_prefix_len + N; balanced plan: partial slots per (request, head)
+  int balanced_wgs; // > 0: balanced plan with this many workgroups (see balanced_share), chunk_keys unused
+  int balanced_tile;// keys per tile of the balanced deal (the tile of the kernel that runs the plan)
   size_t ws_o_off;  // float [B][H][n_splits][N][D]   un-normalised partial outputs
   size_t ws_ml_off; // float [B][H][n_splits][N][2]   running max (log2 domain) and partial sum
   size_t ws_bytes;
@@ -24,6 +26,9 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d);
 
 // Tree queries handled by one workgroup of the attention kernel chosen for this shape
 // (bf16: 16 / 32 in the few-query kernel, 64 / 128 in the wide-tree kernel; float32: all of them).
+#define SPEC_SMALL_TILE_KEYS 32   // keys per wavefront tile of the few-query bf16 kernel (N <= 16)
+#define SPEC_WIDE_TILE_KEYS 64    // keys per workgroup tile of the wide bf16 kernel (N > 16)
+
 inline int attn_queries_per_workgroup(const spec_attn_desc_t& d) {
   if (d.dtype != SPEC_BF16) return SPEC_MAX_TREE_NODES;
   return d.N <= 16 ? 16 : d.N <= 32 ? 32 : d.N <= 64 ? 64 : 128;
@@ -89,6 +94,27 @@ __device__ inline bool tree_is_valid(const int32_t* __restrict__ parent, const i
   }
   __syncthreads();
   return *flag == 0;
+}
+
+// Balanced plan: the key tiles (`tile` keys each) of all (request, head) pairs, ordered by (request,
+// head, key), are dealt to `n_wg` workgroups in equal contiguous shares of `share` tiles (the last may
+// be shorter). A request that does not fit the cache capacity contributes no tiles.
+struct BalancedShare {
+  long total;   // tiles over all requests and heads
+  long share;   // tiles per workgroup (>= 1)
+};
+__device__ inline int request_tiles(int P, int N, int S_cap, int tile) {
+  return (P >= 0 && P <= S_cap - N) ? (P + N + tile - 1) / tile : 0;
+}
+__device__ inline BalancedShare balanced_share(const int32_t* __restrict__ prefix_len, int B, int N, int H, int S_cap,
+                                               int tile, int n_wg) {
+  long tiles = 0;
+  for (int b = 0; b < B; ++b) tiles += request_tiles(prefix_len[b], N, S_cap, tile);
+  BalancedShare r;
+  r.total = tiles * H;
+  r.share = (r.total + n_wg - 1) / n_wg;
+  if (r.share < 1) r.share = 1;
+  return r;
 }
 
 __device__ inline void set_status(int32_t* status, int b, int bit) {

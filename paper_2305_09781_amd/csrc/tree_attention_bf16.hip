@@ -51,30 +51,9 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;   // 16-byte load/store unit (plain vector: stays in registers)
 
-#ifdef SPEC_ATTN_TIMELINE
-// Development aid: per-wavefront timestamps (100 MHz wall clock) written to the workspace. The inline
-// asm keeps each reading where it is written in the program.
-#define SPEC_TS(slot)                                                                                         \
-  {                                                                                                           \
-    unsigned long long ts_;                                                                                   \
-    asm volatile("s_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(ts_)::"memory");                           \
-    if (lane == 0)                                                                                            \
-      ((unsigned long long*)ws_o)[((((long)b * gridDim.y + blockIdx.y) * n_splits + split) * WAVES + wave) * 8 + (slot)] = ts_; \
-  }
-#define SPEC_TS_DEP(slot, dep)                                                                                \
-  {                                                                                                           \
-    unsigned long long ts_;                                                                                   \
-    asm volatile("s_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(ts_) : "s"(dep) : "memory");               \
-    if (lane == 0)                                                                                            \
-      ((unsigned long long*)ws_o)[((((long)b * gridDim.y + blockIdx.y) * n_splits + split) * WAVES + wave) * 8 + (slot)] = ts_; \
-  }
-#else
-#define SPEC_TS(slot)
-#define SPEC_TS_DEP(slot, dep)
-#endif
 
 constexpr float kLog2eB = 1.4426950408889634f;
-constexpr int TILE = 32;          // keys per wavefront tile
+constexpr int TILE = SPEC_SMALL_TILE_KEYS;          // keys per wavefront tile
 constexpr int SWAVES = 4;         // streaming wavefronts
 constexpr int WAVES = SWAVES + 1; // plus the tail wavefront
 constexpr int TAIL = SWAVES;      // its index
@@ -181,14 +160,14 @@ __device__ __forceinline__ void issue_tile_loads(const TileSrc& s, int k0, int P
   issue_k_loads<D, NT, APPEND, CLEAN>(s, k0, P, last_row, r16, Kn);
 }
 
-template <int D, int NT, bool APPEND>
+template <int D, int NT, bool APPEND, bool BAL>
 __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
     const __hip_bfloat16* __restrict__ q, __hip_bfloat16* k_cache, __hip_bfloat16* v_cache,
     const __hip_bfloat16* __restrict__ k_new, const __hip_bfloat16* __restrict__ v_new,
     const int32_t* __restrict__ parent, const int32_t* __restrict__ depth, const int32_t* __restrict__ prefix_len,
-    __hip_bfloat16* __restrict__ out, float* __restrict__ ws_o, float* __restrict__ ws_ml, int32_t* status, int N, int H,
-    int S_cap, int n_qgroups, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long kv_sb, long kv_sh,
-    long kv_ss, float scale_log2) {
+    __hip_bfloat16* __restrict__ out, float* __restrict__ ws_o, float* __restrict__ ws_ml, int32_t* status, int B, int N,
+    int H, int S_cap, int n_qgroups, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long kv_sb,
+    long kv_sh, long kv_ss, float scale_log2) {
   using T = AttnTraits<D, NT>;
   constexpr int KS = T::KS, DB = T::DB, LPR = T::LPR, RPI = T::RPI, NVL = T::NVL, VROW = T::VROW, NQ = T::NQ,
                 MROW = T::MROW;
@@ -203,12 +182,12 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int r16 = lane & 15, g = lane >> 4;
-  const int split = blockIdx.x;
-  const int h = blockIdx.y / n_qgroups, qg = blockIdx.y % n_qgroups;
-  const int b = blockIdx.z;
+
+  // One segment: keys [c0, min(c1_cap, prefix_len + N)) of request b, head h, query group qg. The result is
+  // the final output (part_row < 0) or the float32 partial whose first row in the workspace is part_row.
+  auto segment = [&](const int b, const int h, const int qg, const int c0, const int c1_cap, const long part_row) {
+  const bool final_out = part_row < 0;
   const int q0 = qg * NQ;
-  const int c0 = split * chunk_keys;
-  SPEC_TS(0)
 
   // ---- straight-line prologue (no branch before the first loads, so every kernel argument is
   // fetched in one batch): the streaming wavefronts' first tile does not depend on prefix_len (rows
@@ -225,7 +204,6 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
 
   u32x4 KA[2][KS], VA[NVL];   // tile buffer: loads land here one step ahead of use
   issue_tile_loads<D, NT, false, false>(src, c0 + min(wave, SWAVES - 1) * TILE, 0, S_cap - 1, r16, lane, KA, VA);
-  SPEC_TS(1)
 
   bf16x8 qB[NT][KS];   // Q^T as the B operand: lane (r16, g) holds Q[n = r16][d = ks*32 + g*8 .. +8]
 #pragma unroll
@@ -245,7 +223,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
   const bool cap_ok = (P >= 0) && (P <= S_cap - N);
   const int len = P + N;
   if (!cap_ok) {
-    if (n_splits == 1) {
+    if (final_out) {
       for (int i = t; i < NQ * D; i += NTHREADS) {
         const int n = q0 + i / D;
         if (n < N) out[b * q_sb + n * q_sn + h * q_sh + (i % D)] = __float2bfloat16(0.f);
@@ -255,7 +233,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
     return;
   }
   if (c0 >= len) return;
-  const int c1 = min(c0 + chunk_keys, len);
+  const int c1 = min(c1_cap, len);
   const bool touches_tree = c1 > P;
   const int n_tiles = (c1 - c0 + TILE - 1) / TILE;
   const int n_clean = max(0, min(P, c1) - c0) / TILE;     // tiles entirely inside the prefix and the chunk
@@ -457,7 +435,6 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
     for (int ti = ti_first; ti < ti_end; ti += SWAVES)
       tile_step(ti, ti + SWAVES < ti_end ? ti + SWAVES : -1, std::false_type{});
   }
-  SPEC_TS(5)
 
   // ---- merge the five wavefronts through LDS: layout [wave][n][MROW] floats (O row, m, l)
   if (!T::MERGE_SEPARATE) __syncthreads();   // the merge area overlays the staging tiles still being read
@@ -474,9 +451,8 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
     }
   }
   __syncthreads();
-  SPEC_TS(6)
   if (s_bad_tree != 0) {   // malformed tree: defined result = zeros (written here when this workgroup owns the output)
-    if (n_splits == 1) {
+    if (final_out) {
       for (int i = t; i < NQ * D; i += NTHREADS) {
         const int n = q0 + i / D;
         if (n < N) out[b * q_sb + n * q_sn + h * q_sh + (i % D)] = __float2bfloat16(0.f);
@@ -503,14 +479,14 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
       l += row[D + 1] * wgt;
       o += *(const f32x4*)(row + cg * 4) * wgt;
     }
-    if (n_splits == 1) {
+    if (final_out) {
       const float inv = 1.f / l;
       union { uint2 u; __hip_bfloat16 h4[4]; } pk;
 #pragma unroll
       for (int i = 0; i < 4; ++i) pk.h4[i] = __float2bfloat16(o[i] * inv);
       *(uint2*)(out + b * q_sb + n * q_sn + h * q_sh + cg * 4) = pk.u;
     } else {
-      const long base = (((long)b * H + h) * n_splits + split) * N + n;
+      const long base = part_row + n;
       *(f32x4*)(ws_o + base * D + cg * 4) = o;
       if (cg == 0) {
         ws_ml[base * 2 + 0] = M;
@@ -518,14 +494,48 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
       }
     }
   }
-  SPEC_TS(7)
+  };   // segment
+
+  if constexpr (!BAL) {
+    // grid = (n_splits, H * n_qgroups, B): one fixed-size chunk of one (request, head, query group)
+    const int split = blockIdx.x;
+    const int h = blockIdx.y / n_qgroups, qg = blockIdx.y % n_qgroups;
+    const int b = blockIdx.z;
+    segment(b, h, qg, split * chunk_keys, split * chunk_keys + chunk_keys,
+            n_splits == 1 ? -1l : (((long)b * H + h) * n_splits + split) * N);
+  } else {
+    // Balanced stream: the 32-key tiles of all (request, head) pairs, in (request, head, key) order,
+    // are dealt to the gridDim.x workgroups in equal contiguous shares, whatever the requests'
+    // lengths; a share that crosses a pair boundary becomes several segments. n_splits is the number
+    // of partial slots per pair: the workgroups overlapping a pair fill slots 0, 1, ... in order.
+    const BalancedShare bs = balanced_share(prefix_len, B, N, H, S_cap, TILE, (int)gridDim.x);
+    long pos = (long)blockIdx.x * bs.share;
+    const long end = min(bs.total, pos + bs.share);
+    int b = 0;
+    long req_start = 0;
+    int tb = request_tiles(prefix_len[0], N, S_cap, TILE);
+    while (pos < end) {
+      while (pos >= req_start + (long)H * tb) {   // pos < total: a request with tiles left lies ahead
+        req_start += (long)H * tb;
+        ++b;
+        tb = request_tiles(prefix_len[b], N, S_cap, TILE);
+      }
+      const long in_req = pos - req_start;
+      const int h = (int)(in_req / tb), tile0 = (int)(in_req % tb);
+      const int n_take = (int)min((long)(tb - tile0), end - pos);
+      const int slot = (int)blockIdx.x - (int)((req_start + (long)h * tb) / bs.share);
+      segment(b, h, 0, tile0 * TILE, (tile0 + n_take) * TILE, (((long)b * H + h) * n_splits + slot) * N);
+      pos += n_take;
+      __syncthreads();   // LDS (staging tiles, merge area, flags) is reused by the next segment
+    }
+  }
 }
 
 hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan& plan, const void* q, void* k_cache,
                                       void* v_cache, const void* k_new, const void* v_new, const int32_t* parent,
                                       const int32_t* depth, const int32_t* prefix_len, void* out, void* ws,
                                       int32_t* status, hipStream_t s) {
-  if (d.N > 32)
+  if (d.N > 16)
     return launch_tree_attention_bf16_wide(d, plan, q, k_cache, v_cache, k_new, v_new, parent, depth, prefix_len, out, ws,
                                            status, s);
   const float scale = (d.softmax_scale != 0.f ? d.softmax_scale : 1.0f / sqrtf((float)d.D)) * kLog2eB;
@@ -535,21 +545,24 @@ hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan&
   const int nq = nt * 16;
   const int n_qgroups = (d.N + nq - 1) / nq;
   const bool append = k_new != nullptr;
-  dim3 grid(plan.n_splits, d.H * n_qgroups, d.B);
-#define SPEC_LAUNCH(DD, NTT, APP)                                                                                \
-  hipLaunchKernelGGL((tree_attention_bf16_kernel<DD, NTT, APP>), grid, dim3(WAVES * 64), 0, s,                   \
-                     (const __hip_bfloat16*)q,                                                                        \
-                     (__hip_bfloat16*)k_cache, (__hip_bfloat16*)v_cache, (const __hip_bfloat16*)k_new,                \
-                     (const __hip_bfloat16*)v_new, parent, depth, prefix_len, (__hip_bfloat16*)out, ws_o, ws_ml,      \
-                     status, d.N, d.H, d.S_cap, n_qgroups, plan.chunk_keys, plan.n_splits, (long)d.q_stride_b,        \
-                     (long)d.q_stride_n, (long)d.q_stride_h, (long)d.kv_stride_b, (long)d.kv_stride_h,                \
-                     (long)d.kv_stride_s, scale)
-#define SPEC_DISPATCH(APP)                             \
-  if (d.D == 128 && nt == 1) SPEC_LAUNCH(128, 1, APP);    \
-  else if (d.D == 128) SPEC_LAUNCH(128, 2, APP);          \
-  else if (nt == 1) SPEC_LAUNCH(64, 1, APP);              \
-  else SPEC_LAUNCH(64, 2, APP)
-  if (append) { SPEC_DISPATCH(true); } else { SPEC_DISPATCH(false); }
+  const bool bal = plan.balanced_wgs > 0;
+  const dim3 grid = bal ? dim3(plan.balanced_wgs, 1, 1) : dim3(plan.n_splits, d.H * n_qgroups, d.B);
+#define SPEC_LAUNCH(DD, NTT, APP, BAL)                                                                           \
+  hipLaunchKernelGGL((tree_attention_bf16_kernel<DD, NTT, APP, BAL>), grid, dim3(WAVES * 64), 0, s,              \
+                     (const __hip_bfloat16*)q, (__hip_bfloat16*)k_cache, (__hip_bfloat16*)v_cache,               \
+                     (const __hip_bfloat16*)k_new, (const __hip_bfloat16*)v_new, parent, depth, prefix_len,      \
+                     (__hip_bfloat16*)out, ws_o, ws_ml, status, d.B, d.N, d.H, d.S_cap, n_qgroups,               \
+                     plan.chunk_keys, plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h, \
+                     (long)d.kv_stride_b, (long)d.kv_stride_h, (long)d.kv_stride_s, scale)
+#define SPEC_DISPATCH(APP, BAL)                                \
+  if (d.D == 128 && nt == 1) SPEC_LAUNCH(128, 1, APP, BAL);    \
+  else if (d.D == 128) SPEC_LAUNCH(128, 2, APP, BAL);          \
+  else if (nt == 1) SPEC_LAUNCH(64, 1, APP, BAL);              \
+  else SPEC_LAUNCH(64, 2, APP, BAL)
+  if (append && bal) { SPEC_DISPATCH(true, true); }
+  else if (append) { SPEC_DISPATCH(true, false); }
+  else if (bal) { SPEC_DISPATCH(false, true); }
+  else { SPEC_DISPATCH(false, false); }
 #undef SPEC_DISPATCH
 #undef SPEC_LAUNCH
   return hipGetLastError();

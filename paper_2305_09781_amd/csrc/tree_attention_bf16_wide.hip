@@ -1,12 +1,14 @@
-// Tree attention for bf16 K/V, wide trees (33..128 nodes per request): Definition 4.1 with the
+// Tree attention for bf16 K/V, trees of 17..128 nodes per request: Definition 4.1 with the
 // topology-aware causal mask of Section 4.2, same mathematics as tree_attention_bf16.hip.
 //
-// With many tree queries the wavefronts of a workgroup split the QUERIES (one 16-query tile each: four
-// wavefronts up to 64 nodes, eight up to 128) and share one stream of K and V: every 64-key tile is loaded
-// from HBM once, fully coalesced, staged in LDS (double-buffered, rows padded by 16 bytes), and read
-// from there by every wavefront - K as the MFMA A operand (ds_read_b128), V^T through
-// ds_read_b64_tr_b16. Because a wavefront owns its queries over the whole key range there is nothing
-// to merge at the end.
+// With many tree queries the wavefronts of a workgroup split the QUERIES (one 16-query tile each) and
+// share one stream of K and V: every 64-key tile is loaded from HBM once, fully coalesced, staged in
+// LDS (double-buffered, rows padded by 32 bytes), and read from there by every wavefront - K as the
+// MFMA A operand (ds_read_b128), V^T through ds_read_b64_tr_b16. Shapes:
+//     N <= 32 : 2 query tiles x 2 key halves (each wavefront takes one 32-key half of every tile;
+//               the two halves of a query tile are merged once, through LDS, at the end)
+//     N <= 64 : 4 query tiles, N <= 128 : 8 query tiles (a wavefront owns its queries over the whole
+//               key range: nothing to merge).
 //
 //   prologue:      tiles 0 and 1 are requested together (before prefix_len is known) and staged
 //   iteration ti:  S^T, online softmax, O^T for tile ti from LDS stage ti&1
@@ -14,9 +16,13 @@
 //                  registers holding tile ti+2 -> stage ti&1; request tile ti+4 into them
 //   so two tiles are always in flight from HBM per workgroup, one more is ready in LDS.
 //
-// Masked tiles (those reaching past prefix_len or the end of the chunk) take the MASKED variant of
+// Masked tiles (those reaching past prefix_len or the end of the segment) take the MASKED variant of
 // the compute step; the loader threads zero rows past the end, and with APPEND fetch rows >= prefix_len
-// from k_new / v_new and write them to the cache (query group 0 only).
+// from k_new / v_new and write them to the cache.
+//
+// Work split: fixed chunks, grid = (n_splits, H, B), or (BAL) the balanced deal of 64-key tiles over
+// gridDim.x workgroups described at balanced_share(); a share that crosses a (request, head) boundary
+// is processed as several segments.
 #include <hip/hip_bf16.h>
 
 #include <type_traits>
@@ -32,27 +38,8 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 namespace wide {
 
-#ifdef SPEC_WIDE_TIMELINE
-// Development aid: timestamps of one steady-state iteration (tile 3), per wavefront.
-#define WTS(slot, cond)                                                                                   \
-  if (cond) {                                                                                             \
-    unsigned long long ts_;                                                                               \
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(ts_)::"memory"); \
-    if (lane == 0) ((unsigned long long*)ws_o)[(((long)b * gridDim.y + blockIdx.y) * WAVES + wave) * 8 + (slot)] = ts_; \
-  }
-#define WTS_L(slot, cond)                                                                                 \
-  if (cond) {                                                                                             \
-    unsigned long long ts_;                                                                               \
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_nop 15\n\ts_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(ts_)::"memory"); \
-    if (lane == 0) ((unsigned long long*)ws_o)[(((long)b * gridDim.y + blockIdx.y) * WAVES + wave) * 8 + (slot)] = ts_; \
-  }
-#else
-#define WTS(slot, cond)
-#define WTS_L(slot, cond)
-#endif
-
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr int KT = 64;       // keys per workgroup tile
+constexpr int KT = SPEC_WIDE_TILE_KEYS;   // keys per workgroup tile
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 __device__ __forceinline__ void store_nt(void* p, u32x4 v) {
@@ -69,14 +56,18 @@ __device__ inline float sum_over_lane_groups(float v) {
   return v;
 }
 
-template <int D, int WAVES, int NTW, bool APPEND>
-__global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_wide_kernel(
+// QW query tiles x KW key parts: wavefront w serves query tile w % QW and (KW == 2) the 32-key half
+// w / QW of every 64-key tile.
+template <int D, int QW, int KW, bool APPEND, bool BAL>
+__global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kernel(
     const __hip_bfloat16* __restrict__ q, __hip_bfloat16* k_cache, __hip_bfloat16* v_cache,
     const __hip_bfloat16* __restrict__ k_new, const __hip_bfloat16* __restrict__ v_new,
     const int32_t* __restrict__ parent, const int32_t* __restrict__ depth, const int32_t* __restrict__ prefix_len,
-    __hip_bfloat16* __restrict__ out, float* __restrict__ ws_o, float* __restrict__ ws_ml, int32_t* status, int N, int H,
-    int S_cap, int n_qgroups, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long kv_sb, long kv_sh,
-    long kv_ss, float scale_log2) {
+    __hip_bfloat16* __restrict__ out, float* __restrict__ ws_o, float* __restrict__ ws_ml, int32_t* status, int B, int N,
+    int H, int S_cap, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long kv_sb, long kv_sh, long kv_ss,
+    float scale_log2) {
+  static_assert(KW == 1 || KW == 2, "a 64-key tile is consumed as two 32-key halves");
+  constexpr int WAVES = QW * KW;
   constexpr int NTHREADS = WAVES * 64;
   constexpr int KS = D / 32, DB = D / 16;
   constexpr int LPR = D * 2 / 16;            // 16-byte pieces per row
@@ -84,7 +75,9 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_wide_kernel
   constexpr int ROWB = D * 2 + 32;           // LDS bytes per staged row (+32: consecutive rows shift by 8 banks)
   constexpr int MAT_BYTES = KT * ROWB;       // one staged matrix (K or V)
   constexpr int STAGE_BYTES = 2 * MAT_BYTES;
-  constexpr int NQ = WAVES * NTW * 16;       // queries per workgroup
+  constexpr int ROW_STEP = NTHREADS / LPR;
+  static_assert(NPT >= 1 && KT % ROW_STEP == 0, "loader layout");
+  static_assert(KW == 1 || QW * 64 * (DB * 4 + 2) * 4 <= 2 * STAGE_BYTES, "merge area fits the staging area");
 
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE_BYTES];
   __shared__ unsigned long long s_anc[SPEC_MAX_TREE_NODES][2];
@@ -95,204 +88,183 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_wide_kernel
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int r16 = lane & 15, g = lane >> 4;
-  const int split = blockIdx.x;
-  const int h = blockIdx.y / n_qgroups, qg = blockIdx.y % n_qgroups;
-  const int b = blockIdx.z;
-  const int q0 = qg * NQ + wave * NTW * 16;   // first query of this wavefront
-  const int c0 = split * chunk_keys;
-  WTS_L(0, true)
-
-  // ---- straight-line prologue: first tile (does not depend on prefix_len), Q, one tree node per thread
-  const int P = prefix_len[b];
-  const unsigned cache_row_bytes = (unsigned)kv_ss * 2u, new_row_bytes = (unsigned)q_sn * 2u;
-  const unsigned char* kc = (const unsigned char*)(k_cache + b * kv_sb + h * kv_sh);
-  const unsigned char* vc = (const unsigned char*)(v_cache + b * kv_sb + h * kv_sh);
-  const unsigned char* kn = APPEND ? (const unsigned char*)(k_new + b * q_sb + h * q_sh) : nullptr;
-  const unsigned char* vn = APPEND ? (const unsigned char*)(v_new + b * q_sb + h * q_sh) : nullptr;
-  const long new_minus_cache_k = APPEND ? (long)(kn - kc) : 0, new_minus_cache_v = APPEND ? (long)(vn - vc) : 0;
-  // loader role of this thread: piece j of a tile is row (t + 256 j) / LPR, 16-byte column (t + 256 j) % LPR
+  const int qt = wave % QW, kpart = wave / QW;
+  const int q0 = qt * 16;   // first query of this wavefront
+  // loader role of this thread: piece j of a tile is row (t + NTHREADS j) / LPR, 16-byte column (t % LPR)
   const int ld_row0 = t / LPR, ld_col = (t % LPR) * 16;
-  constexpr int ROW_STEP = NTHREADS / LPR;
 
-  // two register sets: the two tiles in flight from global memory (tiles ti+2 and ti+3 while tile ti is
-  // consumed from LDS and tile ti+1 waits there)
-  u32x4 Kr[NPT], Vr[NPT];
-  u32x4 Kr2[NPT], Vr2[NPT];
-  // SOURCES: 0 = cache rows clamped to the capacity (speculative), 1 = clean (no clamp), 2 = tail (clamp, new rows)
-  auto issue = [&](u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT], int k0, auto mode_tag, int Pk, int last_row) {
-    constexpr int MODE = decltype(mode_tag)::value;
+  // One segment: keys [c0, min(c1_cap, prefix_len + N)) of request b, head h. The result is the final
+  // output (part_row < 0) or the float32 partial whose first row in the workspace is part_row.
+  auto segment = [&](const int b, const int h, const int c0, const int c1_cap, const long part_row) {
+    const bool final_out = part_row < 0;
+
+    // ---- straight-line prologue: first two tiles (they do not depend on prefix_len), Q, one tree node per thread
+    const int P = prefix_len[b];
+    const unsigned cache_row_bytes = (unsigned)kv_ss * 2u, new_row_bytes = (unsigned)q_sn * 2u;
+    const unsigned char* kc = (const unsigned char*)(k_cache + b * kv_sb + h * kv_sh);
+    const unsigned char* vc = (const unsigned char*)(v_cache + b * kv_sb + h * kv_sh);
+    const unsigned char* kn = APPEND ? (const unsigned char*)(k_new + b * q_sb + h * q_sh) : nullptr;
+    const unsigned char* vn = APPEND ? (const unsigned char*)(v_new + b * q_sb + h * q_sh) : nullptr;
+    const long new_minus_cache_k = APPEND ? (long)(kn - kc) : 0, new_minus_cache_v = APPEND ? (long)(vn - vc) : 0;
+
+    // two register sets: the two tiles in flight from global memory (tiles ti+2 and ti+3 while tile ti is
+    // consumed from LDS and tile ti+1 waits there)
+    u32x4 Kr[NPT], Vr[NPT];
+    u32x4 Kr2[NPT], Vr2[NPT];
+    // MODE: 0 = cache rows clamped to the capacity (speculative), 1 = clean (no clamp), 2 = tail (clamp, new rows)
+    auto issue = [&](u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT], int k0, auto mode_tag, int Pk, int last_row) {
+      constexpr int MODE = decltype(mode_tag)::value;
 #pragma unroll
-    for (int j = 0; j < NPT; ++j) {
-      int row = k0 + ld_row0 + j * ROW_STEP;
-      long off_k, off_v;   // byte offsets from the cache bases (new rows: through the distance between the buffers)
-      if (MODE == 1) {
-        off_k = off_v = (long)((unsigned)row * cache_row_bytes);
-      } else {
-        row = min(row, last_row);
-        const bool from_new = (MODE == 2) && APPEND && row >= Pk;
-        const long in_cache = (long)((unsigned)row * cache_row_bytes);
-        const long in_new = (long)((unsigned)(row - Pk) * new_row_bytes);
-        off_k = from_new ? new_minus_cache_k + in_new : in_cache;
-        off_v = from_new ? new_minus_cache_v + in_new : in_cache;
+      for (int j = 0; j < NPT; ++j) {
+        int row = k0 + ld_row0 + j * ROW_STEP;
+        long off_k, off_v;   // byte offsets from the cache bases (new rows: through the distance between the buffers)
+        if (MODE == 1) {
+          off_k = off_v = (long)((unsigned)row * cache_row_bytes);
+        } else {
+          row = min(row, last_row);
+          const bool from_new = (MODE == 2) && APPEND && row >= Pk;
+          const long in_cache = (long)((unsigned)row * cache_row_bytes);
+          const long in_new = (long)((unsigned)(row - Pk) * new_row_bytes);
+          off_k = from_new ? new_minus_cache_k + in_new : in_cache;
+          off_v = from_new ? new_minus_cache_v + in_new : in_cache;
+        }
+        Vd[j] = *(const u32x4*)(vc + off_v + ld_col);
+        Kd[j] = *(const u32x4*)(kc + off_k + ld_col);
       }
-      Vd[j] = *(const u32x4*)(vc + off_v + ld_col);
-      Kd[j] = *(const u32x4*)(kc + off_k + ld_col);
-    }
-  };
-  issue(Kr, Vr, c0, std::integral_constant<int, 0>{}, 0, S_cap - 1);
-  issue(Kr2, Vr2, c0 + KT, std::integral_constant<int, 0>{}, 0, S_cap - 1);
+    };
+    issue(Kr, Vr, c0, std::integral_constant<int, 0>{}, 0, S_cap - 1);
+    issue(Kr2, Vr2, c0 + KT, std::integral_constant<int, 0>{}, 0, S_cap - 1);
 
-  bf16x8 qB[NTW][KS];
+    bf16x8 qB[KS];
+    {
+      const int n = q0 + r16;
 #pragma unroll
-  for (int nt = 0; nt < NTW; ++nt) {
-    const int n = q0 + nt * 16 + r16;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const u32x4 raw = *(const u32x4*)(q + b * q_sb + min(n, N - 1) * q_sn + h * q_sh + ks * 32 + g * 8);
-      qB[nt][ks] = __builtin_bit_cast(bf16x8, raw);
-    }
-  }
-  const int my_parent = parent[(long)b * N + min(t, N - 1)];
-  const int my_depth = depth[(long)b * N + min(t, N - 1)];
-  if (t == 0) s_flag = 0;
-  if (t < N) {
-    s_parent[t] = my_parent;
-    s_depth[t] = my_depth;
-  }
-  lds_barrier();
-
-  const bool cap_ok = (P >= 0) && (P <= S_cap - N);
-  const int len = P + N;
-  auto zero_outputs = [&](int bit) {
-    if (n_splits == 1) {
-      const int qbase = qg * NQ;
-      for (int i = t; i < NQ * D; i += NTHREADS) {
-        const int n = qbase + i / D;
-        if (n < N) out[b * q_sb + n * q_sn + h * q_sh + (i % D)] = __float2bfloat16(0.f);
+      for (int ks = 0; ks < KS; ++ks) {
+        const u32x4 raw = *(const u32x4*)(q + b * q_sb + min(n, N - 1) * q_sn + h * q_sh + ks * 32 + g * 8);
+        qB[ks] = __builtin_bit_cast(bf16x8, raw);
       }
-      if (h == 0 && qg == 0 && t == 0) set_status(status, b, bit);
     }
-  };
-  if (!cap_ok) {
-    zero_outputs(SPEC_ST_CAPACITY);
-    return;
-  }
-  if (c0 >= len) return;
-  const int c1 = min(c0 + chunk_keys, len);
-  const bool touches_tree = c1 > P;
-  const int n_tiles = (c1 - c0 + KT - 1) / KT;
-  const int n_clean = max(0, min(P, c1) - c0) / KT;
-  const int last_row = len - 1;
-
-  // speculative tiles that reach the tree are fetched again from the right sources
-  if (APPEND && n_clean == 0) issue(Kr, Vr, c0, std::integral_constant<int, 2>{}, P, last_row);
-  if (APPEND && n_clean <= 1 && n_tiles > 1) issue(Kr2, Vr2, c0 + KT, std::integral_constant<int, 2>{}, P, last_row);
-
-  // ---- tree: validate, build ancestor-or-self masks (LDS-only barriers: the tile loads stay in flight)
-  unsigned long long anc_lo[NTW], anc_hi[NTW];
-#pragma unroll
-  for (int nt = 0; nt < NTW; ++nt) anc_lo[nt] = anc_hi[nt] = 0ull;
-  if (touches_tree) {
+    const int my_parent = parent[(long)b * N + min(t, N - 1)];
+    const int my_depth = depth[(long)b * N + min(t, N - 1)];
+    if (t == 0) s_flag = 0;
     if (t < N) {
-      bool ok = (t == 0) ? (my_parent == -1 && my_depth == 0) : (my_parent >= 0 && my_parent < t);
-      if (ok && t > 0) ok = my_depth == s_depth[my_parent] + 1;
-      if (!ok) atomicOr(&s_flag, 1);
+      s_parent[t] = my_parent;
+      s_depth[t] = my_depth;
     }
     lds_barrier();
-    if (s_flag != 0) {
-      zero_outputs(SPEC_ST_BAD_TREE);
+
+    const bool cap_ok = (P >= 0) && (P <= S_cap - N);
+    const int len = P + N;
+    auto zero_outputs = [&](int bit) {
+      if (final_out) {
+        for (int i = t; i < QW * 16 * D; i += NTHREADS) {
+          const int n = i / D;
+          if (n < N) out[b * q_sb + n * q_sn + h * q_sh + (i % D)] = __float2bfloat16(0.f);
+        }
+        if (h == 0 && t == 0) set_status(status, b, bit);
+      }
+    };
+    if (!cap_ok) {
+      zero_outputs(SPEC_ST_CAPACITY);
       return;
     }
-    if (t < N) {
-      unsigned long long lo = 0, hi = 0;
-      int u = t;
-      for (int step = 0; step < N && u >= 0; ++step) {
-        if (u < 64) lo |= 1ull << u; else hi |= 1ull << (u - 64);
-        u = s_parent[u];
+    if (c0 >= len) return;
+    const int c1 = min(c1_cap, len);
+    const bool touches_tree = c1 > P;
+    const int n_tiles = (c1 - c0 + KT - 1) / KT;
+    const int n_clean = max(0, min(P, c1) - c0) / KT;
+    const int last_row = len - 1;
+
+    // speculative tiles that reach the tree are fetched again from the right sources
+    if (APPEND && n_clean == 0) issue(Kr, Vr, c0, std::integral_constant<int, 2>{}, P, last_row);
+    if (APPEND && n_clean <= 1 && n_tiles > 1) issue(Kr2, Vr2, c0 + KT, std::integral_constant<int, 2>{}, P, last_row);
+
+    // ---- tree: validate, build ancestor-or-self masks (LDS-only barriers: the tile loads stay in flight)
+    unsigned long long anc_lo = 0ull, anc_hi = 0ull;
+    if (touches_tree) {
+      if (t < N) {
+        bool ok = (t == 0) ? (my_parent == -1 && my_depth == 0) : (my_parent >= 0 && my_parent < t);
+        if (ok && t > 0) ok = my_depth == s_depth[my_parent] + 1;
+        if (!ok) atomicOr(&s_flag, 1);
       }
-      s_anc[t][0] = lo;
-      s_anc[t][1] = hi;
-    }
-    lds_barrier();
-#pragma unroll
-    for (int nt = 0; nt < NTW; ++nt) {
-      const int n = q0 + nt * 16 + r16;
-      if (n < N) { anc_lo[nt] = s_anc[n][0]; anc_hi[nt] = s_anc[n][1]; }
-    }
-  }
-
-  // registers -> LDS stage; masked tiles: rows past the chunk end become zeros, appended rows go to the cache
-  auto stage_tile = [&](u32x4 (&Ks_)[NPT], u32x4 (&Vs_)[NPT], int ti, unsigned char* stage) {
-    const int k0 = c0 + ti * KT;
-    const bool masked = ti >= n_clean;
-#pragma unroll
-    for (int j = 0; j < NPT; ++j) {
-      const int rit = ld_row0 + j * ROW_STEP;
-      if (masked) {
-        const int row = k0 + rit;
-        if (row >= c1) {
-          Ks_[j] = (u32x4){0u, 0u, 0u, 0u};
-          Vs_[j] = (u32x4){0u, 0u, 0u, 0u};
-        } else if (APPEND && qg == 0 && row >= P) {
-          store_nt((unsigned char*)(k_cache + b * kv_sb + h * kv_sh) + (unsigned)row * cache_row_bytes + ld_col, Ks_[j]);
-          store_nt((unsigned char*)(v_cache + b * kv_sb + h * kv_sh) + (unsigned)row * cache_row_bytes + ld_col, Vs_[j]);
-        }
+      lds_barrier();
+      if (s_flag != 0) {
+        zero_outputs(SPEC_ST_BAD_TREE);
+        return;
       }
-      *(u32x4*)(stage + rit * ROWB + ld_col) = Ks_[j];
-      *(u32x4*)(stage + MAT_BYTES + rit * ROWB + ld_col) = Vs_[j];
+      if (t < N) {
+        unsigned long long lo = 0, hi = 0;
+        int u = t;
+        for (int step = 0; step < N && u >= 0; ++step) {
+          if (u < 64) lo |= 1ull << u; else hi |= 1ull << (u - 64);
+          u = s_parent[u];
+        }
+        s_anc[t][0] = lo;
+        s_anc[t][1] = hi;
+      }
+      lds_barrier();
+      const int n = q0 + r16;
+      if (n < N) { anc_lo = s_anc[n][0]; anc_hi = s_anc[n][1]; }
     }
-  };
-  auto issue_tile = [&](u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT], int ti) {
-    const int k0 = c0 + ti * KT;
-    if (k0 + KT <= P) issue(Kd, Vd, k0, std::integral_constant<int, 1>{}, P, last_row);
-    else issue(Kd, Vd, k0, std::integral_constant<int, 2>{}, P, last_row);
-  };
 
-  f32x4 O[NTW][DB];
-  float m_run[NTW], l_run[NTW];
+    // registers -> LDS stage; masked tiles: rows past the segment end become zeros, appended rows go to the cache
+    auto stage_tile = [&](u32x4 (&Ks_)[NPT], u32x4 (&Vs_)[NPT], int ti, unsigned char* stage) {
+      const int k0 = c0 + ti * KT;
+      const bool masked = ti >= n_clean;
 #pragma unroll
-  for (int nt = 0; nt < NTW; ++nt) {
-    m_run[nt] = -INFINITY;
-    l_run[nt] = 0.f;
-#pragma unroll
-    for (int db = 0; db < DB; ++db) O[nt][db] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  }
+      for (int j = 0; j < NPT; ++j) {
+        const int rit = ld_row0 + j * ROW_STEP;
+        if (masked) {
+          const int row = k0 + rit;
+          if (row >= c1) {
+            Ks_[j] = (u32x4){0u, 0u, 0u, 0u};
+            Vs_[j] = (u32x4){0u, 0u, 0u, 0u};
+          } else if (APPEND && row >= P) {
+            store_nt((unsigned char*)(k_cache + b * kv_sb + h * kv_sh) + (unsigned)row * cache_row_bytes + ld_col, Ks_[j]);
+            store_nt((unsigned char*)(v_cache + b * kv_sb + h * kv_sh) + (unsigned)row * cache_row_bytes + ld_col, Vs_[j]);
+          }
+        }
+        *(u32x4*)(stage + rit * ROWB + ld_col) = Ks_[j];
+        *(u32x4*)(stage + MAT_BYTES + rit * ROWB + ld_col) = Vs_[j];
+      }
+    };
+    auto issue_tile = [&](u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT], int ti) {
+      const int k0 = c0 + ti * KT;
+      if (k0 + KT <= P) issue(Kd, Vd, k0, std::integral_constant<int, 1>{}, P, last_row);
+      else issue(Kd, Vd, k0, std::integral_constant<int, 2>{}, P, last_row);
+    };
 
-  auto compute = [&](const int ti, const unsigned char* stage, auto masked_tag) {
-    constexpr bool MASKED = decltype(masked_tag)::value;
-    const int k0 = c0 + ti * KT;
-    const unsigned char* Ks = stage;
-    const unsigned char* Vs = stage + MAT_BYTES;
-    // The 64-key stage is consumed as two 32-key halves (keeps the live score registers small).
+    f32x4 O[DB];
+    float m_run = -INFINITY, l_run = 0.f;
 #pragma unroll
-    for (int grp = 0; grp < 2; ++grp) {
-      // ---- S^T = K Q^T for two 16-key quarters; K operand read once per (quarter, k-step), used by all query tiles
-      f32x4 sc[NTW][2];
+    for (int db = 0; db < DB; ++db) O[db] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    auto compute = [&](const int ti, const unsigned char* stage, auto masked_tag) {
+      constexpr bool MASKED = decltype(masked_tag)::value;
+      const int k0 = c0 + ti * KT;
+      const unsigned char* Ks = stage;
+      const unsigned char* Vs = stage + MAT_BYTES;
+      // The 64-key stage is consumed as 32-key halves: both by this wavefront, or (KW == 2) one each.
 #pragma unroll
-      for (int nt = 0; nt < NTW; ++nt)
+      for (int part = 0; part < 2 / KW; ++part) {
+        const int grp = KW == 2 ? kpart : part;
+        // ---- S^T = K Q^T for two 16-key quarters
+        f32x4 sc[2];
 #pragma unroll
-        for (int hf = 0; hf < 2; ++hf) sc[nt][hf] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int hf = 0; hf < 2; ++hf) {
+          sc[hf] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const bf16x8 a = *(const bf16x8*)(Ks + (grp * 32 + hf * 16 + r16) * ROWB + ks * 64 + g * 16);
-#pragma unroll
-          for (int nt = 0; nt < NTW; ++nt)
-            sc[nt][hf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qB[nt][ks], sc[nt][hf], 0, 0, 0);
+          for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 a = *(const bf16x8*)(Ks + (grp * 32 + hf * 16 + r16) * ROWB + ks * 64 + g * 16);
+            sc[hf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qB[ks], sc[hf], 0, 0, 0);
+          }
         }
 
-#ifdef SPEC_WIDE_TIMELINE
-      asm volatile("" : "+v"(sc[0][0]), "+v"(sc[NTW - 1][1]));
-#endif
-      bf16x8 pB[NTW];
-#pragma unroll
-      for (int nt = 0; nt < NTW; ++nt) {
         float s[8];   // raw scores (before the softmax scale)
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-          for (int v = 0; v < 4; ++v) s[hf * 4 + v] = sc[nt][hf][v];
+          for (int v = 0; v < 4; ++v) s[hf * 4 + v] = sc[hf][v];
         if (MASKED) {
 #pragma unroll
           for (int hf = 0; hf < 2; ++hf)
@@ -302,7 +274,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_wide_kernel
               const int rel = key - P;
               bool vis = key < c1;
               if (vis && rel >= 0) {
-                const unsigned long long w = rel < 64 ? anc_lo[nt] : anc_hi[nt];
+                const unsigned long long w = rel < 64 ? anc_lo : anc_hi;
                 vis = (w >> (rel & 63)) & 1ull;
               }
               if (!vis) s[hf * 4 + v] = -INFINITY;
@@ -315,103 +287,143 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_wide_kernel
         // 2^16 (or it is still -inf); otherwise the tile costs one fma and one exp2 per score.
         const float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7]))) *
                          scale_log2;
-        if (__any(mx > m_run[nt] + 16.f)) {
-          const float m_new = fmaxf(m_run[nt], max_over_lane_groups(mx));
+        if (__any(mx > m_run + 16.f)) {
+          const float m_new = fmaxf(m_run, max_over_lane_groups(mx));
           const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
-          const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_ref);
-          m_run[nt] = m_new;
-          l_run[nt] *= alpha;
+          const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);
+          m_run = m_new;
+          l_run *= alpha;
 #pragma unroll
-          for (int db = 0; db < DB; ++db) O[nt][db] *= alpha;
+          for (int db = 0; db < DB; ++db) O[db] *= alpha;
         }
-        const float neg_m = (m_run[nt] == -INFINITY) ? 0.f : -m_run[nt];
+        const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
         float psum = 0.f;
-        bf16x8 pb;
+        bf16x8 pB;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const float p = __builtin_amdgcn_exp2f(fmaf(s[i], scale_log2, neg_m));   // i<4: first quarter, i>=4: second
           psum += p;
-          pb[i] = (__bf16)p;
+          pB[i] = (__bf16)p;
         }
-        pB[nt] = pb;
-        l_run[nt] += psum;
-      }
+        l_run += psum;
 
-      // ---- O^T += V^T P^T; V^T operand read once per d block, used by all query tiles
+        // ---- O^T += V^T P^T
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const unsigned char* base = Vs + (grp * 32 + 4 * g + (r16 >> 2)) * ROWB + db * 32 + (r16 & 3) * 8;
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(base));
-        const s16x4 hi =
-            __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(base + 16 * ROWB));
-        union { struct { s16x4 a, b; } p; bf16x8 v; } vt;
-        vt.p.a = lo;
-        vt.p.b = hi;
-#pragma unroll
-        for (int nt = 0; nt < NTW; ++nt)
-          O[nt][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt.v, pB[nt], O[nt][db], 0, 0, 0);
+        for (int db = 0; db < DB; ++db) {
+          const unsigned char* base = Vs + (grp * 32 + 4 * g + (r16 >> 2)) * ROWB + db * 32 + (r16 & 3) * 8;
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(base));
+          const s16x4 hi =
+              __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(base + 16 * ROWB));
+          union { struct { s16x4 a, b; } p; bf16x8 v; } vt;
+          vt.p.a = lo;
+          vt.p.b = hi;
+          O[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt.v, pB, O[db], 0, 0, 0);
+        }
       }
-#ifdef SPEC_WIDE_TIMELINE
-      asm volatile("" : "+v"(O[0][0]), "+v"(O[NTW - 1][DB - 1]));
-#endif
-    }
-  };
+    };
 
-  // ---- pipeline. Tiles 0 and 1 were requested together at the start. From then on tile ti is
-  // consumed from LDS stage ti&1 while tile ti+1 sits in the other stage and tiles ti+2, ti+3 are in
-  // flight in the two register sets: after the barrier that ends tile ti, tile ti+2 is written over
-  // it and tile ti+4 is requested into the registers just freed.
-  WTS_L(1, true)
-  stage_tile(Kr, Vr, 0, lds);
-  if (n_tiles > 2) issue_tile(Kr, Vr, 2);
-  if (n_tiles > 1) stage_tile(Kr2, Vr2, 1, lds + STAGE_BYTES);
-  if (n_tiles > 3) issue_tile(Kr2, Vr2, 3);
-  lds_barrier();
-  auto step = [&](int ti, u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT]) {
-    unsigned char* cur = lds + (ti & 1) * STAGE_BYTES;
-    WTS_L(2, ti == 0)
-    WTS_L(3, ti == n_clean)
-    if (ti >= n_clean) compute(ti, cur, std::true_type{});
-    else compute(ti, cur, std::false_type{});
+    // ---- pipeline. Tiles 0 and 1 were requested together at the start. From then on tile ti is
+    // consumed from LDS stage ti&1 while tile ti+1 sits in the other stage and tiles ti+2, ti+3 are in
+    // flight in the two register sets: after the barrier that ends tile ti, tile ti+2 is written over
+    // it and tile ti+4 is requested into the registers just freed.
+    stage_tile(Kr, Vr, 0, lds);
+    if (n_tiles > 2) issue_tile(Kr, Vr, 2);
+    if (n_tiles > 1) stage_tile(Kr2, Vr2, 1, lds + STAGE_BYTES);
+    if (n_tiles > 3) issue_tile(Kr2, Vr2, 3);
     lds_barrier();
-    if (ti + 2 < n_tiles) {
-      stage_tile(Kd, Vd, ti + 2, cur);
-      if (ti + 4 < n_tiles) issue_tile(Kd, Vd, ti + 4);
+    auto step = [&](int ti, u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT]) {
+      unsigned char* cur = lds + (ti & 1) * STAGE_BYTES;
+      if (ti >= n_clean) compute(ti, cur, std::true_type{});
+      else compute(ti, cur, std::false_type{});
+      lds_barrier();
+      if (ti + 2 < n_tiles) {
+        stage_tile(Kd, Vd, ti + 2, cur);
+        if (ti + 4 < n_tiles) issue_tile(Kd, Vd, ti + 4);
+      }
+    };
+    for (int ti = 0; ti < n_tiles; ti += 2) {
+      step(ti, Kr, Vr);
+      if (ti + 1 < n_tiles) step(ti + 1, Kr2, Vr2);
     }
-  };
-  for (int ti = 0; ti < n_tiles; ti += 2) {
-    step(ti, Kr, Vr);
-    if (ti + 1 < n_tiles) step(ti + 1, Kr2, Vr2);
-  }
-  lds_barrier();
-  WTS_L(4, true)
+    lds_barrier();
 
-  // ---- every wavefront owns its queries: normalise and write (or emit the split partial)
+    // ---- two key halves per query tile: the wavefront of the second half hands its state over through
+    // LDS (layout [query tile][register][lane], then m and l), the first merges.
+    float l_tot = sum_over_lane_groups(l_run);
+    if (KW == 2) {
+      float* mg = (float*)lds + qt * (64 * (DB * 4 + 2));
+      if (kpart == 1) {
 #pragma unroll
-  for (int nt = 0; nt < NTW; ++nt) {
-    const int n = q0 + nt * 16 + r16;
-    const float l_tot = sum_over_lane_groups(l_run[nt]);
-    if (n >= N) continue;
-    if (n_splits == 1) {
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) mg[(db * 4 + i) * 64 + lane] = O[db][i];
+        mg[(DB * 4) * 64 + lane] = m_run;
+        mg[(DB * 4 + 1) * 64 + lane] = l_tot;
+      }
+      lds_barrier();
+      if (kpart == 1) return;
+      const float m_other = mg[(DB * 4) * 64 + lane], l_other = mg[(DB * 4 + 1) * 64 + lane];
+      const float m_new = fmaxf(m_run, m_other);
+      const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+      const float a_self = __builtin_amdgcn_exp2f(m_run - m_ref), a_other = __builtin_amdgcn_exp2f(m_other - m_ref);
+      m_run = m_new;
+      l_tot = l_tot * a_self + l_other * a_other;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) O[db][i] = O[db][i] * a_self + mg[(db * 4 + i) * 64 + lane] * a_other;
+    }
+
+    // ---- normalise and write (or emit the partial)
+    const int n = q0 + r16;
+    if (n >= N) return;
+    if (final_out) {
       const float inv = 1.f / l_tot;
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
         union { uint2 u; __hip_bfloat16 h4[4]; } pk;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) pk.h4[i] = __float2bfloat16(O[nt][db][i] * inv);
+        for (int i = 0; i < 4; ++i) pk.h4[i] = __float2bfloat16(O[db][i] * inv);
         *(uint2*)(out + b * q_sb + n * q_sn + h * q_sh + db * 16 + 4 * g) = pk.u;
       }
     } else {
-      const long base = (((long)b * H + h) * n_splits + split) * N + n;
+      const long base = part_row + n;
 #pragma unroll
-      for (int db = 0; db < DB; ++db) *(f32x4*)(ws_o + base * D + db * 16 + 4 * g) = O[nt][db];
+      for (int db = 0; db < DB; ++db) *(f32x4*)(ws_o + base * D + db * 16 + 4 * g) = O[db];
       if (g == 0) {
-        ws_ml[base * 2 + 0] = m_run[nt];
+        ws_ml[base * 2 + 0] = m_run;
         ws_ml[base * 2 + 1] = l_tot;
       }
     }
+  };   // segment
+
+  if constexpr (!BAL) {
+    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    segment(b, h, split * chunk_keys, split * chunk_keys + chunk_keys,
+            n_splits == 1 ? -1l : (((long)b * H + h) * n_splits + split) * N);
+  } else {
+    // n_splits is the number of partial slots per pair: the workgroups overlapping a pair fill slots 0, 1, ...
+    const BalancedShare bs = balanced_share(prefix_len, B, N, H, S_cap, KT, (int)gridDim.x);
+    long pos = (long)blockIdx.x * bs.share;
+    const long end = min(bs.total, pos + bs.share);
+    int b = 0;
+    long req_start = 0;
+    int tb = request_tiles(prefix_len[0], N, S_cap, KT);
+    while (pos < end) {
+      while (pos >= req_start + (long)H * tb) {   // pos < total: a request with tiles left lies ahead
+        req_start += (long)H * tb;
+        ++b;
+        tb = request_tiles(prefix_len[b], N, S_cap, KT);
+      }
+      const long in_req = pos - req_start;
+      const int h = (int)(in_req / tb), tile0 = (int)(in_req % tb);
+      const int n_take = (int)min((long)(tb - tile0), end - pos);
+      const int slot = (int)blockIdx.x - (int)((req_start + (long)h * tb) / bs.share);
+      segment(b, h, tile0 * KT, (tile0 + n_take) * KT, (((long)b * H + h) * n_splits + slot) * N);
+      pos += n_take;
+      lds_barrier();   // LDS (staging tiles, merge area, tree arrays) is reused by the next segment
+    }
   }
-  WTS(5, true)
 }
 
 }  // namespace wide
@@ -423,26 +435,31 @@ hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const Attn
   const float scale = (d.softmax_scale != 0.f ? d.softmax_scale : 1.0f / sqrtf((float)d.D)) * wide::kLog2e;
   float* ws_o = ws ? (float*)((char*)ws + plan.ws_o_off) : nullptr;
   float* ws_ml = ws ? (float*)((char*)ws + plan.ws_ml_off) : nullptr;
-  // one 16-query tile per wavefront: four wavefronts up to 64 nodes, eight up to 128
-  const int waves = d.N <= 64 ? 4 : 8, ntw = 1;
-  const int nq = waves * ntw * 16;
-  const int n_qgroups = (d.N + nq - 1) / nq;
+  // one 16-query tile per wavefront: 2 x 2 key halves up to 32 nodes, four up to 64, eight up to 128
+  const int qw = d.N <= 32 ? 2 : d.N <= 64 ? 4 : 8;
   const bool append = k_new != nullptr;
-  dim3 grid(plan.n_splits, d.H * n_qgroups, d.B);
-#define SPEC_LAUNCH(DD, WW, NTT, APP)                                                                                 \
-  hipLaunchKernelGGL((wide::tree_attention_bf16_wide_kernel<DD, WW, NTT, APP>), grid, dim3(WW * 64), 0, s,            \
+  const bool bal = plan.balanced_wgs > 0;
+  const dim3 grid = bal ? dim3(plan.balanced_wgs, 1, 1) : dim3(plan.n_splits, d.H, d.B);
+#define SPEC_LAUNCH(DD, QQ, KK, APP, BAL)                                                                             \
+  hipLaunchKernelGGL((wide::tree_attention_bf16_wide_kernel<DD, QQ, KK, APP, BAL>), grid, dim3(QQ * KK * 64), 0, s,   \
                      (const __hip_bfloat16*)q, (__hip_bfloat16*)k_cache, (__hip_bfloat16*)v_cache,                    \
                      (const __hip_bfloat16*)k_new, (const __hip_bfloat16*)v_new, parent, depth, prefix_len,           \
-                     (__hip_bfloat16*)out, ws_o, ws_ml, status, d.N, d.H, d.S_cap, n_qgroups, plan.chunk_keys,        \
+                     (__hip_bfloat16*)out, ws_o, ws_ml, status, d.B, d.N, d.H, d.S_cap, plan.chunk_keys,              \
                      plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h, (long)d.kv_stride_b,  \
                      (long)d.kv_stride_h, (long)d.kv_stride_s, scale)
-#define SPEC_DISPATCH(APP)                                    \
-  if (d.D == 128 && waves == 4) SPEC_LAUNCH(128, 4, 1, APP);  \
-  else if (d.D == 128) SPEC_LAUNCH(128, 8, 1, APP);           \
-  else if (waves == 4) SPEC_LAUNCH(64, 4, 1, APP);            \
-  else SPEC_LAUNCH(64, 8, 1, APP)
-  if (append) { SPEC_DISPATCH(true); } else { SPEC_DISPATCH(false); }
+#define SPEC_SHAPES(DD, APP, BAL)                      \
+  if (qw == 2) SPEC_LAUNCH(DD, 2, 2, APP, BAL);        \
+  else if (qw == 4) SPEC_LAUNCH(DD, 4, 1, APP, BAL);   \
+  else SPEC_LAUNCH(DD, 8, 1, APP, BAL)
+#define SPEC_DISPATCH(APP, BAL)                        \
+  if (d.D == 128) { SPEC_SHAPES(128, APP, BAL); }      \
+  else { SPEC_SHAPES(64, APP, BAL); }
+  if (append && bal) { SPEC_DISPATCH(true, true); }
+  else if (append) { SPEC_DISPATCH(true, false); }
+  else if (bal) { SPEC_DISPATCH(false, true); }
+  else { SPEC_DISPATCH(false, false); }
 #undef SPEC_DISPATCH
+#undef SPEC_SHAPES
 #undef SPEC_LAUNCH
   return hipGetLastError();
 }

@@ -165,51 +165,67 @@ __global__ void __launch_bounds__(256) tree_attention_f32_kernel(
   }
 }
 
-// Merge of the per-chunk partials: out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), M = max_s m_s.
-// grid = (H, B), 256 threads; a thread owns 4 consecutive d of some queries. Also the place where a
-// malformed request gets its defined result (zeros) when more than one split is used.
+// Merge of the partials of one (request, head): out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M),
+// M = max_s m_s. grid = (H, B, ceil(N * D/4 / 256)), 256 threads; a thread owns 4 consecutive d of one
+// query. The partials of a pair are `slots` consecutive blocks of N rows; how many are filled follows
+// from the plan: fixed chunks (chunk_keys > 0) or the balanced deal (bal_wgs > 0). Also the place where
+// a malformed request gets its defined result (zeros) and its status bit.
 template <bool BF16>
 __global__ void __launch_bounds__(256) attn_combine_kernel(const float* __restrict__ ws_o, const float* __restrict__ ws_ml,
                                                            const int32_t* __restrict__ parent,
                                                            const int32_t* __restrict__ depth,
                                                            const int32_t* __restrict__ prefix_len, void* __restrict__ out,
-                                                           int32_t* status, int N, int H, int D, int S_cap,
-                                                           int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh) {
+                                                           int32_t* status, int B, int N, int H, int D, int S_cap,
+                                                           int chunk_keys, int slots, int bal_wgs, int bal_tile, long q_sb,
+                                                           long q_sn, long q_sh) {
   __shared__ int s_flag;
   const int h = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
   const int P = prefix_len[b];
   const bool cap_ok = (P >= 0) && (P <= S_cap - N);
   const bool valid = tree_is_valid(parent + (long)b * N, depth + (long)b * N, N, &s_flag) && cap_ok;
-  if (!valid && h == 0 && t == 0) set_status(status, b, cap_ok ? SPEC_ST_BAD_TREE : SPEC_ST_CAPACITY);
-  const int ns = valid ? min(n_splits, (P + N + chunk_keys - 1) / chunk_keys) : 0;
-  const int CG = D / 4;
-  for (int idx = t; idx < N * CG; idx += 256) {
-    const int n = idx / CG, cg = idx % CG;
-    const long base = (((long)b * H + h) * n_splits) * N + n;
-    float M = -INFINITY;
-    for (int s = 0; s < ns; ++s) M = fmaxf(M, ws_ml[(base + (long)s * N) * 2]);
-    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-    float l = 0.f;
-    for (int s = 0; s < ns; ++s) {
-      const float m = ws_ml[(base + (long)s * N) * 2];
-      if (m == -INFINITY) continue;
-      const float w = exp2f(m - M);
-      l = fmaf(ws_ml[(base + (long)s * N) * 2 + 1], w, l);
-      const float4 p = *(const float4*)(ws_o + (base + (long)s * N) * D + cg * 4);
-      o.x = fmaf(p.x, w, o.x); o.y = fmaf(p.y, w, o.y); o.z = fmaf(p.z, w, o.z); o.w = fmaf(p.w, w, o.w);
-    }
-    const float inv = (l > 0.f) ? 1.f / l : 0.f;
-    o.x *= inv; o.y *= inv; o.z *= inv; o.w *= inv;
-    const long off = b * q_sb + n * q_sn + h * q_sh + cg * 4;
-    if (BF16) {
-      __hip_bfloat16* ob = (__hip_bfloat16*)out + off;
-      union { uint2 u; __hip_bfloat16 h4[4]; } pk;
-      pk.h4[0] = __float2bfloat16(o.x); pk.h4[1] = __float2bfloat16(o.y);
-      pk.h4[2] = __float2bfloat16(o.z); pk.h4[3] = __float2bfloat16(o.w);
-      *(uint2*)ob = pk.u;
+  if (!valid && h == 0 && blockIdx.z == 0 && t == 0) set_status(status, b, cap_ok ? SPEC_ST_BAD_TREE : SPEC_ST_CAPACITY);
+  int ns = 0;
+  if (valid) {
+    if (bal_wgs > 0) {
+      const BalancedShare bs = balanced_share(prefix_len, B, N, H, S_cap, bal_tile, bal_wgs);
+      long req_start = 0;
+      for (int bb = 0; bb < b; ++bb) req_start += (long)H * request_tiles(prefix_len[bb], N, S_cap, bal_tile);
+      const int tb = request_tiles(P, N, S_cap, bal_tile);
+      const long pair_start = req_start + (long)h * tb;
+      ns = (int)((pair_start + tb - 1) / bs.share - pair_start / bs.share) + 1;
     } else {
-      *(float4*)((float*)out + off) = o;
+      ns = min(slots, (P + N + chunk_keys - 1) / chunk_keys);
     }
+  }
+  const int CG = D / 4;
+  const int idx = blockIdx.z * 256 + t;
+  if (idx >= N * CG) return;
+  const int n = idx / CG, cg = idx % CG;
+  const long base = (((long)b * H + h) * slots) * N + n;
+  float M = -INFINITY;
+#pragma unroll 4
+  for (int s = 0; s < ns; ++s) M = fmaxf(M, ws_ml[(base + (long)s * N) * 2]);
+  float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+  float l = 0.f;
+#pragma unroll 4
+  for (int s = 0; s < ns; ++s) {
+    const float m = ws_ml[(base + (long)s * N) * 2];
+    const float w = (m == -INFINITY) ? 0.f : exp2f(m - M);   // an all-masked partial carries nothing
+    l = fmaf(ws_ml[(base + (long)s * N) * 2 + 1], w, l);
+    const float4 p = *(const float4*)(ws_o + (base + (long)s * N) * D + cg * 4);
+    o.x = fmaf(p.x, w, o.x); o.y = fmaf(p.y, w, o.y); o.z = fmaf(p.z, w, o.z); o.w = fmaf(p.w, w, o.w);
+  }
+  const float inv = (l > 0.f) ? 1.f / l : 0.f;
+  o.x *= inv; o.y *= inv; o.z *= inv; o.w *= inv;
+  const long off = b * q_sb + n * q_sn + h * q_sh + cg * 4;
+  if (BF16) {
+    __hip_bfloat16* ob = (__hip_bfloat16*)out + off;
+    union { uint2 u; __hip_bfloat16 h4[4]; } pk;
+    pk.h4[0] = __float2bfloat16(o.x); pk.h4[1] = __float2bfloat16(o.y);
+    pk.h4[2] = __float2bfloat16(o.z); pk.h4[3] = __float2bfloat16(o.w);
+    *(uint2*)ob = pk.u;
+  } else {
+    *(float4*)((float*)out + off) = o;
   }
 }
 
@@ -236,15 +252,16 @@ hipError_t launch_attn_combine(const spec_attn_desc_t& d, const AttnPlan& plan, 
                                int32_t* status, hipStream_t s) {
   const float* ws_o = (const float*)((const char*)ws + plan.ws_o_off);
   const float* ws_ml = (const float*)((const char*)ws + plan.ws_ml_off);
-  dim3 grid(d.H, d.B);
+  const int items = d.N * (d.D / 4);
+  dim3 grid(d.H, d.B, (items + 255) / 256);
   if (d.dtype == SPEC_BF16) {
     hipLaunchKernelGGL(attn_combine_kernel<true>, grid, dim3(256), 0, s, ws_o, ws_ml, parent, depth, prefix_len, out,
-                       status, d.N, d.H, d.D, d.S_cap, plan.chunk_keys, plan.n_splits, (long)d.q_stride_b,
-                       (long)d.q_stride_n, (long)d.q_stride_h);
+                       status, d.B, d.N, d.H, d.D, d.S_cap, plan.chunk_keys, plan.n_splits, plan.balanced_wgs, plan.balanced_tile,
+                       (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h);
   } else {
     hipLaunchKernelGGL(attn_combine_kernel<false>, grid, dim3(256), 0, s, ws_o, ws_ml, parent, depth, prefix_len, out,
-                       status, d.N, d.H, d.D, d.S_cap, plan.chunk_keys, plan.n_splits, (long)d.q_stride_b,
-                       (long)d.q_stride_n, (long)d.q_stride_h);
+                       status, d.B, d.N, d.H, d.D, d.S_cap, plan.chunk_keys, plan.n_splits, plan.balanced_wgs, plan.balanced_tile,
+                       (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h);
   }
   return hipGetLastError();
 }

@@ -45,24 +45,34 @@ def _check_attention(out_gpu, ref64, dtype):
     return float(err.max())
 
 
-class _chunk_keys:
-    """Forces the number of keys per workgroup so that small inputs span several chunks."""
+class _plan_env:
+    """Sets one of the library's launch-plan overrides for the duration of a block."""
 
-    def __init__(self, n):
-        self.n = n
+    def __init__(self, name, n):
+        self.name, self.n = name, n
 
     def __enter__(self):
-        self.old = os.environ.get("SPEC_TREE_CHUNK_KEYS")
-        if self.n:
-            os.environ["SPEC_TREE_CHUNK_KEYS"] = str(self.n)
+        self.old = os.environ.get(self.name)
+        if self.n is not None and self.n != 0:
+            os.environ[self.name] = str(self.n)
         else:
-            os.environ.pop("SPEC_TREE_CHUNK_KEYS", None)
+            os.environ.pop(self.name, None)
 
     def __exit__(self, *a):
         if self.old is None:
-            os.environ.pop("SPEC_TREE_CHUNK_KEYS", None)
+            os.environ.pop(self.name, None)
         else:
-            os.environ["SPEC_TREE_CHUNK_KEYS"] = self.old
+            os.environ[self.name] = self.old
+
+
+def _chunk_keys(n):
+    """Forces the number of keys per workgroup so that small inputs span several chunks."""
+    return _plan_env("SPEC_TREE_CHUNK_KEYS", n)
+
+
+def _balanced_wgs(n):
+    """Forces the balanced plan (equal shares of 32-key tiles over n workgroups) on small inputs."""
+    return _plan_env("SPEC_TREE_BALANCED_WGS", n)
 
 
 def _run_append_attention(spec, inp, layer=0, status=None, fused=False):
@@ -121,6 +131,8 @@ SMALL = [
     ("bf16", 2, 2, 128, (0, 5), 16, "random_parent", 0),
     ("bf16", 3, 2, 128, (33, 97), 7, "random_parent", 32),
     ("bf16", 2, 2, 128, (130, 300), 32, "random_branching", 96),
+    ("bf16", 2, 2, 128, (130, 300), 17, "random_branching", 0),
+    ("bf16", 2, 2, 64, (0, 300), 25, "random_parent", 64),
     ("bf16", 2, 2, 128, (130, 300), 33, "random_branching", 128),
     ("bf16", 1, 2, 128, (250, 250), 64, "random_branching", 64),
     ("bf16", 2, 2, 128, (100, 260), 100, "random_branching", 160),
@@ -146,6 +158,37 @@ def test_small_shapes_attention_and_append(spec, case):
             out, kc, vc = _run_append_attention(spec, inp, fused=fused)
         _check_attention(out, ref, cfg.torch_dtype)
         # append is a bit copy: compare the whole cache (float64 conversion of either dtype is exact)
+        assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco), fused
+
+
+BALANCED = [
+    # B, H, D, (P lo, hi), N, tree, workgroups
+    (3, 2, 128, (40, 300), 16, "expansion", 5),
+    (3, 2, 128, (40, 300), 32, "random_branching", 7),
+    (4, 3, 128, (0, 100), 7, "random_parent", 64),      # more workgroups than tiles: shares of one tile
+    (2, 2, 64, (100, 400), 32, "random_branching", 3),
+    (2, 2, 64, (100, 400), 16, "random_parent", 1),     # one workgroup walks every (request, head)
+    (1, 2, 128, (1000, 1000), 16, "expansion", 16),
+    (2, 2, 128, (100, 700), 17, "random_branching", 6),
+    (2, 3, 128, (100, 500), 64, "random_branching", 7),
+    (2, 2, 128, (60, 400), 100, "random_branching", 5),
+    (1, 2, 64, (900, 900), 128, "random_branching", 9),
+]
+
+
+@pytest.mark.parametrize("case", BALANCED, ids=[f"B{c[0]}H{c[1]}D{c[2]}P{c[3][0]}-{c[3][1]}N{c[4]}-{c[5]}-wg{c[6]}" for c in BALANCED])
+def test_balanced_plan_attention_and_append(spec, case):
+    """The balanced plan of the few-query bf16 kernel: shares that start and end inside a pair, cross
+    pair and request boundaries, or are empty."""
+    B, H, D, P, N, tree, wgs = case
+    cfg = wl.Config(92, "balanced", "bf16", B=B, H=H, D=D, P=P if P[0] != P[1] else P[0], N=N, tree=tree,
+                    widths=wl.EXPANSION_EVAL * 2)
+    inp = wl.make_attention_inputs(cfg, seed=2000 + N + D + B + wgs, S_cap=P[1] + N + 5)
+    ref, kco, vco = _oracle_append_attention(inp)
+    for fused in (False, True):
+        with _balanced_wgs(wgs):
+            out, kc, vc = _run_append_attention(spec, inp, fused=fused)
+        _check_attention(out, ref, cfg.torch_dtype)
         assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco), fused
 
 
@@ -180,13 +223,13 @@ def test_large_configs_sampled_heads(spec, c):
 def test_attention_status_bits_and_noop(spec):
     """Malformed trees and requests that do not fit are flagged and produce zeros; others unaffected."""
     cfg = wl.Config(91, "bad", "bf16", B=4, H=2, D=128, P=(40, 90), N=16, tree="random_parent")
-    for chunk, fused in ((0, False), (64, False), (0, True), (64, True)):
+    for chunk, fused, wgs in ((0, False, 0), (64, False, 0), (0, True, 0), (64, True, 0), (0, False, 5), (0, True, 3)):
         inp = wl.make_attention_inputs(cfg, seed=5, S_cap=90 + 16)
         inp["tree_parent"][1, 5] = 9            # parent after child
         inp["tree_depth"][2, 7] += 1            # depth inconsistent with parent
         inp["prefix_len"][3] = 90 + 1           # prefix + N > S_cap
         status = torch.zeros(cfg.B, dtype=torch.int32, device=DEV)
-        with _chunk_keys(chunk):
+        with _chunk_keys(chunk), _balanced_wgs(wgs):
             out, kc, vc = _run_append_attention(spec, inp, status=status, fused=fused)
         st = status.cpu().numpy()
         assert st[0] == 0 and st[1] == orc.ST_BAD_TREE and st[2] == orc.ST_BAD_TREE and st[3] == orc.ST_CAPACITY
