@@ -71,10 +71,11 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d) {
     // more workgroups than pairs, each with at least 512 keys at the stated maximum length.
     const int tile = d.N <= 16 ? SPEC_SMALL_TILE_KEYS : SPEC_WIDE_TILE_KEYS;
     const int resident_per_cu = (d.N > 16 && d.N <= 64) ? 2 : 1;   // four-wavefront workgroups: two per compute unit
+    const long resident = (long)compute_units() * resident_per_cu;
     int wgs = env_int("SPEC_TREE_BALANCED_WGS", -1);
     if (wgs < 0) {
       const long max_tiles = groups * ((max_len + tile - 1) / tile);
-      const long cand = std::min<long>((long)compute_units() * resident_per_cu, max_tiles / (512 / tile));
+      const long cand = std::min<long>(resident, max_tiles / (512 / tile));
       wgs = cand > groups ? (int)cand : 0;
     }
     if (wgs > 0) {

@@ -1,10 +1,12 @@
 // Tree attention for bf16 K/V on the gfx950 matrix cores (Definition 4.1; topology-aware causal mask
-// of Section 4.2), written for the decode-shaped case: few tree queries (N <= 128) against a long
-// cached prefix, so the kernel is bound by streaming K and V from HBM exactly once.
+// of Section 4.2), written for the decode-shaped case: few tree queries (N <= 16, one MFMA query
+// tile; larger trees go to the kernel in tree_attention_bf16_wide.hip) against a long cached prefix,
+// so the kernel is bound by streaming K and V from HBM exactly once.
 //
 // Decomposition
-//   grid = (n_splits, H * n_qgroups, B). A workgroup owns one chunk of the key range of one
-//   (request, head) and a group of NT*16 tree queries. It has five wavefronts:
+//   grid = (n_splits, H, B), or (BAL) gridDim.x workgroups that share the 32-key tiles of all
+//   (request, head) pairs equally (see balanced_share()). A workgroup owns one segment of the key
+//   range of one (request, head) at a time and all its tree queries. It has five wavefronts:
 //     - four streaming wavefronts take the chunk's mask-free 32-key tiles (entirely inside the cached
 //       prefix) round-robin; they never need the tree, a mask, or a barrier inside their loop;
 //     - one tail wavefront owns the ragged end: the tiles that reach past prefix_len (the tree rows,
@@ -35,8 +37,8 @@
 // With APPEND the kernel also performs the KV append of the tree tokens (Section 4.2): rows at and
 // beyond prefix_len are taken from k_new / v_new and written to the cache by query group 0.
 //
-// Results are written as the final bf16 output when one chunk covers the whole key range, else as
-// float32 partials (m, l, O) merged by attn_combine_kernel.
+// Results are written as the final bf16 output when one workgroup covers the whole key range of a
+// pair, else as float32 partials (m, l, O) merged by attn_combine_kernel.
 #include <hip/hip_bf16.h>
 
 #include <cstdlib>
@@ -541,9 +543,7 @@ hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan&
   const float scale = (d.softmax_scale != 0.f ? d.softmax_scale : 1.0f / sqrtf((float)d.D)) * kLog2eB;
   float* ws_o = ws ? (float*)((char*)ws + plan.ws_o_off) : nullptr;
   float* ws_ml = ws ? (float*)((char*)ws + plan.ws_ml_off) : nullptr;
-  const int nt = d.N <= 16 ? 1 : 2;
-  const int nq = nt * 16;
-  const int n_qgroups = (d.N + nq - 1) / nq;
+  const int n_qgroups = 1;   // one 16-query tile covers the trees this kernel serves
   const bool append = k_new != nullptr;
   const bool bal = plan.balanced_wgs > 0;
   const dim3 grid = bal ? dim3(plan.balanced_wgs, 1, 1) : dim3(plan.n_splits, d.H * n_qgroups, d.B);
@@ -554,11 +554,9 @@ hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan&
                      (__hip_bfloat16*)out, ws_o, ws_ml, status, d.B, d.N, d.H, d.S_cap, n_qgroups,               \
                      plan.chunk_keys, plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h, \
                      (long)d.kv_stride_b, (long)d.kv_stride_h, (long)d.kv_stride_s, scale)
-#define SPEC_DISPATCH(APP, BAL)                                \
-  if (d.D == 128 && nt == 1) SPEC_LAUNCH(128, 1, APP, BAL);    \
-  else if (d.D == 128) SPEC_LAUNCH(128, 2, APP, BAL);          \
-  else if (nt == 1) SPEC_LAUNCH(64, 1, APP, BAL);              \
-  else SPEC_LAUNCH(64, 2, APP, BAL)
+#define SPEC_DISPATCH(APP, BAL)                  \
+  if (d.D == 128) SPEC_LAUNCH(128, 1, APP, BAL); \
+  else SPEC_LAUNCH(64, 1, APP, BAL)
   if (append && bal) { SPEC_DISPATCH(true, true); }
   else if (append) { SPEC_DISPATCH(true, false); }
   else if (bal) { SPEC_DISPATCH(false, true); }

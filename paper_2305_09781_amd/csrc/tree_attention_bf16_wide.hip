@@ -20,9 +20,9 @@
 // the compute step; the loader threads zero rows past the end, and with APPEND fetch rows >= prefix_len
 // from k_new / v_new and write them to the cache.
 //
-// Work split: fixed chunks, grid = (n_splits, H, B), or (BAL) the balanced deal of 64-key tiles over
-// gridDim.x workgroups described at balanced_share(); a share that crosses a (request, head) boundary
-// is processed as several segments.
+// Work split (PLAN): fixed chunks, grid = (n_splits, H, B); or the balanced deal of 64-key tiles over
+// gridDim.x workgroups described at balanced_share(), a share that crosses a (request, head) boundary
+// being processed as several segments.
 #include <hip/hip_bf16.h>
 
 #include <type_traits>
@@ -38,8 +38,32 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 namespace wide {
 
+#ifdef SPEC_WIDE_TIMELINE
+// Development aid: per-wavefront timestamps (100 MHz clock) and placement, written to the workspace.
+#define WTL(slot)                                                                                               \
+  {                                                                                                             \
+    unsigned long long ts_;                                                                                     \
+    asm volatile("s_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(ts_)::"memory");                             \
+    if (lane == 0)                                                                                              \
+      ((unsigned long long*)ws_o)[((blockIdx.x + (long)gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)) * WAVES + wave) * 8 + (slot)] = ts_; \
+  }
+#define WTL_HW()                                                                                                \
+  {                                                                                                             \
+    unsigned hw_, xcc_;                                                                                         \
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)\n\ts_getreg_b32 %1, hwreg(HW_REG_XCC_ID)" : "=s"(hw_), "=s"(xcc_)); \
+    if (lane == 0) {                                                                                            \
+      unsigned long long* p_ = (unsigned long long*)ws_o + ((blockIdx.x + (long)gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)) * WAVES + wave) * 8; \
+      p_[2] = hw_; p_[3] = xcc_;                                                                                \
+    }                                                                                                           \
+  }
+#else
+#define WTL(slot)
+#define WTL_HW()
+#endif
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int KT = SPEC_WIDE_TILE_KEYS;   // keys per workgroup tile
+constexpr int PLAN_GRID = 0, PLAN_TILES = 1;   // how work reaches the workgroups (see the end of the kernel)
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 __device__ __forceinline__ void store_nt(void* p, u32x4 v) {
@@ -56,16 +80,16 @@ __device__ inline float sum_over_lane_groups(float v) {
   return v;
 }
 
-// QW query tiles x KW key parts: wavefront w serves query tile w % QW and (KW == 2) the 32-key half
-// w / QW of every 64-key tile.
-template <int D, int QW, int KW, bool APPEND, bool BAL>
+// QW query wavefronts (NTW 16-query tiles each) x KW key parts: wavefront w serves query tiles
+// (w % QW) * NTW .. + NTW and (KW == 2) the 32-key half w / QW of every 64-key tile.
+template <int D, int QW, int NTW, int KW, bool APPEND, int PLAN>
 __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kernel(
     const __hip_bfloat16* __restrict__ q, __hip_bfloat16* k_cache, __hip_bfloat16* v_cache,
     const __hip_bfloat16* __restrict__ k_new, const __hip_bfloat16* __restrict__ v_new,
     const int32_t* __restrict__ parent, const int32_t* __restrict__ depth, const int32_t* __restrict__ prefix_len,
     __hip_bfloat16* __restrict__ out, float* __restrict__ ws_o, float* __restrict__ ws_ml, int32_t* status, int B, int N,
-    int H, int S_cap, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long kv_sb, long kv_sh, long kv_ss,
-    float scale_log2) {
+    int H, int S_cap, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long kv_sb, long kv_sh,
+    long kv_ss, float scale_log2) {
   static_assert(KW == 1 || KW == 2, "a 64-key tile is consumed as two 32-key halves");
   constexpr int WAVES = QW * KW;
   constexpr int NTHREADS = WAVES * 64;
@@ -77,7 +101,7 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
   constexpr int STAGE_BYTES = 2 * MAT_BYTES;
   constexpr int ROW_STEP = NTHREADS / LPR;
   static_assert(NPT >= 1 && KT % ROW_STEP == 0, "loader layout");
-  static_assert(KW == 1 || QW * 64 * (DB * 4 + 2) * 4 <= 2 * STAGE_BYTES, "merge area fits the staging area");
+  static_assert(KW == 1 || QW * NTW * 64 * (DB * 4 + 2) * 4 <= 2 * STAGE_BYTES, "merge area fits the staging area");
 
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE_BYTES];
   __shared__ unsigned long long s_anc[SPEC_MAX_TREE_NODES][2];
@@ -89,9 +113,28 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int r16 = lane & 15, g = lane >> 4;
   const int qt = wave % QW, kpart = wave / QW;
-  const int q0 = qt * 16;   // first query of this wavefront
+  const int q0 = qt * NTW * 16;   // first query of this wavefront
   // loader role of this thread: piece j of a tile is row (t + NTHREADS j) / LPR, 16-byte column (t % LPR)
   const int ld_row0 = t / LPR, ld_col = (t % LPR) * 16;
+  WTL(0)
+  WTL_HW()
+
+  // two register sets: the two tiles in flight from global memory (tiles ti+2 and ti+3 while tile ti is
+  // consumed from LDS and tile ti+1 waits there)
+  u32x4 Kr[NPT], Vr[NPT];
+  u32x4 Kr2[NPT], Vr2[NPT];
+  const unsigned cache_row_bytes = (unsigned)kv_ss * 2u, new_row_bytes = (unsigned)q_sn * 2u;
+  // Speculative request of one tile: cache rows only, clamped to the capacity, no prefix_len needed.
+  auto issue_speculative = [&](u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT], const unsigned char* kbase, const unsigned char* vbase,
+                               int k0) {
+#pragma unroll
+    for (int j = 0; j < NPT; ++j) {
+      const int row = min(k0 + ld_row0 + j * ROW_STEP, S_cap - 1);
+      const long off = (long)((unsigned)row * cache_row_bytes);
+      Vd[j] = *(const u32x4*)(vbase + off + ld_col);
+      Kd[j] = *(const u32x4*)(kbase + off + ld_col);
+    }
+  };
 
   // One segment: keys [c0, min(c1_cap, prefix_len + N)) of request b, head h. The result is the final
   // output (part_row < 0) or the float32 partial whose first row in the workspace is part_row.
@@ -100,18 +143,13 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
 
     // ---- straight-line prologue: first two tiles (they do not depend on prefix_len), Q, one tree node per thread
     const int P = prefix_len[b];
-    const unsigned cache_row_bytes = (unsigned)kv_ss * 2u, new_row_bytes = (unsigned)q_sn * 2u;
     const unsigned char* kc = (const unsigned char*)(k_cache + b * kv_sb + h * kv_sh);
     const unsigned char* vc = (const unsigned char*)(v_cache + b * kv_sb + h * kv_sh);
     const unsigned char* kn = APPEND ? (const unsigned char*)(k_new + b * q_sb + h * q_sh) : nullptr;
     const unsigned char* vn = APPEND ? (const unsigned char*)(v_new + b * q_sb + h * q_sh) : nullptr;
     const long new_minus_cache_k = APPEND ? (long)(kn - kc) : 0, new_minus_cache_v = APPEND ? (long)(vn - vc) : 0;
 
-    // two register sets: the two tiles in flight from global memory (tiles ti+2 and ti+3 while tile ti is
-    // consumed from LDS and tile ti+1 waits there)
-    u32x4 Kr[NPT], Vr[NPT];
-    u32x4 Kr2[NPT], Vr2[NPT];
-    // MODE: 0 = cache rows clamped to the capacity (speculative), 1 = clean (no clamp), 2 = tail (clamp, new rows)
+    // MODE: 1 = clean (no clamp), 2 = tail (clamp, new rows)
     auto issue = [&](u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT], int k0, auto mode_tag, int Pk, int last_row) {
       constexpr int MODE = decltype(mode_tag)::value;
 #pragma unroll
@@ -132,16 +170,17 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
         Kd[j] = *(const u32x4*)(kc + off_k + ld_col);
       }
     };
-    issue(Kr, Vr, c0, std::integral_constant<int, 0>{}, 0, S_cap - 1);
-    issue(Kr2, Vr2, c0 + KT, std::integral_constant<int, 0>{}, 0, S_cap - 1);
+    issue_speculative(Kr, Vr, kc, vc, c0);
+    issue_speculative(Kr2, Vr2, kc, vc, c0 + KT);
 
-    bf16x8 qB[KS];
-    {
-      const int n = q0 + r16;
+    bf16x8 qB[NTW][KS];
+#pragma unroll
+    for (int nt = 0; nt < NTW; ++nt) {
+      const int n = q0 + nt * 16 + r16;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const u32x4 raw = *(const u32x4*)(q + b * q_sb + min(n, N - 1) * q_sn + h * q_sh + ks * 32 + g * 8);
-        qB[ks] = __builtin_bit_cast(bf16x8, raw);
+        qB[nt][ks] = __builtin_bit_cast(bf16x8, raw);
       }
     }
     const int my_parent = parent[(long)b * N + min(t, N - 1)];
@@ -157,7 +196,7 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     const int len = P + N;
     auto zero_outputs = [&](int bit) {
       if (final_out) {
-        for (int i = t; i < QW * 16 * D; i += NTHREADS) {
+        for (int i = t; i < QW * NTW * 16 * D; i += NTHREADS) {
           const int n = i / D;
           if (n < N) out[b * q_sb + n * q_sn + h * q_sh + (i % D)] = __float2bfloat16(0.f);
         }
@@ -180,7 +219,9 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     if (APPEND && n_clean <= 1 && n_tiles > 1) issue(Kr2, Vr2, c0 + KT, std::integral_constant<int, 2>{}, P, last_row);
 
     // ---- tree: validate, build ancestor-or-self masks (LDS-only barriers: the tile loads stay in flight)
-    unsigned long long anc_lo = 0ull, anc_hi = 0ull;
+    unsigned long long anc_lo[NTW], anc_hi[NTW];
+#pragma unroll
+    for (int nt = 0; nt < NTW; ++nt) anc_lo[nt] = anc_hi[nt] = 0ull;
     if (touches_tree) {
       if (t < N) {
         bool ok = (t == 0) ? (my_parent == -1 && my_depth == 0) : (my_parent >= 0 && my_parent < t);
@@ -203,8 +244,11 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
         s_anc[t][1] = hi;
       }
       lds_barrier();
-      const int n = q0 + r16;
-      if (n < N) { anc_lo = s_anc[n][0]; anc_hi = s_anc[n][1]; }
+#pragma unroll
+      for (int nt = 0; nt < NTW; ++nt) {
+        const int n = q0 + nt * 16 + r16;
+        if (n < N) { anc_lo[nt] = s_anc[n][0]; anc_hi[nt] = s_anc[n][1]; }
+      }
     }
 
     // registers -> LDS stage; masked tiles: rows past the segment end become zeros, appended rows go to the cache
@@ -234,10 +278,15 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
       else issue(Kd, Vd, k0, std::integral_constant<int, 2>{}, P, last_row);
     };
 
-    f32x4 O[DB];
-    float m_run = -INFINITY, l_run = 0.f;
+    f32x4 O[NTW][DB];
+    float m_run[NTW], l_run[NTW];
 #pragma unroll
-    for (int db = 0; db < DB; ++db) O[db] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int nt = 0; nt < NTW; ++nt) {
+      m_run[nt] = -INFINITY;
+      l_run[nt] = 0.f;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) O[nt][db] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
 
     auto compute = [&](const int ti, const unsigned char* stage, auto masked_tag) {
       constexpr bool MASKED = decltype(masked_tag)::value;
@@ -248,66 +297,75 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
 #pragma unroll
       for (int part = 0; part < 2 / KW; ++part) {
         const int grp = KW == 2 ? kpart : part;
-        // ---- S^T = K Q^T for two 16-key quarters
-        f32x4 sc[2];
+        // ---- S^T = K Q^T for two 16-key quarters; a K operand is read once and used by all query tiles
+        f32x4 sc[NTW][2];
 #pragma unroll
-        for (int hf = 0; hf < 2; ++hf) {
-          sc[hf] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int nt = 0; nt < NTW; ++nt)
 #pragma unroll
-          for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 a = *(const bf16x8*)(Ks + (grp * 32 + hf * 16 + r16) * ROWB + ks * 64 + g * 16);
-            sc[hf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qB[ks], sc[hf], 0, 0, 0);
-          }
-        }
-
-        float s[8];   // raw scores (before the softmax scale)
+          for (int hf = 0; hf < 2; ++hf) sc[nt][hf] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-          for (int v = 0; v < 4; ++v) s[hf * 4 + v] = sc[hf][v];
-        if (MASKED) {
+          for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 a = *(const bf16x8*)(Ks + (grp * 32 + hf * 16 + r16) * ROWB + ks * 64 + g * 16);
+#pragma unroll
+            for (int nt = 0; nt < NTW; ++nt)
+              sc[nt][hf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qB[nt][ks], sc[nt][hf], 0, 0, 0);
+          }
+
+        bf16x8 pB[NTW];
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) {
+          float s[8];   // raw scores (before the softmax scale)
 #pragma unroll
           for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-              const int key = k0 + grp * 32 + hf * 16 + 4 * g + v;
-              const int rel = key - P;
-              bool vis = key < c1;
-              if (vis && rel >= 0) {
-                const unsigned long long w = rel < 64 ? anc_lo : anc_hi;
-                vis = (w >> (rel & 63)) & 1ull;
+            for (int v = 0; v < 4; ++v) s[hf * 4 + v] = sc[nt][hf][v];
+          if (MASKED) {
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+              for (int v = 0; v < 4; ++v) {
+                const int key = k0 + grp * 32 + hf * 16 + 4 * g + v;
+                const int rel = key - P;
+                bool vis = key < c1;
+                if (vis && rel >= 0) {
+                  const unsigned long long w = rel < 64 ? anc_lo[nt] : anc_hi[nt];
+                  vis = (w >> (rel & 63)) & 1ull;
+                }
+                if (!vis) s[hf * 4 + v] = -INFINITY;
               }
-              if (!vis) s[hf * 4 + v] = -INFINITY;
-            }
-        }
-        // Lazy running maximum. m_run (exp2 domain, identical in the four lanes of a query) only has to
-        // be close to the true maximum: probabilities are exp2(score - m_run) and everything is
-        // normalised by the same sum at the end. It is refreshed, with the exact cross-lane maximum and
-        // the usual rescaling of l and O, only when some score of the wavefront exceeds it by more than
-        // 2^16 (or it is still -inf); otherwise the tile costs one fma and one exp2 per score.
-        const float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7]))) *
-                         scale_log2;
-        if (__any(mx > m_run + 16.f)) {
-          const float m_new = fmaxf(m_run, max_over_lane_groups(mx));
-          const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
-          const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);
-          m_run = m_new;
-          l_run *= alpha;
+          }
+          // Lazy running maximum. m_run (exp2 domain, identical in the four lanes of a query) only has to
+          // be close to the true maximum: probabilities are exp2(score - m_run) and everything is
+          // normalised by the same sum at the end. It is refreshed, with the exact cross-lane maximum and
+          // the usual rescaling of l and O, only when some score of the wavefront exceeds it by more than
+          // 2^16 (or it is still -inf); otherwise the tile costs one fma and one exp2 per score.
+          const float mx =
+              fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7]))) * scale_log2;
+          if (__any(mx > m_run[nt] + 16.f)) {
+            const float m_new = fmaxf(m_run[nt], max_over_lane_groups(mx));
+            const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_ref);
+            m_run[nt] = m_new;
+            l_run[nt] *= alpha;
 #pragma unroll
-          for (int db = 0; db < DB; ++db) O[db] *= alpha;
-        }
-        const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
-        float psum = 0.f;
-        bf16x8 pB;
+            for (int db = 0; db < DB; ++db) O[nt][db] *= alpha;
+          }
+          const float neg_m = (m_run[nt] == -INFINITY) ? 0.f : -m_run[nt];
+          float psum = 0.f;
+          bf16x8 pb;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(s[i], scale_log2, neg_m));   // i<4: first quarter, i>=4: second
-          psum += p;
-          pB[i] = (__bf16)p;
+          for (int i = 0; i < 8; ++i) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(s[i], scale_log2, neg_m));   // i<4: first quarter, i>=4: second
+            psum += p;
+            pb[i] = (__bf16)p;
+          }
+          pB[nt] = pb;
+          l_run[nt] += psum;
         }
-        l_run += psum;
 
-        // ---- O^T += V^T P^T
+        // ---- O^T += V^T P^T; a V^T operand is read once and used by all query tiles
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
           const unsigned char* base = Vs + (grp * 32 + 4 * g + (r16 >> 2)) * ROWB + db * 32 + (r16 & 3) * 8;
@@ -317,7 +375,9 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
           union { struct { s16x4 a, b; } p; bf16x8 v; } vt;
           vt.p.a = lo;
           vt.p.b = hi;
-          O[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt.v, pB, O[db], 0, 0, 0);
+#pragma unroll
+          for (int nt = 0; nt < NTW; ++nt)
+            O[nt][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt.v, pB[nt], O[nt][db], 0, 0, 0);
         }
       }
     };
@@ -331,6 +391,7 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     if (n_tiles > 1) stage_tile(Kr2, Vr2, 1, lds + STAGE_BYTES);
     if (n_tiles > 3) issue_tile(Kr2, Vr2, 3);
     lds_barrier();
+    WTL(4)
     auto step = [&](int ti, u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT]) {
       unsigned char* cur = lds + (ti & 1) * STAGE_BYTES;
       if (ti >= n_clean) compute(ti, cur, std::true_type{});
@@ -346,63 +407,81 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
       if (ti + 1 < n_tiles) step(ti + 1, Kr2, Vr2);
     }
     lds_barrier();
+    WTL(5)
 
     // ---- two key halves per query tile: the wavefront of the second half hands its state over through
-    // LDS (layout [query tile][register][lane], then m and l), the first merges.
-    float l_tot = sum_over_lane_groups(l_run);
+    // LDS (layout [query wavefront][tile][register][lane], then m and l), the first merges.
+    float l_tot[NTW];
+#pragma unroll
+    for (int nt = 0; nt < NTW; ++nt) l_tot[nt] = sum_over_lane_groups(l_run[nt]);
     if (KW == 2) {
-      float* mg = (float*)lds + qt * (64 * (DB * 4 + 2));
+      constexpr int MG_TILE = 64 * (DB * 4 + 2);
+      float* mg = (float*)lds + qt * NTW * MG_TILE;
       if (kpart == 1) {
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+        for (int nt = 0; nt < NTW; ++nt) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) mg[(db * 4 + i) * 64 + lane] = O[db][i];
-        mg[(DB * 4) * 64 + lane] = m_run;
-        mg[(DB * 4 + 1) * 64 + lane] = l_tot;
+          for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) mg[nt * MG_TILE + (db * 4 + i) * 64 + lane] = O[nt][db][i];
+          mg[nt * MG_TILE + (DB * 4) * 64 + lane] = m_run[nt];
+          mg[nt * MG_TILE + (DB * 4 + 1) * 64 + lane] = l_tot[nt];
+        }
       }
       lds_barrier();
-      if (kpart == 1) return;
-      const float m_other = mg[(DB * 4) * 64 + lane], l_other = mg[(DB * 4 + 1) * 64 + lane];
-      const float m_new = fmaxf(m_run, m_other);
-      const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
-      const float a_self = __builtin_amdgcn_exp2f(m_run - m_ref), a_other = __builtin_amdgcn_exp2f(m_other - m_ref);
-      m_run = m_new;
-      l_tot = l_tot * a_self + l_other * a_other;
+      if (kpart == 0) {
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+        for (int nt = 0; nt < NTW; ++nt) {
+          const float m_other = mg[nt * MG_TILE + (DB * 4) * 64 + lane], l_other = mg[nt * MG_TILE + (DB * 4 + 1) * 64 + lane];
+          const float m_new = fmaxf(m_run[nt], m_other);
+          const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+          const float a_self = __builtin_amdgcn_exp2f(m_run[nt] - m_ref), a_other = __builtin_amdgcn_exp2f(m_other - m_ref);
+          m_run[nt] = m_new;
+          l_tot[nt] = l_tot[nt] * a_self + l_other * a_other;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) O[db][i] = O[db][i] * a_self + mg[(db * 4 + i) * 64 + lane] * a_other;
+          for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              O[nt][db][i] = O[nt][db][i] * a_self + mg[nt * MG_TILE + (db * 4 + i) * 64 + lane] * a_other;
+        }
+      }
     }
 
     // ---- normalise and write (or emit the partial)
-    const int n = q0 + r16;
-    if (n >= N) return;
-    if (final_out) {
-      const float inv = 1.f / l_tot;
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        union { uint2 u; __hip_bfloat16 h4[4]; } pk;
+    for (int nt = 0; nt < NTW; ++nt) {
+      const int n = q0 + nt * 16 + r16;
+      if (kpart == 0 && n < N) {
+        if (final_out) {
+          const float inv = 1.f / l_tot[nt];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) pk.h4[i] = __float2bfloat16(O[db][i] * inv);
-        *(uint2*)(out + b * q_sb + n * q_sn + h * q_sh + db * 16 + 4 * g) = pk.u;
-      }
-    } else {
-      const long base = part_row + n;
+          for (int db = 0; db < DB; ++db) {
+            union { uint2 u; __hip_bfloat16 h4[4]; } pk;
 #pragma unroll
-      for (int db = 0; db < DB; ++db) *(f32x4*)(ws_o + base * D + db * 16 + 4 * g) = O[db];
-      if (g == 0) {
-        ws_ml[base * 2 + 0] = m_run;
-        ws_ml[base * 2 + 1] = l_tot;
+            for (int i = 0; i < 4; ++i) pk.h4[i] = __float2bfloat16(O[nt][db][i] * inv);
+            *(uint2*)(out + b * q_sb + n * q_sn + h * q_sh + db * 16 + 4 * g) = pk.u;
+          }
+        } else {
+          const long base = part_row + n;
+#pragma unroll
+          for (int db = 0; db < DB; ++db) *(f32x4*)(ws_o + base * D + db * 16 + 4 * g) = O[nt][db];
+          if (g == 0) {
+            ws_ml[base * 2 + 0] = m_run[nt];
+            ws_ml[base * 2 + 1] = l_tot[nt];
+          }
+        }
       }
     }
   };   // segment
 
-  if constexpr (!BAL) {
+  if constexpr (PLAN == PLAN_GRID) {
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     segment(b, h, split * chunk_keys, split * chunk_keys + chunk_keys,
             n_splits == 1 ? -1l : (((long)b * H + h) * n_splits + split) * N);
   } else {
-    // n_splits is the number of partial slots per pair: the workgroups overlapping a pair fill slots 0, 1, ...
+    // Tiles [pos, end) of the flattened (request, head, key tile) order belong to this workgroup.
+    // n_splits is the number of partial slots per pair; the workgroups overlapping a pair fill slots
+    // 0, 1, ... in order.
     const BalancedShare bs = balanced_share(prefix_len, B, N, H, S_cap, KT, (int)gridDim.x);
     long pos = (long)blockIdx.x * bs.share;
     const long end = min(bs.total, pos + bs.share);
@@ -424,6 +503,10 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
       lds_barrier();   // LDS (staging tiles, merge area, tree arrays) is reused by the next segment
     }
   }
+#ifdef SPEC_WIDE_TIMELINE
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
+  WTL(1)
 }
 
 }  // namespace wide
@@ -438,27 +521,28 @@ hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const Attn
   // one 16-query tile per wavefront: 2 x 2 key halves up to 32 nodes, four up to 64, eight up to 128
   const int qw = d.N <= 32 ? 2 : d.N <= 64 ? 4 : 8;
   const bool append = k_new != nullptr;
-  const bool bal = plan.balanced_wgs > 0;
-  const dim3 grid = bal ? dim3(plan.balanced_wgs, 1, 1) : dim3(plan.n_splits, d.H, d.B);
-#define SPEC_LAUNCH(DD, QQ, KK, APP, BAL)                                                                             \
-  hipLaunchKernelGGL((wide::tree_attention_bf16_wide_kernel<DD, QQ, KK, APP, BAL>), grid, dim3(QQ * KK * 64), 0, s,   \
+  const int mode = plan.balanced_wgs == 0 ? wide::PLAN_GRID : wide::PLAN_TILES;
+  const dim3 grid = mode != wide::PLAN_GRID ? dim3(plan.balanced_wgs, 1, 1) : dim3(plan.n_splits, d.H, d.B);
+#define SPEC_LAUNCH(DD, QQ, NTT, KK, APP, PLAN)                                                                       \
+  hipLaunchKernelGGL((wide::tree_attention_bf16_wide_kernel<DD, QQ, NTT, KK, APP, PLAN>), grid, dim3(QQ * KK * 64), 0, s, \
                      (const __hip_bfloat16*)q, (__hip_bfloat16*)k_cache, (__hip_bfloat16*)v_cache,                    \
                      (const __hip_bfloat16*)k_new, (const __hip_bfloat16*)v_new, parent, depth, prefix_len,           \
                      (__hip_bfloat16*)out, ws_o, ws_ml, status, d.B, d.N, d.H, d.S_cap, plan.chunk_keys,              \
                      plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h, (long)d.kv_stride_b,  \
                      (long)d.kv_stride_h, (long)d.kv_stride_s, scale)
-#define SPEC_SHAPES(DD, APP, BAL)                      \
-  if (qw == 2) SPEC_LAUNCH(DD, 2, 2, APP, BAL);        \
-  else if (qw == 4) SPEC_LAUNCH(DD, 4, 1, APP, BAL);   \
-  else SPEC_LAUNCH(DD, 8, 1, APP, BAL)
-#define SPEC_DISPATCH(APP, BAL)                        \
-  if (d.D == 128) { SPEC_SHAPES(128, APP, BAL); }      \
-  else { SPEC_SHAPES(64, APP, BAL); }
-  if (append && bal) { SPEC_DISPATCH(true, true); }
-  else if (append) { SPEC_DISPATCH(true, false); }
-  else if (bal) { SPEC_DISPATCH(false, true); }
-  else { SPEC_DISPATCH(false, false); }
+#define SPEC_SHAPES(DD, APP, PLAN)                      \
+  if (qw == 2) SPEC_LAUNCH(DD, 2, 1, 2, APP, PLAN);        \
+  else if (qw == 4) SPEC_LAUNCH(DD, 4, 1, 1, APP, PLAN);   \
+  else SPEC_LAUNCH(DD, 8, 1, 1, APP, PLAN)
+#define SPEC_DIMS(APP, PLAN)                            \
+  if (d.D == 128) { SPEC_SHAPES(128, APP, PLAN); }      \
+  else { SPEC_SHAPES(64, APP, PLAN); }
+#define SPEC_DISPATCH(APP)                                              \
+  if (mode == wide::PLAN_GRID) { SPEC_DIMS(APP, wide::PLAN_GRID); }     \
+  else { SPEC_DIMS(APP, wide::PLAN_TILES); }
+  if (append) { SPEC_DISPATCH(true); } else { SPEC_DISPATCH(false); }
 #undef SPEC_DISPATCH
+#undef SPEC_DIMS
 #undef SPEC_SHAPES
 #undef SPEC_LAUNCH
   return hipGetLastError();

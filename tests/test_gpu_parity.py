@@ -178,8 +178,8 @@ BALANCED = [
 
 @pytest.mark.parametrize("case", BALANCED, ids=[f"B{c[0]}H{c[1]}D{c[2]}P{c[3][0]}-{c[3][1]}N{c[4]}-{c[5]}-wg{c[6]}" for c in BALANCED])
 def test_balanced_plan_attention_and_append(spec, case):
-    """The balanced plan of the few-query bf16 kernel: shares that start and end inside a pair, cross
-    pair and request boundaries, or are empty."""
+    """The balanced plan of the bf16 kernels: shares that start and end inside a pair, cross pair and
+    request boundaries, or are empty."""
     B, H, D, P, N, tree, wgs = case
     cfg = wl.Config(92, "balanced", "bf16", B=B, H=H, D=D, P=P if P[0] != P[1] else P[0], N=N, tree=tree,
                     widths=wl.EXPANSION_EVAL * 2)
@@ -220,11 +220,13 @@ def test_large_configs_sampled_heads(spec, c):
     assert np.array_equal(vc[bsel][:, hsel].double().cpu().numpy(), _vco)
 
 
-def test_attention_status_bits_and_noop(spec):
+@pytest.mark.parametrize("N", [16, 40])
+def test_attention_status_bits_and_noop(spec, N):
     """Malformed trees and requests that do not fit are flagged and produce zeros; others unaffected."""
-    cfg = wl.Config(91, "bad", "bf16", B=4, H=2, D=128, P=(40, 90), N=16, tree="random_parent")
-    for chunk, fused, wgs in ((0, False, 0), (64, False, 0), (0, True, 0), (64, True, 0), (0, False, 5), (0, True, 3)):
-        inp = wl.make_attention_inputs(cfg, seed=5, S_cap=90 + 16)
+    cfg = wl.Config(91, "bad", "bf16", B=4, H=2, D=128, P=(40, 90), N=N, tree="random_parent")
+    plans = [(0, False, 0), (64, False, 0), (0, True, 0), (64, True, 0), (0, False, 5), (0, True, 3)]
+    for chunk, fused, wgs in plans:
+        inp = wl.make_attention_inputs(cfg, seed=5, S_cap=90 + N)
         inp["tree_parent"][1, 5] = 9            # parent after child
         inp["tree_depth"][2, 7] += 1            # depth inconsistent with parent
         inp["prefix_len"][3] = 90 + 1           # prefix + N > S_cap
@@ -233,7 +235,7 @@ def test_attention_status_bits_and_noop(spec):
             out, kc, vc = _run_append_attention(spec, inp, status=status, fused=fused)
         st = status.cpu().numpy()
         assert st[0] == 0 and st[1] == orc.ST_BAD_TREE and st[2] == orc.ST_BAD_TREE and st[3] == orc.ST_CAPACITY
-        assert (out[1:].float() == 0).all()
+        assert (out[1:].float() == 0).all(), (chunk, fused, wgs)
         ref, _, _ = _oracle_append_attention(inp, bsel=[0])
         _check_attention(out[:1], ref, torch.bfloat16)
         assert orc.tree_status(inp["tree_parent"][1].numpy()) == orc.ST_BAD_TREE
