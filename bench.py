@@ -23,8 +23,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy of
-# known size (profiles/tree_attention_bf16_config2_hbm_traffic.txt); only for the workload profiled.
-MEASURED_TRAFFIC_BYTES = {2: int((67172.4 * 2.000 + 3144.9) * 1024)}
+# known size (profiles/tree_attention_bf16_configs2-5_hbm_traffic.txt), per launch of the workload's shape.
+MEASURED_TRAFFIC_BYTES = {2: int((67170.0 * 2.000 + 3130.1) * 1024), 3: int((90320.3 * 2.000 + 49152.4) * 1024),
+                          4: int((549054.3 * 2.000 + 49160.4) * 1024),
+                          5: int(((400895.1 + 5217.9) * 2.000 + 12367.2 + 1024.0) * 1024)}
 
 
 def parse():
@@ -188,12 +190,14 @@ def main():
         "config": {"workload": f"config {cfg.cfg}: {cfg.name} B={B} H={H} D={D} prefix={cfg.P} tree N={N} "
                                f"vocab={vcfg.V} layers/pass={L}" + (" (attention only)" if args.attn_only else ""),
                    "launch": "eager" if args.no_graph else "hip-graph replay",
-                   "layer_tree_tokens_per_s": B * N / (attn_us * 1e-6) if args.attn_only else None,
+                   "layer_tree_tokens_per_s": B * N / (attn_us * 1e-6),
                    "attention_us_per_layer": attn_us, "layer_algorithmic_bytes": layer_bytes},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.cfg) if L == cfg.layers else None,
-                     "kernel": "tree_attention_bf16_kernel (KV append fused; + attn_combine_kernel when the key range is split)", "bytes_per_launch": attn_bytes,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.cfg),
+                     "kernel": ("tree_attention_bf16_kernel" if N <= 16 else "tree_attention_bf16_wide_kernel")
+                               + " (KV append fused; + attn_combine_kernel when the key range is split)",
+                     "bytes_per_launch": attn_bytes,
                      "us_per_launch": attn_us},
     }
 
@@ -219,20 +223,21 @@ def cpu_baseline(cfg, vcfg, host, gi, si, L):
         cores = 1
     B, N = cfg.B, cfg.N
     budget_s = 12.0
-    nb = B
-    # attention + append of one layer, on as many requests as fit the time budget
+    # attention + append of one layer, request by request, repeated over the batch until the time
+    # budget is used (about 12 s of CPU work; a slow configuration stops inside the first batch)
     t0 = time.perf_counter()
     done = 0
     pl = host["prefix_len"].numpy()
     par = host["tree_parent"].numpy()
-    for b in range(B):
+    while True:
+        b = done % B
         kc = host["k_cache"][0][b:b + 1].double().numpy()
         vc = host["v_cache"][0][b:b + 1].double().numpy()
         orc.kv_append(kc, vc, host["k_new"][0][b:b + 1].double().numpy(), host["v_new"][0][b:b + 1].double().numpy(),
                       pl[b:b + 1])
         orc.tree_attention(host["q"][0][b:b + 1].double().numpy(), kc, vc, par[b:b + 1], pl[b:b + 1])
         done += 1
-        if time.perf_counter() - t0 > budget_s:
+        if time.perf_counter() - t0 > budget_s or done >= 64 * B:
             break
     t_layer = (time.perf_counter() - t0) * B / done
     t0 = time.perf_counter()
@@ -246,8 +251,8 @@ def cpu_baseline(cfg, vcfg, host, gi, si, L):
     t_commit = time.perf_counter() - t0
     t_pass = L * (t_layer + t_commit) + t_verify
     return {"value": B * N / t_pass, "unit": "tree tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"oracle (numpy float64) timed on {done}/{B} requests of one layer's append+attention "
-                      f"({t_layer:.2f} s/layer extrapolated), one greedy + one stochastic verification "
+            "sample": f"oracle (numpy float64) timed on {done} request-layers of append+attention (batch of {B}; "
+                      f"{t_layer:.2f} s per layer of the batch), one greedy + one stochastic verification "
                       f"({t_verify:.2f} s), one layer's commit ({t_commit:.3f} s); pass time = L*(layer+commit)+verify "
                       f"with L={L}"}
 
