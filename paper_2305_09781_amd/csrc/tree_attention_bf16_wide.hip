@@ -13,8 +13,9 @@
 //   prologue:      tiles 0 and 1 are requested together (before prefix_len is known) and staged
 //   iteration ti:  S^T, online softmax, O^T for tile ti from LDS stage ti&1
 //                  LDS-only barrier (it does not wait for the global loads in flight)
-//                  registers holding tile ti+2 -> stage ti&1; request tile ti+4 into them
-//   so two tiles are always in flight from HBM per workgroup, one more is ready in LDS.
+//                  registers holding tile ti+2 -> stage ti&1; request tile ti+2+DEPTH into them
+//   so DEPTH = 2 tiles are always in flight from HBM per workgroup and one more is ready in LDS (four
+//   in flight measured slower on the eight-wavefront shape, whose loop is bound inside the CU).
 //
 // Masked tiles (those reaching past prefix_len or the end of the segment) take the MASKED variant of
 // the compute step; the loader threads zero rows past the end, and with APPEND fetch rows >= prefix_len
@@ -82,7 +83,7 @@ __device__ inline float sum_over_lane_groups(float v) {
 
 // QW query wavefronts (NTW 16-query tiles each) x KW key parts: wavefront w serves query tiles
 // (w % QW) * NTW .. + NTW and (KW == 2) the 32-key half w / QW of every 64-key tile.
-template <int D, int QW, int NTW, int KW, bool APPEND, int PLAN>
+template <int D, int QW, int NTW, int KW, int DEPTH, bool APPEND, int PLAN>
 __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kernel(
     const __hip_bfloat16* __restrict__ q, __hip_bfloat16* k_cache, __hip_bfloat16* v_cache,
     const __hip_bfloat16* __restrict__ k_new, const __hip_bfloat16* __restrict__ v_new,
@@ -91,6 +92,7 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     int H, int S_cap, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long kv_sb, long kv_sh,
     long kv_ss, float scale_log2) {
   static_assert(KW == 1 || KW == 2, "a 64-key tile is consumed as two 32-key halves");
+  static_assert(DEPTH == 2 || DEPTH == 4, "register sets of tiles in flight");
   constexpr int WAVES = QW * KW;
   constexpr int NTHREADS = WAVES * 64;
   constexpr int KS = D / 32, DB = D / 16;
@@ -119,10 +121,9 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
   WTL(0)
   WTL_HW()
 
-  // two register sets: the two tiles in flight from global memory (tiles ti+2 and ti+3 while tile ti is
-  // consumed from LDS and tile ti+1 waits there)
-  u32x4 Kr[NPT], Vr[NPT];
-  u32x4 Kr2[NPT], Vr2[NPT];
+  // DEPTH register sets: the tiles in flight from global memory (tiles ti+2 .. ti+1+DEPTH while tile ti
+  // is consumed from LDS and tile ti+1 waits there)
+  u32x4 Kr[DEPTH][NPT], Vr[DEPTH][NPT];
   const unsigned cache_row_bytes = (unsigned)kv_ss * 2u, new_row_bytes = (unsigned)q_sn * 2u;
   // Speculative request of one tile: cache rows only, clamped to the capacity, no prefix_len needed.
   auto issue_speculative = [&](u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT], const unsigned char* kbase, const unsigned char* vbase,
@@ -170,8 +171,8 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
         Kd[j] = *(const u32x4*)(kc + off_k + ld_col);
       }
     };
-    issue_speculative(Kr, Vr, kc, vc, c0);
-    issue_speculative(Kr2, Vr2, kc, vc, c0 + KT);
+    issue_speculative(Kr[0], Vr[0], kc, vc, c0);
+    issue_speculative(Kr[1], Vr[1], kc, vc, c0 + KT);
 
     bf16x8 qB[NTW][KS];
 #pragma unroll
@@ -215,8 +216,8 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     const int last_row = len - 1;
 
     // speculative tiles that reach the tree are fetched again from the right sources
-    if (APPEND && n_clean == 0) issue(Kr, Vr, c0, std::integral_constant<int, 2>{}, P, last_row);
-    if (APPEND && n_clean <= 1 && n_tiles > 1) issue(Kr2, Vr2, c0 + KT, std::integral_constant<int, 2>{}, P, last_row);
+    if (APPEND && n_clean == 0) issue(Kr[0], Vr[0], c0, std::integral_constant<int, 2>{}, P, last_row);
+    if (APPEND && n_clean <= 1 && n_tiles > 1) issue(Kr[1], Vr[1], c0 + KT, std::integral_constant<int, 2>{}, P, last_row);
 
     // ---- tree: validate, build ancestor-or-self masks (LDS-only barriers: the tile loads stay in flight)
     unsigned long long anc_lo[NTW], anc_hi[NTW];
@@ -382,29 +383,34 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
       }
     };
 
-    // ---- pipeline. Tiles 0 and 1 were requested together at the start. From then on tile ti is
-    // consumed from LDS stage ti&1 while tile ti+1 sits in the other stage and tiles ti+2, ti+3 are in
-    // flight in the two register sets: after the barrier that ends tile ti, tile ti+2 is written over
-    // it and tile ti+4 is requested into the registers just freed.
-    stage_tile(Kr, Vr, 0, lds);
-    if (n_tiles > 2) issue_tile(Kr, Vr, 2);
-    if (n_tiles > 1) stage_tile(Kr2, Vr2, 1, lds + STAGE_BYTES);
-    if (n_tiles > 3) issue_tile(Kr2, Vr2, 3);
+    // ---- pipeline. Tile ti is consumed from LDS stage ti&1 while tile ti+1 sits in the other stage and
+    // tiles ti+2 .. ti+1+DEPTH are in flight, tile k in register set k % DEPTH. Tiles 0 and 1 were
+    // requested at the start; the others of the first DEPTH are requested now. After the barrier that
+    // ends tile ti, tile ti+2 is written over it from its register set and tile ti+2+DEPTH is requested
+    // into that set.
+#pragma unroll
+    for (int d = 2; d < DEPTH; ++d)
+      if (d < n_tiles) issue_tile(Kr[d], Vr[d], d);
+    stage_tile(Kr[0], Vr[0], 0, lds);
+    if (DEPTH < n_tiles) issue_tile(Kr[0], Vr[0], DEPTH);
+    if (n_tiles > 1) stage_tile(Kr[1], Vr[1], 1, lds + STAGE_BYTES);
+    if (DEPTH + 1 < n_tiles) issue_tile(Kr[1], Vr[1], DEPTH + 1);
     lds_barrier();
     WTL(4)
-    auto step = [&](int ti, u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT]) {
+    auto step = [&](int ti, u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT]) {   // Kd, Vd: the register set of tile ti+2
       unsigned char* cur = lds + (ti & 1) * STAGE_BYTES;
       if (ti >= n_clean) compute(ti, cur, std::true_type{});
       else compute(ti, cur, std::false_type{});
       lds_barrier();
       if (ti + 2 < n_tiles) {
         stage_tile(Kd, Vd, ti + 2, cur);
-        if (ti + 4 < n_tiles) issue_tile(Kd, Vd, ti + 4);
+        if (ti + 2 + DEPTH < n_tiles) issue_tile(Kd, Vd, ti + 2 + DEPTH);
       }
     };
-    for (int ti = 0; ti < n_tiles; ti += 2) {
-      step(ti, Kr, Vr);
-      if (ti + 1 < n_tiles) step(ti + 1, Kr2, Vr2);
+    for (int ti = 0; ti < n_tiles; ti += DEPTH) {
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d)
+        if (ti + d < n_tiles) step(ti + d, Kr[(d + 2) % DEPTH], Vr[(d + 2) % DEPTH]);
     }
     lds_barrier();
     WTL(5)
@@ -523,17 +529,17 @@ hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const Attn
   const bool append = k_new != nullptr;
   const int mode = plan.balanced_wgs == 0 ? wide::PLAN_GRID : wide::PLAN_TILES;
   const dim3 grid = mode != wide::PLAN_GRID ? dim3(plan.balanced_wgs, 1, 1) : dim3(plan.n_splits, d.H, d.B);
-#define SPEC_LAUNCH(DD, QQ, NTT, KK, APP, PLAN)                                                                       \
-  hipLaunchKernelGGL((wide::tree_attention_bf16_wide_kernel<DD, QQ, NTT, KK, APP, PLAN>), grid, dim3(QQ * KK * 64), 0, s, \
+#define SPEC_LAUNCH(DD, QQ, NTT, KK, DP, APP, PLAN)                                                                   \
+  hipLaunchKernelGGL((wide::tree_attention_bf16_wide_kernel<DD, QQ, NTT, KK, DP, APP, PLAN>), grid, dim3(QQ * KK * 64), 0, s, \
                      (const __hip_bfloat16*)q, (__hip_bfloat16*)k_cache, (__hip_bfloat16*)v_cache,                    \
                      (const __hip_bfloat16*)k_new, (const __hip_bfloat16*)v_new, parent, depth, prefix_len,           \
                      (__hip_bfloat16*)out, ws_o, ws_ml, status, d.B, d.N, d.H, d.S_cap, plan.chunk_keys,              \
                      plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h, (long)d.kv_stride_b,  \
                      (long)d.kv_stride_h, (long)d.kv_stride_s, scale)
 #define SPEC_SHAPES(DD, APP, PLAN)                      \
-  if (qw == 2) SPEC_LAUNCH(DD, 2, 1, 2, APP, PLAN);        \
-  else if (qw == 4) SPEC_LAUNCH(DD, 4, 1, 1, APP, PLAN);   \
-  else SPEC_LAUNCH(DD, 8, 1, 1, APP, PLAN)
+  if (qw == 2) SPEC_LAUNCH(DD, 2, 1, 2, 2, APP, PLAN);        \
+  else if (qw == 4) SPEC_LAUNCH(DD, 4, 1, 1, 2, APP, PLAN);   \
+  else SPEC_LAUNCH(DD, 8, 1, 1, 2, APP, PLAN)
 #define SPEC_DIMS(APP, PLAN)                            \
   if (d.D == 128) { SPEC_SHAPES(128, APP, PLAN); }      \
   else { SPEC_SHAPES(64, APP, PLAN); }
