@@ -6,7 +6,7 @@
  * Algorithm 2). The calls below are the per-layer and per-pass steps of that iteration:
  *
  *   for each layer:  spec_kv_append  ->  spec_tree_attention      (or the fused spec_tree_attention_append)
- *   once per pass:   spec_verify_greedy | spec_verify_stochastic  ->  spec_kv_commit (all layers)
+ *   once per pass:   spec_verify_greedy | spec_verify_stochastic | spec_verify_naive  ->  spec_kv_commit (all layers)
  *
  * Conventions common to every call
  *   - Every data pointer is a DEVICE pointer unless its comment says "host". The caller owns all
@@ -134,6 +134,24 @@ int spec_verify_greedy(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, co
                        int32_t Lmax, int32_t* accepted_path /*[B,Lmax]*/, int32_t* accepted_len /*[B]*/,
                        int32_t* out_tokens /*[B,Lmax]*/, int32_t* node_argmax /*[B,N] or NULL*/,
                        void* workspace, size_t workspace_bytes, int32_t* status, void* hip_stream);
+
+/*
+ * Naive-sampling verification (Section 4.3: the straightforward alternative that multi-step
+ * speculative sampling is compared with in Theorem 4.3 and Table 3). For every node u one token
+ * x_u ~ softmax(logits_llm[b,u,:] / temperature) is drawn by inverse CDF over ascending token id: the
+ * first k with cumsum(P)[k] > u_sample[b,u] * sum(P) (uniforms supplied by the caller, float32 in
+ * [0,1)). Starting at the root, while some child v of u has tree_token[b,v] == x_u (lowest node index
+ * if several) the token is emitted and the walk continues from v; otherwise x_u is emitted and the walk
+ * stops. Outputs as for spec_verify_greedy; node_sample[b,u] = x_u (may be NULL).
+ * workspace: spec_verify_naive_workspace_bytes(B, N, V) bytes, 256-byte aligned.
+ */
+size_t spec_verify_naive_workspace_bytes(int32_t B, int32_t N, int32_t V);
+int spec_verify_naive(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, const void* logits_llm,
+                      const int32_t* tree_token /*[B,N]*/, const int32_t* tree_parent /*[B,N]*/,
+                      const float* u_sample /*[B,N]*/, float temperature, int32_t Lmax,
+                      int32_t* accepted_path /*[B,Lmax]*/, int32_t* accepted_len /*[B]*/,
+                      int32_t* out_tokens /*[B,Lmax]*/, int32_t* node_sample /*[B,N] or NULL*/, void* workspace,
+                      size_t workspace_bytes, int32_t* status, void* hip_stream);
 
 /*
  * Stochastic verification (Algorithm 2, VerifyStochastic: multi-step speculative sampling, Section

@@ -13,6 +13,7 @@ What each function follows:
                          1/sqrt(d), masked entries -inf, softmax, times V)
   verify_greedy          Algorithm 2, VerifyGreedy
   verify_stochastic      Algorithm 2, VerifyStochastic (multi-step speculative sampling)
+  sample_nodes, verify_naive  naive sampling, the alternative of Section 4.3 (Theorem 4.3, Table 3)
   kv_commit              Algorithm 2 main loop (verified tokens are appended to the sequence), so the
                          K/V rows of the accepted path must become the contiguous prefix
 
@@ -20,7 +21,9 @@ Parity pins (tests/test_oracle_*.py): per-path brute-force causal attention, cha
 cases against a library routine, constant-V and non-interference invariants (attention); exhaustive
 path enumeration and incremental decoding on a bigram model (greedy); exact cell-by-cell enumeration
 against a closed-form law, Theorem 4.2 and 4.3 in closed form, chi-square over many seeds
-(stochastic); round trips and overlapping-path cases (append / commit). No function is unpinned.
+(stochastic); brute-force inverse CDF, the exact first-step law, the closed-form rejection probability of
+Theorem 4.3 and the low-temperature limit against the greedy verifier (naive sampling); round trips and
+overlapping-path cases (append / commit). No function is unpinned.
 
 Readings taken where the paper is silent are listed next to each function.
 """
@@ -244,6 +247,66 @@ def verify_stochastic(logits, probs_ssm, ssm_row, tree_token, tree_parent, u_acc
     if return_margins:
         return path, ln, toks, status, margins
     return path, ln, toks, status
+
+
+# ---------------------------------------------------------------------------------------------
+# naive sampling  (Section 4.3: the straightforward alternative multi-step speculative sampling is
+# compared with; Theorem 4.3, Table 3)
+# ---------------------------------------------------------------------------------------------
+
+def sample_nodes(logits, u_sample, temperature=1.0):
+    """x_u ~ softmax(logits[u] / temperature) for every node, drawn by inverse CDF over ascending token
+    id with the caller's uniform: the first k with cumsum(P)[k] > u_sample[u] * sum(P).
+
+    Returns node_sample [B,N] and margins [B,N]: the distance of each draw's target from the nearest
+    CDF step as a fraction of the total mass."""
+    logits = np.asarray(logits, dtype=np.float64)
+    B, N, V = logits.shape
+    out = np.zeros((B, N), dtype=np.int32)
+    margins = np.zeros((B, N))
+    for b in range(B):
+        for u in range(N):
+            z = logits[b, u] / float(temperature)
+            P = np.exp(z - z.max())
+            cdf = np.cumsum(P)
+            target = float(np.float32(u_sample[b, u])) * cdf[-1]
+            x = min(int(np.searchsorted(cdf, target, side="right")), V - 1)
+            lo = cdf[x - 1] if x > 0 else -np.inf
+            margins[b, u] = min((target - lo) / cdf[-1], (cdf[x] - target) / cdf[-1])
+            out[b, u] = x
+    return out, margins
+
+
+def verify_naive(logits, tree_token, tree_parent, u_sample, temperature=1.0):
+    """Naive sampling: at node u draw x ~ P(. | u, LLM); if x is the token of a child of u (lowest node
+    index if several children carry it), emit x and move there; otherwise emit x and stop.
+
+    Readings: one uniform per node, supplied by the caller; inverse CDF as in sample_nodes.
+    Returns accepted_path [B,N], accepted_len [B], out_tokens [B,N], node_sample [B,N]."""
+    node_sample, _ = sample_nodes(logits, u_sample, temperature)
+    B, N = node_sample.shape
+    path = np.full((B, N), -1, dtype=np.int32)
+    toks = np.full((B, N), -1, dtype=np.int32)
+    ln = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        u = 0
+        k = 0
+        path[b, 0] = 0
+        while True:
+            x = int(node_sample[b, u])
+            toks[b, k] = x
+            nxt = -1
+            for v in children(tree_parent[b], u):
+                if int(tree_token[b, v]) == x:
+                    nxt = v
+                    break
+            if nxt < 0:
+                break
+            k += 1
+            path[b, k] = nxt
+            u = nxt
+        ln[b] = k + 1
+    return path, ln, toks, node_sample
 
 
 # ---------------------------------------------------------------------------------------------

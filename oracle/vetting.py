@@ -42,3 +42,18 @@ def vet_uniforms(logits, probs_ssm, ssm_row, tree_token, tree_parent, u_accept, 
     if todo:
         raise RuntimeError("could not find robust uniforms")
     return u_accept, u_final, redraws
+
+
+def vet_sample_uniforms(logits, u_sample, rng, temperature=1.0, max_rounds=200):
+    """Returns (u_sample, n_redraws) such that every node's inverse-CDF draw keeps CDF_MARGIN from a step."""
+    u_sample = np.array(u_sample, dtype=np.float32, copy=True)
+    redraws = 0
+    for _ in range(max_rounds):
+        _, margins = orc.sample_nodes(logits, u_sample, temperature)
+        bad = margins < CDF_MARGIN
+        if not bad.any():
+            return u_sample, redraws
+        n = int(bad.sum())
+        u_sample[bad] = np.minimum(rng.random(n, dtype=np.float32), np.float32(1 - 2.0 ** -24))
+        redraws += n
+    raise RuntimeError("could not find robust uniforms")

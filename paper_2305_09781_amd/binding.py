@@ -23,7 +23,8 @@ ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_CAPACITY, ERR_HIP, ERR_WORKSPACE = -1, -2,
 EXPORTED = [
     "spec_kv_append", "spec_tree_attention", "spec_tree_attention_append", "spec_tree_attention_workspace_bytes",
     "spec_verify_greedy",
-    "spec_verify_stochastic", "spec_verify_stochastic_workspace_bytes", "spec_kv_commit", "spec_strerror",
+    "spec_verify_stochastic", "spec_verify_stochastic_workspace_bytes", "spec_verify_naive",
+    "spec_verify_naive_workspace_bytes", "spec_kv_commit", "spec_strerror",
     "spec_version",
 ]
 
@@ -76,6 +77,10 @@ def load():
     lib.spec_verify_stochastic.restype = ctypes.c_int
     lib.spec_verify_stochastic_workspace_bytes.argtypes = [i32, i32, i32]
     lib.spec_verify_stochastic_workspace_bytes.restype = sz
+    lib.spec_verify_naive.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, f32, i32, vp, vp, vp, vp, vp, sz, vp, vp]
+    lib.spec_verify_naive.restype = ctypes.c_int
+    lib.spec_verify_naive_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.spec_verify_naive_workspace_bytes.restype = sz
     lib.spec_kv_commit.argtypes = [dp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i32, vp, vp, vp, vp, vp]
     lib.spec_kv_commit.restype = ctypes.c_int
     lib.spec_strerror.argtypes = [ctypes.c_int]
@@ -227,6 +232,30 @@ def spec_verify_stochastic(logits, probs_ssm, ssm_row, tree_token, tree_parent, 
                                          workspace.numel() * workspace.element_size(), _ptr(status), _stream(stream)),
            "spec_verify_stochastic")
     return path, ln, toks
+
+
+def spec_verify_naive_workspace_bytes(B: int, N: int, V: int) -> int:
+    return int(load().spec_verify_naive_workspace_bytes(B, N, V))
+
+
+def spec_verify_naive(logits, tree_token, tree_parent, u_sample, temperature: float = 1.0, Lmax: Optional[int] = None,
+                      workspace=None, status=None, stream=None, out: Optional[Tuple[torch.Tensor, ...]] = None):
+    """Returns (accepted_path [B,Lmax], accepted_len [B], out_tokens [B,Lmax], node_sample [B,N])."""
+    B, N, V = logits.shape
+    Lmax = N if Lmax is None else Lmax
+    dev = logits.device
+    if workspace is None:
+        workspace = torch.empty(spec_verify_naive_workspace_bytes(B, N, V), dtype=torch.uint8, device=dev)
+    if out is None:
+        out = (torch.empty((B, Lmax), dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+               torch.empty((B, Lmax), dtype=torch.int32, device=dev), torch.empty((B, N), dtype=torch.int32, device=dev))
+    path, ln, toks, samp = out
+    _check(load().spec_verify_naive(B, N, V, _dtype_code(logits.dtype), _ptr(logits), _ptr(tree_token),
+                                    _ptr(tree_parent), _ptr(u_sample), float(temperature), Lmax, _ptr(path), _ptr(ln),
+                                    _ptr(toks), _ptr(samp), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), _ptr(status), _stream(stream)),
+           "spec_verify_naive")
+    return path, ln, toks, samp
 
 
 def spec_kv_commit(k_caches: Sequence[torch.Tensor], v_caches: Sequence[torch.Tensor], accepted_path, accepted_len,

@@ -68,14 +68,14 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d) {
     // Few (request, head) pairs with long key ranges (long-context serving, ragged lengths): the bf16
     // kernels deal the key tiles of all pairs to as many workgroups as the device holds at once, in
     // equal shares, so the stream is balanced whatever the individual lengths are. Used when it gives
-    // more workgroups than pairs, each with at least 512 keys at the stated maximum length.
+    // more workgroups than pairs, each with at least 8 tiles at the stated maximum length.
     const int tile = d.N <= 16 ? SPEC_SMALL_TILE_KEYS : SPEC_WIDE_TILE_KEYS;
     const int resident_per_cu = (d.N > 16 && d.N <= 64) ? 2 : 1;   // four-wavefront workgroups: two per compute unit
     const long resident = (long)compute_units() * resident_per_cu;
     int wgs = env_int("SPEC_TREE_BALANCED_WGS", -1);
     if (wgs < 0) {
       const long max_tiles = groups * ((max_len + tile - 1) / tile);
-      const long cand = std::min<long>(resident, max_tiles / (512 / tile));
+      const long cand = std::min<long>(resident, max_tiles / 8);
       wgs = cand > groups ? (int)cand : 0;
     }
     if (wgs > 0) {
@@ -232,6 +232,38 @@ int spec_verify_greedy(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, co
   if (launch_node_stats(B, N, V, logits_dtype, logits_llm, 1.0f, node_argmax, nullptr, nullptr, s) != hipSuccess)
     return SPEC_ERR_HIP;
   if (launch_greedy_walk(B, N, node_argmax, tree_token, tree_parent, Lmax, accepted_path, accepted_len, out_tokens,
+                         status, s) != hipSuccess)
+    return SPEC_ERR_HIP;
+  return SPEC_OK;
+}
+
+size_t spec_verify_naive_workspace_bytes(int32_t B, int32_t N, int32_t V) {
+  if (B <= 0 || N <= 0 || V <= 0) return 0;
+  // node max, then the sampled tokens when the caller does not want them
+  return round_up((size_t)B * N * sizeof(float), 256) + round_up((size_t)B * N * sizeof(int32_t), 256);
+}
+
+int spec_verify_naive(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, const void* logits_llm,
+                      const int32_t* tree_token, const int32_t* tree_parent, const float* u_sample, float temperature,
+                      int32_t Lmax, int32_t* accepted_path, int32_t* accepted_len, int32_t* out_tokens,
+                      int32_t* node_sample, void* workspace, size_t workspace_bytes, int32_t* status,
+                      void* hip_stream) {
+  const int rc = check_verify_common(B, N, V, logits_dtype, logits_llm, tree_token, tree_parent, Lmax, accepted_path,
+                                     accepted_len, out_tokens);
+  if (rc != SPEC_OK) return rc;
+  if (!u_sample) return SPEC_ERR_INVALID_ARG;
+  if (!(temperature > 0.f) || std::isinf(temperature)) return SPEC_ERR_INVALID_ARG;
+  if (workspace == nullptr || workspace_bytes < spec_verify_naive_workspace_bytes(B, N, V)) return SPEC_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return SPEC_ERR_INVALID_ARG;
+  float* node_max = (float*)workspace;
+  if (node_sample == nullptr) node_sample = (int32_t*)((char*)workspace + round_up((size_t)B * N * sizeof(float), 256));
+  hipStream_t s = (hipStream_t)hip_stream;
+  const float inv_temp = 1.0f / temperature;
+  if (launch_node_stats(B, N, V, logits_dtype, logits_llm, inv_temp, nullptr, node_max, nullptr, s) != hipSuccess)
+    return SPEC_ERR_HIP;
+  if (launch_node_sample(B, N, V, logits_dtype, logits_llm, inv_temp, node_max, u_sample, node_sample, s) != hipSuccess)
+    return SPEC_ERR_HIP;
+  if (launch_greedy_walk(B, N, node_sample, tree_token, tree_parent, Lmax, accepted_path, accepted_len, out_tokens,
                          status, s) != hipSuccess)
     return SPEC_ERR_HIP;
   return SPEC_OK;

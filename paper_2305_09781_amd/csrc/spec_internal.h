@@ -59,6 +59,8 @@ hipError_t launch_attn_combine(const spec_attn_desc_t& d, const AttnPlan& plan, 
                                int32_t* status, hipStream_t s);
 hipError_t launch_node_stats(int B, int N, int V, int logits_dtype, const void* logits, float inv_temp,
                              int32_t* node_argmax, float* node_max, float* node_sumexp, hipStream_t s);
+hipError_t launch_node_sample(int B, int N, int V, int logits_dtype, const void* logits, float inv_temp,
+                              const float* node_max, const float* u_sample, int32_t* node_sample, hipStream_t s);
 hipError_t launch_greedy_walk(int B, int N, const int32_t* node_argmax, const int32_t* token, const int32_t* parent,
                               int Lmax, int32_t* path, int32_t* len, int32_t* out_tokens, int32_t* status,
                               hipStream_t s);

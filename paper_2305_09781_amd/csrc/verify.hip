@@ -12,6 +12,8 @@
 //                          materialises the residual distribution norm(max(0, P - Q)) (one pass over
 //                          the vocabulary per rejection, kept un-normalised with its mass Z). The last
 //                          token is drawn by inverse CDF with a float64 block scan in token-id order.
+//   node_sample_kernel     naive sampling (the alternative of Section 4.3): one inverse-CDF draw per
+//                          (request, node) row; the greedy walk then runs on the sampled tokens.
 #include <hip/hip_bf16.h>
 
 #include "spec_internal.h"
@@ -153,6 +155,74 @@ __global__ void __launch_bounds__(NS_THREADS) node_stats_kernel(const void* __re
 }
 
 // ---------------------------------------------------------------------------------------------
+// Inverse-CDF draw by a block of SW_THREADS threads over V weights in ascending token id:
+// w_i = exp((logits[lrow + i] - mx) * inv_temp) (implicit) or resid[i]. Every thread owns a contiguous
+// range and sums its weights in float64; a block scan finds the thread whose range holds the target
+// r * total, which then walks its range in order. Returns, to every thread, the first index whose
+// inclusive sum exceeds the target (V - 1 if rounding leaves none).
+// ---------------------------------------------------------------------------------------------
+constexpr int SW_THREADS = 1024;
+
+template <bool BF16, int VEC>
+__device__ inline int inverse_cdf_draw(const void* __restrict__ logits, long lrow, const float* resid, bool implicit,
+                                       float mx, float inv_temp, int V, float r, double* s_scan, int* s_pick, int* s_ans) {
+  const int t = threadIdx.x;
+  const int n_groups = V / VEC;
+  const int per_thread = ((V + SW_THREADS - 1) / SW_THREADS + VEC - 1) / VEC;    // groups per thread
+  const int g_lo = min(t * per_thread, n_groups), g_hi = min(g_lo + per_thread, n_groups);
+  double mine = 0.0;
+  for (int g0 = g_lo; g0 < g_hi; g0 += SWEEP_U) {
+    float w[SWEEP_U][VEC];
+#pragma unroll
+    for (int jj = 0; jj < SWEEP_U; ++jj)
+      if (g0 + jj < g_hi) {
+        if (implicit) load_logit_group<VEC, BF16>(logits, lrow + (long)(g0 + jj) * VEC, w[jj]);
+        else load_f32_group<VEC>(resid + (long)(g0 + jj) * VEC, w[jj]);
+      }
+#pragma unroll
+    for (int jj = 0; jj < SWEEP_U; ++jj)
+      if (g0 + jj < g_hi) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) mine += (double)(implicit ? expf((w[jj][e] - mx) * inv_temp) : w[jj][e]);
+      }
+  }
+  // inclusive scan over threads: wave-level shuffles, then wave totals
+  double incl = mine;
+  const int lane = t & 63, wv = t >> 6;
+  for (int o = 1; o < 64; o <<= 1) {
+    const double up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
+  }
+  __syncthreads();   // earlier readers of the shared slots are done
+  if (lane == 63) s_scan[wv] = incl;
+  if (t == 0) { *s_pick = 0x7fffffff; *s_ans = V - 1; }
+  __syncthreads();
+  double before = 0.0, total = 0.0;
+  for (int w = 0; w < SW_THREADS / 64; ++w) {
+    if (w < wv) before += s_scan[w];
+    total += s_scan[w];
+  }
+  incl += before;
+  const double excl = incl - mine;
+  const double target = (double)r * total;
+  // the first thread whose inclusive sum exceeds the target holds the answer
+  if (incl > target && excl <= target && g_hi > g_lo) atomicMin(s_pick, t);
+  __syncthreads();
+  if (t == *s_pick) {
+    double run = excl;
+    int ans = g_hi * VEC - 1;
+    for (int i = g_lo * VEC; i < g_hi * VEC; ++i) {
+      const float w = implicit ? expf((load_logit<BF16>(logits, lrow + i) - mx) * inv_temp) : resid[i];
+      run += (double)w;
+      if (run > target) { ans = i; break; }
+    }
+    *s_ans = ans;
+  }
+  __syncthreads();
+  return *s_ans;
+}
+
+// ---------------------------------------------------------------------------------------------
 // greedy walk: blockDim = 128, thread v <-> node v
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(128) greedy_walk_kernel(int N, const int32_t* __restrict__ node_argmax,
@@ -202,7 +272,6 @@ __global__ void __launch_bounds__(128) greedy_walk_kernel(int N, const int32_t* 
 // ---------------------------------------------------------------------------------------------
 // stochastic walk: blockDim = 1024
 // ---------------------------------------------------------------------------------------------
-constexpr int SW_THREADS = 1024;
 
 template <bool BF16, int VEC>
 __global__ void __launch_bounds__(SW_THREADS) stochastic_walk_kernel(
@@ -217,7 +286,7 @@ __global__ void __launch_bounds__(SW_THREADS) stochastic_walk_kernel(
   __shared__ int s_nchild;
   __shared__ float s_fsum[SW_THREADS / 64];
   __shared__ double s_scan[SW_THREADS / 64];
-  __shared__ int s_pick;
+  __shared__ int s_pick, s_ans;
 
   const int b = blockIdx.x, t = threadIdx.x;
   float* resid0 = resid_all + (long)b * V;
@@ -346,65 +415,31 @@ __global__ void __launch_bounds__(SW_THREADS) stochastic_walk_kernel(
     __syncthreads();
   }
 
-  // final token: inverse CDF in ascending token id. Every thread owns a contiguous range of the
-  // vocabulary and sums its weights in float64; a block scan finds the thread whose range holds the
-  // target, which then walks its range in order.
-  const long lrow = ((long)b * N + u) * V;
-  const int per_thread = ((V + SW_THREADS - 1) / SW_THREADS + VEC - 1) / VEC;    // groups per thread
-  const int g_lo = min(t * per_thread, n_groups), g_hi = min(g_lo + per_thread, n_groups);
-  double mine = 0.0;
-  for (int g0 = g_lo; g0 < g_hi; g0 += SWEEP_U) {
-    float w[SWEEP_U][VEC];
-#pragma unroll
-    for (int jj = 0; jj < SWEEP_U; ++jj)
-      if (g0 + jj < g_hi) {
-        if (implicit) load_logit_group<VEC, BF16>(logits, lrow + (long)(g0 + jj) * VEC, w[jj]);
-        else load_f32_group<VEC>(resid + (long)(g0 + jj) * VEC, w[jj]);
-      }
-#pragma unroll
-    for (int jj = 0; jj < SWEEP_U; ++jj)
-      if (g0 + jj < g_hi) {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) mine += (double)(implicit ? expf((w[jj][e] - mx) * inv_temp) : w[jj][e]);
-      }
-  }
-  // inclusive scan over threads: wave-level shuffles, then wave totals
-  double incl = mine;
-  const int lane = t & 63, wv = t >> 6;
-  for (int o = 1; o < 64; o <<= 1) {
-    const double up = __shfl_up(incl, o);
-    if (lane >= o) incl += up;
-  }
-  if (lane == 63) s_scan[wv] = incl;
-  if (t == 0) s_pick = 0x7fffffff;
-  __syncthreads();
-  double before = 0.0, total = 0.0;
-  for (int w = 0; w < SW_THREADS / 64; ++w) {
-    if (w < wv) before += s_scan[w];
-    total += s_scan[w];
-  }
-  incl += before;
-  const double excl = incl - mine;
-  const double target = (double)u_final[b] * total;
-  // the first thread whose inclusive sum exceeds the target holds the answer
-  if (incl > target && excl <= target && g_hi > g_lo) atomicMin(&s_pick, t);
-  __syncthreads();
-  const int pick = s_pick;
-  if (pick == 0x7fffffff) {
-    if (t == 0) { out_tokens[(long)b * Lmax + k] = V - 1; len[b] = k + 1; }
-    return;
-  }
-  if (t == pick) {
-    double run = excl;
-    int ans = g_hi * VEC - 1;
-    for (int i = g_lo * VEC; i < g_hi * VEC; ++i) {
-      const float w = implicit ? expf((load_logit<BF16>(logits, lrow + i) - mx) * inv_temp) : resid[i];
-      run += (double)w;
-      if (run > target) { ans = i; break; }
-    }
+  // final token: inverse CDF in ascending token id over the current P
+  const int ans = inverse_cdf_draw<BF16, VEC>(logits, ((long)b * N + u) * V, resid, implicit, mx, inv_temp, V, u_final[b],
+                                              s_scan, &s_pick, &s_ans);
+  if (t == 0) {
     out_tokens[(long)b * Lmax + k] = ans;
     len[b] = k + 1;
   }
+}
+
+// ---------------------------------------------------------------------------------------------
+// naive sampling (Section 4.3): x_u ~ softmax(logits[u] / T) for every node at once, one block per
+// (request, node) row, by inverse CDF with the caller's uniform. The walk that follows is the greedy
+// walk on these tokens: move to the child whose token equals x_u, else emit x_u and stop.
+// ---------------------------------------------------------------------------------------------
+template <bool BF16, int VEC>
+__global__ void __launch_bounds__(SW_THREADS) node_sample_kernel(const void* __restrict__ logits, int V, float inv_temp,
+                                                                 const float* __restrict__ node_max,
+                                                                 const float* __restrict__ u_sample,
+                                                                 int32_t* __restrict__ node_sample) {
+  __shared__ double s_scan[SW_THREADS / 64];
+  __shared__ int s_pick, s_ans;
+  const long row = blockIdx.x;
+  const int ans = inverse_cdf_draw<BF16, VEC>(logits, row * V, nullptr, true, node_max[row], inv_temp, V, u_sample[row],
+                                              s_scan, &s_pick, &s_ans);
+  if (threadIdx.x == 0) node_sample[row] = ans;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -419,6 +454,20 @@ hipError_t launch_node_stats(int B, int N, int V, int logits_dtype, const void* 
   else if (vec) SPEC_NS(false, 4);
   else SPEC_NS(false, 1);
 #undef SPEC_NS
+  return hipGetLastError();
+}
+
+hipError_t launch_node_sample(int B, int N, int V, int logits_dtype, const void* logits, float inv_temp,
+                              const float* node_max, const float* u_sample, int32_t* node_sample, hipStream_t s) {
+  const bool bf16 = logits_dtype == SPEC_BF16, vec = (V % 4 == 0);
+#define SPEC_NSM(BF, VE)                                                                                          \
+  hipLaunchKernelGGL((node_sample_kernel<BF, VE>), dim3(B * N), dim3(SW_THREADS), 0, s, logits, V, inv_temp, node_max, \
+                     u_sample, node_sample)
+  if (bf16 && vec) SPEC_NSM(true, 4);
+  else if (bf16) SPEC_NSM(true, 1);
+  else if (vec) SPEC_NSM(false, 4);
+  else SPEC_NSM(false, 1);
+#undef SPEC_NSM
   return hipGetLastError();
 }
 

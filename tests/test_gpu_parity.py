@@ -3,6 +3,7 @@
 Bars: attention max-abs 1e-5 for float32 inputs, |g-o| <= 2e-2 + 1e-2*|o| for bf16 inputs (oracle in
 float64, not rounded); append, commit, verification decisions, paths and tokens bit-exact.
 """
+import dataclasses
 import os
 
 import numpy as np
@@ -341,6 +342,79 @@ def test_stochastic_many_rejections_and_temperature(spec, seed):
 
 def test_stochastic_bf16_logits(spec):
     _stochastic_case(spec, wl.CONFIGS[2], seed=31, logits_dtype=torch.bfloat16)
+
+
+def _naive_case(spec, cfg, seed=None, temperature=1.0, logits_dtype=torch.float32, tau=1.2):
+    """Naive sampling (Section 4.3) on the stochastic workload's trees (children sampled from the drafts)."""
+    inp = wl.make_verify_inputs(cfg, seed=seed, mode="stochastic", tau=tau, logits_dtype=logits_dtype)
+    lg = inp["logits"].float().numpy()
+    us = inp["rng"].random((cfg.B, cfg.N), dtype=np.float32)
+    us, redraws = vetting.vet_sample_uniforms(lg, us, inp["rng"], temperature=temperature)
+    rp, rl, rt, rsamp = orc.verify_naive(lg, inp["tree_token"].numpy(), inp["tree_parent"].numpy(), us, temperature)
+    status = torch.zeros(cfg.B, dtype=torch.int32, device=DEV)
+    path, ln, toks, samp = spec.spec_verify_naive(_dev(inp["logits"]), _dev(inp["tree_token"]), _dev(inp["tree_parent"]),
+                                                  _dev(torch.from_numpy(us)), temperature=temperature, status=status)
+    torch.cuda.synchronize()
+    assert np.array_equal(samp.cpu().numpy(), rsamp)          # every node's draw, visited or not
+    assert np.array_equal(ln.cpu().numpy(), rl), (ln.cpu().numpy(), rl)
+    assert np.array_equal(path.cpu().numpy(), rp) and np.array_equal(toks.cpu().numpy(), rt)
+    assert (status.cpu().numpy() == 0).all()
+    return rl, redraws
+
+
+@pytest.mark.parametrize("c", [1, 2, 3])
+def test_naive_sampling_configs(spec, c):
+    rl, redraws = _naive_case(spec, wl.CONFIGS[c], tau=None if c == 1 else 1.2)
+    print(f"config {c}: accepted lengths {rl.tolist()}, re-drawn uniforms {redraws}")
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_naive_sampling_odd_vocabulary_temperature_bf16(spec, seed):
+    cfg = wl.Config(97, "ns", "f32", B=5, H=1, D=64, P=1, N=33, tree="random_branching", V=777, n_ssm=2)
+    _naive_case(spec, cfg, seed=seed, temperature=[1.0, 0.6, 1.7][seed])
+    cfg = wl.Config(98, "ns2", "f32", B=3, H=1, D=64, P=1, N=9, tree="random_parent", V=5, n_ssm=1)
+    _naive_case(spec, cfg, seed=seed, tau=None)
+    _naive_case(spec, wl.CONFIGS[2], seed=40 + seed, logits_dtype=torch.bfloat16)
+
+
+def test_naive_sampling_flags_malformed_tree_and_checks_arguments(spec):
+    cfg = wl.CONFIGS[1]
+    inp = wl.make_verify_inputs(cfg, mode="greedy")
+    par = inp["tree_parent"].clone()
+    par[0, 3] = 5
+    us = torch.rand(cfg.B, cfg.N)
+    status = torch.zeros(cfg.B, dtype=torch.int32, device=DEV)
+    path, ln, toks, _ = spec.spec_verify_naive(_dev(inp["logits"]), _dev(inp["tree_token"]), _dev(par), _dev(us), status=status)
+    torch.cuda.synchronize()
+    assert ln.cpu().numpy()[0] == 0 and status.cpu().numpy()[0] == orc.ST_BAD_TREE
+    with pytest.raises(spec.SpecError) as e:
+        spec.spec_verify_naive(_dev(inp["logits"]), _dev(inp["tree_token"]), _dev(inp["tree_parent"]), _dev(us), temperature=0.0)
+    assert e.value.code == spec.ERR_INVALID_ARG
+    with pytest.raises(spec.SpecError) as e:
+        spec.spec_verify_naive(_dev(inp["logits"]), _dev(inp["tree_token"]), _dev(inp["tree_parent"]), _dev(us),
+                               workspace=torch.empty(256, dtype=torch.uint8, device=DEV)[:16])
+    assert e.value.code == spec.ERR_WORKSPACE
+
+
+def test_multi_step_sampling_verifies_more_tokens_than_naive_sampling(spec):
+    """The comparison of Table 3 on synthetic drafts: same trees (width 3 at one level, children sampled
+    from drafts close to the LLM), many seeds; multi-step speculative sampling accepts at least as many
+    tokens per step on average (Theorem 4.3 gives the per-node inequality)."""
+    cfg = dataclasses.replace(wl.CONFIGS[2], B=64, V=512)
+    tot_mss = tot_ns = 0
+    for seed in range(4):
+        inp = wl.make_verify_inputs(cfg, seed=900 + seed, mode="stochastic", tau=1.2)
+        us = torch.from_numpy(inp["rng"].random((cfg.B, cfg.N), dtype=np.float32))
+        _, ln_m, _ = spec.spec_verify_stochastic(_dev(inp["logits"]), _dev(inp["probs_ssm"]), _dev(inp["ssm_row"]),
+                                                 _dev(inp["tree_token"]), _dev(inp["tree_parent"]), _dev(inp["u_accept"]),
+                                                 _dev(inp["u_order"]), _dev(inp["u_final"]))
+        _, ln_n, _, _ = spec.spec_verify_naive(_dev(inp["logits"]), _dev(inp["tree_token"]), _dev(inp["tree_parent"]), _dev(us))
+        torch.cuda.synchronize()
+        tot_mss += int(ln_m.sum())
+        tot_ns += int(ln_n.sum())
+    n = 4 * cfg.B
+    print(f"tokens verified per step: multi-step {tot_mss / n:.3f}, naive {tot_ns / n:.3f}, ratio {tot_mss / tot_ns:.3f}")
+    assert tot_mss > tot_ns
 
 
 # ------------------------------------------------------------------------------------------------
