@@ -5,6 +5,7 @@
  * speculated token tree in a single pass of the LLM (SpecInfer, arxiv 2305.09781, Section 4 and
  * Algorithm 2). The calls below are the per-layer and per-pass steps of that iteration:
  *
+ *   before the pass: spec_tree_expand_topk (per speculation step) | spec_tree_merge   (build the token tree)
  *   for each layer:  spec_kv_append  ->  spec_tree_attention      (or the fused spec_tree_attention_append)
  *   once per pass:   spec_verify_greedy | spec_verify_stochastic | spec_verify_naive  ->  spec_kv_commit (all layers)
  *
@@ -43,6 +44,8 @@ extern "C" {
 #endif
 
 #define SPEC_MAX_TREE_NODES 128
+#define SPEC_MAX_MERGE_INPUT_NODES 1024 /* spec_tree_merge: trees per request x node slots per tree */
+#define SPEC_MAX_TOPK 16                /* spec_tree_expand_topk: children per frontier node        */
 #define SPEC_MAX_COMMIT_LAYERS 128
 
 /* return codes */
@@ -120,6 +123,40 @@ int spec_tree_attention_append(const spec_attn_desc_t* desc, const void* q, cons
                                void* hip_stream);
 
 /*
+ * Expansion-based token tree construction, one step (Section 3): for every frontier node f of every
+ * request, the k tokens with the largest ssm_logits[b,f,:] (largest first; ties: lowest token id) become
+ * the tokens of its children: tree_token[b, child_slot[f*k + j]] = j-th pick. The tree's shape is fixed
+ * by the static expansion configuration <k_1,...,k_m>, so parent / depth arrays and child_slot are
+ * the caller's constants; only tokens are data. child_slot: DEVICE array [F,k] of node indices in
+ * [0, N); an index outside sets SPEC_ST_BAD_TREE for the request and writes nothing. 1 <= k <=
+ * min(V, SPEC_MAX_TOPK). ssm_logits: SPEC_F32 or SPEC_BF16, [B,F,V] contiguous.
+ */
+int spec_tree_expand_topk(int32_t B, int32_t F, int32_t V, int32_t logits_dtype, const void* ssm_logits, int32_t k,
+                          const int32_t* child_slot /*[F,k]*/, int32_t N, int32_t* tree_token /*[B,N]*/,
+                          int32_t* status /*[B] or NULL*/, void* hip_stream);
+
+/*
+ * Token tree merge (Definition 3.2): the M token trees of a request (one per SSM) become one tree that
+ * holds exactly their token sequences S_u, each once. Input tree i of request b uses the first
+ * in_size[b,i] of its Nin slots (root first, in_parent < own index, tokens >= 0); all roots carry the
+ * same token (the last verified token). M * Nin <= SPEC_MAX_MERGE_INPUT_NODES, Nout <= SPEC_MAX_TREE_NODES.
+ * Output, per request, Nout slots: merged nodes numbered depth-first (pre-order), the children of a node
+ * ordered by first appearance when the trees are scanned i = 0..M-1, nodes in index order;
+ * out_ssm[b,n] = lowest tree index whose tree holds node n's sequence (the draft distribution
+ * spec_verify_stochastic should test it against); out_size[b] = number of merged nodes; slots at and
+ * beyond it are padding nodes (parent 0, depth 1, token -1, ssm -1) that no verifier accepts, so the
+ * arrays can go straight to the attention and verification calls with N = Nout.
+ * node_map[b,i,u] (may be NULL) = merged index of input node u of tree i, -1 for unused slots.
+ * Status: SPEC_ST_BAD_TREE (malformed input tree, differing roots) or SPEC_ST_CAPACITY (more than Nout
+ * sequences): out_size = 0, a root slot plus padding, node_map = -1.
+ */
+int spec_tree_merge(int32_t B, int32_t M, int32_t Nin, const int32_t* in_parent /*[B,M,Nin]*/,
+                    const int32_t* in_token /*[B,M,Nin]*/, const int32_t* in_size /*[B,M]*/, int32_t Nout,
+                    int32_t* out_parent /*[B,Nout]*/, int32_t* out_depth /*[B,Nout]*/, int32_t* out_token /*[B,Nout]*/,
+                    int32_t* out_ssm /*[B,Nout]*/, int32_t* out_size /*[B]*/, int32_t* node_map /*[B,M,Nin] or NULL*/,
+                    int32_t* status /*[B] or NULL*/, void* hip_stream);
+
+/*
  * Greedy verification (Algorithm 2, VerifyGreedy). O(u) = argmax_x logits_llm[b,u,x] (lowest token id
  * on ties). Starting at the root, while some child v of u has tree_token[b,v] == O(u) (lowest node
  * index if several) accept v and continue from it; finally emit the bonus token O(u).
@@ -162,6 +199,8 @@ int spec_verify_naive(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, con
  * When no child is left (or u is a leaf) the last token is drawn from the current P by inverse CDF
  * over ascending token id: the first k with cumsum(P)[k] > u_final[b] * sum(P).
  * The uniforms are supplied by the caller (float32 in [0,1)); the library draws no random numbers.
+ * A node with a negative tree_token is a padding node (spec_tree_merge produces them): no verifier
+ * ever accepts it.
  * Outputs as for spec_verify_greedy. SPEC_ST_ZERO_RESIDUAL: a residual had no mass; the previous P
  * was kept. workspace: spec_verify_stochastic_workspace_bytes(B, N, V) bytes.
  */

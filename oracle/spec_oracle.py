@@ -14,6 +14,7 @@ What each function follows:
   verify_greedy          Algorithm 2, VerifyGreedy
   verify_stochastic      Algorithm 2, VerifyStochastic (multi-step speculative sampling)
   sample_nodes, verify_naive  naive sampling, the alternative of Section 4.3 (Theorem 4.3, Table 3)
+  expand_topk, tree_merge     Section 3: one step of expansion-based construction; Definition 3.2
   kv_commit              Algorithm 2 main loop (verified tokens are appended to the sequence), so the
                          K/V rows of the accepted path must become the contiguous prefix
 
@@ -23,7 +24,9 @@ path enumeration and incremental decoding on a bigram model (greedy); exact cell
 against a closed-form law, Theorem 4.2 and 4.3 in closed form, chi-square over many seeds
 (stochastic); brute-force inverse CDF, the exact first-step law, the closed-form rejection probability of
 Theorem 4.3 and the low-temperature limit against the greedy verifier (naive sampling); round trips and
-overlapping-path cases (append / commit). No function is unpinned.
+overlapping-path cases (append / commit); sequence-set equality by brute force, idempotence, chains
+merging into a trie (tree merge); scalar selection loop and the argmax special case (top-k). No function
+is unpinned.
 
 Readings taken where the paper is silent are listed next to each function.
 """
@@ -189,7 +192,8 @@ def verify_stochastic(logits, probs_ssm, ssm_row, tree_token, tree_parent, u_acc
     ascending token id: the first k with cumsum(P)[k] > u_final * sum(P).
 
     Readings: the residual persists only across the siblings of one node; an all-zero residual keeps
-    the previous P and sets ST_ZERO_RESIDUAL; uniforms are float32 in [0,1) supplied by the caller.
+    the previous P and sets ST_ZERO_RESIDUAL; uniforms are float32 in [0,1) supplied by the caller; a
+    node with a negative token is padding (see tree_merge) and is skipped.
 
     Returns accepted_path [B,N], accepted_len [B], out_tokens [B,N], status [B] and, if asked,
     margins [B,2]: [:,0] the smallest relative gap |r Q(x) - P(x)| / max(...) over the ratio tests
@@ -211,7 +215,8 @@ def verify_stochastic(logits, probs_ssm, ssm_row, tree_token, tree_parent, u_acc
             z = logits[b, u] / float(temperature)
             P = np.exp(z - z.max())
             P = P / P.sum()
-            H = sorted(children(tree_parent[b], u), key=lambda v: (float(u_order[b, v]), v))
+            H = sorted((v for v in children(tree_parent[b], u) if int(tree_token[b, v]) >= 0),
+                       key=lambda v: (float(u_order[b, v]), v))   # token < 0: padding node, never a candidate
             accepted = False
             for s in H:
                 x = int(tree_token[b, s])
@@ -307,6 +312,90 @@ def verify_naive(logits, tree_token, tree_parent, u_sample, temperature=1.0):
             u = nxt
         ln[b] = k + 1
     return path, ln, toks, node_sample
+
+
+# ---------------------------------------------------------------------------------------------
+# token-tree construction  (Section 3: expansion-based construction, Definition 3.2 token tree merge)
+# ---------------------------------------------------------------------------------------------
+
+def expand_topk(logits, k):
+    """Expansion-based construction, one step: the k most likely next tokens of every frontier node,
+    most likely first (ties: lowest token id). logits [..., V] -> token ids [..., k]."""
+    logits = np.asarray(logits, dtype=np.float64)
+    V = logits.shape[-1]
+    flat = logits.reshape(-1, V)
+    out = np.zeros((flat.shape[0], k), dtype=np.int32)
+    for r in range(flat.shape[0]):
+        ids = sorted(range(V), key=lambda i: (-flat[r, i], i))
+        out[r] = ids[:k]
+    return out.reshape(logits.shape[:-1] + (k,))
+
+
+def tree_merge(in_parent, in_token, in_size, n_out):
+    """Token tree merge (Definition 3.2) of the M trees of one request: the merged tree holds exactly the
+    token sequences S_u of the input trees, each once. Input tree i has in_size[i] nodes (root first,
+    parent[u] < u) out of the Nin slots of in_parent[i] / in_token[i]; all roots carry the same token.
+
+    Readings (the paper fixes none of these): a merged node's children are ordered by first appearance
+    when the trees are scanned in order i = 0..M-1, nodes in index order; nodes are numbered in
+    depth-first (pre-)order; out_ssm is the lowest tree index whose tree holds the node's sequence;
+    slots past the merged size are padding nodes (parent 0, depth 1, token -1, ssm -1) that no verifier
+    ever accepts.
+
+    Returns (parent [n_out], depth [n_out], token [n_out], ssm [n_out], size, node_map [M,Nin], status):
+    node_map[i,u] = merged index of input node u of tree i (-1 for unused slots); status ST_BAD_TREE for
+    a malformed input tree or differing root tokens, ST_CAPACITY if more than n_out sequences (size 0)."""
+    in_parent = np.asarray(in_parent)
+    in_token = np.asarray(in_token)
+    M, Nin = in_parent.shape
+    node_map = np.full((M, Nin), -1, dtype=np.int32)
+    pad = (np.zeros(n_out, np.int32), np.ones(n_out, np.int32), np.full(n_out, -1, np.int32), np.full(n_out, -1, np.int32))
+
+    def fail(bit):
+        par, dep, tok, ssm = (a.copy() for a in pad)
+        par[0], dep[0] = -1, 0
+        return par, dep, tok, ssm, 0, np.full((M, Nin), -1, dtype=np.int32), bit
+
+    nodes = []          # merged nodes in order of first appearance: [parent id, token, tree index]
+    trie = {}
+    for i in range(M):
+        sz = int(in_size[i])
+        if sz < 1 or sz > Nin or int(in_parent[i, 0]) != -1 or int(in_token[i, 0]) != int(in_token[0, 0]):
+            return fail(ST_BAD_TREE)
+        if i == 0:
+            nodes.append([-1, int(in_token[0, 0]), 0])
+        ids = [0] * sz
+        for u in range(1, sz):
+            p = int(in_parent[i, u])
+            if not (0 <= p < u) or int(in_token[i, u]) < 0:
+                return fail(ST_BAD_TREE)
+            key = (ids[p], int(in_token[i, u]))
+            if key not in trie:
+                trie[key] = len(nodes)
+                nodes.append([ids[p], int(in_token[i, u]), i])
+            ids[u] = trie[key]
+        node_map[i, :sz] = ids
+    if len(nodes) > n_out:
+        return fail(ST_CAPACITY)
+    kids = [[] for _ in nodes]
+    for j in range(1, len(nodes)):
+        kids[nodes[j][0]].append(j)
+    order = []          # depth-first pre-order
+    stack = [0]
+    while stack:
+        j = stack.pop()
+        order.append(j)
+        stack.extend(reversed(kids[j]))
+    new_id = {j: n for n, j in enumerate(order)}
+    par, dep, tok, ssm = (a.copy() for a in pad)
+    for j, (pj, tj, sj) in enumerate(nodes):
+        n = new_id[j]
+        par[n] = -1 if pj < 0 else new_id[pj]
+        tok[n], ssm[n] = tj, sj
+    for n in range(len(nodes)):
+        dep[n] = 0 if par[n] < 0 else dep[par[n]] + 1
+    node_map = np.where(node_map >= 0, np.vectorize(lambda j: new_id.get(j, -1))(node_map), -1).astype(np.int32)
+    return par, dep, tok, ssm, len(nodes), node_map, 0
 
 
 # ---------------------------------------------------------------------------------------------

@@ -24,7 +24,7 @@ EXPORTED = [
     "spec_kv_append", "spec_tree_attention", "spec_tree_attention_append", "spec_tree_attention_workspace_bytes",
     "spec_verify_greedy",
     "spec_verify_stochastic", "spec_verify_stochastic_workspace_bytes", "spec_verify_naive",
-    "spec_verify_naive_workspace_bytes", "spec_kv_commit", "spec_strerror",
+    "spec_verify_naive_workspace_bytes", "spec_tree_expand_topk", "spec_tree_merge", "spec_kv_commit", "spec_strerror",
     "spec_version",
 ]
 
@@ -81,6 +81,10 @@ def load():
     lib.spec_verify_naive.restype = ctypes.c_int
     lib.spec_verify_naive_workspace_bytes.argtypes = [i32, i32, i32]
     lib.spec_verify_naive_workspace_bytes.restype = sz
+    lib.spec_tree_expand_topk.argtypes = [i32, i32, i32, i32, vp, i32, vp, i32, vp, vp, vp]
+    lib.spec_tree_expand_topk.restype = ctypes.c_int
+    lib.spec_tree_merge.argtypes = [i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.spec_tree_merge.restype = ctypes.c_int
     lib.spec_kv_commit.argtypes = [dp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i32, vp, vp, vp, vp, vp]
     lib.spec_kv_commit.restype = ctypes.c_int
     lib.spec_strerror.argtypes = [ctypes.c_int]
@@ -256,6 +260,35 @@ def spec_verify_naive(logits, tree_token, tree_parent, u_sample, temperature: fl
                                     workspace.numel() * workspace.element_size(), _ptr(status), _stream(stream)),
            "spec_verify_naive")
     return path, ln, toks, samp
+
+
+def spec_tree_expand_topk(ssm_logits, k: int, child_slot, tree_token, status=None, stream=None):
+    """tree_token[b, child_slot[f, j]] = j-th most likely token of ssm_logits[b, f, :] (in place)."""
+    B, F, V = ssm_logits.shape
+    N = tree_token.shape[1]
+    if child_slot.dtype != torch.int32 or tuple(child_slot.shape) != (F, k) or not child_slot.is_contiguous():
+        raise ValueError("child_slot must be contiguous int32 [F, k]")
+    if not ssm_logits.is_contiguous() or not tree_token.is_contiguous() or tree_token.dtype != torch.int32:
+        raise ValueError("ssm_logits and tree_token (int32) must be contiguous")
+    _check(load().spec_tree_expand_topk(B, F, V, _dtype_code(ssm_logits.dtype), _ptr(ssm_logits), k, _ptr(child_slot), N,
+                                        _ptr(tree_token), _ptr(status), _stream(stream)), "spec_tree_expand_topk")
+    return tree_token
+
+
+def spec_tree_merge(in_parent, in_token, in_size, Nout: int, status=None, stream=None, want_node_map: bool = True):
+    """Returns (parent [B,Nout], depth, token, ssm, size [B], node_map [B,M,Nin] or None)."""
+    B, M, Nin = in_parent.shape
+    dev = in_parent.device
+    for t in (in_parent, in_token, in_size):
+        if t.dtype != torch.int32 or not t.is_contiguous():
+            raise ValueError("tree_merge inputs must be contiguous int32")
+    mk = lambda *shape: torch.empty(shape, dtype=torch.int32, device=dev)
+    par, dep, tok, ssm, size = mk(B, Nout), mk(B, Nout), mk(B, Nout), mk(B, Nout), mk(B)
+    node_map = mk(B, M, Nin) if want_node_map else None
+    _check(load().spec_tree_merge(B, M, Nin, _ptr(in_parent), _ptr(in_token), _ptr(in_size), Nout, _ptr(par), _ptr(dep),
+                                  _ptr(tok), _ptr(ssm), _ptr(size), _ptr(node_map), _ptr(status), _stream(stream)),
+           "spec_tree_merge")
+    return par, dep, tok, ssm, size, node_map
 
 
 def spec_kv_commit(k_caches: Sequence[torch.Tensor], v_caches: Sequence[torch.Tensor], accepted_path, accepted_len,

@@ -217,6 +217,31 @@ static int check_verify_common(int32_t B, int32_t N, int32_t V, int32_t logits_d
   return SPEC_OK;
 }
 
+int spec_tree_expand_topk(int32_t B, int32_t F, int32_t V, int32_t logits_dtype, const void* ssm_logits, int32_t k,
+                          const int32_t* child_slot, int32_t N, int32_t* tree_token, int32_t* status, void* hip_stream) {
+  if (B <= 0 || F <= 0 || V <= 0 || N <= 0 || k <= 0) return SPEC_ERR_INVALID_ARG;
+  if (k > V || k > SPEC_MAX_TOPK || N > SPEC_MAX_TREE_NODES) return SPEC_ERR_UNSUPPORTED;
+  if (logits_dtype != SPEC_F32 && logits_dtype != SPEC_BF16) return SPEC_ERR_UNSUPPORTED;
+  if (!ssm_logits || !child_slot || !tree_token) return SPEC_ERR_INVALID_ARG;
+  return launch_expand_topk(B, F, V, logits_dtype, ssm_logits, k, child_slot, N, tree_token, status,
+                            (hipStream_t)hip_stream) == hipSuccess
+             ? SPEC_OK
+             : SPEC_ERR_HIP;
+}
+
+int spec_tree_merge(int32_t B, int32_t M, int32_t Nin, const int32_t* in_parent, const int32_t* in_token,
+                    const int32_t* in_size, int32_t Nout, int32_t* out_parent, int32_t* out_depth, int32_t* out_token,
+                    int32_t* out_ssm, int32_t* out_size, int32_t* node_map, int32_t* status, void* hip_stream) {
+  if (B <= 0 || M <= 0 || Nin <= 0 || Nout <= 0) return SPEC_ERR_INVALID_ARG;
+  if ((long)M * Nin > SPEC_MAX_MERGE_INPUT_NODES || Nout > SPEC_MAX_TREE_NODES) return SPEC_ERR_UNSUPPORTED;
+  if (!in_parent || !in_token || !in_size || !out_parent || !out_depth || !out_token || !out_ssm || !out_size)
+    return SPEC_ERR_INVALID_ARG;
+  return launch_tree_merge(B, M, Nin, in_parent, in_token, in_size, Nout, out_parent, out_depth, out_token, out_ssm,
+                           out_size, node_map, status, (hipStream_t)hip_stream) == hipSuccess
+             ? SPEC_OK
+             : SPEC_ERR_HIP;
+}
+
 int spec_verify_greedy(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, const void* logits_llm,
                        const int32_t* tree_token, const int32_t* tree_parent, int32_t Lmax, int32_t* accepted_path,
                        int32_t* accepted_len, int32_t* out_tokens, int32_t* node_argmax, void* workspace,

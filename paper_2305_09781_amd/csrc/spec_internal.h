@@ -57,6 +57,12 @@ hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const Attn
 hipError_t launch_attn_combine(const spec_attn_desc_t& d, const AttnPlan& plan, const int32_t* parent,
                                const int32_t* depth, const int32_t* prefix_len, const void* ws, void* out,
                                int32_t* status, hipStream_t s);
+hipError_t launch_expand_topk(int B, int F, int V, int logits_dtype, const void* logits, int k, const int32_t* child_slot,
+                              int N, int32_t* tree_token, int32_t* status, hipStream_t s);
+hipError_t launch_tree_merge(int B, int M, int Nin, const int32_t* in_parent, const int32_t* in_token,
+                             const int32_t* in_size, int Nout, int32_t* out_parent, int32_t* out_depth,
+                             int32_t* out_token, int32_t* out_ssm, int32_t* out_size, int32_t* node_map, int32_t* status,
+                             hipStream_t s);
 hipError_t launch_node_stats(int B, int N, int V, int logits_dtype, const void* logits, float inv_temp,
                              int32_t* node_argmax, float* node_max, float* node_sumexp, hipStream_t s);
 hipError_t launch_node_sample(int B, int N, int V, int logits_dtype, const void* logits, float inv_temp,

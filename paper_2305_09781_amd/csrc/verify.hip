@@ -301,9 +301,9 @@ __global__ void __launch_bounds__(SW_THREADS) stochastic_walk_kernel(
   __syncthreads();
   if (t == 0) s_flag = 0;
   __syncthreads();
-  if (valid && t >= 1 && t < N) {
+  if (valid && t >= 1 && t < N) {   // a negative token marks a padding node: never a candidate, nothing to check
     const int x = tok[t], r = ssm_row[(long)b * N + t];
-    if (x < 0 || x >= V || r < 0 || r >= R) atomicOr(&s_flag, 1);
+    if (x >= 0 && (x >= V || r < 0 || r >= R)) atomicOr(&s_flag, 1);
   }
   __syncthreads();
   valid = valid && (s_flag == 0);
@@ -326,7 +326,7 @@ __global__ void __launch_bounds__(SW_THREADS) stochastic_walk_kernel(
     // children of u in ascending (u_order, index)
     if (t == 0) s_nchild = 0;
     __syncthreads();
-    if (t < N && par[t] == u) s_child[atomicAdd(&s_nchild, 1)] = t;
+    if (t < N && par[t] == u && tok[t] >= 0) s_child[atomicAdd(&s_nchild, 1)] = t;
     __syncthreads();
     const int nchild = (k + 1 < Lmax) ? s_nchild : 0;
     if (nchild == 0) break;
