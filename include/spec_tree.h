@@ -91,6 +91,22 @@ int spec_kv_append(const spec_attn_desc_t* desc, const void* k_new, const void* 
                    void* hip_stream);
 
 /*
+ * KV append with the rotary position embedding applied to the keys on the way in (the paper's LLaMA
+ * models rotate q and k by position; the paper itself is silent on where). Tree token i of request b
+ * sits at sequence position prefix_len[b] + tree_depth[b,i] - its depth below the last verified
+ * token, not its row in the cache. Half-split pairing: dimension j < D/2 rotates with j + D/2,
+ *     k'[j] = k[j] cos - k[j+D/2] sin,   k'[j+D/2] = k[j+D/2] cos + k[j] sin,
+ * cos / sin = rope_cos / rope_sin[position, j] (float32 DEVICE tables [rope_len, D/2] supplied by the
+ * caller), computed in float32 and rounded to the cache's element type; V is copied unchanged.
+ * A request that does not fit the cache or has a position outside [0, rope_len) is left untouched and
+ * flagged SPEC_ST_CAPACITY. Queries are expected to arrive already rotated.
+ */
+int spec_kv_append_rope(const spec_attn_desc_t* desc, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                        const int32_t* tree_depth /*[B,N]*/, const int32_t* prefix_len /*[B]*/,
+                        const float* rope_cos /*[rope_len, D/2]*/, const float* rope_sin /*[rope_len, D/2]*/,
+                        int32_t rope_len, int32_t* status /*[B] or NULL*/, void* hip_stream);
+
+/*
  * Tree attention (Definition 4.1; attention equations of Section 4.1; topology-aware causal mask of
  * Section 4.2). For every request b, head h and tree node i:
  *     out[b,i,h,:] = softmax_j( q[b,i,h,:] . k[b,h,j,:] * scale ) . v[b,h,j,:]

@@ -9,6 +9,8 @@ What each function follows:
                          causal mask: a tree token may see its ancestors and itself, nothing else)
   kv_append              Section 4.2, "depth-first search to update key-value cache": one cache
                          region holds the whole tree, token i at row prefix_len + i
+  rope_rotate, kv_append_rope  the same append with the rotary embedding of the paper's LLaMA models
+                         applied to the keys at position prefix_len + depth (a step adjacent to the path)
   tree_attention         Definition 4.1 with the attention equations of Section 4.1 (scores scaled by
                          1/sqrt(d), masked entries -inf, softmax, times V)
   verify_greedy          Algorithm 2, VerifyGreedy
@@ -100,6 +102,44 @@ def kv_append(k_cache, v_cache, k_new, v_new, prefix_len):
             continue
         for i in range(N):
             k_cache[b, :, p + i, :] = k_new[b, i, :, :]
+            v_cache[b, :, p + i, :] = v_new[b, i, :, :]
+    return status
+
+
+def rope_rotate(x, cos, sin):
+    """Rotary position embedding of one position, half-split pairing: dimension i < D/2 is paired with
+    i + D/2 and the pair is rotated by the angle whose cosine / sine are cos[i] / sin[i].
+    x [..., D], cos, sin [D/2]; float64."""
+    x = np.asarray(x, dtype=np.float64)
+    h = x.shape[-1] // 2
+    x1, x2 = x[..., :h], x[..., h:]
+    return np.concatenate([x1 * cos - x2 * sin, x2 * cos + x1 * sin], axis=-1)
+
+
+def kv_append_rope(k_cache, v_cache, k_new, v_new, prefix_len, tree_depth, rope_cos, rope_sin, storage="bf16"):
+    """KV append with the rotary embedding applied to the keys on the way in: tree token i of request b
+    sits at sequence position prefix_len[b] + tree_depth[b,i] (its depth below the last verified token,
+    not its row in the cache), K is rotated by that position's table row and rounded to the cache's
+    storage type ("bf16" or "f32"); V is copied. rope_cos, rope_sin: [rope_len, D/2] tables supplied by
+    the caller (float32 values). Returns status [B]: ST_CAPACITY if the tree does not fit the cache or a
+    position lies outside the tables (request untouched)."""
+    import torch
+    B, N = k_new.shape[0], k_new.shape[1]
+    S_cap = k_cache.shape[2]
+    rope_cos = np.asarray(rope_cos, dtype=np.float64)
+    rope_sin = np.asarray(rope_sin, dtype=np.float64)
+    status = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        p = int(prefix_len[b])
+        pos = [p + int(tree_depth[b, i]) for i in range(N)]
+        if p < 0 or p + N > S_cap or min(pos) < 0 or max(pos) >= rope_cos.shape[0]:
+            status[b] |= ST_CAPACITY
+            continue
+        for i in range(N):
+            rot = rope_rotate(k_new[b, i], rope_cos[pos[i]], rope_sin[pos[i]])          # [H, D]
+            t = torch.from_numpy(rot)
+            t = t.to(torch.bfloat16) if storage == "bf16" else t.to(torch.float32)
+            k_cache[b, :, p + i, :] = t.double().numpy()
             v_cache[b, :, p + i, :] = v_new[b, i, :, :]
     return status
 

@@ -21,7 +21,7 @@ ST_BAD_TREE, ST_CAPACITY, ST_BAD_PATH, ST_ZERO_RESIDUAL = 1, 2, 4, 8
 ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_CAPACITY, ERR_HIP, ERR_WORKSPACE = -1, -2, -3, -4, -5
 
 EXPORTED = [
-    "spec_kv_append", "spec_tree_attention", "spec_tree_attention_append", "spec_tree_attention_workspace_bytes",
+    "spec_kv_append", "spec_kv_append_rope", "spec_tree_attention", "spec_tree_attention_append", "spec_tree_attention_workspace_bytes",
     "spec_verify_greedy",
     "spec_verify_stochastic", "spec_verify_stochastic_workspace_bytes", "spec_verify_naive",
     "spec_verify_naive_workspace_bytes", "spec_tree_expand_topk", "spec_tree_merge", "spec_kv_commit", "spec_strerror",
@@ -64,6 +64,8 @@ def load():
     dp = ctypes.POINTER(AttnDesc)
     lib.spec_kv_append.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
     lib.spec_kv_append.restype = ctypes.c_int
+    lib.spec_kv_append_rope.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
+    lib.spec_kv_append_rope.restype = ctypes.c_int
     lib.spec_tree_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
     lib.spec_tree_attention.restype = ctypes.c_int
     lib.spec_tree_attention_append.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
@@ -148,6 +150,20 @@ def spec_kv_append(k_new, v_new, k_cache, v_cache, prefix_len, status=None, stre
     d = desc if desc is not None else make_desc(k_new, k_cache)
     _check(load().spec_kv_append(ctypes.byref(d), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
                                  _ptr(prefix_len), _ptr(status), _stream(stream)), "spec_kv_append")
+
+
+def spec_kv_append_rope(k_new, v_new, k_cache, v_cache, tree_depth, prefix_len, rope_cos, rope_sin, status=None, stream=None):
+    """KV append with the rotary embedding applied to K at position prefix_len + tree_depth (in place)."""
+    _same_layout(k_cache, v_cache, "k_cache and v_cache")
+    _same_layout(k_new, v_new, "k_new and v_new")
+    D = k_new.shape[-1]
+    for tab in (rope_cos, rope_sin):
+        if tab.dtype != torch.float32 or tab.dim() != 2 or tab.shape[1] != D // 2 or not tab.is_contiguous():
+            raise ValueError("rope tables must be contiguous float32 [rope_len, D/2]")
+    d = make_desc(k_new, k_cache)
+    _check(load().spec_kv_append_rope(ctypes.byref(d), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                      _ptr(tree_depth), _ptr(prefix_len), _ptr(rope_cos), _ptr(rope_sin),
+                                      rope_cos.shape[0], _ptr(status), _stream(stream)), "spec_kv_append_rope")
 
 
 def spec_tree_attention_workspace_bytes(desc: AttnDesc) -> int:

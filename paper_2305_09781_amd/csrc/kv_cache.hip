@@ -2,6 +2,8 @@
 // cache region for the whole tree) and commit of the accepted path (Algorithm 2 main loop: the
 // verified tokens join the sequence, so their rows become the contiguous continuation of the prefix).
 // Both are pure 16-byte-vector copies; they are bound by HBM traffic that is tiny next to attention.
+#include <hip/hip_bf16.h>
+
 #include "spec_internal.h"
 
 namespace spec {
@@ -31,6 +33,95 @@ __global__ void __launch_bounds__(256) kv_append_kernel(const uint4* __restrict_
   const long dst = b * kv_sb + h * kv_sh + (long)(p + i) * kv_ss + c;
   k_cache[dst] = k_new[src];
   v_cache[dst] = v_new[src];
+}
+
+// KV append with the rotary position embedding applied to K on the way in (half-split pairing:
+// dimension i < D/2 rotates with i + D/2). Token i of request b sits at position prefix_len[b] +
+// tree_depth[b,i]; cos / sin come from the caller's tables [rope_len, D/2]. grid = (chunks, B); a
+// block first checks that the request fits the cache and that all its positions lie inside the tables
+// (else it is left untouched and flagged), then every thread moves the two 16-byte pieces of one K row
+// that rotate with each other, and the same two pieces of V unchanged.
+template <bool BF16>
+__global__ void __launch_bounds__(256) kv_append_rope_kernel(const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
+                                                             uint4* __restrict__ k_cache, uint4* __restrict__ v_cache,
+                                                             const int32_t* __restrict__ tree_depth,
+                                                             const int32_t* __restrict__ prefix_len,
+                                                             const float* __restrict__ rope_cos,
+                                                             const float* __restrict__ rope_sin, int rope_len,
+                                                             int32_t* status, int N, int H, int D, int S_cap,
+                                                             int vec_per_row, long q_sb, long q_sn, long q_sh,
+                                                             long kv_sb, long kv_sh, long kv_ss) {
+  constexpr int EPV = BF16 ? 8 : 4;   // elements per 16-byte piece
+  __shared__ int s_bad;
+  const int b = blockIdx.y, t = threadIdx.x;
+  const int p = prefix_len[b];
+  if (t == 0) s_bad = (p < 0 || p > S_cap - N) ? 1 : 0;
+  __syncthreads();
+  for (int i = t; i < N; i += 256) {
+    const long pos = (long)p + tree_depth[(long)b * N + i];
+    if (pos < 0 || pos >= rope_len) atomicOr(&s_bad, 1);
+  }
+  __syncthreads();
+  if (s_bad != 0) {
+    if (blockIdx.x == 0 && t == 0) set_status(status, b, SPEC_ST_CAPACITY);
+    return;
+  }
+  const int half = vec_per_row / 2;
+  const long total = (long)N * H * half;
+  long idx = (long)blockIdx.x * 256 + t;
+  if (idx >= total) return;
+  const int c = (int)(idx % half);
+  idx /= half;
+  const int h = (int)(idx % H);
+  const int i = (int)(idx / H);
+  const int pos = p + tree_depth[(long)b * N + i];
+  const long src = b * q_sb + i * q_sn + h * q_sh + c;
+  const long dst = b * kv_sb + h * kv_sh + (long)(p + i) * kv_ss + c;
+  const uint4 lo = k_new[src], hi = k_new[src + half];
+  float x1[EPV], x2[EPV];
+  if (BF16) {
+    const unsigned a[4] = {lo.x, lo.y, lo.z, lo.w}, bb[4] = {hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      x1[2 * j] = __uint_as_float(a[j] << 16);
+      x1[2 * j + 1] = __uint_as_float(a[j] & 0xffff0000u);
+      x2[2 * j] = __uint_as_float(bb[j] << 16);
+      x2[2 * j + 1] = __uint_as_float(bb[j] & 0xffff0000u);
+    }
+  } else {
+    x1[0] = __uint_as_float(lo.x); x1[1] = __uint_as_float(lo.y); x1[2] = __uint_as_float(lo.z); x1[3] = __uint_as_float(lo.w);
+    x2[0] = __uint_as_float(hi.x); x2[1] = __uint_as_float(hi.y); x2[2] = __uint_as_float(hi.z); x2[3] = __uint_as_float(hi.w);
+  }
+  const float* cs = rope_cos + (long)pos * (D / 2) + c * EPV;
+  const float* sn = rope_sin + (long)pos * (D / 2) + c * EPV;
+  float y1[EPV], y2[EPV];
+#pragma unroll
+  for (int j = 0; j < EPV; ++j) {
+    const float co = cs[j], si = sn[j];
+    y1[j] = x1[j] * co - x2[j] * si;
+    y2[j] = x2[j] * co + x1[j] * si;
+  }
+  uint4 olo, ohi;
+  if (BF16) {
+    unsigned o1[4], o2[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      union { __hip_bfloat16 h; unsigned short u; } a0, a1, b0, b1;
+      a0.h = __float2bfloat16(y1[2 * j]); a1.h = __float2bfloat16(y1[2 * j + 1]);
+      b0.h = __float2bfloat16(y2[2 * j]); b1.h = __float2bfloat16(y2[2 * j + 1]);
+      o1[j] = (unsigned)a0.u | ((unsigned)a1.u << 16);
+      o2[j] = (unsigned)b0.u | ((unsigned)b1.u << 16);
+    }
+    olo = make_uint4(o1[0], o1[1], o1[2], o1[3]);
+    ohi = make_uint4(o2[0], o2[1], o2[2], o2[3]);
+  } else {
+    olo = make_uint4(__float_as_uint(y1[0]), __float_as_uint(y1[1]), __float_as_uint(y1[2]), __float_as_uint(y1[3]));
+    ohi = make_uint4(__float_as_uint(y2[0]), __float_as_uint(y2[1]), __float_as_uint(y2[2]), __float_as_uint(y2[3]));
+  }
+  k_cache[dst] = olo;
+  k_cache[dst + half] = ohi;
+  v_cache[dst] = v_new[src];
+  v_cache[dst + half] = v_new[src + half];
 }
 
 struct LayerPtrs {
@@ -113,6 +204,26 @@ hipError_t launch_kv_append(const spec_attn_desc_t& d, const void* k_new, const 
                      (uint4*)k_cache, (uint4*)v_cache, prefix_len, status, d.B, d.N, d.H, d.S_cap, vec_per_row,
                      d.q_stride_b / per16, d.q_stride_n / per16, d.q_stride_h / per16, d.kv_stride_b / per16,
                      d.kv_stride_h / per16, d.kv_stride_s / per16);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_append_rope(const spec_attn_desc_t& d, const void* k_new, const void* v_new, void* k_cache,
+                                 void* v_cache, const int32_t* tree_depth, const int32_t* prefix_len,
+                                 const float* rope_cos, const float* rope_sin, int rope_len, int32_t* status,
+                                 hipStream_t s) {
+  const int e = elem_bytes(d.dtype);
+  const int per16 = 16 / e;
+  const int vec_per_row = d.D / per16;
+  const long per_request = (long)d.N * d.H * (vec_per_row / 2);
+  const dim3 grid((unsigned)((per_request + 255) / 256), d.B);
+#define SPEC_ROPE(BF)                                                                                                 \
+  hipLaunchKernelGGL(kv_append_rope_kernel<BF>, grid, dim3(256), 0, s, (const uint4*)k_new, (const uint4*)v_new,      \
+                     (uint4*)k_cache, (uint4*)v_cache, tree_depth, prefix_len, rope_cos, rope_sin, rope_len, status,  \
+                     d.N, d.H, d.D, d.S_cap, vec_per_row, d.q_stride_b / per16, d.q_stride_n / per16,                 \
+                     d.q_stride_h / per16, d.kv_stride_b / per16, d.kv_stride_h / per16, d.kv_stride_s / per16)
+  if (d.dtype == SPEC_BF16) SPEC_ROPE(true);
+  else SPEC_ROPE(false);
+#undef SPEC_ROPE
   return hipGetLastError();
 }
 

@@ -148,6 +148,20 @@ int spec_kv_append(const spec_attn_desc_t* desc, const void* k_new, const void* 
              : SPEC_ERR_HIP;
 }
 
+int spec_kv_append_rope(const spec_attn_desc_t* desc, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                        const int32_t* tree_depth, const int32_t* prefix_len, const float* rope_cos, const float* rope_sin,
+                        int32_t rope_len, int32_t* status, void* hip_stream) {
+  const int rc = check_desc(desc);
+  if (rc != SPEC_OK) return rc;
+  if (!k_new || !v_new || !k_cache || !v_cache || !prefix_len || !tree_depth || !rope_cos || !rope_sin) return SPEC_ERR_INVALID_ARG;
+  if (rope_len <= 0) return SPEC_ERR_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache)) return SPEC_ERR_INVALID_ARG;
+  return launch_kv_append_rope(*desc, k_new, v_new, k_cache, v_cache, tree_depth, prefix_len, rope_cos, rope_sin, rope_len,
+                               status, (hipStream_t)hip_stream) == hipSuccess
+             ? SPEC_OK
+             : SPEC_ERR_HIP;
+}
+
 size_t spec_tree_attention_workspace_bytes(const spec_attn_desc_t* desc) {
   if (check_desc(desc) != SPEC_OK) return 0;
   return make_attn_plan(*desc).ws_bytes;

@@ -37,6 +37,10 @@ inline int attn_queries_per_workgroup(const spec_attn_desc_t& d) {
 // Kernel launchers (defined in the .hip files). All return hipError_t of the launch.
 hipError_t launch_kv_append(const spec_attn_desc_t& d, const void* k_new, const void* v_new, void* k_cache,
                             void* v_cache, const int32_t* prefix_len, int32_t* status, hipStream_t s);
+hipError_t launch_kv_append_rope(const spec_attn_desc_t& d, const void* k_new, const void* v_new, void* k_cache,
+                                 void* v_cache, const int32_t* tree_depth, const int32_t* prefix_len,
+                                 const float* rope_cos, const float* rope_sin, int rope_len, int32_t* status,
+                                 hipStream_t s);
 hipError_t launch_kv_commit(const spec_attn_desc_t& d, int n_layers, void* const* k_caches, void* const* v_caches,
                             const int32_t* path, int Lmax, const int32_t* len, const int32_t* prefix_len,
                             int32_t* prefix_len_out, int32_t* status, hipStream_t s);

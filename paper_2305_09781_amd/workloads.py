@@ -387,3 +387,11 @@ def random_accepted_paths(rng: np.random.Generator, parent: np.ndarray, max_len:
         path[b, :len(chain)] = chain
         ln[b] = len(chain)
     return path, ln
+
+
+def make_rope_tables(n_positions: int, D: int, theta: float = 10000.0):
+    """cos / sin tables [n_positions, D/2] of the rotary embedding, float32 (computed in float64):
+    angle(position, j) = position * theta ** (-2 j / D). Inputs of the append-with-rotation call."""
+    j = np.arange(D // 2, dtype=np.float64)
+    ang = np.arange(n_positions, dtype=np.float64)[:, None] * theta ** (-2.0 * j / D)[None, :]
+    return torch.from_numpy(np.cos(ang).astype(np.float32)), torch.from_numpy(np.sin(ang).astype(np.float32))

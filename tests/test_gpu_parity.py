@@ -162,6 +162,47 @@ def test_small_shapes_attention_and_append(spec, case):
         assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco), fused
 
 
+@pytest.mark.parametrize("case", [("bf16", 3, 4, 128, (30, 200), 16, "expansion"), ("bf16", 2, 3, 64, (0, 90), 40, "random_branching"),
+                                  ("f32", 2, 2, 64, (5, 60), 9, "random_parent"), ("f32", 1, 2, 128, (100, 100), 128, "random_branching")])
+def test_kv_append_with_rotary_embedding(spec, case):
+    """K rotated at position prefix_len + depth on the way into the cache: within one unit in the last place
+    of the storage type of the float64 oracle (the kernel rotates in float32), V a bit copy."""
+    dtype, B, H, D, P, N, tree = case
+    cfg = wl.Config(96, "rope", dtype, B=B, H=H, D=D, P=P if P[0] != P[1] else P[0], N=N, tree=tree,
+                    widths=wl.EXPANSION_EVAL * 2)
+    inp = wl.make_attention_inputs(cfg, seed=300 + N, S_cap=P[1] + N + 2)
+    cos, sin = wl.make_rope_tables(P[1] + N + 2, D)
+    kco, vco = _f64(inp["k_cache"][0]), _f64(inp["v_cache"][0])
+    st_ref = orc.kv_append_rope(kco, vco, _f64(inp["k_new"][0]), _f64(inp["v_new"][0]), inp["prefix_len"].numpy(),
+                                inp["tree_depth"].numpy(), cos.numpy(), sin.numpy(), dtype)
+    assert (st_ref == 0).all()
+    kc, vc = _dev(inp["k_cache"][0]), _dev(inp["v_cache"][0])
+    status = torch.zeros(B, dtype=torch.int32, device=DEV)
+    spec.spec_kv_append_rope(_dev(inp["k_new"][0]), _dev(inp["v_new"][0]), kc, vc, _dev(inp["tree_depth"]),
+                             _dev(inp["prefix_len"]), _dev(cos), _dev(sin), status=status)
+    torch.cuda.synchronize()
+    assert (status.cpu().numpy() == 0).all()
+    assert np.array_equal(vc.double().cpu().numpy(), vco)
+    got = kc.double().cpu().numpy()
+    ulp = 2.0 ** -7 if dtype == "bf16" else 2.0 ** -21      # one unit in the last place, relative, at worst
+    assert (np.abs(got - kco) <= ulp * np.abs(kco) + 1e-6).all()   # + float32 cancellation noise of x1 cos - x2 sin
+    if dtype == "bf16":
+        assert (got != kco).mean() < 0.02                   # flips of the last bit are rare
+    # tables too short for one request: that request is untouched and flagged, the others are done
+    short = int(inp["prefix_len"].max())
+    kc2 = _dev(inp["k_cache"][0])
+    status.zero_()
+    spec.spec_kv_append_rope(_dev(inp["k_new"][0]), _dev(inp["v_new"][0]), kc2, _dev(inp["v_cache"][0]), _dev(inp["tree_depth"]),
+                             _dev(inp["prefix_len"]), _dev(cos[:short].contiguous()), _dev(sin[:short].contiguous()), status=status)
+    torch.cuda.synchronize()
+    kref = _f64(inp["k_cache"][0])
+    st2 = orc.kv_append_rope(kref, _f64(inp["v_cache"][0]), _f64(inp["k_new"][0]), _f64(inp["v_new"][0]),
+                             inp["prefix_len"].numpy(), inp["tree_depth"].numpy(), cos[:short].numpy(), sin[:short].numpy(), dtype)
+    assert np.array_equal(status.cpu().numpy(), st2) and (st2 != 0).any()
+    for b in np.nonzero(st2)[0]:
+        assert np.array_equal(_bits(kc2[b]), _bits(inp["k_cache"][0][b]))
+
+
 BALANCED = [
     # B, H, D, (P lo, hi), N, tree, workgroups
     (3, 2, 128, (40, 300), 16, "expansion", 5),

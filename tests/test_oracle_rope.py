@@ -1,0 +1,75 @@
+"""Pins for the oracle's rotary-embedding append (a step adjacent to the path: the paper's LLaMA models
+rotate keys by position; tree tokens sit at prefix_len + depth). CPU only. The rotation is pinned to complex
+multiplication written separately, to its group properties and to the plain append at angle zero."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import spec_oracle as orc
+from paper_2305_09781_amd import workloads as wl
+
+
+def test_rotation_is_complex_multiplication_and_preserves_norms():
+    rng = np.random.default_rng(0)
+    D = 16
+    x = rng.standard_normal((3, D))
+    ang = rng.uniform(-7, 7, size=D // 2)
+    got = orc.rope_rotate(x, np.cos(ang), np.sin(ang))
+    z = (x[:, :D // 2] + 1j * x[:, D // 2:]) * np.exp(1j * ang)           # pair (j, j + D/2) as a complex number
+    assert np.allclose(got[:, :D // 2], z.real, atol=1e-14) and np.allclose(got[:, D // 2:], z.imag, atol=1e-14)
+    assert np.allclose((got ** 2).sum(-1), (x ** 2).sum(-1))
+    quarter = orc.rope_rotate(x, np.zeros(D // 2), np.ones(D // 2))      # 90 degrees: (a, b) -> (-b, a)
+    assert np.array_equal(quarter[:, :D // 2], -x[:, D // 2:]) and np.array_equal(quarter[:, D // 2:], x[:, :D // 2])
+    back = orc.rope_rotate(got, np.cos(-ang), np.sin(-ang))
+    assert np.allclose(back, x, atol=1e-13)
+
+
+def test_scores_depend_only_on_relative_position():
+    """The property rotary embeddings exist for: <R(m) q, R(n) k> is a function of m - n."""
+    rng = np.random.default_rng(1)
+    D = 32
+    cos, sin = (t.double().numpy() for t in wl.make_rope_tables(64, D))
+    q, k = rng.standard_normal(D), rng.standard_normal(D)
+    ref = orc.rope_rotate(q, cos[9], sin[9]) @ orc.rope_rotate(k, cos[4], sin[4])
+    for m, n in ((5, 0), (30, 25), (63, 58)):
+        assert abs(orc.rope_rotate(q, cos[m], sin[m]) @ orc.rope_rotate(k, cos[n], sin[n]) - ref) < 1e-5
+    assert abs(orc.rope_rotate(q, cos[9], sin[9]) @ orc.rope_rotate(k, cos[5], sin[5]) - ref) > 1e-3
+    # table generator: position 0 is the identity, frequency 0 advances one radian per position
+    assert np.array_equal(cos[0], np.ones(D // 2)) and np.array_equal(sin[0], np.zeros(D // 2))
+    assert abs(cos[3, 0] - np.cos(3.0)) < 1e-7 and abs(sin[3, D // 2 - 1] - np.sin(3.0 * 10000.0 ** (-(D - 2) / D))) < 1e-7
+
+
+@pytest.mark.parametrize("storage", ["bf16", "f32"])
+def test_append_with_rotation_positions_rounding_and_status(storage):
+    cfg = wl.Config(95, "rope", storage, B=3, H=2, D=16, P=(3, 9), N=6, tree="random_parent")
+    inp = wl.make_attention_inputs(cfg, seed=4, S_cap=9 + 6)
+    f64 = lambda t: t.double().numpy()
+    kn, vn = f64(inp["k_new"][0]), f64(inp["v_new"][0])
+    pl, dep = inp["prefix_len"].numpy(), inp["tree_depth"].numpy()
+    cos, sin = wl.make_rope_tables(9 + 6, cfg.D)
+    # all-zero angles: exactly the plain append
+    kc, vc = f64(inp["k_cache"][0]), f64(inp["v_cache"][0])
+    kc0, vc0 = kc.copy(), vc.copy()
+    orc.kv_append(kc0, vc0, kn, vn, pl)
+    st = orc.kv_append_rope(kc, vc, kn, vn, pl, dep, np.ones((15, 8)), np.zeros((15, 8)), storage)
+    assert (st == 0).all() and np.array_equal(kc, kc0) and np.array_equal(vc, vc0)
+    # real tables: row p+i holds k_new[i] rotated by position p + depth[i] (not p + i), rounded to the storage type
+    kc, vc = f64(inp["k_cache"][0]), f64(inp["v_cache"][0])
+    st = orc.kv_append_rope(kc, vc, kn, vn, pl, dep, cos, sin, storage)
+    assert (st == 0).all() and np.array_equal(vc, vc0)
+    dt = torch.bfloat16 if storage == "bf16" else torch.float32
+    for b in range(cfg.B):
+        for i in range(cfg.N):
+            pos = pl[b] + dep[b, i]
+            z = (kn[b, i, :, :8] + 1j * kn[b, i, :, 8:]) * np.exp(1j * np.arctan2(f64(sin)[pos], f64(cos)[pos]))
+            want = torch.from_numpy(np.concatenate([z.real, z.imag], -1)).to(dt).double().numpy()
+            got = kc[b, :, pl[b] + i]
+            assert np.abs(got - want).max() <= (2.0 ** -7 if storage == "bf16" else 2e-6) * np.abs(want).max()
+            assert np.array_equal(torch.from_numpy(got).to(dt).double().numpy(), got)      # representable in the storage type
+    siblings = [(i, j) for i in range(cfg.N) for j in range(i) if dep[0, i] == dep[0, j]]
+    assert siblings, "the tree should have two nodes of equal depth (same position, different rows)"
+    # a position outside the tables or a tree that does not fit: request untouched, flagged
+    kc = f64(inp["k_cache"][0])
+    before = kc.copy()
+    st = orc.kv_append_rope(kc, vc, kn, vn, pl, dep, cos[:int(pl.max())], sin[:int(pl.max())], storage)
+    assert st[np.argmax(pl)] == orc.ST_CAPACITY and np.array_equal(kc[np.argmax(pl)], before[np.argmax(pl)])
