@@ -51,7 +51,8 @@ extern "C" {
 /* return codes */
 #define SPEC_OK 0
 #define SPEC_ERR_INVALID_ARG (-1) /* null pointer, non-positive size, bad stride or alignment        */
-#define SPEC_ERR_UNSUPPORTED (-2) /* D not in {64,128}, N > SPEC_MAX_TREE_NODES, H_kv != H, dtype    */
+#define SPEC_ERR_UNSUPPORTED (-2) /* D not in {64,128}, N > SPEC_MAX_TREE_NODES, dtype, H_kv not a   */
+                                  /* divisor of H, bf16 with (H/H_kv) * ceil(N/16) > 8               */
 #define SPEC_ERR_CAPACITY (-3)    /* N > S_cap, max_prefix_len + N > S_cap                           */
 #define SPEC_ERR_HIP (-4)         /* a HIP runtime call failed (launch error)                        */
 #define SPEC_ERR_WORKSPACE (-5)   /* workspace NULL or smaller than *_workspace_bytes reports        */
@@ -68,14 +69,18 @@ typedef enum { SPEC_F32 = 0, SPEC_BF16 = 1 } spec_dtype_t;
 typedef struct spec_attn_desc {
   int32_t B;              /* requests in the batch                                                   */
   int32_t H;              /* query heads                                                             */
-  int32_t H_kv;           /* key/value heads; must equal H (the paper's models are multi-head)       */
+  int32_t H_kv;           /* key/value heads, a divisor of H. H_kv = H: multi-head (the paper's      */
+                          /* models); H_kv < H: grouped-query heads, query head h reads K/V head      */
+                          /* h / (H / H_kv)                                                           */
   int32_t D;              /* head dimension: 64 or 128                                               */
   int32_t N;              /* tree nodes per request, 1..SPEC_MAX_TREE_NODES                          */
   int32_t S_cap;          /* rows per (request, head) in the cache                                   */
   int32_t dtype;          /* spec_dtype_t of q, out, k_new, v_new and the caches                     */
   int32_t max_prefix_len; /* upper bound of prefix_len[b], sizes grid and workspace; 0 = S_cap - N   */
-  int64_t q_stride_b, q_stride_n, q_stride_h;
-  int64_t kv_stride_b, kv_stride_h, kv_stride_s;
+  int64_t q_stride_b, q_stride_n, q_stride_h;       /* q, out: [B,N,H,D], in elements                */
+  int64_t kv_stride_b, kv_stride_h, kv_stride_s;    /* caches: [B,H_kv,S_cap,D]                      */
+  int64_t new_stride_b, new_stride_n, new_stride_h; /* k_new, v_new: [B,N,H_kv,D]; all 0 = the q     */
+                                                    /* strides (only meaningful when H_kv = H)       */
   float softmax_scale;    /* 0 = 1/sqrt(D)                                                           */
   int32_t reserved;       /* must be 0                                                               */
 } spec_attn_desc_t;

@@ -151,7 +151,9 @@ def kv_append_rope(k_cache, v_cache, k_new, v_new, prefix_len, tree_depth, rope_
 def tree_attention(q, k_cache, v_cache, tree_parent, prefix_len, softmax_scale=None):
     """Attention output of every tree node over (cached prefix) ++ (its own root-to-node path).
 
-    q: [B,N,H,D]; caches [B,H,S_cap,D] already holding the tree rows at prefix_len[b] + i.
+    q: [B,N,H,D]; caches [B,H_kv,S_cap,D] already holding the tree rows at prefix_len[b] + i. H_kv = H
+    is the paper's multi-head attention; with fewer K/V heads (grouped-query attention, an extension)
+    query head h reads K/V head h // (H / H_kv).
     Returns float64 [B,N,H,D]. A = Q K^T / sqrt(d); mask(A) puts -inf wherever key j is a tree token
     that is neither node i nor one of its ancestors; H = softmax(mask(A)) V.
     Readings: d is the head dimension; a row is never fully masked (a node sees itself)."""
@@ -163,9 +165,10 @@ def tree_attention(q, k_cache, v_cache, tree_parent, prefix_len, softmax_scale=N
         p = int(prefix_len[b])
         L = p + N
         visible = np.concatenate([np.ones((N, p), dtype=bool), ancestor_matrix(tree_parent[b])], axis=1)
+        group = H // k_cache.shape[1]
         for h in range(H):
-            K = np.asarray(k_cache[b, h, :L, :], dtype=np.float64)
-            V = np.asarray(v_cache[b, h, :L, :], dtype=np.float64)
+            K = np.asarray(k_cache[b, h // group, :L, :], dtype=np.float64)
+            V = np.asarray(v_cache[b, h // group, :L, :], dtype=np.float64)
             A = (q[b, :, h, :] @ K.T) * scale
             A = np.where(visible, A, -np.inf)
             W = np.exp(A - A.max(axis=1, keepdims=True))

@@ -43,6 +43,7 @@ class AttnDesc(ctypes.Structure):
         ("max_prefix_len", ctypes.c_int32),
         ("q_stride_b", ctypes.c_int64), ("q_stride_n", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
         ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64), ("kv_stride_s", ctypes.c_int64),
+        ("new_stride_b", ctypes.c_int64), ("new_stride_n", ctypes.c_int64), ("new_stride_h", ctypes.c_int64),
         ("softmax_scale", ctypes.c_float), ("reserved", ctypes.c_int32),
     ]
 
@@ -124,15 +125,21 @@ def _check(rc: int, where: str):
 
 
 def make_desc(q_like: torch.Tensor, k_cache: torch.Tensor, max_prefix_len: int = 0,
-              softmax_scale: float = 0.0) -> AttnDesc:
-    """Descriptor from a [B,N,H,D] tensor (q / out / k_new / v_new) and a [B,H,S_cap,D] cache."""
+              softmax_scale: float = 0.0, k_new: Optional[torch.Tensor] = None) -> AttnDesc:
+    """Descriptor from a [B,N,H,D] tensor (q / out), a [B,H_kv,S_cap,D] cache and, for grouped-query heads,
+    the [B,N,H_kv,D] k_new (its strides; without it k_new / v_new are taken to be laid out like q)."""
     B, N, H, D = q_like.shape
     Bc, Hkv, S_cap, Dc = k_cache.shape
     if (Bc, Dc) != (B, D) or q_like.stride(3) != 1 or k_cache.stride(3) != 1:
         raise ValueError("q must be [B,N,H,D], cache [B,H_kv,S_cap,D], D contiguous")
+    new = (0, 0, 0)
+    if k_new is not None:
+        if tuple(k_new.shape) != (B, N, Hkv, D) or k_new.stride(3) != 1:
+            raise ValueError("k_new / v_new must be [B,N,H_kv,D], D contiguous")
+        new = (k_new.stride(0), k_new.stride(1), k_new.stride(2))
     return AttnDesc(B, H, Hkv, D, N, S_cap, _dtype_code(q_like.dtype), int(max_prefix_len),
                     q_like.stride(0), q_like.stride(1), q_like.stride(2),
-                    k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), float(softmax_scale), 0)
+                    k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), *new, float(softmax_scale), 0)
 
 
 def _same_layout(a: torch.Tensor, b: torch.Tensor, what: str):
@@ -192,12 +199,11 @@ def spec_tree_attention_append(q, k_new, v_new, k_cache, v_cache, tree_parent, t
                                stream=None, desc=None):
     """KV append of the tree rows fused with the tree attention over them."""
     _same_layout(k_cache, v_cache, "k_cache and v_cache")
-    _same_layout(q, k_new, "q and k_new")
-    _same_layout(q, v_new, "q and v_new")
+    _same_layout(k_new, v_new, "k_new and v_new")
     if out is None:
         out = torch.empty_like(q)
     _same_layout(q, out, "q and out")
-    d = desc if desc is not None else make_desc(q, k_cache, max_prefix_len, softmax_scale)
+    d = desc if desc is not None else make_desc(q, k_cache, max_prefix_len, softmax_scale, k_new=k_new)
     need = spec_tree_attention_workspace_bytes(d)
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
@@ -317,7 +323,7 @@ def spec_kv_commit(k_caches: Sequence[torch.Tensor], v_caches: Sequence[torch.Te
         _same_layout(vc, k0, "all layer caches")
     B, H, S_cap, D = k0.shape
     d = AttnDesc(B, H, H, D, N, S_cap, _dtype_code(k0.dtype), 0, N * H * D, H * D, D,
-                 k0.stride(0), k0.stride(1), k0.stride(2), 0.0, 0)
+                 k0.stride(0), k0.stride(1), k0.stride(2), 0, 0, 0, 0.0, 0)
     if prefix_len_out is None:
         prefix_len_out = torch.empty_like(prefix_len)
     arr_t = ctypes.c_void_p * L

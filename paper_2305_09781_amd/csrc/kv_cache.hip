@@ -198,12 +198,13 @@ hipError_t launch_kv_append(const spec_attn_desc_t& d, const void* k_new, const 
   const int e = elem_bytes(d.dtype);
   const int per16 = 16 / e;
   const int vec_per_row = d.D / per16;
-  const long total = (long)d.B * d.N * d.H * vec_per_row;
+  const long total = (long)d.B * d.N * d.H_kv * vec_per_row;
   const int grid = (int)((total + 255) / 256);
+  const NewStrides ns = attn_new_strides(d);
   hipLaunchKernelGGL(kv_append_kernel, dim3(grid), dim3(256), 0, s, (const uint4*)k_new, (const uint4*)v_new,
-                     (uint4*)k_cache, (uint4*)v_cache, prefix_len, status, d.B, d.N, d.H, d.S_cap, vec_per_row,
-                     d.q_stride_b / per16, d.q_stride_n / per16, d.q_stride_h / per16, d.kv_stride_b / per16,
-                     d.kv_stride_h / per16, d.kv_stride_s / per16);
+                     (uint4*)k_cache, (uint4*)v_cache, prefix_len, status, d.B, d.N, d.H_kv, d.S_cap, vec_per_row,
+                     ns.b / per16, ns.n / per16, ns.h / per16, d.kv_stride_b / per16, d.kv_stride_h / per16,
+                     d.kv_stride_s / per16);
   return hipGetLastError();
 }
 
@@ -214,13 +215,14 @@ hipError_t launch_kv_append_rope(const spec_attn_desc_t& d, const void* k_new, c
   const int e = elem_bytes(d.dtype);
   const int per16 = 16 / e;
   const int vec_per_row = d.D / per16;
-  const long per_request = (long)d.N * d.H * (vec_per_row / 2);
+  const long per_request = (long)d.N * d.H_kv * (vec_per_row / 2);
   const dim3 grid((unsigned)((per_request + 255) / 256), d.B);
+  const NewStrides ns = attn_new_strides(d);
 #define SPEC_ROPE(BF)                                                                                                 \
   hipLaunchKernelGGL(kv_append_rope_kernel<BF>, grid, dim3(256), 0, s, (const uint4*)k_new, (const uint4*)v_new,      \
                      (uint4*)k_cache, (uint4*)v_cache, tree_depth, prefix_len, rope_cos, rope_sin, rope_len, status,  \
-                     d.N, d.H, d.D, d.S_cap, vec_per_row, d.q_stride_b / per16, d.q_stride_n / per16,                 \
-                     d.q_stride_h / per16, d.kv_stride_b / per16, d.kv_stride_h / per16, d.kv_stride_s / per16)
+                     d.N, d.H_kv, d.D, d.S_cap, vec_per_row, ns.b / per16, ns.n / per16, ns.h / per16,                \
+                     d.kv_stride_b / per16, d.kv_stride_h / per16, d.kv_stride_s / per16)
   if (d.dtype == SPEC_BF16) SPEC_ROPE(true);
   else SPEC_ROPE(false);
 #undef SPEC_ROPE
@@ -238,10 +240,10 @@ hipError_t launch_kv_commit(const spec_attn_desc_t& d, int n_layers, void* const
     ptrs.k[l] = (uint4*)(l < n_layers ? k_caches[l] : nullptr);
     ptrs.v[l] = (uint4*)(l < n_layers ? v_caches[l] : nullptr);
   }
-  const int cols = d.H * vec_per_row;
+  const int cols = d.H_kv * vec_per_row;
   dim3 grid((cols + 255) / 256, n_layers, d.B);
   hipLaunchKernelGGL(kv_commit_kernel, grid, dim3(256), 0, s, ptrs, path, len, prefix_len, prefix_len_out, status, d.N,
-                     d.H, d.S_cap, Lmax, vec_per_row, d.kv_stride_b / per16, d.kv_stride_h / per16,
+                     d.H_kv, d.S_cap, Lmax, vec_per_row, d.kv_stride_b / per16, d.kv_stride_h / per16,
                      d.kv_stride_s / per16);
   return hipGetLastError();
 }

@@ -28,7 +28,12 @@ static int check_desc(const spec_attn_desc_t* d) {
   if (d->dtype != SPEC_F32 && d->dtype != SPEC_BF16) return SPEC_ERR_UNSUPPORTED;
   if (d->D != 64 && d->D != 128) return SPEC_ERR_UNSUPPORTED;
   if (d->N > SPEC_MAX_TREE_NODES) return SPEC_ERR_UNSUPPORTED;
-  if (d->H_kv != d->H) return SPEC_ERR_UNSUPPORTED;
+  if (d->H % d->H_kv != 0) return SPEC_ERR_UNSUPPORTED;
+  if (d->dtype == SPEC_BF16 && attn_query_tiles(*d) > 8) return SPEC_ERR_UNSUPPORTED;
+  {
+    const bool none = d->new_stride_b == 0 && d->new_stride_n == 0 && d->new_stride_h == 0;
+    if (!none && (d->new_stride_b <= 0 || d->new_stride_n <= 0 || d->new_stride_h < d->D)) return SPEC_ERR_INVALID_ARG;
+  }
   if (d->N > d->S_cap) return SPEC_ERR_CAPACITY;
   if (d->max_prefix_len < 0 || (long)d->max_prefix_len + d->N > d->S_cap) return SPEC_ERR_CAPACITY;
   if (!(d->softmax_scale >= 0.f) || std::isinf(d->softmax_scale)) return SPEC_ERR_INVALID_ARG;
@@ -36,8 +41,16 @@ static int check_desc(const spec_attn_desc_t* d) {
   const int64_t strides[6] = {d->q_stride_b, d->q_stride_n, d->q_stride_h, d->kv_stride_b, d->kv_stride_h, d->kv_stride_s};
   for (int64_t s : strides)
     if (s <= 0 || s % per16 != 0) return SPEC_ERR_INVALID_ARG;
+  const int64_t new_strides[3] = {d->new_stride_b, d->new_stride_n, d->new_stride_h};
+  for (int64_t s : new_strides)
+    if (s % per16 != 0) return SPEC_ERR_INVALID_ARG;
   if (d->q_stride_h < d->D || d->kv_stride_s < d->D) return SPEC_ERR_INVALID_ARG;
   return SPEC_OK;
+}
+
+// k_new / v_new cannot share q's layout when there are fewer K/V heads than query heads.
+static bool new_strides_missing(const spec_attn_desc_t* d) {
+  return d->H_kv != d->H && d->new_stride_b == 0 && d->new_stride_n == 0 && d->new_stride_h == 0;
 }
 
 // Compute units of the current device (256 when no device can be queried, e.g. sizing a workspace on a
@@ -61,16 +74,22 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d) {
   p.balanced_tile = 0;
   const int max_prefix = d.max_prefix_len > 0 ? d.max_prefix_len : d.S_cap - d.N;
   const int max_len = max_prefix + d.N;
-  const int nq = attn_queries_per_workgroup(d);
-  const long groups = (long)d.B * d.H * ((d.N + nq - 1) / nq);
+  // bf16: one workgroup serves all query heads of a K/V head; float32: one per query head
+  const long groups = (long)d.B * (d.dtype == SPEC_BF16 ? d.H_kv : d.H);
+  const int tiles = attn_query_tiles(d);   // 16-query tiles per (request, K/V head)
+  // The few-query kernel serves one query tile per K/V head with k_new / v_new laid out like q; everything
+  // else in bf16 runs on the wide kernel.
+  const NewStrides ns = attn_new_strides(d);
+  p.wide = d.dtype == SPEC_BF16 &&
+           (tiles > 1 || ns.b != d.q_stride_b || ns.n != d.q_stride_n || ns.h != d.q_stride_h);
   int chunk = env_int("SPEC_TREE_CHUNK_KEYS", 0);
   if (chunk <= 0 && d.dtype == SPEC_BF16) {
     // Few (request, head) pairs with long key ranges (long-context serving, ragged lengths): the bf16
     // kernels deal the key tiles of all pairs to as many workgroups as the device holds at once, in
     // equal shares, so the stream is balanced whatever the individual lengths are. Used when it gives
     // more workgroups than pairs, each with at least 8 tiles at the stated maximum length.
-    const int tile = d.N <= 16 ? SPEC_SMALL_TILE_KEYS : SPEC_WIDE_TILE_KEYS;
-    const int resident_per_cu = (d.N > 16 && d.N <= 64) ? 2 : 1;   // four-wavefront workgroups: two per compute unit
+    const int tile = p.wide ? SPEC_WIDE_TILE_KEYS : SPEC_SMALL_TILE_KEYS;
+    const int resident_per_cu = (p.wide && tiles <= 4) ? 2 : 1;   // four-wavefront workgroups: two per compute unit
     const long resident = (long)compute_units() * resident_per_cu;
     int wgs = env_int("SPEC_TREE_BALANCED_WGS", -1);
     if (wgs < 0) {
@@ -82,7 +101,7 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d) {
       p.balanced_wgs = wgs;
       p.balanced_tile = tile;
       p.chunk_keys = 0;
-      p.n_splits = (wgs + d.H - 1) / d.H + 1;   // a pair is overlapped by at most this many shares
+      p.n_splits = (wgs + d.H_kv - 1) / d.H_kv + 1;   // a pair is overlapped by at most this many shares
     }
   }
   if (p.balanced_wgs == 0) {
@@ -143,6 +162,7 @@ int spec_kv_append(const spec_attn_desc_t* desc, const void* k_new, const void* 
   if (rc != SPEC_OK) return rc;
   if (!k_new || !v_new || !k_cache || !v_cache || !prefix_len) return SPEC_ERR_INVALID_ARG;
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache)) return SPEC_ERR_INVALID_ARG;
+  if (new_strides_missing(desc)) return SPEC_ERR_INVALID_ARG;
   return launch_kv_append(*desc, k_new, v_new, k_cache, v_cache, prefix_len, status, (hipStream_t)hip_stream) == hipSuccess
              ? SPEC_OK
              : SPEC_ERR_HIP;
@@ -154,7 +174,7 @@ int spec_kv_append_rope(const spec_attn_desc_t* desc, const void* k_new, const v
   const int rc = check_desc(desc);
   if (rc != SPEC_OK) return rc;
   if (!k_new || !v_new || !k_cache || !v_cache || !prefix_len || !tree_depth || !rope_cos || !rope_sin) return SPEC_ERR_INVALID_ARG;
-  if (rope_len <= 0) return SPEC_ERR_INVALID_ARG;
+  if (rope_len <= 0 || new_strides_missing(desc)) return SPEC_ERR_INVALID_ARG;
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache)) return SPEC_ERR_INVALID_ARG;
   return launch_kv_append_rope(*desc, k_new, v_new, k_cache, v_cache, tree_depth, prefix_len, rope_cos, rope_sin, rope_len,
                                status, (hipStream_t)hip_stream) == hipSuccess
@@ -177,7 +197,8 @@ static int tree_attention_impl(const spec_attn_desc_t* desc, const void* q, cons
   if (!q || !k_cache || !v_cache || !tree_parent || !tree_depth || !prefix_len || !out) return SPEC_ERR_INVALID_ARG;
   if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out)) return SPEC_ERR_INVALID_ARG;
   const bool append = k_new != nullptr || v_new != nullptr;
-  if (append && (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new))) return SPEC_ERR_INVALID_ARG;
+  if (append && (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new) || new_strides_missing(desc)))
+    return SPEC_ERR_INVALID_ARG;
   const AttnPlan plan = make_attn_plan(*desc);
   if (plan.ws_bytes > 0) {
     if (workspace == nullptr || workspace_bytes < plan.ws_bytes) return SPEC_ERR_WORKSPACE;

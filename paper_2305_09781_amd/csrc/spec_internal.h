@@ -17,6 +17,7 @@ struct AttnPlan {
   int n_splits;     // chunks covering max_prefix_len + N; balanced plan: partial slots per (request, head)
   int balanced_wgs; // > 0: balanced plan with this many workgroups (see balanced_share), chunk_keys unused
   int balanced_tile;// keys per tile of the balanced deal (the tile of the kernel that runs the plan)
+  bool wide;        // bf16: the wide kernel runs the plan (several query tiles per K/V head, or k_new not laid out like q)
   size_t ws_o_off;  // float [B][H][n_splits][N][D]   un-normalised partial outputs
   size_t ws_ml_off; // float [B][H][n_splits][N][2]   running max (log2 domain) and partial sum
   size_t ws_bytes;
@@ -32,6 +33,19 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d);
 inline int attn_queries_per_workgroup(const spec_attn_desc_t& d) {
   if (d.dtype != SPEC_BF16) return SPEC_MAX_TREE_NODES;
   return d.N <= 16 ? 16 : d.N <= 32 ? 32 : d.N <= 64 ? 64 : 128;
+}
+
+// Query heads per key/value head, and the 16-query MFMA tiles one (request, K/V head) pair needs: every
+// query head of the group brings ceil(N / 16) tiles. The bf16 kernels hold at most 8 tiles per workgroup.
+inline int attn_group_size(const spec_attn_desc_t& d) { return d.H / d.H_kv; }
+inline int attn_query_tiles(const spec_attn_desc_t& d) { return attn_group_size(d) * ((d.N + 15) / 16); }
+
+// Strides of k_new / v_new (all zero in the descriptor: laid out like q).
+struct NewStrides { long b, n, h; };
+inline NewStrides attn_new_strides(const spec_attn_desc_t& d) {
+  if (d.new_stride_b == 0 && d.new_stride_n == 0 && d.new_stride_h == 0)
+    return {(long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h};
+  return {(long)d.new_stride_b, (long)d.new_stride_n, (long)d.new_stride_h};
 }
 
 // Kernel launchers (defined in the .hip files). All return hipError_t of the launch.

@@ -537,7 +537,9 @@ hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan&
                                       void* v_cache, const void* k_new, const void* v_new, const int32_t* parent,
                                       const int32_t* depth, const int32_t* prefix_len, void* out, void* ws,
                                       int32_t* status, hipStream_t s) {
-  if (d.N > 16)
+  // This kernel: one 16-query tile per K/V head, k_new / v_new laid out like q. Larger trees, grouped-query
+  // heads and separately laid out k_new go to the wide kernel (the plan decides).
+  if (plan.wide)
     return launch_tree_attention_bf16_wide(d, plan, q, k_cache, v_cache, k_new, v_new, parent, depth, prefix_len, out, ws,
                                            status, s);
   const float scale = (d.softmax_scale != 0.f ? d.softmax_scale : 1.0f / sqrtf((float)d.D)) * kLog2eB;

@@ -1,7 +1,9 @@
 // Tree attention for bf16 K/V, trees of 17..128 nodes per request: Definition 4.1 with the
 // topology-aware causal mask of Section 4.2, same mathematics as tree_attention_bf16.hip.
 //
-// With many tree queries the wavefronts of a workgroup split the QUERIES (one 16-query tile each) and
+// With many queries per K/V head (a tree of more than 16 nodes, or grouped-query heads: the query heads
+// that share a K/V head bring ceil(N/16) tiles each) the wavefronts of a workgroup split the QUERIES
+// (one 16-query tile each) and
 // share one stream of K and V: every 64-key tile is loaded from HBM once, fully coalesced, staged in
 // LDS (double-buffered, rows padded by 32 bytes), and read from there by every wavefront - K as the
 // MFMA A operand (ds_read_b128), V^T through ds_read_b64_tr_b16. Shapes:
@@ -89,8 +91,8 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     const __hip_bfloat16* __restrict__ k_new, const __hip_bfloat16* __restrict__ v_new,
     const int32_t* __restrict__ parent, const int32_t* __restrict__ depth, const int32_t* __restrict__ prefix_len,
     __hip_bfloat16* __restrict__ out, float* __restrict__ ws_o, float* __restrict__ ws_ml, int32_t* status, int B, int N,
-    int H, int S_cap, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long kv_sb, long kv_sh,
-    long kv_ss, float scale_log2) {
+    int H, int H_kv, int S_cap, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long n_sb, long n_sn,
+    long n_sh, long kv_sb, long kv_sh, long kv_ss, float scale_log2) {
   static_assert(KW == 1 || KW == 2, "a 64-key tile is consumed as two 32-key halves");
   static_assert(DEPTH == 2 || DEPTH == 4, "register sets of tiles in flight");
   constexpr int WAVES = QW * KW;
@@ -115,7 +117,6 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int r16 = lane & 15, g = lane >> 4;
   const int qt = wave % QW, kpart = wave / QW;
-  const int q0 = qt * NTW * 16;   // first query of this wavefront
   // loader role of this thread: piece j of a tile is row (t + NTHREADS j) / LPR, 16-byte column (t % LPR)
   const int ld_row0 = t / LPR, ld_col = (t % LPR) * 16;
   WTL(0)
@@ -124,7 +125,7 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
   // DEPTH register sets: the tiles in flight from global memory (tiles ti+2 .. ti+1+DEPTH while tile ti
   // is consumed from LDS and tile ti+1 waits there)
   u32x4 Kr[DEPTH][NPT], Vr[DEPTH][NPT];
-  const unsigned cache_row_bytes = (unsigned)kv_ss * 2u, new_row_bytes = (unsigned)q_sn * 2u;
+  const unsigned cache_row_bytes = (unsigned)kv_ss * 2u, new_row_bytes = (unsigned)n_sn * 2u;
   // Speculative request of one tile: cache rows only, clamped to the capacity, no prefix_len needed.
   auto issue_speculative = [&](u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT], const unsigned char* kbase, const unsigned char* vbase,
                                int k0) {
@@ -137,17 +138,17 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     }
   };
 
-  // One segment: keys [c0, min(c1_cap, prefix_len + N)) of request b, head h. The result is the final
-  // output (part_row < 0) or the float32 partial whose first row in the workspace is part_row.
-  auto segment = [&](const int b, const int h, const int c0, const int c1_cap, const long part_row) {
-    const bool final_out = part_row < 0;
+  // One segment: keys [c0, min(c1_cap, prefix_len + N)) of request b, K/V head h. The result is the final
+  // output (slot < 0) or float32 partials in slot `slot` of every query head of the group.
+  auto segment = [&](const int b, const int h, const int c0, const int c1_cap, const int slot) {
+    const bool final_out = slot < 0;
 
     // ---- straight-line prologue: first two tiles (they do not depend on prefix_len), Q, one tree node per thread
     const int P = prefix_len[b];
     const unsigned char* kc = (const unsigned char*)(k_cache + b * kv_sb + h * kv_sh);
     const unsigned char* vc = (const unsigned char*)(v_cache + b * kv_sb + h * kv_sh);
-    const unsigned char* kn = APPEND ? (const unsigned char*)(k_new + b * q_sb + h * q_sh) : nullptr;
-    const unsigned char* vn = APPEND ? (const unsigned char*)(v_new + b * q_sb + h * q_sh) : nullptr;
+    const unsigned char* kn = APPEND ? (const unsigned char*)(k_new + b * n_sb + h * n_sh) : nullptr;
+    const unsigned char* vn = APPEND ? (const unsigned char*)(v_new + b * n_sb + h * n_sh) : nullptr;
     const long new_minus_cache_k = APPEND ? (long)(kn - kc) : 0, new_minus_cache_v = APPEND ? (long)(vn - vc) : 0;
 
     // MODE: 1 = clean (no clamp), 2 = tail (clamp, new rows)
@@ -174,13 +175,26 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     issue_speculative(Kr[0], Vr[0], kc, vc, c0);
     issue_speculative(Kr[1], Vr[1], kc, vc, c0 + KT);
 
+    // Query tiles of a (request, K/V head) pair: the `group` query heads that share the K/V head, ceil(N/16)
+    // tiles each (multi-head attention: group = 1). Tile tl of this wavefront serves query head
+    // h * group + tl / tiles_per_head, nodes (tl % tiles_per_head) * 16 .. + 16; tiles past the group idle.
+    const int group = H / H_kv, tiles_per_head = (N + 15) / 16;
+    int tile_head[NTW], tile_node[NTW];   // head within the group (clamped), node of this lane (may be >= N)
+    bool tile_live[NTW];
+#pragma unroll
+    for (int nt = 0; nt < NTW; ++nt) {
+      const int tl = (qt * NTW + nt);
+      tile_live[nt] = tl / tiles_per_head < group;
+      tile_head[nt] = min(tl / tiles_per_head, group - 1);
+      tile_node[nt] = (tl % tiles_per_head) * 16 + r16;
+    }
     bf16x8 qB[NTW][KS];
 #pragma unroll
     for (int nt = 0; nt < NTW; ++nt) {
-      const int n = q0 + nt * 16 + r16;
+      const int n = tile_node[nt], head = h * group + tile_head[nt];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const u32x4 raw = *(const u32x4*)(q + b * q_sb + min(n, N - 1) * q_sn + h * q_sh + ks * 32 + g * 8);
+        const u32x4 raw = *(const u32x4*)(q + b * q_sb + min(n, N - 1) * q_sn + head * q_sh + ks * 32 + g * 8);
         qB[nt][ks] = __builtin_bit_cast(bf16x8, raw);
       }
     }
@@ -197,9 +211,9 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     const int len = P + N;
     auto zero_outputs = [&](int bit) {
       if (final_out) {
-        for (int i = t; i < QW * NTW * 16 * D; i += NTHREADS) {
-          const int n = i / D;
-          if (n < N) out[b * q_sb + n * q_sn + h * q_sh + (i % D)] = __float2bfloat16(0.f);
+        for (int i = t; i < group * N * D; i += NTHREADS) {   // every query head of the group, every node
+          const int hg = i / (N * D), n = (i / D) % N;
+          out[b * q_sb + n * q_sn + (h * group + hg) * q_sh + (i % D)] = __float2bfloat16(0.f);
         }
         if (h == 0 && t == 0) set_status(status, b, bit);
       }
@@ -247,7 +261,7 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
       lds_barrier();
 #pragma unroll
       for (int nt = 0; nt < NTW; ++nt) {
-        const int n = q0 + nt * 16 + r16;
+        const int n = tile_node[nt];
         if (n < N) { anc_lo[nt] = s_anc[n][0]; anc_hi[nt] = s_anc[n][1]; }
       }
     }
@@ -456,8 +470,8 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     // ---- normalise and write (or emit the partial)
 #pragma unroll
     for (int nt = 0; nt < NTW; ++nt) {
-      const int n = q0 + nt * 16 + r16;
-      if (kpart == 0 && n < N) {
+      const int n = tile_node[nt], head = h * group + tile_head[nt];
+      if (kpart == 0 && tile_live[nt] && n < N) {
         if (final_out) {
           const float inv = 1.f / l_tot[nt];
 #pragma unroll
@@ -465,10 +479,10 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
             union { uint2 u; __hip_bfloat16 h4[4]; } pk;
 #pragma unroll
             for (int i = 0; i < 4; ++i) pk.h4[i] = __float2bfloat16(O[nt][db][i] * inv);
-            *(uint2*)(out + b * q_sb + n * q_sn + h * q_sh + db * 16 + 4 * g) = pk.u;
+            *(uint2*)(out + b * q_sb + n * q_sn + head * q_sh + db * 16 + 4 * g) = pk.u;
           }
         } else {
-          const long base = part_row + n;
+          const long base = (((long)b * H + head) * n_splits + slot) * N + n;
 #pragma unroll
           for (int db = 0; db < DB; ++db) *(f32x4*)(ws_o + base * D + db * 16 + 4 * g) = O[nt][db];
           if (g == 0) {
@@ -482,21 +496,20 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
 
   if constexpr (PLAN == PLAN_GRID) {
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    segment(b, h, split * chunk_keys, split * chunk_keys + chunk_keys,
-            n_splits == 1 ? -1l : (((long)b * H + h) * n_splits + split) * N);
+    segment(b, h, split * chunk_keys, split * chunk_keys + chunk_keys, n_splits == 1 ? -1 : split);
   } else {
     // Tiles [pos, end) of the flattened (request, head, key tile) order belong to this workgroup.
     // n_splits is the number of partial slots per pair; the workgroups overlapping a pair fill slots
     // 0, 1, ... in order.
-    const BalancedShare bs = balanced_share(prefix_len, B, N, H, S_cap, KT, (int)gridDim.x);
+    const BalancedShare bs = balanced_share(prefix_len, B, N, H_kv, S_cap, KT, (int)gridDim.x);
     long pos = (long)blockIdx.x * bs.share;
     const long end = min(bs.total, pos + bs.share);
     int b = 0;
     long req_start = 0;
     int tb = request_tiles(prefix_len[0], N, S_cap, KT);
     while (pos < end) {
-      while (pos >= req_start + (long)H * tb) {   // pos < total: a request with tiles left lies ahead
-        req_start += (long)H * tb;
+      while (pos >= req_start + (long)H_kv * tb) {   // pos < total: a request with tiles left lies ahead
+        req_start += (long)H_kv * tb;
         ++b;
         tb = request_tiles(prefix_len[b], N, S_cap, KT);
       }
@@ -504,7 +517,7 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
       const int h = (int)(in_req / tb), tile0 = (int)(in_req % tb);
       const int n_take = (int)min((long)(tb - tile0), end - pos);
       const int slot = (int)blockIdx.x - (int)((req_start + (long)h * tb) / bs.share);
-      segment(b, h, tile0 * KT, (tile0 + n_take) * KT, (((long)b * H + h) * n_splits + slot) * N);
+      segment(b, h, tile0 * KT, (tile0 + n_take) * KT, slot);
       pos += n_take;
       lds_barrier();   // LDS (staging tiles, merge area, tree arrays) is reused by the next segment
     }
@@ -525,17 +538,19 @@ hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const Attn
   float* ws_o = ws ? (float*)((char*)ws + plan.ws_o_off) : nullptr;
   float* ws_ml = ws ? (float*)((char*)ws + plan.ws_ml_off) : nullptr;
   // one 16-query tile per wavefront: 2 x 2 key halves up to 32 nodes, four up to 64, eight up to 128
-  const int qw = d.N <= 32 ? 2 : d.N <= 64 ? 4 : 8;
+  const int tiles = attn_query_tiles(d);   // (query heads per K/V head) x ceil(N / 16)
+  const int qw = tiles <= 2 ? 2 : tiles <= 4 ? 4 : 8;
+  const NewStrides ns = attn_new_strides(d);
   const bool append = k_new != nullptr;
   const int mode = plan.balanced_wgs == 0 ? wide::PLAN_GRID : wide::PLAN_TILES;
-  const dim3 grid = mode != wide::PLAN_GRID ? dim3(plan.balanced_wgs, 1, 1) : dim3(plan.n_splits, d.H, d.B);
+  const dim3 grid = mode != wide::PLAN_GRID ? dim3(plan.balanced_wgs, 1, 1) : dim3(plan.n_splits, d.H_kv, d.B);
 #define SPEC_LAUNCH(DD, QQ, NTT, KK, DP, APP, PLAN)                                                                   \
   hipLaunchKernelGGL((wide::tree_attention_bf16_wide_kernel<DD, QQ, NTT, KK, DP, APP, PLAN>), grid, dim3(QQ * KK * 64), 0, s, \
                      (const __hip_bfloat16*)q, (__hip_bfloat16*)k_cache, (__hip_bfloat16*)v_cache,                    \
                      (const __hip_bfloat16*)k_new, (const __hip_bfloat16*)v_new, parent, depth, prefix_len,           \
-                     (__hip_bfloat16*)out, ws_o, ws_ml, status, d.B, d.N, d.H, d.S_cap, plan.chunk_keys,              \
-                     plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h, (long)d.kv_stride_b,  \
-                     (long)d.kv_stride_h, (long)d.kv_stride_s, scale)
+                     (__hip_bfloat16*)out, ws_o, ws_ml, status, d.B, d.N, d.H, d.H_kv, d.S_cap, plan.chunk_keys,      \
+                     plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h, ns.b, ns.n, ns.h,     \
+                     (long)d.kv_stride_b, (long)d.kv_stride_h, (long)d.kv_stride_s, scale)
 #define SPEC_SHAPES(DD, APP, PLAN)                      \
   if (qw == 2) SPEC_LAUNCH(DD, 2, 1, 2, 2, APP, PLAN);        \
   else if (qw == 4) SPEC_LAUNCH(DD, 4, 1, 1, 2, APP, PLAN);   \

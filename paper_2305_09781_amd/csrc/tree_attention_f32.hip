@@ -23,8 +23,8 @@ __global__ void __launch_bounds__(256) tree_attention_f32_kernel(
     const float* __restrict__ q, const float* __restrict__ k_cache, const float* __restrict__ v_cache,
     const int32_t* __restrict__ parent, const int32_t* __restrict__ depth, const int32_t* __restrict__ prefix_len,
     float* __restrict__ out, float* __restrict__ ws_o, float* __restrict__ ws_ml, int32_t* status, int N, int H,
-    int S_cap, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long kv_sb, long kv_sh, long kv_ss,
-    float scale_log2) {
+    int S_cap, int group, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long kv_sb, long kv_sh,
+    long kv_ss, float scale_log2) {
   extern __shared__ float smem[];
   __shared__ unsigned long long s_anc[SPEC_MAX_TREE_NODES][2];
   __shared__ int s_flag;
@@ -74,8 +74,8 @@ __global__ void __launch_bounds__(256) tree_attention_f32_kernel(
 #pragma unroll
   for (int r = 0; r < RMAX; ++r) acc[r] = make_float4(0.f, 0.f, 0.f, 0.f);
 
-  const float* kb = k_cache + b * kv_sb + h * kv_sh;
-  const float* vb = v_cache + b * kv_sb + h * kv_sh;
+  const float* kb = k_cache + b * kv_sb + (h / group) * kv_sh;   // grouped-query heads: `group` query heads per K/V head
+  const float* vb = v_cache + b * kv_sb + (h / group) * kv_sh;
 
   for (int k0 = c0; k0 < c1; k0 += F32_TK) {
     const int tk = min(F32_TK, c1 - k0);
@@ -175,9 +175,9 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const float* __restri
                                                            const int32_t* __restrict__ parent,
                                                            const int32_t* __restrict__ depth,
                                                            const int32_t* __restrict__ prefix_len, void* __restrict__ out,
-                                                           int32_t* status, int B, int N, int H, int D, int S_cap,
-                                                           int chunk_keys, int slots, int bal_wgs, int bal_tile, long q_sb,
-                                                           long q_sn, long q_sh) {
+                                                           int32_t* status, int B, int N, int H, int H_kv, int D,
+                                                           int S_cap, int chunk_keys, int slots, int bal_wgs,
+                                                           int bal_tile, long q_sb, long q_sn, long q_sh) {
   __shared__ int s_flag;
   const int h = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
   const int P = prefix_len[b];
@@ -187,11 +187,12 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const float* __restri
   int ns = 0;
   if (valid) {
     if (bal_wgs > 0) {
-      const BalancedShare bs = balanced_share(prefix_len, B, N, H, S_cap, bal_tile, bal_wgs);
+      // the deal is over (request, K/V head) pairs; every query head of a group has the same partial slots
+      const BalancedShare bs = balanced_share(prefix_len, B, N, H_kv, S_cap, bal_tile, bal_wgs);
       long req_start = 0;
-      for (int bb = 0; bb < b; ++bb) req_start += (long)H * request_tiles(prefix_len[bb], N, S_cap, bal_tile);
+      for (int bb = 0; bb < b; ++bb) req_start += (long)H_kv * request_tiles(prefix_len[bb], N, S_cap, bal_tile);
       const int tb = request_tiles(P, N, S_cap, bal_tile);
-      const long pair_start = req_start + (long)h * tb;
+      const long pair_start = req_start + (long)(h / (H / H_kv)) * tb;
       ns = (int)((pair_start + tb - 1) / bs.share - pair_start / bs.share) + 1;
     } else {
       ns = min(slots, (P + N + chunk_keys - 1) / chunk_keys);
@@ -242,7 +243,7 @@ hipError_t launch_tree_attention_f32(const spec_attn_desc_t& d, const AttnPlan& 
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, q, k_cache, v_cache, parent, depth, prefix_len, out, ws_o, ws_ml,
-                     status, d.N, d.H, d.S_cap, plan.chunk_keys, plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n,
+                     status, d.N, d.H, d.S_cap, d.H / d.H_kv, plan.chunk_keys, plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n,
                      (long)d.q_stride_h, (long)d.kv_stride_b, (long)d.kv_stride_h, (long)d.kv_stride_s, scale);
   return hipGetLastError();
 }
@@ -256,11 +257,11 @@ hipError_t launch_attn_combine(const spec_attn_desc_t& d, const AttnPlan& plan, 
   dim3 grid(d.H, d.B, (items + 255) / 256);
   if (d.dtype == SPEC_BF16) {
     hipLaunchKernelGGL(attn_combine_kernel<true>, grid, dim3(256), 0, s, ws_o, ws_ml, parent, depth, prefix_len, out,
-                       status, d.B, d.N, d.H, d.D, d.S_cap, plan.chunk_keys, plan.n_splits, plan.balanced_wgs, plan.balanced_tile,
+                       status, d.B, d.N, d.H, d.H_kv, d.D, d.S_cap, plan.chunk_keys, plan.n_splits, plan.balanced_wgs, plan.balanced_tile,
                        (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h);
   } else {
     hipLaunchKernelGGL(attn_combine_kernel<false>, grid, dim3(256), 0, s, ws_o, ws_ml, parent, depth, prefix_len, out,
-                       status, d.B, d.N, d.H, d.D, d.S_cap, plan.chunk_keys, plan.n_splits, plan.balanced_wgs, plan.balanced_tile,
+                       status, d.B, d.N, d.H, d.H_kv, d.D, d.S_cap, plan.chunk_keys, plan.n_splits, plan.balanced_wgs, plan.balanced_tile,
                        (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h);
   }
   return hipGetLastError();

@@ -48,6 +48,11 @@ class Config:
     logit_std: float = 3.0
     n_ssm: int = 1
     layers: int = 32      # layers of the model the shape comes from
+    H_kv: int = 0         # key/value heads (0: as many as query heads)
+
+    @property
+    def kv_heads(self) -> int:
+        return self.H_kv if self.H_kv > 0 else self.H
 
     @property
     def torch_dtype(self):
@@ -218,7 +223,7 @@ def make_attention_inputs(cfg: Config, seed: Optional[int] = None, n_layers: int
 
     Cache rows at and beyond prefix_len[b] hold large finite garbage (N(0,1)*100) so that any read of
     a row that should not be visible shows up in the outputs.
-    Returns CPU tensors: q, k_new, v_new : [L][B,N,H,D]; k_cache, v_cache : [L][B,H,S_cap,D];
+    Returns CPU tensors: q : [L][B,N,H,D]; k_new, v_new : [L][B,N,H_kv,D]; k_cache, v_cache : [L][B,H_kv,S_cap,D];
     prefix_len [B] int32; tree_parent, tree_depth [B,N] int32.
     """
     rng = np.random.default_rng(cfg.seed if seed is None else seed)
@@ -237,14 +242,14 @@ def make_attention_inputs(cfg: Config, seed: Optional[int] = None, n_layers: int
     }
     for _ in range(n_layers):
         out["q"].append(_normal(rng, (cfg.B, cfg.N, cfg.H, cfg.D), dt))
-        out["k_new"].append(_normal(rng, (cfg.B, cfg.N, cfg.H, cfg.D), dt))
-        out["v_new"].append(_normal(rng, (cfg.B, cfg.N, cfg.H, cfg.D), dt))
+        out["k_new"].append(_normal(rng, (cfg.B, cfg.N, cfg.kv_heads, cfg.D), dt))
+        out["v_new"].append(_normal(rng, (cfg.B, cfg.N, cfg.kv_heads, cfg.D), dt))
         for name in ("k_cache", "v_cache"):
-            c = torch.empty((cfg.B, cfg.H, S, cfg.D), dtype=dt)
+            c = torch.empty((cfg.B, cfg.kv_heads, S, cfg.D), dtype=dt)
             for b in range(cfg.B):
                 p = int(prefix_len[b])
-                c[b, :, :p] = _normal(rng, (cfg.H, p, cfg.D), dt)
-                c[b, :, p:] = _normal(rng, (cfg.H, S - p, cfg.D), dt, scale=100.0)
+                c[b, :, :p] = _normal(rng, (cfg.kv_heads, p, cfg.D), dt)
+                c[b, :, p:] = _normal(rng, (cfg.kv_heads, S - p, cfg.D), dt, scale=100.0)
             out[name].append(c)
     return out
 

@@ -30,7 +30,8 @@ def test_library_exports_every_declared_symbol():
 def _desc(**kw):
     base = dict(B=1, H=4, H_kv=4, D=64, N=8, S_cap=136, dtype=binding.SPEC_F32, max_prefix_len=0,
                 q_stride_b=8 * 4 * 64, q_stride_n=4 * 64, q_stride_h=64,
-                kv_stride_b=4 * 136 * 64, kv_stride_h=136 * 64, kv_stride_s=64, softmax_scale=0.0, reserved=0)
+                kv_stride_b=4 * 136 * 64, kv_stride_h=136 * 64, kv_stride_s=64, new_stride_b=0, new_stride_n=0,
+                new_stride_h=0, softmax_scale=0.0, reserved=0)
     base.update(kw)
     return binding.AttnDesc(**base)
 
@@ -39,7 +40,10 @@ def _desc(**kw):
     (dict(), binding.ERR_INVALID_ARG),                       # null data pointers
     (dict(D=96), binding.ERR_UNSUPPORTED),
     (dict(N=129, S_cap=400), binding.ERR_UNSUPPORTED),
-    (dict(H_kv=2), binding.ERR_UNSUPPORTED),
+    (dict(H_kv=3), binding.ERR_UNSUPPORTED),                 # not a divisor of H
+    (dict(H_kv=2, new_stride_b=8 * 2 * 64, new_stride_n=2 * 64, new_stride_h=32), binding.ERR_INVALID_ARG),
+    (dict(dtype=binding.SPEC_BF16, H=32, H_kv=2, new_stride_b=8 * 2 * 64, new_stride_n=2 * 64, new_stride_h=64,
+          q_stride_b=8 * 32 * 64, q_stride_n=32 * 64), binding.ERR_UNSUPPORTED),   # 16 query tiles per K/V head
     (dict(dtype=5), binding.ERR_UNSUPPORTED),
     (dict(N=8, S_cap=4), binding.ERR_CAPACITY),
     (dict(max_prefix_len=130), binding.ERR_CAPACITY),

@@ -98,12 +98,16 @@ def _oracle_append_attention(inp, layer=0, bsel=None, hsel=None):
     """Oracle on a (request, head) subset; caches are converted to float64 for the subset only."""
     bsel = list(range(inp["q"][layer].shape[0])) if bsel is None else bsel
     hsel = list(range(inp["q"][layer].shape[2])) if hsel is None else hsel
-    ix = np.ix_(bsel, hsel)
-    kc = _f64(inp["k_cache"][layer][bsel][:, hsel])
-    vc = _f64(inp["v_cache"][layer][bsel][:, hsel])
+    if inp["k_cache"][layer].shape[1] != inp["q"][layer].shape[2]:
+        assert hsel == list(range(inp["q"][layer].shape[2])), "head subsets are for multi-head inputs"
+        ksel = list(range(inp["k_cache"][layer].shape[1]))
+    else:
+        ksel = hsel
+    kc = _f64(inp["k_cache"][layer][bsel][:, ksel])
+    vc = _f64(inp["v_cache"][layer][bsel][:, ksel])
     q = _f64(inp["q"][layer][bsel][:, :, hsel])
-    kn = _f64(inp["k_new"][layer][bsel][:, :, hsel])
-    vn = _f64(inp["v_new"][layer][bsel][:, :, hsel])
+    kn = _f64(inp["k_new"][layer][bsel][:, :, ksel])
+    vn = _f64(inp["v_new"][layer][bsel][:, :, ksel])
     pl = inp["prefix_len"].numpy()[bsel]
     st = orc.kv_append(kc, vc, kn, vn, pl)
     assert (st == 0).all()
@@ -203,6 +207,70 @@ def test_kv_append_with_rotary_embedding(spec, case):
         assert np.array_equal(_bits(kc2[b]), _bits(inp["k_cache"][0][b]))
 
 
+GROUPED = [
+    # dtype, B, H, H_kv, D, (P lo, hi), N, tree, forced chunk, balanced workgroups
+    ("bf16", 2, 4, 2, 128, (70, 300), 16, "expansion", 0, 0),        # 2 query tiles per K/V head
+    ("bf16", 2, 8, 2, 128, (70, 300), 16, "random_parent", 64, 0),   # 4 tiles
+    ("bf16", 2, 8, 1, 128, (40, 200), 16, "expansion", 0, 0),        # 8 tiles, one K/V head
+    ("bf16", 2, 8, 1, 64, (40, 200), 7, "random_parent", 0, 5),      # 8 partly filled tiles, balanced plan
+    ("bf16", 3, 6, 3, 128, (0, 130), 40, "random_branching", 96, 0), # 2 heads x 3 tiles
+    ("bf16", 2, 4, 2, 64, (100, 500), 33, "random_branching", 0, 7),
+    ("bf16", 1, 16, 2, 128, (600, 600), 1, "random_parent", 0, 0),   # decode-shaped: one node, 8 heads per group
+    ("f32", 2, 6, 2, 64, (30, 120), 12, "random_parent", 64, 0),
+]
+
+
+@pytest.mark.parametrize("case", GROUPED, ids=[f"{c[0]}-B{c[1]}H{c[2]}kv{c[3]}D{c[4]}N{c[6]}-ck{c[8]}-wg{c[9]}" for c in GROUPED])
+def test_grouped_query_heads(spec, case):
+    """Fewer K/V heads than query heads (an extension next to the path): the query heads of a group share
+    one K/V stream; append, attention (fused and not) and status handling as for multi-head inputs."""
+    dtype, B, H, H_kv, D, P, N, tree, chunk, wgs = case
+    cfg = wl.Config(98, "gqa", dtype, B=B, H=H, D=D, P=P if P[0] != P[1] else P[0], N=N, tree=tree,
+                    widths=wl.EXPANSION_EVAL * 2, H_kv=H_kv)
+    inp = wl.make_attention_inputs(cfg, seed=3000 + N + H, S_cap=P[1] + N + 5)
+    ref, kco, vco = _oracle_append_attention(inp)
+    for fused in (False, True):
+        with _chunk_keys(chunk), _balanced_wgs(wgs):
+            out, kc, vc = _run_append_attention(spec, inp, fused=fused)
+        _check_attention(out, ref, cfg.torch_dtype)
+        assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco), fused
+    # malformed tree / request that does not fit: zeros for every query head of the group
+    inp["tree_parent"][0, N - 1] = N + 3 if N > 1 else 0
+    inp["prefix_len"][B - 1] = inp["k_cache"][0].shape[2] - N + 1
+    status = torch.zeros(B, dtype=torch.int32, device=DEV)
+    with _chunk_keys(chunk), _balanced_wgs(wgs):
+        out, _, _ = _run_append_attention(spec, inp, status=status, fused=True)
+    st = status.cpu().numpy()
+    assert st[B - 1] == orc.ST_CAPACITY and (out[B - 1].float() == 0).all()
+    if B > 1:
+        assert st[0] == orc.ST_BAD_TREE and (out[0].float() == 0).all()
+
+
+def test_new_rows_in_their_own_layout(spec):
+    """Multi-head inputs whose k_new / v_new are not laid out like q (views into wider tensors): the
+    descriptor carries their strides and the fused call still appends and attends correctly."""
+    cfg = wl.Config(99, "strides", "bf16", B=2, H=3, D=128, P=(50, 260), N=16, tree="expansion", widths=wl.EXPANSION_EVAL * 2)
+    inp = wl.make_attention_inputs(cfg, seed=17, S_cap=260 + 16 + 3)
+    ref, kco, vco = _oracle_append_attention(inp)
+    wide_k = torch.zeros((cfg.B, cfg.N, cfg.H, 2 * cfg.D), dtype=torch.bfloat16, device=DEV)
+    wide_v = torch.zeros_like(wide_k)
+    kn, vn = wide_k[..., :cfg.D], wide_v[..., :cfg.D]
+    kn.copy_(inp["k_new"][0]); vn.copy_(inp["v_new"][0])
+    assert kn.stride() != _dev(inp["q"][0]).stride()
+    for wgs in (0, 3):
+        kc, vc = _dev(inp["k_cache"][0]), _dev(inp["v_cache"][0])
+        with _balanced_wgs(wgs):
+            out = spec.spec_tree_attention_append(_dev(inp["q"][0]), kn, vn, kc, vc, _dev(inp["tree_parent"]),
+                                                  _dev(inp["tree_depth"]), _dev(inp["prefix_len"]), max_prefix_len=260)
+        torch.cuda.synchronize()
+        _check_attention(out, ref, torch.bfloat16)
+        assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco)
+    kc, vc = _dev(inp["k_cache"][0]), _dev(inp["v_cache"][0])
+    spec.spec_kv_append(kn, vn, kc, vc, _dev(inp["prefix_len"]))
+    torch.cuda.synchronize()
+    assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco)
+
+
 BALANCED = [
     # B, H, D, (P lo, hi), N, tree, workgroups
     (3, 2, 128, (40, 300), 16, "expansion", 5),
@@ -293,7 +361,7 @@ def test_host_side_errors(spec):
     par, dep, pl = _dev(inp["tree_parent"]), _dev(inp["tree_depth"]), _dev(inp["prefix_len"])
     d = spec.make_desc(q, kc)
     for field, val, code in (("D", 96, spec.ERR_UNSUPPORTED), ("N", 129, spec.ERR_UNSUPPORTED),
-                             ("H_kv", 1, spec.ERR_UNSUPPORTED), ("max_prefix_len", 30, spec.ERR_CAPACITY),
+                             ("H_kv", 3, spec.ERR_UNSUPPORTED), ("max_prefix_len", 30, spec.ERR_CAPACITY),
                              ("q_stride_h", 100, spec.ERR_INVALID_ARG), ("dtype", 7, spec.ERR_UNSUPPORTED)):
         bad = spec.make_desc(q, kc)
         setattr(bad, field, val)

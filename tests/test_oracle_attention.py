@@ -250,3 +250,19 @@ def test_config_tree_shapes():
         if cfg.cfg == 3:
             assert max(wl.depth_of(par[b]).max() for b in range(cfg.B)) <= 16
             assert max(len(c) for b in range(cfg.B) for c in wl.children_of(par[b])) <= 4
+
+
+def test_grouped_query_heads_equal_multi_head_with_repeated_kv():
+    """Fewer K/V heads than query heads: query head h reads K/V head h // group, i.e. multi-head attention
+    on caches whose heads are repeated group times."""
+    cfg = wl.Config(97, "gqa", "f32", B=2, H=6, D=16, P=(3, 9), N=7, tree="random_parent", H_kv=2)
+    inp = wl.make_attention_inputs(cfg, seed=11)
+    kc, vc = inp["k_cache"][0].double().numpy(), inp["v_cache"][0].double().numpy()
+    assert kc.shape[1] == 2 and inp["k_new"][0].shape[2] == 2
+    orc.kv_append(kc, vc, inp["k_new"][0].double().numpy(), inp["v_new"][0].double().numpy(), inp["prefix_len"].numpy())
+    q = inp["q"][0].double().numpy()
+    got = orc.tree_attention(q, kc, vc, inp["tree_parent"].numpy(), inp["prefix_len"].numpy())
+    want = orc.tree_attention(q, np.repeat(kc, 3, axis=1), np.repeat(vc, 3, axis=1), inp["tree_parent"].numpy(),
+                              inp["prefix_len"].numpy())
+    assert np.array_equal(got, want)
+    assert not np.allclose(got[:, :, 0], got[:, :, 3])       # heads of different groups see different K/V
