@@ -94,7 +94,13 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d) {
     int wgs = env_int("SPEC_TREE_BALANCED_WGS", -1);
     if (wgs < 0) {
       const long max_tiles = groups * ((max_len + tile - 1) / tile);
-      const long cand = std::min<long>(resident, max_tiles / 8);
+      long cand = std::min<long>(resident, max_tiles / 8);
+      // every workgroup writes (and the combine step reads back) float32 partials for all queries of its
+      // pair: keep that traffic under a quarter of the K/V stream (it matters with grouped-query heads,
+      // where a pair has many queries and the batch few pairs)
+      const double stream_bytes = (double)groups * max_len * d.D * 2.0 * 2.0;
+      const double partial_bytes_per_wg = 2.0 * (double)(d.H / d.H_kv) * d.N * (d.D + 2) * 4.0;
+      cand = std::min<long>(cand, (long)(0.25 * stream_bytes / partial_bytes_per_wg));
       wgs = cand > groups ? (int)cand : 0;
     }
     if (wgs > 0) {
