@@ -134,11 +134,14 @@ def tree_expansion(widths: Sequence[int], n: int) -> np.ndarray:
     parent = [-1]
     level = [0]
     for k in widths:
+        if len(parent) >= n:      # only the first n nodes in generation order are kept
+            break
         nxt = []
         for u in level:
             for _ in range(k):
-                parent.append(u)
-                nxt.append(len(parent) - 1)
+                if len(parent) < n:
+                    parent.append(u)
+                    nxt.append(len(parent) - 1)
         level = nxt
     if len(parent) < n:
         raise ValueError(f"expansion {tuple(widths)} yields {len(parent)} nodes < {n}")

@@ -271,6 +271,36 @@ def test_new_rows_in_their_own_layout(spec):
     assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_randomised_shapes_and_plans(spec, seed):
+    """Random small shapes (heads, grouped heads, head dim, tree size, ragged prefixes down to zero, cache
+    capacity exactly prefix + N) under a random launch plan, fused or not: parity and bit-exact append."""
+    rng = np.random.default_rng(5000 + seed)
+    dtype = "bf16" if rng.random() < 0.8 else "f32"
+    D = int(rng.choice([64, 128]))
+    H_kv = int(rng.integers(1, 4))
+    N = int(rng.choice([1, 2, 5, 15, 16, 17, 31, 32, 33, 48, 63, 64, 65, 97, 127, 128]))
+    tiles_per_head = (N + 15) // 16
+    group = int(rng.integers(1, max(1, 8 // tiles_per_head) + 1)) if dtype == "bf16" else int(rng.integers(1, 4))
+    H = H_kv * group
+    B = int(rng.integers(1, 5))
+    hi = int(rng.choice([0, 3, 40, 130, 400]))
+    lo = int(rng.integers(0, hi + 1))
+    tree = str(rng.choice(["random_parent", "random_branching", "expansion"]))
+    cfg = wl.Config(90, "rand", dtype, B=B, H=H, D=D, P=(lo, hi) if lo != hi else hi, N=N, tree=tree,
+                    widths=wl.EXPANSION_EVAL * 16, H_kv=H_kv)
+    inp = wl.make_attention_inputs(cfg, seed=6000 + seed, S_cap=hi + N + int(rng.choice([0, 1, 7])))
+    plan = int(rng.integers(0, 3))
+    chunk = int(rng.choice([32, 64, 96, 160])) if plan == 1 else 0
+    wgs = int(rng.integers(1, 12)) if plan == 2 and dtype == "bf16" else 0
+    fused = bool(rng.integers(0, 2))
+    ref, kco, vco = _oracle_append_attention(inp)
+    with _chunk_keys(chunk), _balanced_wgs(wgs):
+        out, kc, vc = _run_append_attention(spec, inp, fused=fused)
+    _check_attention(out, ref, cfg.torch_dtype)
+    assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco)
+
+
 BALANCED = [
     # B, H, D, (P lo, hi), N, tree, workgroups
     (3, 2, 128, (40, 300), 16, "expansion", 5),
