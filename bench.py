@@ -181,6 +181,25 @@ def main():
     achieved = attn_bytes / (attn_us * 1e-6) / 1e9
     layer_bytes = attn_bytes
 
+    # practical ceiling on this machine for a launch of this size: a plain read kernel, one launch per buffer,
+    # over distinct buffers of the attention launch's byte count (>= 2 GB in total, far beyond the 256 MB
+    # Infinity Cache), timed the same way
+    n_probe = max(2, int(2e9 // attn_bytes) + 1)
+    probes = [torch.empty(attn_bytes // 16 * 16, dtype=torch.uint8, device=dev).fill_(l + 1) for l in range(n_probe)]
+    sink = torch.zeros(16, dtype=torch.uint8, device=dev)
+    def read_all():
+        for pb in probes:
+            spec.spec_probe_read_stream(pb, sink)
+    read_all()
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(3):
+        read_all()
+    ev1.record()
+    torch.cuda.synchronize()
+    read_stream_gbs = 3 * n_probe * (attn_bytes // 16 * 16) / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del probes
+
     result = {
         "metric": "verified tree tokens/sec (whole verification pass: L layers of KV append + tree attention, "
                   "greedy + stochastic verification, KV commit) + achieved HBM GB/s",
@@ -198,7 +217,8 @@ def main():
                      "kernel": ("tree_attention_bf16_kernel" if N <= 16 else "tree_attention_bf16_wide_kernel")
                                + " (KV append fused; + attn_combine_kernel when the key range is split)",
                      "bytes_per_launch": attn_bytes,
-                     "us_per_launch": attn_us},
+                     "us_per_launch": attn_us,
+                     "measured_read_stream_gbs": read_stream_gbs, "frac_of_measured_read_stream": achieved / read_stream_gbs},
     }
 
     if args.pmc_calibration:

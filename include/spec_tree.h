@@ -252,6 +252,14 @@ int spec_kv_commit(const spec_attn_desc_t* desc, int32_t n_layers, void* const* 
                    int32_t* prefix_len_out /*[B]*/, int32_t* status, void* hip_stream);
 
 /* Text for a SPEC_ERR_* code (static storage). Library version as major*10000 + minor*100 + patch. */
+/*
+ * Measurement aid (no passage of the paper): reads `bytes` (a multiple of 16 is used) from buf once with
+ * plain 16-byte loads and writes nothing (sink: 16 device bytes that are never written in practice). Timed
+ * over a buffer much larger than the on-chip caches it gives the read bandwidth this machine sustains,
+ * the practical ceiling next to the published HBM peak.
+ */
+int spec_probe_read_stream(const void* buf, size_t bytes, void* sink, void* hip_stream);
+
 const char* spec_strerror(int code);
 int spec_version(void);
 

@@ -24,7 +24,7 @@ EXPORTED = [
     "spec_kv_append", "spec_kv_append_rope", "spec_tree_attention", "spec_tree_attention_append", "spec_tree_attention_workspace_bytes",
     "spec_verify_greedy",
     "spec_verify_stochastic", "spec_verify_stochastic_workspace_bytes", "spec_verify_naive",
-    "spec_verify_naive_workspace_bytes", "spec_tree_expand_topk", "spec_tree_merge", "spec_kv_commit", "spec_strerror",
+    "spec_verify_naive_workspace_bytes", "spec_tree_expand_topk", "spec_tree_merge", "spec_kv_commit", "spec_probe_read_stream", "spec_strerror",
     "spec_version",
 ]
 
@@ -90,6 +90,8 @@ def load():
     lib.spec_tree_merge.restype = ctypes.c_int
     lib.spec_kv_commit.argtypes = [dp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i32, vp, vp, vp, vp, vp]
     lib.spec_kv_commit.restype = ctypes.c_int
+    lib.spec_probe_read_stream.argtypes = [vp, sz, vp, vp]
+    lib.spec_probe_read_stream.restype = ctypes.c_int
     lib.spec_strerror.argtypes = [ctypes.c_int]
     lib.spec_strerror.restype = ctypes.c_char_p
     lib.spec_version.restype = ctypes.c_int
@@ -333,3 +335,9 @@ def spec_kv_commit(k_caches: Sequence[torch.Tensor], v_caches: Sequence[torch.Te
                                  _ptr(accepted_len), _ptr(prefix_len), _ptr(prefix_len_out), _ptr(status),
                                  _stream(stream)), "spec_kv_commit")
     return prefix_len_out
+
+
+def spec_probe_read_stream(buf: torch.Tensor, sink: torch.Tensor, stream=None):
+    """Measurement aid: one plain read pass over `buf` (device tensor); `sink` holds at least 16 device bytes."""
+    _check(load().spec_probe_read_stream(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream(stream)),
+           "spec_probe_read_stream")

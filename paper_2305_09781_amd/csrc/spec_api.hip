@@ -150,6 +150,13 @@ extern "C" {
 
 int spec_version(void) { return 100; }
 
+int spec_probe_read_stream(const void* buf, size_t bytes, void* sink, void* hip_stream) {
+  if (!buf || !sink || bytes < 16 || !aligned16(buf) || !aligned16(sink)) return SPEC_ERR_INVALID_ARG;
+  // enough workgroups to fill every compute unit several times over
+  return launch_read_stream(buf, bytes, sink, compute_units() * 8, (hipStream_t)hip_stream) == hipSuccess ? SPEC_OK
+                                                                                                             : SPEC_ERR_HIP;
+}
+
 const char* spec_strerror(int code) {
   switch (code) {
     case SPEC_OK: return "ok";

@@ -81,6 +81,7 @@ hipError_t launch_tree_merge(int B, int M, int Nin, const int32_t* in_parent, co
                              const int32_t* in_size, int Nout, int32_t* out_parent, int32_t* out_depth,
                              int32_t* out_token, int32_t* out_ssm, int32_t* out_size, int32_t* node_map, int32_t* status,
                              hipStream_t s);
+hipError_t launch_read_stream(const void* buf, size_t bytes, void* sink, int workgroups, hipStream_t s);
 hipError_t launch_node_stats(int B, int N, int V, int logits_dtype, const void* logits, float inv_temp,
                              int32_t* node_argmax, float* node_max, float* node_sumexp, hipStream_t s);
 hipError_t launch_node_sample(int B, int N, int V, int logits_dtype, const void* logits, float inv_temp,

@@ -342,13 +342,13 @@ def test_config2_bf16_full(spec, fused):
     assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco)
 
 
-@pytest.mark.parametrize("c", [3, 4, 5])
-def test_large_configs_sampled_heads(spec, c):
-    """Full-size launch (the configuration the benchmark times); the oracle checks sampled
+@pytest.mark.parametrize("c,fused", [(3, True), (4, True), (4, False), (5, True)])
+def test_large_configs_sampled_heads(spec, c, fused):
+    """Full-size launch (fused = the configuration the benchmark times); the oracle checks sampled
     (request, head) pairs completely, every node and channel."""
     cfg = wl.CONFIGS[c]
     inp = wl.make_attention_inputs(cfg)
-    out, kc, vc = _run_append_attention(spec, inp, fused=(c != 4))
+    out, kc, vc = _run_append_attention(spec, inp, fused=fused)
     assert torch.isfinite(out.float()).all()
     rng = np.random.default_rng(c)
     bsel = sorted(set(int(x) for x in rng.integers(0, cfg.B, size=3)) | {cfg.B - 1})
