@@ -52,7 +52,7 @@ extern "C" {
 #define SPEC_OK 0
 #define SPEC_ERR_INVALID_ARG (-1) /* null pointer, non-positive size, bad stride or alignment        */
 #define SPEC_ERR_UNSUPPORTED (-2) /* D not in {64,128}, N > SPEC_MAX_TREE_NODES, dtype, H_kv not a   */
-                                  /* divisor of H, bf16 with (H/H_kv) * ceil(N/16) > 8               */
+                                  /* divisor of H                                                    */
 #define SPEC_ERR_CAPACITY (-3)    /* N > S_cap, max_prefix_len + N > S_cap                           */
 #define SPEC_ERR_HIP (-4)         /* a HIP runtime call failed (launch error)                        */
 #define SPEC_ERR_WORKSPACE (-5)   /* workspace NULL or smaller than *_workspace_bytes reports        */

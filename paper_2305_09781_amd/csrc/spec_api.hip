@@ -29,7 +29,6 @@ static int check_desc(const spec_attn_desc_t* d) {
   if (d->D != 64 && d->D != 128) return SPEC_ERR_UNSUPPORTED;
   if (d->N > SPEC_MAX_TREE_NODES) return SPEC_ERR_UNSUPPORTED;
   if (d->H % d->H_kv != 0) return SPEC_ERR_UNSUPPORTED;
-  if (d->dtype == SPEC_BF16 && attn_query_tiles(*d) > 8) return SPEC_ERR_UNSUPPORTED;
   {
     const bool none = d->new_stride_b == 0 && d->new_stride_n == 0 && d->new_stride_h == 0;
     if (!none && (d->new_stride_b <= 0 || d->new_stride_n <= 0 || d->new_stride_h < d->D)) return SPEC_ERR_INVALID_ARG;
@@ -75,8 +74,10 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d) {
   const int max_prefix = d.max_prefix_len > 0 ? d.max_prefix_len : d.S_cap - d.N;
   const int max_len = max_prefix + d.N;
   // bf16: one workgroup serves all query heads of a K/V head; float32: one per query head
-  const long groups = (long)d.B * (d.dtype == SPEC_BF16 ? d.H_kv : d.H);
-  const int tiles = attn_query_tiles(d);   // 16-query tiles per (request, K/V head)
+  const QueryGroups qg = attn_query_groups(d);
+  const int virtual_heads = d.H_kv * qg.n_qgroups;
+  const long groups = (long)d.B * (d.dtype == SPEC_BF16 ? virtual_heads : d.H);
+  const int tiles = qg.tiles_per_wg;   // 16-query tiles per workgroup
   // The few-query kernel serves one query tile per K/V head with k_new / v_new laid out like q; everything
   // else in bf16 runs on the wide kernel.
   const NewStrides ns = attn_new_strides(d);
@@ -98,8 +99,8 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d) {
       // every workgroup writes (and the combine step reads back) float32 partials for all queries of its
       // pair: keep that traffic under a quarter of the K/V stream (it matters with grouped-query heads,
       // where a pair has many queries and the batch few pairs)
-      const double stream_bytes = (double)groups * max_len * d.D * 2.0 * 2.0;
-      const double partial_bytes_per_wg = 2.0 * (double)(d.H / d.H_kv) * d.N * (d.D + 2) * 4.0;
+      const double stream_bytes = (double)d.B * d.H_kv * max_len * d.D * 2.0 * 2.0;
+      const double partial_bytes_per_wg = 2.0 * (double)qg.heads_per_wg * d.N * (d.D + 2) * 4.0;
       cand = std::min<long>(cand, (long)(0.25 * stream_bytes / partial_bytes_per_wg));
       wgs = cand > groups ? (int)cand : 0;
     }
@@ -107,7 +108,7 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d) {
       p.balanced_wgs = wgs;
       p.balanced_tile = tile;
       p.chunk_keys = 0;
-      p.n_splits = (wgs + d.H_kv - 1) / d.H_kv + 1;   // a pair is overlapped by at most this many shares
+      p.n_splits = (wgs + virtual_heads - 1) / virtual_heads + 1;   // a pair is overlapped by at most this many shares
     }
   }
   if (p.balanced_wgs == 0) {

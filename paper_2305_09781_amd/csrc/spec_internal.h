@@ -35,10 +35,27 @@ inline int attn_queries_per_workgroup(const spec_attn_desc_t& d) {
   return d.N <= 16 ? 16 : d.N <= 32 ? 32 : d.N <= 64 ? 64 : 128;
 }
 
-// Query heads per key/value head, and the 16-query MFMA tiles one (request, K/V head) pair needs: every
-// query head of the group brings ceil(N / 16) tiles. The bf16 kernels hold at most 8 tiles per workgroup.
-inline int attn_group_size(const spec_attn_desc_t& d) { return d.H / d.H_kv; }
-inline int attn_query_tiles(const spec_attn_desc_t& d) { return attn_group_size(d) * ((d.N + 15) / 16); }
+// Query heads per key/value head, and how the bf16 kernels split them. Every query head of a group brings
+// ceil(N / 16) 16-query MFMA tiles; a workgroup holds at most 8 tiles, i.e. `heads_per_wg` whole heads, so a
+// (request, K/V head) pair is served by `n_qgroups` workgroups ("virtual heads" hv = h_kv * n_qgroups + qg),
+// each streaming the pair's K/V for its own heads (the repeats are served by the caches).
+struct QueryGroups {
+  int group;          // query heads per K/V head
+  int tiles_per_head; // ceil(N / 16)
+  int heads_per_wg;   // query heads one workgroup serves
+  int n_qgroups;      // workgroups per (request, K/V head) pair
+  int tiles_per_wg;   // heads_per_wg * tiles_per_head, 1..8
+};
+inline QueryGroups attn_query_groups(const spec_attn_desc_t& d) {
+  QueryGroups g;
+  g.group = d.H / d.H_kv;
+  g.tiles_per_head = (d.N + 15) / 16;
+  const int fit = 8 / g.tiles_per_head > 0 ? 8 / g.tiles_per_head : 1;
+  g.heads_per_wg = g.group < fit ? g.group : fit;
+  g.n_qgroups = (g.group + g.heads_per_wg - 1) / g.heads_per_wg;
+  g.tiles_per_wg = g.heads_per_wg * g.tiles_per_head;
+  return g;
+}
 
 // Strides of k_new / v_new (all zero in the descriptor: laid out like q).
 struct NewStrides { long b, n, h; };

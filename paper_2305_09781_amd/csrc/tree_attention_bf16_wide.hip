@@ -91,7 +91,7 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     const __hip_bfloat16* __restrict__ k_new, const __hip_bfloat16* __restrict__ v_new,
     const int32_t* __restrict__ parent, const int32_t* __restrict__ depth, const int32_t* __restrict__ prefix_len,
     __hip_bfloat16* __restrict__ out, float* __restrict__ ws_o, float* __restrict__ ws_ml, int32_t* status, int B, int N,
-    int H, int H_kv, int S_cap, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long n_sb, long n_sn,
+    int H, int H_v, int n_qg, int hpw, int S_cap, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long n_sb, long n_sn,
     long n_sh, long kv_sb, long kv_sh, long kv_ss, float scale_log2) {
   static_assert(KW == 1 || KW == 2, "a 64-key tile is consumed as two 32-key halves");
   static_assert(DEPTH == 2 || DEPTH == 4, "register sets of tiles in flight");
@@ -138,10 +138,12 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     }
   };
 
-  // One segment: keys [c0, min(c1_cap, prefix_len + N)) of request b, K/V head h. The result is the final
-  // output (slot < 0) or float32 partials in slot `slot` of every query head of the group.
-  auto segment = [&](const int b, const int h, const int c0, const int c1_cap, const int slot) {
+  // One segment: keys [c0, min(c1_cap, prefix_len + N)) of request b, virtual head hv = K/V head h and query
+  // group qg (hpw of the H / H_kv query heads that share h). The result is the final output (slot < 0) or
+  // float32 partials in slot `slot` of every query head served here.
+  auto segment = [&](const int b, const int hv, const int c0, const int c1_cap, const int slot) {
     const bool final_out = slot < 0;
+    const int h = hv / n_qg, qg = hv % n_qg;
 
     // ---- straight-line prologue: first two tiles (they do not depend on prefix_len), Q, one tree node per thread
     const int P = prefix_len[b];
@@ -175,17 +177,19 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     issue_speculative(Kr[0], Vr[0], kc, vc, c0);
     issue_speculative(Kr[1], Vr[1], kc, vc, c0 + KT);
 
-    // Query tiles of a (request, K/V head) pair: the `group` query heads that share the K/V head, ceil(N/16)
-    // tiles each (multi-head attention: group = 1). Tile tl of this wavefront serves query head
-    // h * group + tl / tiles_per_head, nodes (tl % tiles_per_head) * 16 .. + 16; tiles past the group idle.
-    const int group = H / H_kv, tiles_per_head = (N + 15) / 16;
+    // Query tiles of this workgroup: hpw of the `group` query heads that share the K/V head (heads
+    // qg * hpw .. of the group), ceil(N/16) tiles each (multi-head attention: group = hpw = 1). Tile tl of
+    // a wavefront serves head h * group + qg * hpw + tl / tiles_per_head, nodes (tl % tiles_per_head) * 16 ..
+    // + 16; tiles past the workgroup's heads idle.
+    const int group = H / (H_v / n_qg), tiles_per_head = (N + 15) / 16;
     int tile_head[NTW], tile_node[NTW];   // head within the group (clamped), node of this lane (may be >= N)
     bool tile_live[NTW];
 #pragma unroll
     for (int nt = 0; nt < NTW; ++nt) {
       const int tl = (qt * NTW + nt);
-      tile_live[nt] = tl / tiles_per_head < group;
-      tile_head[nt] = min(tl / tiles_per_head, group - 1);
+      const int hg = qg * hpw + tl / tiles_per_head;
+      tile_live[nt] = tl / tiles_per_head < hpw && hg < group;
+      tile_head[nt] = min(hg, group - 1);
       tile_node[nt] = (tl % tiles_per_head) * 16 + r16;
     }
     bf16x8 qB[NTW][KS];
@@ -211,11 +215,11 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     const int len = P + N;
     auto zero_outputs = [&](int bit) {
       if (final_out) {
-        for (int i = t; i < group * N * D; i += NTHREADS) {   // every query head of the group, every node
-          const int hg = i / (N * D), n = (i / D) % N;
-          out[b * q_sb + n * q_sn + (h * group + hg) * q_sh + (i % D)] = __float2bfloat16(0.f);
+        for (int i = t; i < hpw * N * D; i += NTHREADS) {   // every query head served here, every node
+          const int hg = qg * hpw + i / (N * D), n = (i / D) % N;
+          if (hg < group) out[b * q_sb + n * q_sn + (h * group + hg) * q_sh + (i % D)] = __float2bfloat16(0.f);
         }
-        if (h == 0 && t == 0) set_status(status, b, bit);
+        if (hv == 0 && t == 0) set_status(status, b, bit);
       }
     };
     if (!cap_ok) {
@@ -278,7 +282,7 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
           if (row >= c1) {
             Ks_[j] = (u32x4){0u, 0u, 0u, 0u};
             Vs_[j] = (u32x4){0u, 0u, 0u, 0u};
-          } else if (APPEND && row >= P) {
+          } else if (APPEND && qg == 0 && row >= P) {   // the pair's first query group writes the new rows
             store_nt((unsigned char*)(k_cache + b * kv_sb + h * kv_sh) + (unsigned)row * cache_row_bytes + ld_col, Ks_[j]);
             store_nt((unsigned char*)(v_cache + b * kv_sb + h * kv_sh) + (unsigned)row * cache_row_bytes + ld_col, Vs_[j]);
           }
@@ -495,29 +499,37 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
   };   // segment
 
   if constexpr (PLAN == PLAN_GRID) {
-    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    segment(b, h, split * chunk_keys, split * chunk_keys + chunk_keys, n_splits == 1 ? -1 : split);
+    const int split = blockIdx.x, b = blockIdx.z;
+    int hv = blockIdx.y;
+    // Workgroups are handed to the eight XCDs round-robin in launch order and every XCD has its own L2. The
+    // query groups of one (request, K/V head) pair read the same K/V: numbering them 8 apart puts them on
+    // one XCD, close in time, so that the repeats can be L2 hits.
+    if (n_qg > 1 && (H_v / n_qg) % 8 == 0 && gridDim.x == 1) {
+      const int r = hv % (8 * n_qg), blk = hv / (8 * n_qg);
+      hv = (blk * 8 + r % 8) * n_qg + r / 8;
+    }
+    segment(b, hv, split * chunk_keys, split * chunk_keys + chunk_keys, n_splits == 1 ? -1 : split);
   } else {
     // Tiles [pos, end) of the flattened (request, head, key tile) order belong to this workgroup.
     // n_splits is the number of partial slots per pair; the workgroups overlapping a pair fill slots
     // 0, 1, ... in order.
-    const BalancedShare bs = balanced_share(prefix_len, B, N, H_kv, S_cap, KT, (int)gridDim.x);
+    const BalancedShare bs = balanced_share(prefix_len, B, N, H_v, S_cap, KT, (int)gridDim.x);
     long pos = (long)blockIdx.x * bs.share;
     const long end = min(bs.total, pos + bs.share);
     int b = 0;
     long req_start = 0;
     int tb = request_tiles(prefix_len[0], N, S_cap, KT);
     while (pos < end) {
-      while (pos >= req_start + (long)H_kv * tb) {   // pos < total: a request with tiles left lies ahead
-        req_start += (long)H_kv * tb;
+      while (pos >= req_start + (long)H_v * tb) {   // pos < total: a request with tiles left lies ahead
+        req_start += (long)H_v * tb;
         ++b;
         tb = request_tiles(prefix_len[b], N, S_cap, KT);
       }
       const long in_req = pos - req_start;
-      const int h = (int)(in_req / tb), tile0 = (int)(in_req % tb);
+      const int hv = (int)(in_req / tb), tile0 = (int)(in_req % tb);
       const int n_take = (int)min((long)(tb - tile0), end - pos);
-      const int slot = (int)blockIdx.x - (int)((req_start + (long)h * tb) / bs.share);
-      segment(b, h, tile0 * KT, (tile0 + n_take) * KT, slot);
+      const int slot = (int)blockIdx.x - (int)((req_start + (long)hv * tb) / bs.share);
+      segment(b, hv, tile0 * KT, (tile0 + n_take) * KT, slot);
       pos += n_take;
       lds_barrier();   // LDS (staging tiles, merge area, tree arrays) is reused by the next segment
     }
@@ -538,17 +550,20 @@ hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const Attn
   float* ws_o = ws ? (float*)((char*)ws + plan.ws_o_off) : nullptr;
   float* ws_ml = ws ? (float*)((char*)ws + plan.ws_ml_off) : nullptr;
   // one 16-query tile per wavefront: 2 x 2 key halves up to 32 nodes, four up to 64, eight up to 128
-  const int tiles = attn_query_tiles(d);   // (query heads per K/V head) x ceil(N / 16)
+  const QueryGroups qgr = attn_query_groups(d);
+  const int tiles = qgr.tiles_per_wg;   // (query heads per workgroup) x ceil(N / 16)
+  const int virtual_heads = d.H_kv * qgr.n_qgroups;
   const int qw = tiles <= 2 ? 2 : tiles <= 4 ? 4 : 8;
   const NewStrides ns = attn_new_strides(d);
   const bool append = k_new != nullptr;
   const int mode = plan.balanced_wgs == 0 ? wide::PLAN_GRID : wide::PLAN_TILES;
-  const dim3 grid = mode != wide::PLAN_GRID ? dim3(plan.balanced_wgs, 1, 1) : dim3(plan.n_splits, d.H_kv, d.B);
+  const dim3 grid = mode != wide::PLAN_GRID ? dim3(plan.balanced_wgs, 1, 1) : dim3(plan.n_splits, virtual_heads, d.B);
 #define SPEC_LAUNCH(DD, QQ, NTT, KK, DP, APP, PLAN)                                                                   \
   hipLaunchKernelGGL((wide::tree_attention_bf16_wide_kernel<DD, QQ, NTT, KK, DP, APP, PLAN>), grid, dim3(QQ * KK * 64), 0, s, \
                      (const __hip_bfloat16*)q, (__hip_bfloat16*)k_cache, (__hip_bfloat16*)v_cache,                    \
                      (const __hip_bfloat16*)k_new, (const __hip_bfloat16*)v_new, parent, depth, prefix_len,           \
-                     (__hip_bfloat16*)out, ws_o, ws_ml, status, d.B, d.N, d.H, d.H_kv, d.S_cap, plan.chunk_keys,      \
+                     (__hip_bfloat16*)out, ws_o, ws_ml, status, d.B, d.N, d.H, virtual_heads, qgr.n_qgroups,           \
+                     qgr.heads_per_wg, d.S_cap, plan.chunk_keys,                                                      \
                      plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h, ns.b, ns.n, ns.h,     \
                      (long)d.kv_stride_b, (long)d.kv_stride_h, (long)d.kv_stride_s, scale)
 #define SPEC_SHAPES(DD, APP, PLAN)                      \

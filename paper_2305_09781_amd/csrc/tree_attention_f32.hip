@@ -175,9 +175,9 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const float* __restri
                                                            const int32_t* __restrict__ parent,
                                                            const int32_t* __restrict__ depth,
                                                            const int32_t* __restrict__ prefix_len, void* __restrict__ out,
-                                                           int32_t* status, int B, int N, int H, int H_kv, int D,
-                                                           int S_cap, int chunk_keys, int slots, int bal_wgs,
-                                                           int bal_tile, long q_sb, long q_sn, long q_sh) {
+                                                           int32_t* status, int B, int N, int H, int H_kv, int n_qg,
+                                                           int hpw, int D, int S_cap, int chunk_keys, int slots,
+                                                           int bal_wgs, int bal_tile, long q_sb, long q_sn, long q_sh) {
   __shared__ int s_flag;
   const int h = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
   const int P = prefix_len[b];
@@ -187,12 +187,15 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const float* __restri
   int ns = 0;
   if (valid) {
     if (bal_wgs > 0) {
-      // the deal is over (request, K/V head) pairs; every query head of a group has the same partial slots
-      const BalancedShare bs = balanced_share(prefix_len, B, N, H_kv, S_cap, bal_tile, bal_wgs);
+      // the deal is over (request, virtual head) pairs: virtual head = K/V head and query group (hpw query
+      // heads); the query heads of one virtual head have the same partial slots
+      const int H_v = H_kv * n_qg, group = H / H_kv;
+      const int hv = (h / group) * n_qg + (h % group) / hpw;
+      const BalancedShare bs = balanced_share(prefix_len, B, N, H_v, S_cap, bal_tile, bal_wgs);
       long req_start = 0;
-      for (int bb = 0; bb < b; ++bb) req_start += (long)H_kv * request_tiles(prefix_len[bb], N, S_cap, bal_tile);
+      for (int bb = 0; bb < b; ++bb) req_start += (long)H_v * request_tiles(prefix_len[bb], N, S_cap, bal_tile);
       const int tb = request_tiles(P, N, S_cap, bal_tile);
-      const long pair_start = req_start + (long)(h / (H / H_kv)) * tb;
+      const long pair_start = req_start + (long)hv * tb;
       ns = (int)((pair_start + tb - 1) / bs.share - pair_start / bs.share) + 1;
     } else {
       ns = min(slots, (P + N + chunk_keys - 1) / chunk_keys);
@@ -254,14 +257,16 @@ hipError_t launch_attn_combine(const spec_attn_desc_t& d, const AttnPlan& plan, 
   const float* ws_o = (const float*)((const char*)ws + plan.ws_o_off);
   const float* ws_ml = (const float*)((const char*)ws + plan.ws_ml_off);
   const int items = d.N * (d.D / 4);
+  const QueryGroups qg = attn_query_groups(d);
+  const int n_qg = d.dtype == SPEC_BF16 ? qg.n_qgroups : 1, hpw = d.dtype == SPEC_BF16 ? qg.heads_per_wg : 1;
   dim3 grid(d.H, d.B, (items + 255) / 256);
   if (d.dtype == SPEC_BF16) {
     hipLaunchKernelGGL(attn_combine_kernel<true>, grid, dim3(256), 0, s, ws_o, ws_ml, parent, depth, prefix_len, out,
-                       status, d.B, d.N, d.H, d.H_kv, d.D, d.S_cap, plan.chunk_keys, plan.n_splits, plan.balanced_wgs, plan.balanced_tile,
+                       status, d.B, d.N, d.H, d.H_kv, n_qg, hpw, d.D, d.S_cap, plan.chunk_keys, plan.n_splits, plan.balanced_wgs, plan.balanced_tile,
                        (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h);
   } else {
     hipLaunchKernelGGL(attn_combine_kernel<false>, grid, dim3(256), 0, s, ws_o, ws_ml, parent, depth, prefix_len, out,
-                       status, d.B, d.N, d.H, d.H_kv, d.D, d.S_cap, plan.chunk_keys, plan.n_splits, plan.balanced_wgs, plan.balanced_tile,
+                       status, d.B, d.N, d.H, d.H_kv, n_qg, hpw, d.D, d.S_cap, plan.chunk_keys, plan.n_splits, plan.balanced_wgs, plan.balanced_tile,
                        (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h);
   }
   return hipGetLastError();

@@ -42,8 +42,6 @@ def _desc(**kw):
     (dict(N=129, S_cap=400), binding.ERR_UNSUPPORTED),
     (dict(H_kv=3), binding.ERR_UNSUPPORTED),                 # not a divisor of H
     (dict(H_kv=2, new_stride_b=8 * 2 * 64, new_stride_n=2 * 64, new_stride_h=32), binding.ERR_INVALID_ARG),
-    (dict(dtype=binding.SPEC_BF16, H=32, H_kv=2, new_stride_b=8 * 2 * 64, new_stride_n=2 * 64, new_stride_h=64,
-          q_stride_b=8 * 32 * 64, q_stride_n=32 * 64), binding.ERR_UNSUPPORTED),   # 16 query tiles per K/V head
     (dict(dtype=5), binding.ERR_UNSUPPORTED),
     (dict(N=8, S_cap=4), binding.ERR_CAPACITY),
     (dict(max_prefix_len=130), binding.ERR_CAPACITY),

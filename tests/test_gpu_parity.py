@@ -217,6 +217,12 @@ GROUPED = [
     ("bf16", 2, 4, 2, 64, (100, 500), 33, "random_branching", 0, 7),
     ("bf16", 1, 16, 2, 128, (600, 600), 1, "random_parent", 0, 0),   # decode-shaped: one node, 8 heads per group
     ("f32", 2, 6, 2, 64, (30, 120), 12, "random_parent", 64, 0),
+    # more than 8 query tiles per K/V head: several workgroups (query groups) per pair
+    ("bf16", 2, 16, 1, 128, (40, 300), 16, "expansion", 0, 0),        # 16 heads, one K/V head: 2 query groups of 8
+    ("bf16", 2, 12, 2, 128, (40, 300), 33, "random_branching", 64, 0),  # 3 tiles per head: 2 heads per workgroup, 3 groups
+    ("bf16", 1, 71, 1, 64, (100, 100), 16, "expansion", 0, 0),       # multi-query attention, 71 heads: 9 groups, last one short
+    ("bf16", 2, 20, 2, 64, (30, 500), 16, "random_parent", 0, 9),    # query groups under the balanced plan
+    ("bf16", 1, 6, 1, 128, (64, 64), 128, "random_branching", 0, 4), # 8 tiles per head: one head per workgroup
 ]
 
 
@@ -271,7 +277,7 @@ def test_new_rows_in_their_own_layout(spec):
     assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco)
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(32))
 def test_randomised_shapes_and_plans(spec, seed):
     """Random small shapes (heads, grouped heads, head dim, tree size, ragged prefixes down to zero, cache
     capacity exactly prefix + N) under a random launch plan, fused or not: parity and bit-exact append."""
@@ -281,7 +287,7 @@ def test_randomised_shapes_and_plans(spec, seed):
     H_kv = int(rng.integers(1, 4))
     N = int(rng.choice([1, 2, 5, 15, 16, 17, 31, 32, 33, 48, 63, 64, 65, 97, 127, 128]))
     tiles_per_head = (N + 15) // 16
-    group = int(rng.integers(1, max(1, 8 // tiles_per_head) + 1)) if dtype == "bf16" else int(rng.integers(1, 4))
+    group = int(rng.integers(1, 13)) if rng.random() < 0.3 else int(rng.integers(1, 4))
     H = H_kv * group
     B = int(rng.integers(1, 5))
     hi = int(rng.choice([0, 3, 40, 130, 400]))
