@@ -307,6 +307,22 @@ def test_randomised_shapes_and_plans(spec, seed):
     assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco)
 
 
+@pytest.mark.parametrize("N,scale", [(16, 6.0), (40, 6.0), (128, 4.0), (16, 0.01), (64, 0.01)])
+def test_peaked_and_flat_score_distributions(spec, N, scale):
+    """Scores far outside the unit range (the running maximum moves by many powers of two between tiles,
+    softmax weights underflow) and nearly constant scores: the online softmax stays within the bf16 bar."""
+    cfg = wl.Config(89, "peaked", "bf16", B=2, H=2, D=128, P=(200, 700), N=N, tree="random_branching")
+    inp = wl.make_attention_inputs(cfg, seed=71 + N, S_cap=700 + N)
+    for name in ("q", "k_new", "k_cache"):
+        inp[name][0] = (inp[name][0].float() * scale).to(torch.bfloat16)
+    ref, kco, vco = _oracle_append_attention(inp)
+    for wgs in (0, 5):
+        with _balanced_wgs(wgs):
+            out, kc, vc = _run_append_attention(spec, inp, fused=True)
+        assert torch.isfinite(out.float()).all()
+        _check_attention(out, ref, torch.bfloat16)
+
+
 BALANCED = [
     # B, H, D, (P lo, hi), N, tree, workgroups
     (3, 2, 128, (40, 300), 16, "expansion", 5),
