@@ -102,7 +102,8 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d) {
       const double stream_bytes = (double)d.B * d.H_kv * max_len * d.D * 2.0 * 2.0;
       const double partial_bytes_per_wg = 2.0 * (double)qg.heads_per_wg * d.N * (d.D + 2) * 4.0;
       cand = std::min<long>(cand, (long)(0.25 * stream_bytes / partial_bytes_per_wg));
-      wgs = cand > groups ? (int)cand : 0;
+      // every workgroup walks prefix_len[0..B) with scalar loads to find its share: only for small batches
+      wgs = (cand > groups && d.B <= 64) ? (int)cand : 0;
     }
     if (wgs > 0) {
       p.balanced_wgs = wgs;
