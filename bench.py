@@ -181,6 +181,26 @@ def main():
     achieved = attn_bytes / (attn_us * 1e-6) / 1e9
     layer_bytes = attn_bytes
 
+    # the once-per-pass steps, each timed on its own (graph replay, events): verified tree tokens per second of
+    # verification time, as the metric's per-verifier figure
+    def time_us(fn, reps=20):
+        r = make_runner(fn)
+        for _ in range(3):
+            r()
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(reps):
+            r()
+        ev1.record()
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) * 1e3 / reps
+    greedy_us = time_us(lambda: spec.spec_verify_greedy(g_logits, g_tok, par, Lmax=Lmax, status=status, out=g_out))
+    stoch_us = time_us(lambda: spec.spec_verify_stochastic(
+        s_dev["logits"], s_dev["probs_ssm"], s_dev["ssm_row"], s_dev["tree_token"], par, s_dev["u_accept"], s_dev["u_order"],
+        s_dev["u_final"], Lmax=Lmax, workspace=s_ws, status=status, out=s_out))
+    commit_us = time_us(lambda: spec.spec_kv_commit(W["k_cache"], W["v_cache"], g_out[0], g_out[1], pl, N,
+                                                    prefix_len_out=pl_out, status=status))
+
     # practical ceiling on this machine for a launch of this size: a plain read kernel, one launch per buffer,
     # over distinct buffers of the attention launch's byte count (>= 2 GB in total, far beyond the 256 MB
     # Infinity Cache), timed the same way
@@ -210,7 +230,10 @@ def main():
                                f"vocab={vcfg.V} layers/pass={L}" + (" (attention only)" if args.attn_only else ""),
                    "launch": "eager" if args.no_graph else "hip-graph replay",
                    "layer_tree_tokens_per_s": B * N / (attn_us * 1e-6),
-                   "attention_us_per_layer": attn_us, "layer_algorithmic_bytes": layer_bytes},
+                   "attention_us_per_layer": attn_us, "layer_algorithmic_bytes": layer_bytes,
+                   "greedy_verify_us": greedy_us, "greedy_verify_tree_tokens_per_s": B * N / (greedy_us * 1e-6),
+                   "stochastic_verify_us": stoch_us, "stochastic_verify_tree_tokens_per_s": B * N / (stoch_us * 1e-6),
+                   "commit_all_layers_us": commit_us},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.cfg),
