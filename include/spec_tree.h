@@ -76,7 +76,9 @@ typedef struct spec_attn_desc {
   int32_t N;              /* tree nodes per request, 1..SPEC_MAX_TREE_NODES                          */
   int32_t S_cap;          /* rows per (request, head) in the cache                                   */
   int32_t dtype;          /* spec_dtype_t of q, out, k_new, v_new and the caches                     */
-  int32_t max_prefix_len; /* upper bound of prefix_len[b], sizes grid and workspace; 0 = S_cap - N   */
+  int32_t max_prefix_len; /* upper bound of prefix_len[b], sizes grid and workspace; 0 = S_cap - N.  */
+                          /* The attention calls treat a request above it like one that does not fit */
+                          /* (SPEC_ST_CAPACITY, out = 0, not appended)                               */
   int64_t q_stride_b, q_stride_n, q_stride_h;       /* q, out: [B,N,H,D], in elements                */
   int64_t kv_stride_b, kv_stride_h, kv_stride_s;    /* caches: [B,H_kv,S_cap,D]                      */
   int64_t new_stride_b, new_stride_n, new_stride_h; /* k_new, v_new: [B,N,H_kv,D]; all 0 = the q     */

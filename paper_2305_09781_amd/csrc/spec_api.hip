@@ -219,22 +219,27 @@ static int tree_attention_impl(const spec_attn_desc_t* desc, const void* q, cons
     if (workspace == nullptr || workspace_bytes < plan.ws_bytes) return SPEC_ERR_WORKSPACE;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return SPEC_ERR_INVALID_ARG;
   }
+  // The launch plan covers keys up to max_prefix_len + N. A request whose prefix_len exceeds the stated
+  // maximum must not be attended over a truncated key range: the kernels treat the stated maximum as the
+  // capacity, so such a request is flagged SPEC_ST_CAPACITY like one that does not fit the cache.
+  spec_attn_desc_t d = *desc;
+  if (d.max_prefix_len > 0) d.S_cap = d.max_prefix_len + d.N;   // <= S_cap (checked above); strides are unchanged
   hipStream_t s = (hipStream_t)hip_stream;
   hipError_t e;
-  if (desc->dtype == SPEC_BF16) {
-    e = launch_tree_attention_bf16(*desc, plan, q, k_cache, v_cache, k_new, v_new, tree_parent, tree_depth, prefix_len,
-                                   out, workspace, status, s);
+  if (d.dtype == SPEC_BF16) {
+    e = launch_tree_attention_bf16(d, plan, q, k_cache, v_cache, k_new, v_new, tree_parent, tree_depth, prefix_len, out,
+                                   workspace, status, s);
   } else {
     if (append) {
-      e = launch_kv_append(*desc, k_new, v_new, k_cache, v_cache, prefix_len, status, s);
+      e = launch_kv_append(d, k_new, v_new, k_cache, v_cache, prefix_len, status, s);
       if (e != hipSuccess) return SPEC_ERR_HIP;
     }
-    e = launch_tree_attention_f32(*desc, plan, (const float*)q, (const float*)k_cache, (const float*)v_cache, tree_parent,
+    e = launch_tree_attention_f32(d, plan, (const float*)q, (const float*)k_cache, (const float*)v_cache, tree_parent,
                                   tree_depth, prefix_len, (float*)out, workspace, status, s);
   }
   if (e != hipSuccess) return SPEC_ERR_HIP;
   if (plan.n_splits > 1 || plan.balanced_wgs > 0) {
-    e = launch_attn_combine(*desc, plan, tree_parent, tree_depth, prefix_len, workspace, out, status, s);
+    e = launch_attn_combine(d, plan, tree_parent, tree_depth, prefix_len, workspace, out, status, s);
     if (e != hipSuccess) return SPEC_ERR_HIP;
   }
   return SPEC_OK;

@@ -323,6 +323,29 @@ def test_peaked_and_flat_score_distributions(spec, N, scale):
         _check_attention(out, ref, torch.bfloat16)
 
 
+@pytest.mark.parametrize("N,dtype", [(16, "bf16"), (40, "bf16"), (8, "f32")])
+def test_prefix_above_the_stated_maximum_is_flagged_not_truncated(spec, N, dtype):
+    """max_prefix_len sizes the launch; a request whose prefix_len exceeds it must not be attended over a
+    truncated key range: flagged SPEC_ST_CAPACITY, zeros, not appended; the others unaffected."""
+    cfg = wl.Config(88, "hint", dtype, B=3, H=2, D=64, P=(50, 100), N=N, tree="random_parent")
+    inp = wl.make_attention_inputs(cfg, seed=13, S_cap=400 + N)
+    inp["prefix_len"][1] = 300                                    # fits the cache, exceeds the stated maximum
+    for chunk, wgs in ((0, 0), (64, 0), (0, 4)):
+        if dtype == "f32" and wgs:
+            continue
+        kc, vc = _dev(inp["k_cache"][0]), _dev(inp["v_cache"][0])
+        status = torch.zeros(3, dtype=torch.int32, device=DEV)
+        with _chunk_keys(chunk), _balanced_wgs(wgs):
+            out = spec.spec_tree_attention_append(_dev(inp["q"][0]), _dev(inp["k_new"][0]), _dev(inp["v_new"][0]), kc, vc,
+                                                  _dev(inp["tree_parent"]), _dev(inp["tree_depth"]), _dev(inp["prefix_len"]),
+                                                  status=status, max_prefix_len=100)
+        torch.cuda.synchronize()
+        assert status.cpu().tolist() == [0, orc.ST_CAPACITY, 0]
+        assert (out[1].float() == 0).all() and np.array_equal(_bits(kc[1]), _bits(inp["k_cache"][0][1]))
+        ref, _, _ = _oracle_append_attention(inp, bsel=[0, 2])
+        _check_attention(out[[0, 2]], ref, cfg.torch_dtype)
+
+
 BALANCED = [
     # B, H, D, (P lo, hi), N, tree, workgroups
     (3, 2, 128, (40, 300), 16, "expansion", 5),
