@@ -697,6 +697,78 @@ def test_end_to_end_iteration_config5_two_layers(spec):
             assert np.array_equal(vcs[l][b, :, :n].double().cpu().numpy(), vco[b, :, :n])
 
 
+def test_decoding_loop_in_one_graph_with_lengths_advancing_on_the_device(spec):
+    """Algorithm 2's loop: every iteration appends and attends a tree behind the current prefix, verifies it
+    and commits the accepted path; prefix lengths live on the device only. Two iterations (ping-pong length
+    buffers) are captured in one HIP graph and replayed; caches, lengths and the last iteration's attention
+    outputs must equal the oracle's simulation of the same four iterations."""
+    K, L = 4, 2
+    cfg = wl.Config(87, "loop", "bf16", B=3, H=2, D=64, P=(10, 40), N=16, tree="expansion", widths=wl.EXPANSION_EVAL, V=64)
+    cap = 40 + K * cfg.N + cfg.N
+    inp = wl.make_attention_inputs(cfg, seed=23, n_layers=L, S_cap=cap)
+    ver = wl.make_verify_inputs(cfg, seed=23, mode="greedy", parent=inp["tree_parent"].numpy())
+    par, dep = _dev(inp["tree_parent"]), _dev(inp["tree_depth"])
+    q, kn, vn = [_dev(x) for x in inp["q"]], [_dev(x) for x in inp["k_new"]], [_dev(x) for x in inp["v_new"]]
+    kcs, vcs = [_dev(x) for x in inp["k_cache"]], [_dev(x) for x in inp["v_cache"]]
+    outs = [torch.empty_like(x) for x in q]
+    logits, tok = _dev(ver["logits"]), _dev(ver["tree_token"])
+    pl = [_dev(inp["prefix_len"]), torch.zeros(cfg.B, dtype=torch.int32, device=DEV)]
+    status = torch.zeros(cfg.B, dtype=torch.int32, device=DEV)
+    desc = spec.make_desc(q[0], kcs[0], max_prefix_len=cap - cfg.N)
+    ws = torch.empty(max(spec.spec_tree_attention_workspace_bytes(desc), 256), dtype=torch.uint8, device=DEV)
+    vout = (torch.empty((cfg.B, cfg.N), dtype=torch.int32, device=DEV), torch.empty(cfg.B, dtype=torch.int32, device=DEV),
+            torch.empty((cfg.B, cfg.N), dtype=torch.int32, device=DEV), torch.empty((cfg.B, cfg.N), dtype=torch.int32, device=DEV))
+
+    def iteration(src, dst):
+        for l in range(L):
+            spec.spec_tree_attention_append(q[l], kn[l], vn[l], kcs[l], vcs[l], par, dep, pl[src], out=outs[l], workspace=ws,
+                                            status=status, desc=desc)
+        spec.spec_verify_greedy(logits, tok, par, status=status, out=vout)
+        spec.spec_kv_commit(kcs, vcs, vout[0], vout[1], pl[src], cfg.N, prefix_len_out=pl[dst], status=status)
+
+    # warm-up outside capture on copies of the state, then restore it
+    saved = [x.clone() for x in kcs + vcs], pl[0].clone()
+    iteration(0, 1)
+    torch.cuda.synchronize()
+    for dst_t, src_t in zip(kcs + vcs, saved[0]):
+        dst_t.copy_(src_t)
+    pl[0].copy_(saved[1])
+    status.zero_()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        iteration(0, 1)
+        iteration(1, 0)
+    for dst_t, src_t in zip(kcs + vcs, saved[0]):      # capture does not execute, but keep the state explicit
+        dst_t.copy_(src_t)
+    pl[0].copy_(saved[1])
+    for _ in range(K // 2):
+        graph.replay()
+    torch.cuda.synchronize()
+    assert (status.cpu().numpy() == 0).all()
+
+    # oracle: the same K iterations
+    f64 = lambda t: t.double().numpy()
+    kco, vco = [f64(x) for x in inp["k_cache"]], [f64(x) for x in inp["v_cache"]]
+    plen = inp["prefix_len"].numpy().copy()
+    rp, rl, rt, _ = orc.verify_greedy(ver["logits"].numpy(), ver["tree_token"].numpy(), inp["tree_parent"].numpy())
+    assert rl.max() > 1                                  # something is accepted, so prefixes advance unevenly
+    refs = None
+    for it in range(K):
+        refs = []
+        for l in range(L):
+            assert (orc.kv_append(kco[l], vco[l], f64(inp["k_new"][l]), f64(inp["v_new"][l]), plen) == 0).all()
+            refs.append(orc.tree_attention(f64(inp["q"][l]), kco[l], vco[l], inp["tree_parent"].numpy(), plen))
+        plen, st = orc.kv_commit(kco, vco, rp, rl, plen, N=cfg.N)
+        assert (st == 0).all()
+    assert np.array_equal(pl[0].cpu().numpy(), plen)
+    assert np.array_equal(vout[0].cpu().numpy(), rp) and np.array_equal(vout[2].cpu().numpy(), rt)
+    for l in range(L):
+        _check_attention(outs[l], refs[l], torch.bfloat16)
+        for b in range(cfg.B):
+            assert np.array_equal(kcs[l][b, :, :plen[b]].double().cpu().numpy(), kco[l][b, :, :plen[b]])
+            assert np.array_equal(vcs[l][b, :, :plen[b]].double().cpu().numpy(), vco[l][b, :, :plen[b]])
+
+
 def test_hip_graph_replays_match_eager(spec):
     """The benchmark replays a captured pass; every replay must reproduce the eager results, with
     eager launches and synchronisations in between."""
