@@ -99,3 +99,32 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libspectree.so")
     with pytest.raises(RuntimeError, match="not found"):
         binding.load()
+
+
+def test_header_is_plain_c_and_links_from_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 with warnings as errors, and a C program that
+    includes it links against the library and calls entry points that need no GPU."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "abi.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <string.h>\n#include "spec_tree.h"\n'
+        "int main(void) {\n"
+        "  spec_attn_desc_t d; memset(&d, 0, sizeof d);\n"
+        "  if (spec_version() < 100) return 1;\n"
+        "  if (spec_kv_append(&d, 0, 0, 0, 0, 0, 0, 0) != SPEC_ERR_INVALID_ARG) return 2;\n"
+        "  if (spec_tree_attention_workspace_bytes(&d) != 0) return 3;\n"
+        '  if (strstr(spec_strerror(SPEC_ERR_WORKSPACE), "workspace") == 0) return 4;\n'
+        '  printf("ok %d\\n", (int)sizeof(spec_attn_desc_t));\n  return 0;\n}\n')
+    lib_dir = os.path.dirname(binding.lib_path())
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                    "-fsyntax-only", str(src)], check=True)
+    exe = tmp_path / "abi"
+    subprocess.run([gcc, "-std=c99", "-I", os.path.join(root, "include"), str(src), "-o", str(exe), "-L", lib_dir,
+                    "-lspectree", "-Wl,-rpath," + lib_dir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    assert out.startswith("ok ") and int(out.split()[1]) == ctypes.sizeof(binding.AttnDesc)
