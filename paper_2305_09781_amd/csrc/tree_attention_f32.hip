@@ -178,8 +178,28 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const float* __restri
                                                            int32_t* status, int B, int N, int H, int H_kv, int n_qg,
                                                            int hpw, int D, int S_cap, int chunk_keys, int slots,
                                                            int bal_wgs, int bal_tile, long q_sb, long q_sn, long q_sh) {
+  constexpr int CH = 4;   // partial slots fetched together
   __shared__ int s_flag;
   const int h = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
+  const int CG = D / 4;
+  const int idx = blockIdx.z * 256 + t;
+  const bool active = idx < N * CG;
+  const int n = active ? idx / CG : 0, cg = active ? idx % CG : 0;
+  const long base = (((long)b * H + h) * slots) * N + n;
+  // The first slots are fetched before anything is known about the request (every slot exists in the
+  // workspace, whatever it holds), so that the reads overlap the tree check and the slot count below.
+  float m_s[CH], l_s[CH];
+  float4 o_s[CH];
+  auto fetch = [&](int s0) {
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      const long row = base + (long)min(s0 + j, slots - 1) * N;
+      m_s[j] = ws_ml[row * 2];
+      l_s[j] = ws_ml[row * 2 + 1];
+      o_s[j] = *(const float4*)(ws_o + row * D + cg * 4);
+    }
+  };
+  fetch(0);
   const int P = prefix_len[b];
   const bool cap_ok = (P >= 0) && (P <= S_cap - N);
   const bool valid = tree_is_valid(parent + (long)b * N, depth + (long)b * N, N, &s_flag) && cap_ok;
@@ -201,23 +221,28 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const float* __restri
       ns = min(slots, (P + N + chunk_keys - 1) / chunk_keys);
     }
   }
-  const int CG = D / 4;
-  const int idx = blockIdx.z * 256 + t;
-  if (idx >= N * CG) return;
-  const int n = idx / CG, cg = idx % CG;
-  const long base = (((long)b * H + h) * slots) * N + n;
-  float M = -INFINITY;
-#pragma unroll 4
-  for (int s = 0; s < ns; ++s) M = fmaxf(M, ws_ml[(base + (long)s * N) * 2]);
+  if (!active) return;
+  // online merge over chunks of CH slots (slots at and beyond ns hold nothing meaningful: skipped)
+  float M = -INFINITY, l = 0.f;
   float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-  float l = 0.f;
-#pragma unroll 4
-  for (int s = 0; s < ns; ++s) {
-    const float m = ws_ml[(base + (long)s * N) * 2];
-    const float w = (m == -INFINITY) ? 0.f : exp2f(m - M);   // an all-masked partial carries nothing
-    l = fmaf(ws_ml[(base + (long)s * N) * 2 + 1], w, l);
-    const float4 p = *(const float4*)(ws_o + (base + (long)s * N) * D + cg * 4);
-    o.x = fmaf(p.x, w, o.x); o.y = fmaf(p.y, w, o.y); o.z = fmaf(p.z, w, o.z); o.w = fmaf(p.w, w, o.w);
+  for (int s0 = 0; s0 < ns || s0 == 0; s0 += CH) {
+    if (s0 > 0) fetch(s0);
+    float Mc = M;
+#pragma unroll
+    for (int j = 0; j < CH; ++j)
+      if (s0 + j < ns) Mc = fmaxf(Mc, m_s[j]);
+    const float keep = (M == -INFINITY) ? 0.f : exp2f(M - Mc);   // Mc = -inf only while nothing carried mass
+    l *= keep;
+    o.x *= keep; o.y *= keep; o.z *= keep; o.w *= keep;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      if (s0 + j < ns && m_s[j] != -INFINITY) {   // an all-masked partial carries nothing
+        const float w = exp2f(m_s[j] - Mc);
+        l = fmaf(l_s[j], w, l);
+        o.x = fmaf(o_s[j].x, w, o.x); o.y = fmaf(o_s[j].y, w, o.y); o.z = fmaf(o_s[j].z, w, o.z); o.w = fmaf(o_s[j].w, w, o.w);
+      }
+    }
+    M = Mc;
   }
   const float inv = (l > 0.f) ? 1.f / l : 0.f;
   o.x *= inv; o.y *= inv; o.z *= inv; o.w *= inv;
