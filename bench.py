@@ -220,6 +220,7 @@ def main():
     read_stream_gbs = 3 * n_probe * (attn_bytes // 16 * 16) / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
     del probes
 
+    dense_flops = 4.0 * H * D * N * float(W["host"]["prefix_len"].double().add(N).sum())
     result = {
         "metric": "verified tree tokens/sec (whole verification pass: L layers of KV append + tree attention, "
                   "greedy + stochastic verification, KV commit) + achieved HBM GB/s",
@@ -241,7 +242,11 @@ def main():
                                + " (KV append fused; + attn_combine_kernel when the key range is split)",
                      "bytes_per_launch": attn_bytes,
                      "us_per_launch": attn_us,
-                     "measured_read_stream_gbs": read_stream_gbs, "frac_of_measured_read_stream": achieved / read_stream_gbs},
+                     "measured_read_stream_gbs": read_stream_gbs, "frac_of_measured_read_stream": achieved / read_stream_gbs,
+                     # the two products as dense contractions over all N x (prefix + N) pairs, against the bf16
+                     # MFMA peak: what the matrix cores would be charged with if this were the bound (it is not)
+                     "dense_equivalent_tflops": dense_flops / (attn_us * 1e-6) / 1e12,
+                     "frac_of_bf16_mfma_peak": dense_flops / (attn_us * 1e-6) / 2.5e15},
     }
 
     if args.pmc_calibration:

@@ -8,6 +8,7 @@
  *   before the pass: spec_tree_expand_topk (per speculation step) | spec_tree_merge   (build the token tree)
  *   for each layer:  spec_kv_append  ->  spec_tree_attention      (or the fused spec_tree_attention_append)
  *   once per pass:   spec_verify_greedy | spec_verify_stochastic | spec_verify_naive  ->  spec_kv_commit (all layers)
+ *   every cache-touching call also exists as *_paged, for caches kept as pools of blocks behind a block table
  *
  * Conventions common to every call
  *   - Every data pointer is a DEVICE pointer unless its comment says "host". The caller owns all
@@ -62,6 +63,8 @@ extern "C" {
 #define SPEC_ST_CAPACITY 2      /* prefix_len[b] < 0 or prefix_len[b] + N > S_cap                    */
 #define SPEC_ST_BAD_PATH 4      /* accepted path: len out of range, path[0] != 0, not increasing     */
 #define SPEC_ST_ZERO_RESIDUAL 8 /* stochastic verify: residual distribution had no mass left         */
+#define SPEC_ST_BAD_BLOCK 16    /* paged cache: a block-table entry the request uses is not in       */
+                                /* [0, n_blocks)                                                     */
 
 typedef enum { SPEC_F32 = 0, SPEC_BF16 = 1 } spec_dtype_t;
 
@@ -253,7 +256,52 @@ int spec_kv_commit(const spec_attn_desc_t* desc, int32_t n_layers, void* const* 
                    int32_t Lmax, const int32_t* accepted_len /*[B]*/, const int32_t* prefix_len /*[B]*/,
                    int32_t* prefix_len_out /*[B]*/, int32_t* status, void* hip_stream);
 
-/* Text for a SPEC_ERR_* code (static storage). Library version as major*10000 + minor*100 + patch. */
+/*
+ * Paged KV caches (beyond the paper, whose cache is one contiguous region per request; the steps are
+ * those of Section 4.2 and Algorithm 2 unchanged, only the place of a cache row differs). Each cache is
+ * a pool of n_blocks blocks of block_tokens rows, [n_blocks, H_kv, block_tokens, D]: in the descriptor
+ * kv_stride_b is the stride between BLOCKS, kv_stride_h / kv_stride_s those inside a block, and S_cap the
+ * logical capacity of a request in rows (S_cap <= max_blocks * block_tokens). Logical row s of request b
+ * is row s % block_tokens of block block_table[b, s / block_tokens]; every call below is its contiguous
+ * namesake with that one substitution. Requests may share blocks they only read (a common prefix);
+ * rows a call writes (appended rows, committed rows) must lie in blocks no other request of the call
+ * uses. A table entry outside [0, n_blocks) among the blocks a request uses sets SPEC_ST_BAD_BLOCK:
+ * rows of such a block are never written, reads are redirected to a block inside the pool, and the
+ * request's outputs are unspecified; no memory outside the caches is touched. Entries of blocks a
+ * request does not reach (beyond prefix_len[b] + N rows) may hold any value. bf16 attention reads one
+ * table entry per key tile; next to the contiguous calls this costs about 5 % on short prefixes and
+ * nothing measurable on long ones.
+ */
+typedef struct spec_kv_pages {
+  const int32_t* block_table; /* DEVICE, [B, max_blocks]: physical block of each logical block        */
+  int32_t max_blocks;         /* row length of block_table                                            */
+  int32_t block_tokens;       /* rows per block: a power of two, 64 .. 65536                          */
+  int32_t n_blocks;           /* blocks in each cache                                                 */
+} spec_kv_pages_t;
+
+int spec_kv_append_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, const void* k_new,
+                         const void* v_new, void* k_cache, void* v_cache, const int32_t* prefix_len,
+                         int32_t* status, void* hip_stream);
+int spec_kv_append_rope_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, const void* k_new,
+                              const void* v_new, void* k_cache, void* v_cache, const int32_t* tree_depth,
+                              const int32_t* prefix_len, const float* rope_cos, const float* rope_sin,
+                              int32_t rope_len, int32_t* status, void* hip_stream);
+int spec_tree_attention_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, const void* q,
+                              const void* k_cache, const void* v_cache, const int32_t* tree_parent,
+                              const int32_t* tree_depth, const int32_t* prefix_len, void* out, void* workspace,
+                              size_t workspace_bytes, int32_t* status, void* hip_stream);
+int spec_tree_attention_append_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, const void* q,
+                                     const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                                     const int32_t* tree_parent, const int32_t* tree_depth,
+                                     const int32_t* prefix_len, void* out, void* workspace, size_t workspace_bytes,
+                                     int32_t* status, void* hip_stream);
+/* workspace of the two paged attention calls (the launch plan of a paged call may differ) */
+size_t spec_tree_attention_paged_workspace_bytes(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages);
+int spec_kv_commit_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, int32_t n_layers,
+                         void* const* k_caches /*host*/, void* const* v_caches /*host*/,
+                         const int32_t* accepted_path, int32_t Lmax, const int32_t* accepted_len,
+                         const int32_t* prefix_len, int32_t* prefix_len_out, int32_t* status, void* hip_stream);
+
 /*
  * Measurement aid (no passage of the paper): reads `bytes` (a multiple of 16 is used) from buf once with
  * plain 16-byte loads and writes nothing (sink: 16 device bytes that are never written in practice). Timed
@@ -261,6 +309,8 @@ int spec_kv_commit(const spec_attn_desc_t* desc, int32_t n_layers, void* const* 
  * the practical ceiling next to the published HBM peak.
  */
 int spec_probe_read_stream(const void* buf, size_t bytes, void* sink, void* hip_stream);
+
+/* Text for a SPEC_ERR_* code (static storage). Library version as major*10000 + minor*100 + patch. */
 
 const char* spec_strerror(int code);
 int spec_version(void);

@@ -19,6 +19,10 @@ What each function follows:
   expand_topk, tree_merge     Section 3: one step of expansion-based construction; Definition 3.2
   kv_commit              Algorithm 2 main loop (verified tokens are appended to the sequence), so the
                          K/V rows of the accepted path must become the contiguous prefix
+  paged_rows, paged_gather, kv_append_paged, tree_attention_paged, kv_commit_paged
+                         the same steps on a cache kept as a pool of blocks behind a block table (a
+                         storage layout next to the path, not in the paper): logical row s of request b
+                         is row s % block_tokens of block table[b, s // block_tokens], nothing else changes
 
 Parity pins (tests/test_oracle_*.py): per-path brute-force causal attention, chain/star/N=1 special
 cases against a library routine, constant-V and non-interference invariants (attention); exhaustive
@@ -27,8 +31,9 @@ against a closed-form law, Theorem 4.2 and 4.3 in closed form, chi-square over m
 (stochastic); brute-force inverse CDF, the exact first-step law, the closed-form rejection probability of
 Theorem 4.3 and the low-temperature limit against the greedy verifier (naive sampling); round trips and
 overlapping-path cases (append / commit); sequence-set equality by brute force, idempotence, chains
-merging into a trie (tree merge); scalar selection loop and the argmax special case (top-k). No function
-is unpinned.
+merging into a trie (tree merge); scalar selection loop and the argmax special case (top-k); identity
+tables against the contiguous functions, invariance under a relabelling of the blocks, shared prefix blocks
+and a hand-derived two-block case (paged caches). No function is unpinned.
 
 Readings taken where the paper is silent are listed next to each function.
 """
@@ -41,6 +46,7 @@ ST_BAD_TREE = 1        # parent[0] != -1, or parent[i] not in [0, i), or depth[i
 ST_CAPACITY = 2        # prefix_len + N > S_cap, or prefix_len < 0
 ST_BAD_PATH = 4        # accepted path: len out of range, path[0] != 0, not strictly increasing, or out of range
 ST_ZERO_RESIDUAL = 8   # residual distribution had no mass left (kept previous distribution)
+ST_BAD_BLOCK = 16      # paged cache: a block-table entry the request uses lies outside the pool
 
 
 # ---------------------------------------------------------------------------------------------
@@ -484,5 +490,95 @@ def kv_commit(k_caches, v_caches, accepted_path, accepted_len, prefix_len, N=Non
             for k in range(n):           # increasing k is safe: destination row <= source row
                 kc[b, :, p + k, :] = kc[b, :, p + pb[k], :]
                 vc[b, :, p + k, :] = vc[b, :, p + pb[k], :]
+        out_len[b] = p + n
+    return out_len, status
+
+
+# ---------------------------------------------------------------------------------------------
+# Paged caches: the same steps on a pool of blocks behind a block table
+# ---------------------------------------------------------------------------------------------
+
+def paged_rows(block_table, block_tokens, n_blocks, b, rows):
+    """(block, row inside the block, entry inside the pool?) of every logical row in `rows` of request b."""
+    out = []
+    for s in rows:
+        e = int(block_table[b, s // block_tokens])
+        out.append((e, s % block_tokens, 0 <= e < n_blocks))
+    return out
+
+
+def paged_gather(pool, block_table, block_tokens, n_rows):
+    """The logical caches [B,H,max(n_rows),D] a pool [n_blocks,H,block_tokens,D] stands for: rows
+    0..n_rows[b]-1 of request b (the rest zero). Every entry used must lie inside the pool."""
+    B = block_table.shape[0]
+    n_blocks, H, _, D = pool.shape
+    out = np.zeros((B, H, int(max(n_rows)), D), dtype=pool.dtype)
+    for b in range(B):
+        for s, (e, r, ok) in enumerate(paged_rows(block_table, block_tokens, n_blocks, b, range(int(n_rows[b])))):
+            assert ok, "paged_gather: block-table entry outside the pool"
+            out[b, :, s, :] = pool[e, :, r, :]
+    return out
+
+
+def kv_append_paged(k_pool, v_pool, block_table, block_tokens, S_cap, k_new, v_new, prefix_len):
+    """kv_append on paged caches: logical row prefix_len[b] + i of request b receives new[b, i]. In place.
+    A request that does not fit its logical capacity S_cap is skipped (ST_CAPACITY); a row whose block
+    lies outside the pool is not written and the request is flagged ST_BAD_BLOCK."""
+    B, N = k_new.shape[0], k_new.shape[1]
+    status = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        p = int(prefix_len[b])
+        if p < 0 or p + N > S_cap:
+            status[b] |= ST_CAPACITY
+            continue
+        for i, (e, r, ok) in enumerate(paged_rows(block_table, block_tokens, k_pool.shape[0], b, range(p, p + N))):
+            if not ok:
+                status[b] |= ST_BAD_BLOCK
+                continue
+            k_pool[e, :, r, :] = k_new[b, i, :, :]
+            v_pool[e, :, r, :] = v_new[b, i, :, :]
+    return status
+
+
+def tree_attention_paged(q, k_pool, v_pool, block_table, block_tokens, tree_parent, prefix_len, softmax_scale=None):
+    """tree_attention over the logical caches the pools stand for (every request must fit and use blocks
+    inside the pool: the failure cases are those of the contiguous function plus ST_BAD_BLOCK, whose output
+    is unspecified)."""
+    N = q.shape[1]
+    n_rows = [int(p) + N for p in prefix_len]
+    k = paged_gather(k_pool, block_table, block_tokens, n_rows)
+    v = paged_gather(v_pool, block_table, block_tokens, n_rows)
+    return tree_attention(q, k, v, tree_parent, prefix_len, softmax_scale)
+
+
+def kv_commit_paged(k_pools, v_pools, block_table, block_tokens, S_cap, accepted_path, accepted_len, prefix_len, N):
+    """kv_commit on paged caches: logical row prefix_len + k <- logical row prefix_len + path[k]. In place.
+    Returns (prefix_len_out, status). A request with a block of its tree rows [prefix_len, prefix_len + N)
+    outside the pool is left untouched and flagged ST_BAD_BLOCK."""
+    B = len(prefix_len)
+    out_len = np.array(prefix_len, dtype=np.int32).copy()
+    status = np.zeros(B, dtype=np.int32)
+    n_blocks = k_pools[0].shape[0]
+    for b in range(B):
+        p = int(prefix_len[b])
+        n = int(accepted_len[b])
+        pb = [int(x) for x in accepted_path[b][:max(n, 0)]]
+        if p < 0 or p + N > S_cap:
+            status[b] |= ST_CAPACITY
+            continue
+        ok = 1 <= n <= len(accepted_path[b]) and n <= N and pb[0] == 0 and \
+            all(pb[k] > pb[k - 1] for k in range(1, n)) and pb[-1] < N
+        if not ok:
+            status[b] |= ST_BAD_PATH
+            continue
+        where = paged_rows(block_table, block_tokens, n_blocks, b, range(p, p + N))
+        if not all(w[2] for w in where):
+            status[b] |= ST_BAD_BLOCK
+            continue
+        for kc, vc in zip(k_pools, v_pools):
+            for k in range(n):           # increasing k is safe: destination row <= source row
+                (ed, rd, _), (es, rs, _) = where[k], where[pb[k]]
+                kc[ed, :, rd, :] = kc[es, :, rs, :]
+                vc[ed, :, rd, :] = vc[es, :, rs, :]
         out_len[b] = p + n
     return out_len, status

@@ -17,7 +17,7 @@ _lib = None
 
 SPEC_F32, SPEC_BF16 = 0, 1
 SPEC_MAX_TREE_NODES = 128
-ST_BAD_TREE, ST_CAPACITY, ST_BAD_PATH, ST_ZERO_RESIDUAL = 1, 2, 4, 8
+ST_BAD_TREE, ST_CAPACITY, ST_BAD_PATH, ST_ZERO_RESIDUAL, ST_BAD_BLOCK = 1, 2, 4, 8, 16
 ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_CAPACITY, ERR_HIP, ERR_WORKSPACE = -1, -2, -3, -4, -5
 
 EXPORTED = [
@@ -26,6 +26,8 @@ EXPORTED = [
     "spec_verify_stochastic", "spec_verify_stochastic_workspace_bytes", "spec_verify_naive",
     "spec_verify_naive_workspace_bytes", "spec_tree_expand_topk", "spec_tree_merge", "spec_kv_commit", "spec_probe_read_stream", "spec_strerror",
     "spec_version",
+    "spec_kv_append_paged", "spec_kv_append_rope_paged", "spec_tree_attention_paged", "spec_tree_attention_append_paged",
+    "spec_tree_attention_paged_workspace_bytes", "spec_kv_commit_paged",
 ]
 
 
@@ -46,6 +48,11 @@ class AttnDesc(ctypes.Structure):
         ("new_stride_b", ctypes.c_int64), ("new_stride_n", ctypes.c_int64), ("new_stride_h", ctypes.c_int64),
         ("softmax_scale", ctypes.c_float), ("reserved", ctypes.c_int32),
     ]
+
+
+class KvPages(ctypes.Structure):
+    _fields_ = [("block_table", ctypes.c_void_p), ("max_blocks", ctypes.c_int32), ("block_tokens", ctypes.c_int32),
+                ("n_blocks", ctypes.c_int32)]
 
 
 def lib_path() -> str:
@@ -90,6 +97,19 @@ def load():
     lib.spec_tree_merge.restype = ctypes.c_int
     lib.spec_kv_commit.argtypes = [dp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i32, vp, vp, vp, vp, vp]
     lib.spec_kv_commit.restype = ctypes.c_int
+    pp = ctypes.POINTER(KvPages)
+    lib.spec_kv_append_paged.argtypes = [dp, pp, vp, vp, vp, vp, vp, vp, vp]
+    lib.spec_kv_append_paged.restype = ctypes.c_int
+    lib.spec_kv_append_rope_paged.argtypes = [dp, pp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
+    lib.spec_kv_append_rope_paged.restype = ctypes.c_int
+    lib.spec_tree_attention_paged.argtypes = [dp, pp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
+    lib.spec_tree_attention_paged.restype = ctypes.c_int
+    lib.spec_tree_attention_append_paged.argtypes = [dp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
+    lib.spec_tree_attention_append_paged.restype = ctypes.c_int
+    lib.spec_tree_attention_paged_workspace_bytes.argtypes = [dp, pp]
+    lib.spec_tree_attention_paged_workspace_bytes.restype = sz
+    lib.spec_kv_commit_paged.argtypes = [dp, pp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i32, vp, vp, vp, vp, vp]
+    lib.spec_kv_commit_paged.restype = ctypes.c_int
     lib.spec_probe_read_stream.argtypes = [vp, sz, vp, vp]
     lib.spec_probe_read_stream.restype = ctypes.c_int
     lib.spec_strerror.argtypes = [ctypes.c_int]
@@ -334,6 +354,119 @@ def spec_kv_commit(k_caches: Sequence[torch.Tensor], v_caches: Sequence[torch.Te
     _check(load().spec_kv_commit(ctypes.byref(d), L, ks, vs, _ptr(accepted_path), accepted_path.shape[1],
                                  _ptr(accepted_len), _ptr(prefix_len), _ptr(prefix_len_out), _ptr(status),
                                  _stream(stream)), "spec_kv_commit")
+    return prefix_len_out
+
+
+# ------------------------------------------------------------------------------------------------
+# paged caches: pools [n_blocks, H_kv, block_tokens, D] behind a block table [B, max_blocks]
+# ------------------------------------------------------------------------------------------------
+
+def make_paged_desc(q_like: torch.Tensor, k_pool: torch.Tensor, block_table: torch.Tensor, max_prefix_len: int = 0,
+                    softmax_scale: float = 0.0, k_new: Optional[torch.Tensor] = None) -> Tuple[AttnDesc, KvPages]:
+    """Descriptor and page description from a [B,N,H,D] tensor, a pool and the int32 block table (device).
+    The logical capacity of a request is max_blocks * block_tokens rows."""
+    B, N, H, D = q_like.shape
+    n_blocks, Hkv, bt, Dc = k_pool.shape
+    if Dc != D or q_like.stride(3) != 1 or k_pool.stride(3) != 1:
+        raise ValueError("q must be [B,N,H,D], pool [n_blocks,H_kv,block_tokens,D], D contiguous")
+    if block_table.dtype != torch.int32 or block_table.dim() != 2 or block_table.shape[0] != B or \
+            not block_table.is_contiguous():
+        raise ValueError("block_table must be contiguous int32 [B, max_blocks]")
+    new = (0, 0, 0)
+    if k_new is not None:
+        if tuple(k_new.shape) != (B, N, Hkv, D) or k_new.stride(3) != 1:
+            raise ValueError("k_new / v_new must be [B,N,H_kv,D], D contiguous")
+        new = (k_new.stride(0), k_new.stride(1), k_new.stride(2))
+    max_blocks = block_table.shape[1]
+    d = AttnDesc(B, H, Hkv, D, N, max_blocks * bt, _dtype_code(q_like.dtype), int(max_prefix_len),
+                 q_like.stride(0), q_like.stride(1), q_like.stride(2),
+                 k_pool.stride(0), k_pool.stride(1), k_pool.stride(2), new[0], new[1], new[2], float(softmax_scale), 0)
+    return d, KvPages(block_table.data_ptr(), max_blocks, bt, n_blocks)
+
+
+def spec_tree_attention_paged_workspace_bytes(desc: AttnDesc, pages: KvPages) -> int:
+    return int(load().spec_tree_attention_paged_workspace_bytes(ctypes.byref(desc), ctypes.byref(pages)))
+
+
+def spec_kv_append_paged(k_new, v_new, k_pool, v_pool, block_table, prefix_len, status=None, stream=None):
+    _same_layout(k_new, v_new, "k_new and v_new")
+    _same_layout(k_pool, v_pool, "k_pool and v_pool")
+    d, pg = make_paged_desc(k_new, k_pool, block_table, k_new=k_new if k_new.shape[2] == k_pool.shape[1] else None)
+    _check(load().spec_kv_append_paged(ctypes.byref(d), ctypes.byref(pg), _ptr(k_new), _ptr(v_new), _ptr(k_pool),
+                                       _ptr(v_pool), _ptr(prefix_len), _ptr(status), _stream(stream)),
+           "spec_kv_append_paged")
+
+
+def spec_kv_append_rope_paged(k_new, v_new, k_pool, v_pool, block_table, tree_depth, prefix_len, rope_cos, rope_sin,
+                              status=None, stream=None):
+    _same_layout(k_new, v_new, "k_new and v_new")
+    _same_layout(k_pool, v_pool, "k_pool and v_pool")
+    D = k_new.shape[-1]
+    for tab in (rope_cos, rope_sin):
+        if tab.dtype != torch.float32 or tab.dim() != 2 or tab.shape[1] != D // 2 or not tab.is_contiguous():
+            raise ValueError("rope tables must be contiguous float32 [rope_len, D/2]")
+    d, pg = make_paged_desc(k_new, k_pool, block_table, k_new=k_new)
+    _check(load().spec_kv_append_rope_paged(ctypes.byref(d), ctypes.byref(pg), _ptr(k_new), _ptr(v_new), _ptr(k_pool),
+                                            _ptr(v_pool), _ptr(tree_depth), _ptr(prefix_len), _ptr(rope_cos),
+                                            _ptr(rope_sin), rope_cos.shape[0], _ptr(status), _stream(stream)),
+           "spec_kv_append_rope_paged")
+
+
+def spec_tree_attention_paged(q, k_pool, v_pool, block_table, tree_parent, tree_depth, prefix_len, out=None,
+                              workspace=None, status=None, max_prefix_len: int = 0, softmax_scale: float = 0.0,
+                              stream=None, k_new=None, v_new=None):
+    """Tree attention over paged caches; with k_new / v_new the KV append of the tree rows is fused in."""
+    _same_layout(k_pool, v_pool, "k_pool and v_pool")
+    if out is None:
+        out = torch.empty_like(q)
+    _same_layout(q, out, "q and out")
+    d, pg = make_paged_desc(q, k_pool, block_table, max_prefix_len, softmax_scale, k_new=k_new)
+    need = spec_tree_attention_paged_workspace_bytes(d, pg)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    if k_new is None:
+        _check(load().spec_tree_attention_paged(ctypes.byref(d), ctypes.byref(pg), _ptr(q), _ptr(k_pool), _ptr(v_pool),
+                                                _ptr(tree_parent), _ptr(tree_depth), _ptr(prefix_len), _ptr(out),
+                                                _ptr(workspace), ws_bytes, _ptr(status), _stream(stream)),
+               "spec_tree_attention_paged")
+    else:
+        _same_layout(k_new, v_new, "k_new and v_new")
+        _check(load().spec_tree_attention_append_paged(ctypes.byref(d), ctypes.byref(pg), _ptr(q), _ptr(k_new),
+                                                       _ptr(v_new), _ptr(k_pool), _ptr(v_pool), _ptr(tree_parent),
+                                                       _ptr(tree_depth), _ptr(prefix_len), _ptr(out), _ptr(workspace),
+                                                       ws_bytes, _ptr(status), _stream(stream)),
+               "spec_tree_attention_append_paged")
+    return out
+
+
+def spec_tree_attention_append_paged(q, k_new, v_new, k_pool, v_pool, block_table, tree_parent, tree_depth, prefix_len,
+                                     **kw):
+    return spec_tree_attention_paged(q, k_pool, v_pool, block_table, tree_parent, tree_depth, prefix_len, k_new=k_new,
+                                     v_new=v_new, **kw)
+
+
+def spec_kv_commit_paged(k_pools: Sequence[torch.Tensor], v_pools: Sequence[torch.Tensor], block_table, accepted_path,
+                         accepted_len, prefix_len, N: int, prefix_len_out=None, status=None, stream=None):
+    """Commits the accepted path in every layer's paged cache; returns prefix_len_out [B]."""
+    L = len(k_pools)
+    k0 = k_pools[0]
+    for kc, vc in zip(k_pools, v_pools):
+        _same_layout(kc, k0, "all layer pools")
+        _same_layout(vc, k0, "all layer pools")
+    n_blocks, H, bt, D = k0.shape
+    B, max_blocks = block_table.shape
+    d = AttnDesc(B, H, H, D, N, max_blocks * bt, _dtype_code(k0.dtype), 0, N * H * D, H * D, D,
+                 k0.stride(0), k0.stride(1), k0.stride(2), 0, 0, 0, 0.0, 0)
+    pg = KvPages(block_table.data_ptr(), max_blocks, bt, n_blocks)
+    if prefix_len_out is None:
+        prefix_len_out = torch.empty_like(prefix_len)
+    arr_t = ctypes.c_void_p * L
+    ks = arr_t(*[kc.data_ptr() for kc in k_pools])
+    vs = arr_t(*[vc.data_ptr() for vc in v_pools])
+    _check(load().spec_kv_commit_paged(ctypes.byref(d), ctypes.byref(pg), L, ks, vs, _ptr(accepted_path),
+                                       accepted_path.shape[1], _ptr(accepted_len), _ptr(prefix_len), _ptr(prefix_len_out),
+                                       _ptr(status), _stream(stream)), "spec_kv_commit_paged")
     return prefix_len_out
 
 

@@ -14,7 +14,7 @@ __global__ void __launch_bounds__(256) kv_append_kernel(const uint4* __restrict_
                                                         const int32_t* __restrict__ prefix_len, int32_t* status,
                                                         int B, int N, int H, int S_cap, int vec_per_row,
                                                         long q_sb, long q_sn, long q_sh,     // in uint4 units
-                                                        long kv_sb, long kv_sh, long kv_ss) {
+                                                        long kv_sb, long kv_sh, long kv_ss, Pages pg) {
   const long total = (long)B * N * H * vec_per_row;
   long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
@@ -30,7 +30,12 @@ __global__ void __launch_bounds__(256) kv_append_kernel(const uint4* __restrict_
     return;
   }
   const long src = b * q_sb + i * q_sn + h * q_sh + c;
-  const long dst = b * kv_sb + h * kv_sh + (long)(p + i) * kv_ss + c;
+  bool blk_ok;
+  const long dst = cache_row_offset(pg, b, p + i, kv_sb, kv_ss, &blk_ok) + h * kv_sh + c;
+  if (!blk_ok) {   // a row of a block outside the pool is not written
+    if (h == 0 && c == 0) set_status(status, b, SPEC_ST_BAD_BLOCK);
+    return;
+  }
   k_cache[dst] = k_new[src];
   v_cache[dst] = v_new[src];
 }
@@ -50,7 +55,7 @@ __global__ void __launch_bounds__(256) kv_append_rope_kernel(const uint4* __rest
                                                              const float* __restrict__ rope_sin, int rope_len,
                                                              int32_t* status, int N, int H, int D, int S_cap,
                                                              int vec_per_row, long q_sb, long q_sn, long q_sh,
-                                                             long kv_sb, long kv_sh, long kv_ss) {
+                                                             long kv_sb, long kv_sh, long kv_ss, Pages pg) {
   constexpr int EPV = BF16 ? 8 : 4;   // elements per 16-byte piece
   __shared__ int s_bad;
   const int b = blockIdx.y, t = threadIdx.x;
@@ -76,7 +81,12 @@ __global__ void __launch_bounds__(256) kv_append_rope_kernel(const uint4* __rest
   const int i = (int)(idx / H);
   const int pos = p + tree_depth[(long)b * N + i];
   const long src = b * q_sb + i * q_sn + h * q_sh + c;
-  const long dst = b * kv_sb + h * kv_sh + (long)(p + i) * kv_ss + c;
+  bool blk_ok;
+  const long dst = cache_row_offset(pg, b, p + i, kv_sb, kv_ss, &blk_ok) + h * kv_sh + c;
+  if (!blk_ok) {   // a row of a block outside the pool is not written
+    if (h == 0 && c == 0) set_status(status, b, SPEC_ST_BAD_BLOCK);
+    return;
+  }
   const uint4 lo = k_new[src], hi = k_new[src + half];
   float x1[EPV], x2[EPV];
   if (BF16) {
@@ -138,7 +148,7 @@ __global__ void __launch_bounds__(256) kv_commit_kernel(LayerPtrs ptrs, const in
                                                         const int32_t* __restrict__ prefix_len,
                                                         int32_t* __restrict__ prefix_len_out, int32_t* status, int N,
                                                         int H, int S_cap, int Lmax, int vec_per_row, long kv_sb,
-                                                        long kv_sh, long kv_ss) {
+                                                        long kv_sh, long kv_ss, Pages pg) {
   __shared__ int s_path[SPEC_MAX_TREE_NODES];
   __shared__ int s_bad;
   const int b = blockIdx.z;
@@ -159,33 +169,47 @@ __global__ void __launch_bounds__(256) kv_commit_kernel(LayerPtrs ptrs, const in
     }
   }
   __syncthreads();
-  const bool ok = head_ok && s_bad == 0;
-  if (blockIdx.x == 0 && layer == 0 && t == 0) {
-    prefix_len_out[b] = ok ? p + n : p;
-    if (!ok) set_status(status, b, cap_ok ? SPEC_ST_BAD_PATH : SPEC_ST_CAPACITY);
+  bool ok = head_ok && s_bad == 0;
+  // paged cache: every block that holds a row of the tree must lie inside the pool, else nothing moves
+  bool blocks_ok = true;
+  if (ok && pg.table != nullptr) {
+    for (int j = (p >> pg.log2_tokens) + t; j <= ((p + N - 1) >> pg.log2_tokens); j += blockDim.x) {
+      const int e = pg.table[(long)b * pg.max_blocks + j];
+      if (e < 0 || e >= pg.n_blocks) atomicOr(&s_bad, 2);
+    }
+    __syncthreads();
+    blocks_ok = s_bad == 0;
   }
-  if (!ok) return;
+  if (blockIdx.x == 0 && layer == 0 && t == 0) {
+    prefix_len_out[b] = (ok && blocks_ok) ? p + n : p;
+    if (!ok) set_status(status, b, cap_ok ? SPEC_ST_BAD_PATH : SPEC_ST_CAPACITY);
+    else if (!blocks_ok) set_status(status, b, SPEC_ST_BAD_BLOCK);
+  }
+  if (!ok || !blocks_ok) return;
   const int col = blockIdx.x * blockDim.x + t;
   if (col >= H * vec_per_row) return;
   const int h = col / vec_per_row, c = col % vec_per_row;
-  uint4* kc = ptrs.k[layer] + b * kv_sb + h * kv_sh + c;
-  uint4* vc = ptrs.v[layer] + b * kv_sb + h * kv_sh + c;
+  uint4* kc = ptrs.k[layer] + h * kv_sh + c;
+  uint4* vc = ptrs.v[layer] + h * kv_sh + c;
+  bool in_pool;   // checked for all of the tree's blocks above
   for (int k0 = 0; k0 < n; k0 += 8) {
     uint4 kr[8], vr[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int k = k0 + j;
       if (k < n && s_path[k] != k) {
-        kr[j] = kc[(long)(p + s_path[k]) * kv_ss];
-        vr[j] = vc[(long)(p + s_path[k]) * kv_ss];
+        const long src = cache_row_offset(pg, b, p + s_path[k], kv_sb, kv_ss, &in_pool);
+        kr[j] = kc[src];
+        vr[j] = vc[src];
       }
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int k = k0 + j;
       if (k < n && s_path[k] != k) {
-        kc[(long)(p + k) * kv_ss] = kr[j];
-        vc[(long)(p + k) * kv_ss] = vr[j];
+        const long dst = cache_row_offset(pg, b, p + k, kv_sb, kv_ss, &in_pool);
+        kc[dst] = kr[j];
+        vc[dst] = vr[j];
       }
     }
   }
@@ -193,8 +217,8 @@ __global__ void __launch_bounds__(256) kv_commit_kernel(LayerPtrs ptrs, const in
 
 static inline int elem_bytes(int dtype) { return dtype == SPEC_F32 ? 4 : 2; }
 
-hipError_t launch_kv_append(const spec_attn_desc_t& d, const void* k_new, const void* v_new, void* k_cache,
-                            void* v_cache, const int32_t* prefix_len, int32_t* status, hipStream_t s) {
+hipError_t launch_kv_append(const spec_attn_desc_t& d, const Pages& pg, const void* k_new, const void* v_new,
+                            void* k_cache, void* v_cache, const int32_t* prefix_len, int32_t* status, hipStream_t s) {
   const int e = elem_bytes(d.dtype);
   const int per16 = 16 / e;
   const int vec_per_row = d.D / per16;
@@ -204,12 +228,12 @@ hipError_t launch_kv_append(const spec_attn_desc_t& d, const void* k_new, const 
   hipLaunchKernelGGL(kv_append_kernel, dim3(grid), dim3(256), 0, s, (const uint4*)k_new, (const uint4*)v_new,
                      (uint4*)k_cache, (uint4*)v_cache, prefix_len, status, d.B, d.N, d.H_kv, d.S_cap, vec_per_row,
                      ns.b / per16, ns.n / per16, ns.h / per16, d.kv_stride_b / per16, d.kv_stride_h / per16,
-                     d.kv_stride_s / per16);
+                     d.kv_stride_s / per16, pg);
   return hipGetLastError();
 }
 
-hipError_t launch_kv_append_rope(const spec_attn_desc_t& d, const void* k_new, const void* v_new, void* k_cache,
-                                 void* v_cache, const int32_t* tree_depth, const int32_t* prefix_len,
+hipError_t launch_kv_append_rope(const spec_attn_desc_t& d, const Pages& pg, const void* k_new, const void* v_new,
+                                 void* k_cache, void* v_cache, const int32_t* tree_depth, const int32_t* prefix_len,
                                  const float* rope_cos, const float* rope_sin, int rope_len, int32_t* status,
                                  hipStream_t s) {
   const int e = elem_bytes(d.dtype);
@@ -222,14 +246,15 @@ hipError_t launch_kv_append_rope(const spec_attn_desc_t& d, const void* k_new, c
   hipLaunchKernelGGL(kv_append_rope_kernel<BF>, grid, dim3(256), 0, s, (const uint4*)k_new, (const uint4*)v_new,      \
                      (uint4*)k_cache, (uint4*)v_cache, tree_depth, prefix_len, rope_cos, rope_sin, rope_len, status,  \
                      d.N, d.H_kv, d.D, d.S_cap, vec_per_row, ns.b / per16, ns.n / per16, ns.h / per16,                \
-                     d.kv_stride_b / per16, d.kv_stride_h / per16, d.kv_stride_s / per16)
+                     d.kv_stride_b / per16, d.kv_stride_h / per16, d.kv_stride_s / per16, pg)
   if (d.dtype == SPEC_BF16) SPEC_ROPE(true);
   else SPEC_ROPE(false);
 #undef SPEC_ROPE
   return hipGetLastError();
 }
 
-hipError_t launch_kv_commit(const spec_attn_desc_t& d, int n_layers, void* const* k_caches, void* const* v_caches,
+hipError_t launch_kv_commit(const spec_attn_desc_t& d, const Pages& pg, int n_layers, void* const* k_caches,
+                            void* const* v_caches,
                             const int32_t* path, int Lmax, const int32_t* len, const int32_t* prefix_len,
                             int32_t* prefix_len_out, int32_t* status, hipStream_t s) {
   const int e = elem_bytes(d.dtype);
@@ -244,7 +269,7 @@ hipError_t launch_kv_commit(const spec_attn_desc_t& d, int n_layers, void* const
   dim3 grid((cols + 255) / 256, n_layers, d.B);
   hipLaunchKernelGGL(kv_commit_kernel, grid, dim3(256), 0, s, ptrs, path, len, prefix_len, prefix_len_out, status, d.N,
                      d.H_kv, d.S_cap, Lmax, vec_per_row, d.kv_stride_b / per16, d.kv_stride_h / per16,
-                     d.kv_stride_s / per16);
+                     d.kv_stride_s / per16, pg);
   return hipGetLastError();
 }
 

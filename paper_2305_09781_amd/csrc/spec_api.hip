@@ -52,6 +52,18 @@ static bool new_strides_missing(const spec_attn_desc_t* d) {
   return d->H_kv != d->H && d->new_stride_b == 0 && d->new_stride_n == 0 && d->new_stride_h == 0;
 }
 
+// Host-checkable part of a paged-cache description; fills the form the kernels take.
+static int check_pages(const spec_attn_desc_t* d, const spec_kv_pages_t* p, Pages* out) {
+  if (p == nullptr || p->block_table == nullptr || p->max_blocks <= 0 || p->n_blocks <= 0) return SPEC_ERR_INVALID_ARG;
+  const int bt = p->block_tokens;
+  if (bt < 64 || bt > 65536 || (bt & (bt - 1)) != 0) return SPEC_ERR_UNSUPPORTED;
+  if ((long)d->S_cap > (long)p->max_blocks * bt) return SPEC_ERR_CAPACITY;
+  int lg = 0;
+  while ((1 << lg) < bt) ++lg;
+  *out = Pages{p->block_table, p->max_blocks, lg, p->n_blocks};
+  return SPEC_OK;
+}
+
 // Compute units of the current device (256 when no device can be queried, e.g. sizing a workspace on a
 // machine without a GPU).
 static int compute_units() {
@@ -67,7 +79,7 @@ static int compute_units() {
   return cached;
 }
 
-AttnPlan make_attn_plan(const spec_attn_desc_t& d) {
+AttnPlan make_attn_plan(const spec_attn_desc_t& d, bool paged) {
   AttnPlan p;
   p.balanced_wgs = 0;
   p.balanced_tile = 0;
@@ -127,7 +139,8 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d) {
       chunk = (int)((max_len + splits - 1) / splits);
       if (chunk < 128) chunk = 128;
     }
-    chunk = (int)round_up((size_t)chunk, 32);
+    // chunks start at tile boundaries (with paged caches a tile must not straddle two blocks)
+    chunk = (int)round_up((size_t)chunk, (paged && p.wide) ? SPEC_WIDE_TILE_KEYS : 32);
     p.chunk_keys = chunk;
     p.n_splits = (max_len + chunk - 1) / chunk;
   }
@@ -171,14 +184,46 @@ const char* spec_strerror(int code) {
   }
 }
 
-int spec_kv_append(const spec_attn_desc_t* desc, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
-                   const int32_t* prefix_len, int32_t* status, void* hip_stream) {
-  const int rc = check_desc(desc);
+// Every cache-touching entry point exists in a contiguous and a paged form; `pages` is NULL in the first.
+static int kv_append_impl(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, bool paged, const void* k_new,
+                          const void* v_new, void* k_cache, void* v_cache, const int32_t* prefix_len, int32_t* status,
+                          void* hip_stream) {
+  int rc = check_desc(desc);
   if (rc != SPEC_OK) return rc;
+  Pages pg = no_pages();
+  if (paged && (rc = check_pages(desc, pages, &pg)) != SPEC_OK) return rc;
   if (!k_new || !v_new || !k_cache || !v_cache || !prefix_len) return SPEC_ERR_INVALID_ARG;
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache)) return SPEC_ERR_INVALID_ARG;
   if (new_strides_missing(desc)) return SPEC_ERR_INVALID_ARG;
-  return launch_kv_append(*desc, k_new, v_new, k_cache, v_cache, prefix_len, status, (hipStream_t)hip_stream) == hipSuccess
+  return launch_kv_append(*desc, pg, k_new, v_new, k_cache, v_cache, prefix_len, status, (hipStream_t)hip_stream) ==
+                 hipSuccess
+             ? SPEC_OK
+             : SPEC_ERR_HIP;
+}
+
+int spec_kv_append(const spec_attn_desc_t* desc, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                   const int32_t* prefix_len, int32_t* status, void* hip_stream) {
+  return kv_append_impl(desc, nullptr, false, k_new, v_new, k_cache, v_cache, prefix_len, status, hip_stream);
+}
+
+int spec_kv_append_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, const void* k_new, const void* v_new,
+                         void* k_cache, void* v_cache, const int32_t* prefix_len, int32_t* status, void* hip_stream) {
+  return kv_append_impl(desc, pages, true, k_new, v_new, k_cache, v_cache, prefix_len, status, hip_stream);
+}
+
+static int kv_append_rope_impl(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, bool paged, const void* k_new,
+                               const void* v_new, void* k_cache, void* v_cache, const int32_t* tree_depth,
+                               const int32_t* prefix_len, const float* rope_cos, const float* rope_sin, int32_t rope_len,
+                               int32_t* status, void* hip_stream) {
+  int rc = check_desc(desc);
+  if (rc != SPEC_OK) return rc;
+  Pages pg = no_pages();
+  if (paged && (rc = check_pages(desc, pages, &pg)) != SPEC_OK) return rc;
+  if (!k_new || !v_new || !k_cache || !v_cache || !prefix_len || !tree_depth || !rope_cos || !rope_sin) return SPEC_ERR_INVALID_ARG;
+  if (rope_len <= 0 || new_strides_missing(desc)) return SPEC_ERR_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache)) return SPEC_ERR_INVALID_ARG;
+  return launch_kv_append_rope(*desc, pg, k_new, v_new, k_cache, v_cache, tree_depth, prefix_len, rope_cos, rope_sin,
+                               rope_len, status, (hipStream_t)hip_stream) == hipSuccess
              ? SPEC_OK
              : SPEC_ERR_HIP;
 }
@@ -186,15 +231,16 @@ int spec_kv_append(const spec_attn_desc_t* desc, const void* k_new, const void* 
 int spec_kv_append_rope(const spec_attn_desc_t* desc, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                         const int32_t* tree_depth, const int32_t* prefix_len, const float* rope_cos, const float* rope_sin,
                         int32_t rope_len, int32_t* status, void* hip_stream) {
-  const int rc = check_desc(desc);
-  if (rc != SPEC_OK) return rc;
-  if (!k_new || !v_new || !k_cache || !v_cache || !prefix_len || !tree_depth || !rope_cos || !rope_sin) return SPEC_ERR_INVALID_ARG;
-  if (rope_len <= 0 || new_strides_missing(desc)) return SPEC_ERR_INVALID_ARG;
-  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache)) return SPEC_ERR_INVALID_ARG;
-  return launch_kv_append_rope(*desc, k_new, v_new, k_cache, v_cache, tree_depth, prefix_len, rope_cos, rope_sin, rope_len,
-                               status, (hipStream_t)hip_stream) == hipSuccess
-             ? SPEC_OK
-             : SPEC_ERR_HIP;
+  return kv_append_rope_impl(desc, nullptr, false, k_new, v_new, k_cache, v_cache, tree_depth, prefix_len, rope_cos,
+                             rope_sin, rope_len, status, hip_stream);
+}
+
+int spec_kv_append_rope_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, const void* k_new,
+                              const void* v_new, void* k_cache, void* v_cache, const int32_t* tree_depth,
+                              const int32_t* prefix_len, const float* rope_cos, const float* rope_sin, int32_t rope_len,
+                              int32_t* status, void* hip_stream) {
+  return kv_append_rope_impl(desc, pages, true, k_new, v_new, k_cache, v_cache, tree_depth, prefix_len, rope_cos, rope_sin,
+                             rope_len, status, hip_stream);
 }
 
 size_t spec_tree_attention_workspace_bytes(const spec_attn_desc_t* desc) {
@@ -202,19 +248,27 @@ size_t spec_tree_attention_workspace_bytes(const spec_attn_desc_t* desc) {
   return make_attn_plan(*desc).ws_bytes;
 }
 
+size_t spec_tree_attention_paged_workspace_bytes(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages) {
+  Pages pg;
+  if (check_desc(desc) != SPEC_OK || check_pages(desc, pages, &pg) != SPEC_OK) return 0;
+  return make_attn_plan(*desc, true).ws_bytes;
+}
+
 // Shared body of spec_tree_attention (k_new == NULL) and spec_tree_attention_append.
-static int tree_attention_impl(const spec_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,
-                               void* k_cache, void* v_cache, const int32_t* tree_parent, const int32_t* tree_depth,
-                               const int32_t* prefix_len, void* out, void* workspace, size_t workspace_bytes,
-                               int32_t* status, void* hip_stream) {
-  const int rc = check_desc(desc);
+static int tree_attention_impl(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, bool paged, const void* q,
+                               const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                               const int32_t* tree_parent, const int32_t* tree_depth, const int32_t* prefix_len, void* out,
+                               void* workspace, size_t workspace_bytes, int32_t* status, void* hip_stream) {
+  int rc = check_desc(desc);
   if (rc != SPEC_OK) return rc;
+  Pages pg = no_pages();
+  if (paged && (rc = check_pages(desc, pages, &pg)) != SPEC_OK) return rc;
   if (!q || !k_cache || !v_cache || !tree_parent || !tree_depth || !prefix_len || !out) return SPEC_ERR_INVALID_ARG;
   if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out)) return SPEC_ERR_INVALID_ARG;
   const bool append = k_new != nullptr || v_new != nullptr;
   if (append && (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new) || new_strides_missing(desc)))
     return SPEC_ERR_INVALID_ARG;
-  const AttnPlan plan = make_attn_plan(*desc);
+  const AttnPlan plan = make_attn_plan(*desc, paged);
   if (plan.ws_bytes > 0) {
     if (workspace == nullptr || workspace_bytes < plan.ws_bytes) return SPEC_ERR_WORKSPACE;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return SPEC_ERR_INVALID_ARG;
@@ -227,14 +281,14 @@ static int tree_attention_impl(const spec_attn_desc_t* desc, const void* q, cons
   hipStream_t s = (hipStream_t)hip_stream;
   hipError_t e;
   if (d.dtype == SPEC_BF16) {
-    e = launch_tree_attention_bf16(d, plan, q, k_cache, v_cache, k_new, v_new, tree_parent, tree_depth, prefix_len, out,
+    e = launch_tree_attention_bf16(d, plan, pg, q, k_cache, v_cache, k_new, v_new, tree_parent, tree_depth, prefix_len, out,
                                    workspace, status, s);
   } else {
     if (append) {
-      e = launch_kv_append(d, k_new, v_new, k_cache, v_cache, prefix_len, status, s);
+      e = launch_kv_append(d, pg, k_new, v_new, k_cache, v_cache, prefix_len, status, s);
       if (e != hipSuccess) return SPEC_ERR_HIP;
     }
-    e = launch_tree_attention_f32(d, plan, (const float*)q, (const float*)k_cache, (const float*)v_cache, tree_parent,
+    e = launch_tree_attention_f32(d, plan, pg, (const float*)q, (const float*)k_cache, (const float*)v_cache, tree_parent,
                                   tree_depth, prefix_len, (float*)out, workspace, status, s);
   }
   if (e != hipSuccess) return SPEC_ERR_HIP;
@@ -248,8 +302,18 @@ static int tree_attention_impl(const spec_attn_desc_t* desc, const void* q, cons
 int spec_tree_attention(const spec_attn_desc_t* desc, const void* q, const void* k_cache, const void* v_cache,
                         const int32_t* tree_parent, const int32_t* tree_depth, const int32_t* prefix_len, void* out,
                         void* workspace, size_t workspace_bytes, int32_t* status, void* hip_stream) {
-  return tree_attention_impl(desc, q, nullptr, nullptr, const_cast<void*>(k_cache), const_cast<void*>(v_cache),
-                             tree_parent, tree_depth, prefix_len, out, workspace, workspace_bytes, status, hip_stream);
+  return tree_attention_impl(desc, nullptr, false, q, nullptr, nullptr, const_cast<void*>(k_cache),
+                             const_cast<void*>(v_cache), tree_parent, tree_depth, prefix_len, out, workspace,
+                             workspace_bytes, status, hip_stream);
+}
+
+int spec_tree_attention_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, const void* q,
+                              const void* k_cache, const void* v_cache, const int32_t* tree_parent,
+                              const int32_t* tree_depth, const int32_t* prefix_len, void* out, void* workspace,
+                              size_t workspace_bytes, int32_t* status, void* hip_stream) {
+  return tree_attention_impl(desc, pages, true, q, nullptr, nullptr, const_cast<void*>(k_cache),
+                             const_cast<void*>(v_cache), tree_parent, tree_depth, prefix_len, out, workspace,
+                             workspace_bytes, status, hip_stream);
 }
 
 int spec_tree_attention_append(const spec_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,
@@ -257,8 +321,18 @@ int spec_tree_attention_append(const spec_attn_desc_t* desc, const void* q, cons
                                const int32_t* prefix_len, void* out, void* workspace, size_t workspace_bytes,
                                int32_t* status, void* hip_stream) {
   if (!k_new || !v_new) return check_desc(desc) != SPEC_OK ? check_desc(desc) : SPEC_ERR_INVALID_ARG;
-  return tree_attention_impl(desc, q, k_new, v_new, k_cache, v_cache, tree_parent, tree_depth, prefix_len, out,
-                             workspace, workspace_bytes, status, hip_stream);
+  return tree_attention_impl(desc, nullptr, false, q, k_new, v_new, k_cache, v_cache, tree_parent, tree_depth,
+                             prefix_len, out, workspace, workspace_bytes, status, hip_stream);
+}
+
+int spec_tree_attention_append_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, const void* q,
+                                     const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                                     const int32_t* tree_parent, const int32_t* tree_depth, const int32_t* prefix_len,
+                                     void* out, void* workspace, size_t workspace_bytes, int32_t* status,
+                                     void* hip_stream) {
+  if (!k_new || !v_new) return check_desc(desc) != SPEC_OK ? check_desc(desc) : SPEC_ERR_INVALID_ARG;
+  return tree_attention_impl(desc, pages, true, q, k_new, v_new, k_cache, v_cache, tree_parent, tree_depth, prefix_len,
+                             out, workspace, workspace_bytes, status, hip_stream);
 }
 
 static int check_verify_common(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, const void* logits,
@@ -384,21 +458,39 @@ int spec_verify_stochastic(int32_t B, int32_t N, int32_t V, int32_t logits_dtype
   return SPEC_OK;
 }
 
-int spec_kv_commit(const spec_attn_desc_t* desc, int32_t n_layers, void* const* k_caches, void* const* v_caches,
-                   const int32_t* accepted_path, int32_t Lmax, const int32_t* accepted_len, const int32_t* prefix_len,
-                   int32_t* prefix_len_out, int32_t* status, void* hip_stream) {
-  const int rc = check_desc(desc);
+static int kv_commit_impl(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, bool paged, int32_t n_layers,
+                          void* const* k_caches, void* const* v_caches, const int32_t* accepted_path, int32_t Lmax,
+                          const int32_t* accepted_len, const int32_t* prefix_len, int32_t* prefix_len_out, int32_t* status,
+                          void* hip_stream) {
+  int rc = check_desc(desc);
   if (rc != SPEC_OK) return rc;
+  Pages pg = no_pages();
+  if (paged && (rc = check_pages(desc, pages, &pg)) != SPEC_OK) return rc;
   if (n_layers <= 0 || Lmax <= 0) return SPEC_ERR_INVALID_ARG;
   if (n_layers > SPEC_MAX_COMMIT_LAYERS) return SPEC_ERR_UNSUPPORTED;
   if (!k_caches || !v_caches || !accepted_path || !accepted_len || !prefix_len || !prefix_len_out) return SPEC_ERR_INVALID_ARG;
   if (prefix_len_out == prefix_len) return SPEC_ERR_INVALID_ARG;
   for (int l = 0; l < n_layers; ++l)
     if (!k_caches[l] || !v_caches[l] || !aligned16(k_caches[l]) || !aligned16(v_caches[l])) return SPEC_ERR_INVALID_ARG;
-  return launch_kv_commit(*desc, n_layers, k_caches, v_caches, accepted_path, Lmax, accepted_len, prefix_len,
+  return launch_kv_commit(*desc, pg, n_layers, k_caches, v_caches, accepted_path, Lmax, accepted_len, prefix_len,
                           prefix_len_out, status, (hipStream_t)hip_stream) == hipSuccess
              ? SPEC_OK
              : SPEC_ERR_HIP;
+}
+
+int spec_kv_commit(const spec_attn_desc_t* desc, int32_t n_layers, void* const* k_caches, void* const* v_caches,
+                   const int32_t* accepted_path, int32_t Lmax, const int32_t* accepted_len, const int32_t* prefix_len,
+                   int32_t* prefix_len_out, int32_t* status, void* hip_stream) {
+  return kv_commit_impl(desc, nullptr, false, n_layers, k_caches, v_caches, accepted_path, Lmax, accepted_len, prefix_len,
+                        prefix_len_out, status, hip_stream);
+}
+
+int spec_kv_commit_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, int32_t n_layers,
+                         void* const* k_caches, void* const* v_caches, const int32_t* accepted_path, int32_t Lmax,
+                         const int32_t* accepted_len, const int32_t* prefix_len, int32_t* prefix_len_out, int32_t* status,
+                         void* hip_stream) {
+  return kv_commit_impl(desc, pages, true, n_layers, k_caches, v_caches, accepted_path, Lmax, accepted_len, prefix_len,
+                        prefix_len_out, status, hip_stream);
 }
 
 }  // extern "C"

@@ -23,7 +23,18 @@ struct AttnPlan {
   size_t ws_bytes;
 };
 
-AttnPlan make_attn_plan(const spec_attn_desc_t& d);
+// Block table of a paged cache as the kernels take it (by value). table == nullptr: the cache is contiguous,
+// [B, H_kv, S_cap, D]. Otherwise the cache is [n_blocks, H_kv, 2^log2_tokens, D] and the descriptor's
+// kv_stride_b is the stride between blocks.
+struct Pages {
+  const int32_t* table;   // [B, max_blocks]
+  int max_blocks;
+  int log2_tokens;
+  int n_blocks;
+};
+inline Pages no_pages() { return Pages{nullptr, 0, 0, 0}; }
+
+AttnPlan make_attn_plan(const spec_attn_desc_t& d, bool paged = false);
 
 // Tree queries handled by one workgroup of the attention kernel chosen for this shape
 // (bf16: 16 / 32 in the few-query kernel, 64 / 128 in the wide-tree kernel; float32: all of them).
@@ -66,26 +77,27 @@ inline NewStrides attn_new_strides(const spec_attn_desc_t& d) {
 }
 
 // Kernel launchers (defined in the .hip files). All return hipError_t of the launch.
-hipError_t launch_kv_append(const spec_attn_desc_t& d, const void* k_new, const void* v_new, void* k_cache,
-                            void* v_cache, const int32_t* prefix_len, int32_t* status, hipStream_t s);
-hipError_t launch_kv_append_rope(const spec_attn_desc_t& d, const void* k_new, const void* v_new, void* k_cache,
-                                 void* v_cache, const int32_t* tree_depth, const int32_t* prefix_len,
+hipError_t launch_kv_append(const spec_attn_desc_t& d, const Pages& pg, const void* k_new, const void* v_new,
+                            void* k_cache, void* v_cache, const int32_t* prefix_len, int32_t* status, hipStream_t s);
+hipError_t launch_kv_append_rope(const spec_attn_desc_t& d, const Pages& pg, const void* k_new, const void* v_new,
+                                 void* k_cache, void* v_cache, const int32_t* tree_depth, const int32_t* prefix_len,
                                  const float* rope_cos, const float* rope_sin, int rope_len, int32_t* status,
                                  hipStream_t s);
-hipError_t launch_kv_commit(const spec_attn_desc_t& d, int n_layers, void* const* k_caches, void* const* v_caches,
+hipError_t launch_kv_commit(const spec_attn_desc_t& d, const Pages& pg, int n_layers, void* const* k_caches,
+                            void* const* v_caches,
                             const int32_t* path, int Lmax, const int32_t* len, const int32_t* prefix_len,
                             int32_t* prefix_len_out, int32_t* status, hipStream_t s);
-hipError_t launch_tree_attention_f32(const spec_attn_desc_t& d, const AttnPlan& plan, const float* q,
+hipError_t launch_tree_attention_f32(const spec_attn_desc_t& d, const AttnPlan& plan, const Pages& pg, const float* q,
                                      const float* k_cache, const float* v_cache, const int32_t* parent,
                                      const int32_t* depth, const int32_t* prefix_len, float* out, void* ws,
                                      int32_t* status, hipStream_t s);
 // k_new / v_new non-null: the kernel also appends the tree rows to the cache (fused KV append).
-hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan& plan, const void* q, void* k_cache,
+hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan& plan, const Pages& pg, const void* q, void* k_cache,
                                       void* v_cache, const void* k_new, const void* v_new, const int32_t* parent,
                                       const int32_t* depth, const int32_t* prefix_len, void* out, void* ws,
                                       int32_t* status, hipStream_t s);
 // Wide trees (N > 32): the workgroup's wavefronts split the queries and share the K/V stream through LDS.
-hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const AttnPlan& plan, const void* q, void* k_cache,
+hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const AttnPlan& plan, const Pages& pg, const void* q, void* k_cache,
                                            void* v_cache, const void* k_new, const void* v_new, const int32_t* parent,
                                            const int32_t* depth, const int32_t* prefix_len, void* out, void* ws,
                                            int32_t* status, hipStream_t s);
@@ -163,6 +175,18 @@ __device__ inline BalancedShare balanced_share(const int32_t* __restrict__ prefi
 
 __device__ inline void set_status(int32_t* status, int b, int bit) {
   if (status != nullptr) atomicOr(&status[b], bit);
+}
+
+// Offset, in the units of the two strides, of logical cache row `row` of request b before the head and
+// column terms. Paged: `ok` tells whether the table entry lies inside the pool; an entry outside is
+// replaced by one inside (block 0 or the last), so the offset always stays within the cache.
+__device__ inline long cache_row_offset(const Pages& pg, int b, int row, long kv_sb, long kv_ss, bool* ok) {
+  *ok = true;
+  if (pg.table == nullptr) return b * kv_sb + (long)row * kv_ss;
+  const int e = pg.table[(long)b * pg.max_blocks + (row >> pg.log2_tokens)];
+  *ok = e >= 0 && e < pg.n_blocks;
+  const int blk = min(max(e, 0), pg.n_blocks - 1);
+  return blk * kv_sb + (long)(row & ((1 << pg.log2_tokens) - 1)) * kv_ss;
 }
 
 #endif  // __HIPCC__

@@ -121,34 +121,36 @@ struct TileSrc {
 // APPEND rows >= P come from the new K/V.
 template <int D, int NT, bool APPEND, bool CLEAN>
 __device__ __forceinline__ void issue_v_loads(const TileSrc& s, int k0, int P, int last_row, int lane,
-                                              u32x4 (&Vn)[AttnTraits<D, NT>::NVL]) {
+                                              u32x4 (&Vn)[AttnTraits<D, NT>::NVL], long shift = 0) {
   using T = AttnTraits<D, NT>;
 #pragma unroll
   for (int j = 0; j < T::NVL; ++j) {
     int row = k0 + j * T::RPI + lane / T::LPR;
     const unsigned char* p;
     if (CLEAN) {
-      p = s.vc + (unsigned)row * s.cache_row_bytes;
+      p = s.vc + (unsigned)row * s.cache_row_bytes + shift;
     } else {
       row = min(row, last_row);
-      p = (APPEND && row >= P) ? s.vn + (unsigned)(row - P) * s.new_row_bytes : s.vc + (unsigned)row * s.cache_row_bytes;
+      p = (APPEND && row >= P) ? s.vn + (unsigned)(row - P) * s.new_row_bytes
+                               : s.vc + (unsigned)row * s.cache_row_bytes + shift;
     }
     Vn[j] = *(const u32x4*)p;
   }
 }
 template <int D, int NT, bool APPEND, bool CLEAN>
 __device__ __forceinline__ void issue_k_loads(const TileSrc& s, int k0, int P, int last_row, int r16,
-                                              u32x4 (&Kn)[2][AttnTraits<D, NT>::KS]) {
+                                              u32x4 (&Kn)[2][AttnTraits<D, NT>::KS], long shift = 0) {
   using T = AttnTraits<D, NT>;
 #pragma unroll
   for (int hf = 0; hf < 2; ++hf) {
     int row = k0 + hf * 16 + r16;
     const unsigned char* p;
     if (CLEAN) {
-      p = s.kc + (unsigned)row * s.cache_row_bytes;
+      p = s.kc + (unsigned)row * s.cache_row_bytes + shift;
     } else {
       row = min(row, last_row);
-      p = (APPEND && row >= P) ? s.kn + (unsigned)(row - P) * s.new_row_bytes : s.kc + (unsigned)row * s.cache_row_bytes;
+      p = (APPEND && row >= P) ? s.kn + (unsigned)(row - P) * s.new_row_bytes
+                               : s.kc + (unsigned)row * s.cache_row_bytes + shift;
     }
 #pragma unroll
     for (int ks = 0; ks < T::KS; ++ks) Kn[hf][ks] = *(const u32x4*)(p + ks * 64);
@@ -157,19 +159,22 @@ __device__ __forceinline__ void issue_k_loads(const TileSrc& s, int k0, int P, i
 template <int D, int NT, bool APPEND, bool CLEAN>
 __device__ __forceinline__ void issue_tile_loads(const TileSrc& s, int k0, int P, int last_row, int r16, int lane,
                                                  u32x4 (&Kn)[2][AttnTraits<D, NT>::KS],
-                                                 u32x4 (&Vn)[AttnTraits<D, NT>::NVL]) {
-  issue_v_loads<D, NT, APPEND, CLEAN>(s, k0, P, last_row, lane, Vn);
-  issue_k_loads<D, NT, APPEND, CLEAN>(s, k0, P, last_row, r16, Kn);
+                                                 u32x4 (&Vn)[AttnTraits<D, NT>::NVL], long shift = 0) {
+  issue_v_loads<D, NT, APPEND, CLEAN>(s, k0, P, last_row, lane, Vn, shift);
+  issue_k_loads<D, NT, APPEND, CLEAN>(s, k0, P, last_row, r16, Kn, shift);
 }
 
-template <int D, int NT, bool APPEND, bool BAL>
+// PAGED: the caches are pools of blocks addressed through pg.table (see cache_row_offset). A wavefront's
+// 32-key tile starts at a multiple of 32 rows and a block holds a multiple of 64, so a tile lies inside one
+// block: its rows are addressed as in a contiguous cache plus one per-tile offset (page_shift below).
+template <int D, int NT, bool APPEND, bool BAL, bool PAGED>
 __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
     const __hip_bfloat16* __restrict__ q, __hip_bfloat16* k_cache, __hip_bfloat16* v_cache,
     const __hip_bfloat16* __restrict__ k_new, const __hip_bfloat16* __restrict__ v_new,
     const int32_t* __restrict__ parent, const int32_t* __restrict__ depth, const int32_t* __restrict__ prefix_len,
     __hip_bfloat16* __restrict__ out, float* __restrict__ ws_o, float* __restrict__ ws_ml, int32_t* status, int B, int N,
     int H, int S_cap, int n_qgroups, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long kv_sb,
-    long kv_sh, long kv_ss, float scale_log2) {
+    long kv_sh, long kv_ss, float scale_log2, Pages pg) {
   using T = AttnTraits<D, NT>;
   constexpr int KS = T::KS, DB = T::DB, LPR = T::LPR, RPI = T::RPI, NVL = T::NVL, VROW = T::VROW, NQ = T::NQ,
                 MROW = T::MROW;
@@ -185,6 +190,17 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int r16 = lane & 15, g = lane >> 4;
 
+  // Paged cache: byte offset that, added to `row * row_bytes`, gives the place of logical row `row` of request
+  // b for every row of the 32-row tile at k0 (clamped rows stay inside the tile, hence inside its block).
+  // `ok`: the table entry lies inside the pool; one that does not is replaced by a block of the pool.
+  auto page_shift = [&](int b, int k0, bool* ok) -> long {
+    const int j = __builtin_amdgcn_readfirstlane(min(k0, S_cap - 1) >> pg.log2_tokens);
+    const int e = pg.table[(long)b * pg.max_blocks + j];
+    *ok = e >= 0 && e < pg.n_blocks;
+    const int blk = min(max(e, 0), pg.n_blocks - 1);
+    return (long)blk * kv_sb * 2 - (long)((unsigned)(j << pg.log2_tokens) * ((unsigned)kv_ss * 2u));
+  };
+
   // One segment: keys [c0, min(c1_cap, prefix_len + N)) of request b, head h, query group qg. The result is
   // the final output (part_row < 0) or the float32 partial whose first row in the workspace is part_row.
   auto segment = [&](const int b, const int h, const int qg, const int c0, const int c1_cap, const long part_row) {
@@ -199,13 +215,15 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
   TileSrc src;
   src.cache_row_bytes = (unsigned)kv_ss * 2u;
   src.new_row_bytes = (unsigned)q_sn * 2u;
-  src.kc = (const unsigned char*)(k_cache + b * kv_sb + h * kv_sh) + g * 16;
-  src.vc = (const unsigned char*)(v_cache + b * kv_sb + h * kv_sh) + (lane % LPR) * 16;
+  src.kc = (const unsigned char*)(k_cache + (PAGED ? 0 : b * kv_sb) + h * kv_sh) + g * 16;
+  src.vc = (const unsigned char*)(v_cache + (PAGED ? 0 : b * kv_sb) + h * kv_sh) + (lane % LPR) * 16;
   src.kn = APPEND ? (const unsigned char*)(k_new + b * q_sb + h * q_sh) + g * 16 : nullptr;
   src.vn = APPEND ? (const unsigned char*)(v_new + b * q_sb + h * q_sh) + (lane % LPR) * 16 : nullptr;
 
   u32x4 KA[2][KS], VA[NVL];   // tile buffer: loads land here one step ahead of use
-  issue_tile_loads<D, NT, false, false>(src, c0 + min(wave, SWAVES - 1) * TILE, 0, S_cap - 1, r16, lane, KA, VA);
+  bool in_pool;   // entries past the request's end may hold anything: the speculative tile does not judge them
+  issue_tile_loads<D, NT, false, false>(src, c0 + min(wave, SWAVES - 1) * TILE, 0, S_cap - 1, r16, lane, KA, VA,
+                                        PAGED ? page_shift(b, c0 + min(wave, SWAVES - 1) * TILE, &in_pool) : 0);
 
   bf16x8 qB[NT][KS];   // Q^T as the B operand: lane (r16, g) holds Q[n = r16][d = ks*32 + g*8 .. +8]
 #pragma unroll
@@ -247,7 +265,14 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
   const int ti_stride = is_tail ? 1 : SWAVES;
   const int ti_end = is_tail ? n_tiles : n_clean;
   if (is_tail && ti_first < ti_end)   // the tail wavefront's first tile (needs prefix_len: rows >= P have other sources)
-    issue_tile_loads<D, NT, APPEND, false>(src, c0 + ti_first * TILE, P, last_row, r16, lane, KA, VA);
+    issue_tile_loads<D, NT, APPEND, false>(src, c0 + ti_first * TILE, P, last_row, r16, lane, KA, VA,
+                                           PAGED ? page_shift(b, c0 + ti_first * TILE, &in_pool) : 0);
+  if (PAGED && is_tail) {   // every block this segment reads must lie inside the pool
+    for (int j = (c0 >> pg.log2_tokens) + lane; j <= ((c1 - 1) >> pg.log2_tokens); j += 64) {
+      const int e = pg.table[(long)b * pg.max_blocks + j];
+      if (e < 0 || e >= pg.n_blocks) set_status(status, b, SPEC_ST_BAD_BLOCK);
+    }
+  }
 
   f32x4 O[NT][DB];
   float m_run[NT], l_run[NT];
@@ -318,18 +343,19 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
       for (int j = 0; j < NVL; ++j)
         if (k0 + j * RPI + lane / LPR >= c1) VA[j] = (u32x4){0u, 0u, 0u, 0u};
       if (APPEND && qg == 0) {   // this tile carries tree rows taken from k_new / v_new: put them in the cache
+        bool dst_ok = true;      // paged cache: rows of a block outside the pool are not written
+        const long dst_shift = PAGED ? page_shift(b, k0, &dst_ok) : 0;
 #pragma unroll
         for (int j = 0; j < NVL; ++j) {
           const int row = k0 + j * RPI + lane / LPR;
-          if (row >= P && row < c1)
-            store_cache_row((unsigned char*)(v_cache + b * kv_sb + h * kv_sh) + (unsigned)row * src.cache_row_bytes +
-                                (lane % LPR) * 16, VA[j]);
+          if (row >= P && row < c1 && dst_ok)
+            store_cache_row((unsigned char*)src.vc + (unsigned)row * src.cache_row_bytes + dst_shift, VA[j]);
         }
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf) {
           const int row = k0 + hf * 16 + r16;
-          if (row >= P && row < c1) {
-            unsigned char* dst = (unsigned char*)(k_cache + b * kv_sb + h * kv_sh) + (unsigned)row * src.cache_row_bytes + g * 16;
+          if (row >= P && row < c1 && dst_ok) {
+            unsigned char* dst = (unsigned char*)src.kc + (unsigned)row * src.cache_row_bytes + dst_shift;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) store_cache_row(dst + ks * 64, KA[hf][ks]);
           }
@@ -341,13 +367,15 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
     // Refill: V's registers are free once staged. K's are free after the S^T products; with one query
     // tile there is room to copy K aside and request the next K at once, with two there is not.
     const int kn0 = c0 + ti_refill * TILE;
-    if (ti_refill >= 0) issue_v_loads<D, NT, APPEND, !MASKED>(src, kn0, P, last_row, lane, VA);
+    bool refill_ok;
+    const long refill_shift = (PAGED && ti_refill >= 0) ? page_shift(b, kn0, &refill_ok) : 0;
+    if (ti_refill >= 0) issue_v_loads<D, NT, APPEND, !MASKED>(src, kn0, P, last_row, lane, VA, refill_shift);
     bf16x8 Kc[2][KS];
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) Kc[hf][ks] = __builtin_bit_cast(bf16x8, KA[hf][ks]);
-    if (NT == 1 && ti_refill >= 0) issue_k_loads<D, NT, APPEND, !MASKED>(src, kn0, P, last_row, r16, KA);
+    if (NT == 1 && ti_refill >= 0) issue_k_loads<D, NT, APPEND, !MASKED>(src, kn0, P, last_row, r16, KA, refill_shift);
 
     // ---- S^T = K Q^T : sc[nt][hf][v] = score of query nt*16+r16 and key k0 + hf*16 + 4g + v
     f32x4 sc[NT][2];
@@ -364,7 +392,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
     if (NT != 1 && ti_refill >= 0) {
       // the products above must have read K before the loads below overwrite it
       asm volatile("" : "+v"(sc[0][0]), "+v"(sc[NT - 1][1]));
-      issue_k_loads<D, NT, APPEND, !MASKED>(src, kn0, P, last_row, r16, KA);
+      issue_k_loads<D, NT, APPEND, !MASKED>(src, kn0, P, last_row, r16, KA, refill_shift);
     }
 
     bf16x8 pB[NT];
@@ -533,14 +561,14 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
   }
 }
 
-hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan& plan, const void* q, void* k_cache,
+hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan& plan, const Pages& pg, const void* q, void* k_cache,
                                       void* v_cache, const void* k_new, const void* v_new, const int32_t* parent,
                                       const int32_t* depth, const int32_t* prefix_len, void* out, void* ws,
                                       int32_t* status, hipStream_t s) {
   // This kernel: one 16-query tile per K/V head, k_new / v_new laid out like q. Larger trees, grouped-query
   // heads and separately laid out k_new go to the wide kernel (the plan decides).
   if (plan.wide)
-    return launch_tree_attention_bf16_wide(d, plan, q, k_cache, v_cache, k_new, v_new, parent, depth, prefix_len, out, ws,
+    return launch_tree_attention_bf16_wide(d, plan, pg, q, k_cache, v_cache, k_new, v_new, parent, depth, prefix_len, out, ws,
                                            status, s);
   const float scale = (d.softmax_scale != 0.f ? d.softmax_scale : 1.0f / sqrtf((float)d.D)) * kLog2eB;
   float* ws_o = ws ? (float*)((char*)ws + plan.ws_o_off) : nullptr;
@@ -549,21 +577,25 @@ hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan&
   const bool append = k_new != nullptr;
   const bool bal = plan.balanced_wgs > 0;
   const dim3 grid = bal ? dim3(plan.balanced_wgs, 1, 1) : dim3(plan.n_splits, d.H * n_qgroups, d.B);
-#define SPEC_LAUNCH(DD, NTT, APP, BAL)                                                                           \
-  hipLaunchKernelGGL((tree_attention_bf16_kernel<DD, NTT, APP, BAL>), grid, dim3(WAVES * 64), 0, s,              \
+#define SPEC_LAUNCH(DD, NTT, APP, BAL, PGD)                                                                      \
+  hipLaunchKernelGGL((tree_attention_bf16_kernel<DD, NTT, APP, BAL, PGD>), grid, dim3(WAVES * 64), 0, s,         \
                      (const __hip_bfloat16*)q, (__hip_bfloat16*)k_cache, (__hip_bfloat16*)v_cache,               \
                      (const __hip_bfloat16*)k_new, (const __hip_bfloat16*)v_new, parent, depth, prefix_len,      \
                      (__hip_bfloat16*)out, ws_o, ws_ml, status, d.B, d.N, d.H, d.S_cap, n_qgroups,               \
                      plan.chunk_keys, plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h, \
-                     (long)d.kv_stride_b, (long)d.kv_stride_h, (long)d.kv_stride_s, scale)
-#define SPEC_DISPATCH(APP, BAL)                  \
-  if (d.D == 128) SPEC_LAUNCH(128, 1, APP, BAL); \
-  else SPEC_LAUNCH(64, 1, APP, BAL)
+                     (long)d.kv_stride_b, (long)d.kv_stride_h, (long)d.kv_stride_s, scale, pg)
+#define SPEC_DIMS(APP, BAL, PGD)                      \
+  if (d.D == 128) SPEC_LAUNCH(128, 1, APP, BAL, PGD); \
+  else SPEC_LAUNCH(64, 1, APP, BAL, PGD)
+#define SPEC_DISPATCH(APP, BAL)                             \
+  if (pg.table != nullptr) { SPEC_DIMS(APP, BAL, true); }   \
+  else { SPEC_DIMS(APP, BAL, false); }
   if (append && bal) { SPEC_DISPATCH(true, true); }
   else if (append) { SPEC_DISPATCH(true, false); }
   else if (bal) { SPEC_DISPATCH(false, true); }
   else { SPEC_DISPATCH(false, false); }
 #undef SPEC_DISPATCH
+#undef SPEC_DIMS
 #undef SPEC_LAUNCH
   return hipGetLastError();
 }

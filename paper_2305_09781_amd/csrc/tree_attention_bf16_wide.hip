@@ -85,14 +85,17 @@ __device__ inline float sum_over_lane_groups(float v) {
 
 // QW query wavefronts (NTW 16-query tiles each) x KW key parts: wavefront w serves query tiles
 // (w % QW) * NTW .. + NTW and (KW == 2) the 32-key half w / QW of every 64-key tile.
-template <int D, int QW, int NTW, int KW, int DEPTH, bool APPEND, int PLAN>
+// PAGED: the caches are pools of blocks addressed through pg.table (see cache_row_offset). Key tiles start
+// at multiples of 64 rows and a block holds a multiple of 64 rows, so a tile lies inside one block: its
+// rows are addressed as in a contiguous cache plus one per-tile offset (page_shift below).
+template <int D, int QW, int NTW, int KW, int DEPTH, bool APPEND, int PLAN, bool PAGED>
 __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kernel(
     const __hip_bfloat16* __restrict__ q, __hip_bfloat16* k_cache, __hip_bfloat16* v_cache,
     const __hip_bfloat16* __restrict__ k_new, const __hip_bfloat16* __restrict__ v_new,
     const int32_t* __restrict__ parent, const int32_t* __restrict__ depth, const int32_t* __restrict__ prefix_len,
     __hip_bfloat16* __restrict__ out, float* __restrict__ ws_o, float* __restrict__ ws_ml, int32_t* status, int B, int N,
     int H, int H_v, int n_qg, int hpw, int S_cap, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long n_sb, long n_sn,
-    long n_sh, long kv_sb, long kv_sh, long kv_ss, float scale_log2) {
+    long n_sh, long kv_sb, long kv_sh, long kv_ss, float scale_log2, Pages pg) {
   static_assert(KW == 1 || KW == 2, "a 64-key tile is consumed as two 32-key halves");
   static_assert(DEPTH == 2 || DEPTH == 4, "register sets of tiles in flight");
   constexpr int WAVES = QW * KW;
@@ -127,12 +130,23 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
   u32x4 Kr[DEPTH][NPT], Vr[DEPTH][NPT];
   const unsigned cache_row_bytes = (unsigned)kv_ss * 2u, new_row_bytes = (unsigned)n_sn * 2u;
   // Speculative request of one tile: cache rows only, clamped to the capacity, no prefix_len needed.
+  // Paged cache: byte offset that, added to `row * cache_row_bytes`, gives the place of logical row `row` of
+  // request b for every row of the 64-row tile at k0 (rows clamped to the capacity or to the request's last
+  // row stay inside the tile, hence inside its block). `ok`: the table entry lies inside the pool; one that
+  // does not is replaced by a block of the pool.
+  auto page_shift = [&](int b, int k0, bool* ok) -> long {
+    const int j = __builtin_amdgcn_readfirstlane(min(k0, S_cap - 1) >> pg.log2_tokens);
+    const int e = pg.table[(long)b * pg.max_blocks + j];
+    *ok = e >= 0 && e < pg.n_blocks;
+    const int blk = min(max(e, 0), pg.n_blocks - 1);
+    return (long)blk * kv_sb * 2 - (long)((unsigned)(j << pg.log2_tokens) * cache_row_bytes);
+  };
   auto issue_speculative = [&](u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT], const unsigned char* kbase, const unsigned char* vbase,
-                               int k0) {
+                               int k0, long shift) {
 #pragma unroll
     for (int j = 0; j < NPT; ++j) {
       const int row = min(k0 + ld_row0 + j * ROW_STEP, S_cap - 1);
-      const long off = (long)((unsigned)row * cache_row_bytes);
+      const long off = (long)((unsigned)row * cache_row_bytes) + shift;
       Vd[j] = *(const u32x4*)(vbase + off + ld_col);
       Kd[j] = *(const u32x4*)(kbase + off + ld_col);
     }
@@ -147,8 +161,8 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
 
     // ---- straight-line prologue: first two tiles (they do not depend on prefix_len), Q, one tree node per thread
     const int P = prefix_len[b];
-    const unsigned char* kc = (const unsigned char*)(k_cache + b * kv_sb + h * kv_sh);
-    const unsigned char* vc = (const unsigned char*)(v_cache + b * kv_sb + h * kv_sh);
+    const unsigned char* kc = (const unsigned char*)(k_cache + (PAGED ? 0 : b * kv_sb) + h * kv_sh);
+    const unsigned char* vc = (const unsigned char*)(v_cache + (PAGED ? 0 : b * kv_sb) + h * kv_sh);
     const unsigned char* kn = APPEND ? (const unsigned char*)(k_new + b * n_sb + h * n_sh) : nullptr;
     const unsigned char* vn = APPEND ? (const unsigned char*)(v_new + b * n_sb + h * n_sh) : nullptr;
     const long new_minus_cache_k = APPEND ? (long)(kn - kc) : 0, new_minus_cache_v = APPEND ? (long)(vn - vc) : 0;
@@ -156,16 +170,18 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     // MODE: 1 = clean (no clamp), 2 = tail (clamp, new rows)
     auto issue = [&](u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT], int k0, auto mode_tag, int Pk, int last_row) {
       constexpr int MODE = decltype(mode_tag)::value;
+      bool in_pool;
+      const long shift = PAGED ? page_shift(b, k0, &in_pool) : 0;
 #pragma unroll
       for (int j = 0; j < NPT; ++j) {
         int row = k0 + ld_row0 + j * ROW_STEP;
         long off_k, off_v;   // byte offsets from the cache bases (new rows: through the distance between the buffers)
         if (MODE == 1) {
-          off_k = off_v = (long)((unsigned)row * cache_row_bytes);
+          off_k = off_v = (long)((unsigned)row * cache_row_bytes) + shift;
         } else {
           row = min(row, last_row);
           const bool from_new = (MODE == 2) && APPEND && row >= Pk;
-          const long in_cache = (long)((unsigned)row * cache_row_bytes);
+          const long in_cache = (long)((unsigned)row * cache_row_bytes) + shift;
           const long in_new = (long)((unsigned)(row - Pk) * new_row_bytes);
           off_k = from_new ? new_minus_cache_k + in_new : in_cache;
           off_v = from_new ? new_minus_cache_v + in_new : in_cache;
@@ -174,8 +190,11 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
         Kd[j] = *(const u32x4*)(kc + off_k + ld_col);
       }
     };
-    issue_speculative(Kr[0], Vr[0], kc, vc, c0);
-    issue_speculative(Kr[1], Vr[1], kc, vc, c0 + KT);
+    {
+      bool in_pool;   // entries past the request's end may hold anything: not judged here
+      issue_speculative(Kr[0], Vr[0], kc, vc, c0, PAGED ? page_shift(b, c0, &in_pool) : 0);
+      issue_speculative(Kr[1], Vr[1], kc, vc, c0 + KT, PAGED ? page_shift(b, c0 + KT, &in_pool) : 0);
+    }
 
     // Query tiles of this workgroup: hpw of the `group` query heads that share the K/V head (heads
     // qg * hpw .. of the group), ceil(N/16) tiles each (multi-head attention: group = hpw = 1). Tile tl of
@@ -232,6 +251,12 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     const int n_tiles = (c1 - c0 + KT - 1) / KT;
     const int n_clean = max(0, min(P, c1) - c0) / KT;
     const int last_row = len - 1;
+    if (PAGED) {   // every block this segment reads must lie inside the pool
+      for (int j = (c0 >> pg.log2_tokens) + t; j <= ((c1 - 1) >> pg.log2_tokens); j += NTHREADS) {
+        const int e = pg.table[(long)b * pg.max_blocks + j];
+        if (e < 0 || e >= pg.n_blocks) set_status(status, b, SPEC_ST_BAD_BLOCK);
+      }
+    }
 
     // speculative tiles that reach the tree are fetched again from the right sources
     if (APPEND && n_clean == 0) issue(Kr[0], Vr[0], c0, std::integral_constant<int, 2>{}, P, last_row);
@@ -274,6 +299,8 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     auto stage_tile = [&](u32x4 (&Ks_)[NPT], u32x4 (&Vs_)[NPT], int ti, unsigned char* stage) {
       const int k0 = c0 + ti * KT;
       const bool masked = ti >= n_clean;
+      bool in_pool = true;   // paged cache: rows of a block outside the pool are not written
+      const long shift = (PAGED && APPEND && masked) ? page_shift(b, k0, &in_pool) : 0;
 #pragma unroll
       for (int j = 0; j < NPT; ++j) {
         const int rit = ld_row0 + j * ROW_STEP;
@@ -282,9 +309,9 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
           if (row >= c1) {
             Ks_[j] = (u32x4){0u, 0u, 0u, 0u};
             Vs_[j] = (u32x4){0u, 0u, 0u, 0u};
-          } else if (APPEND && qg == 0 && row >= P) {   // the pair's first query group writes the new rows
-            store_nt((unsigned char*)(k_cache + b * kv_sb + h * kv_sh) + (unsigned)row * cache_row_bytes + ld_col, Ks_[j]);
-            store_nt((unsigned char*)(v_cache + b * kv_sb + h * kv_sh) + (unsigned)row * cache_row_bytes + ld_col, Vs_[j]);
+          } else if (APPEND && qg == 0 && row >= P && in_pool) {   // the pair's first query group writes the new rows
+            store_nt((unsigned char*)kc + (unsigned)row * cache_row_bytes + shift + ld_col, Ks_[j]);
+            store_nt((unsigned char*)vc + (unsigned)row * cache_row_bytes + shift + ld_col, Vs_[j]);
           }
         }
         *(u32x4*)(stage + rit * ROWB + ld_col) = Ks_[j];
@@ -542,7 +569,7 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
 
 }  // namespace wide
 
-hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const AttnPlan& plan, const void* q, void* k_cache,
+hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const AttnPlan& plan, const Pages& pg, const void* q, void* k_cache,
                                            void* v_cache, const void* k_new, const void* v_new, const int32_t* parent,
                                            const int32_t* depth, const int32_t* prefix_len, void* out, void* ws,
                                            int32_t* status, hipStream_t s) {
@@ -558,26 +585,30 @@ hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const Attn
   const bool append = k_new != nullptr;
   const int mode = plan.balanced_wgs == 0 ? wide::PLAN_GRID : wide::PLAN_TILES;
   const dim3 grid = mode != wide::PLAN_GRID ? dim3(plan.balanced_wgs, 1, 1) : dim3(plan.n_splits, virtual_heads, d.B);
-#define SPEC_LAUNCH(DD, QQ, NTT, KK, DP, APP, PLAN)                                                                   \
-  hipLaunchKernelGGL((wide::tree_attention_bf16_wide_kernel<DD, QQ, NTT, KK, DP, APP, PLAN>), grid, dim3(QQ * KK * 64), 0, s, \
+#define SPEC_LAUNCH(DD, QQ, NTT, KK, DP, APP, PLAN, PGD)                                                              \
+  hipLaunchKernelGGL((wide::tree_attention_bf16_wide_kernel<DD, QQ, NTT, KK, DP, APP, PLAN, PGD>), grid, dim3(QQ * KK * 64), 0, s, \
                      (const __hip_bfloat16*)q, (__hip_bfloat16*)k_cache, (__hip_bfloat16*)v_cache,                    \
                      (const __hip_bfloat16*)k_new, (const __hip_bfloat16*)v_new, parent, depth, prefix_len,           \
                      (__hip_bfloat16*)out, ws_o, ws_ml, status, d.B, d.N, d.H, virtual_heads, qgr.n_qgroups,           \
                      qgr.heads_per_wg, d.S_cap, plan.chunk_keys,                                                      \
                      plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h, ns.b, ns.n, ns.h,     \
-                     (long)d.kv_stride_b, (long)d.kv_stride_h, (long)d.kv_stride_s, scale)
-#define SPEC_SHAPES(DD, APP, PLAN)                      \
-  if (qw == 2) SPEC_LAUNCH(DD, 2, 1, 2, 2, APP, PLAN);        \
-  else if (qw == 4) SPEC_LAUNCH(DD, 4, 1, 1, 2, APP, PLAN);   \
-  else SPEC_LAUNCH(DD, 8, 1, 1, 2, APP, PLAN)
-#define SPEC_DIMS(APP, PLAN)                            \
-  if (d.D == 128) { SPEC_SHAPES(128, APP, PLAN); }      \
-  else { SPEC_SHAPES(64, APP, PLAN); }
-#define SPEC_DISPATCH(APP)                                              \
-  if (mode == wide::PLAN_GRID) { SPEC_DIMS(APP, wide::PLAN_GRID); }     \
-  else { SPEC_DIMS(APP, wide::PLAN_TILES); }
+                     (long)d.kv_stride_b, (long)d.kv_stride_h, (long)d.kv_stride_s, scale, pg)
+#define SPEC_SHAPES(DD, APP, PLAN, PGD)                          \
+  if (qw == 2) SPEC_LAUNCH(DD, 2, 1, 2, 2, APP, PLAN, PGD);      \
+  else if (qw == 4) SPEC_LAUNCH(DD, 4, 1, 1, 2, APP, PLAN, PGD); \
+  else SPEC_LAUNCH(DD, 8, 1, 1, 2, APP, PLAN, PGD)
+#define SPEC_DIMS(APP, PLAN, PGD)                            \
+  if (d.D == 128) { SPEC_SHAPES(128, APP, PLAN, PGD); }      \
+  else { SPEC_SHAPES(64, APP, PLAN, PGD); }
+#define SPEC_PLANS(APP, PGD)                                                 \
+  if (mode == wide::PLAN_GRID) { SPEC_DIMS(APP, wide::PLAN_GRID, PGD); }     \
+  else { SPEC_DIMS(APP, wide::PLAN_TILES, PGD); }
+#define SPEC_DISPATCH(APP)                               \
+  if (pg.table != nullptr) { SPEC_PLANS(APP, true); }    \
+  else { SPEC_PLANS(APP, false); }
   if (append) { SPEC_DISPATCH(true); } else { SPEC_DISPATCH(false); }
 #undef SPEC_DISPATCH
+#undef SPEC_PLANS
 #undef SPEC_DIMS
 #undef SPEC_SHAPES
 #undef SPEC_LAUNCH

@@ -24,7 +24,7 @@ __global__ void __launch_bounds__(256) tree_attention_f32_kernel(
     const int32_t* __restrict__ parent, const int32_t* __restrict__ depth, const int32_t* __restrict__ prefix_len,
     float* __restrict__ out, float* __restrict__ ws_o, float* __restrict__ ws_ml, int32_t* status, int N, int H,
     int S_cap, int group, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long kv_sb, long kv_sh,
-    long kv_ss, float scale_log2) {
+    long kv_ss, float scale_log2, Pages pg) {
   extern __shared__ float smem[];
   __shared__ unsigned long long s_anc[SPEC_MAX_TREE_NODES][2];
   __shared__ int s_flag;
@@ -74,11 +74,16 @@ __global__ void __launch_bounds__(256) tree_attention_f32_kernel(
 #pragma unroll
   for (int r = 0; r < RMAX; ++r) acc[r] = make_float4(0.f, 0.f, 0.f, 0.f);
 
-  const float* kb = k_cache + b * kv_sb + (h / group) * kv_sh;   // grouped-query heads: `group` query heads per K/V head
-  const float* vb = v_cache + b * kv_sb + (h / group) * kv_sh;
+  const long head_off = (h / group) * kv_sh;   // grouped-query heads: `group` query heads per K/V head
 
   for (int k0 = c0; k0 < c1; k0 += F32_TK) {
     const int tk = min(F32_TK, c1 - k0);
+    // a tile starts at a multiple of 32 rows, so it lies inside one block of a paged cache
+    bool blk_ok;
+    const long tile_off = head_off + cache_row_offset(pg, b, k0, kv_sb, kv_ss, &blk_ok);
+    if (!blk_ok && t == 0) set_status(status, b, SPEC_ST_BAD_BLOCK);
+    const float* kb = k_cache + tile_off;
+    const float* vb = v_cache + tile_off;
     // scores of (query n, key k0+kk)
     for (int idx = t; idx < N * F32_TK; idx += 256) {
       const int n = idx / F32_TK, kk = idx % F32_TK;
@@ -89,7 +94,7 @@ __global__ void __launch_bounds__(256) tree_attention_f32_kernel(
         bool vis = rel < 0;
         if (!vis) vis = (s_anc[n][rel >> 6] >> (rel & 63)) & 1ull;
         if (vis) {
-          const float4* kr = (const float4*)(kb + (long)key * kv_ss);
+          const float4* kr = (const float4*)(kb + (long)kk * kv_ss);
           const float4* qr = (const float4*)(q_s + n * D);
           float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
 #pragma unroll 8
@@ -131,7 +136,7 @@ __global__ void __launch_bounds__(256) tree_attention_f32_kernel(
         a.x *= alpha; a.y *= alpha; a.z *= alpha; a.w *= alpha;
         for (int kk = 0; kk < tk; ++kk) {
           const float p = s_s[n * (F32_TK + 1) + kk];
-          const float4 vv = *(const float4*)(vb + (long)(k0 + kk) * kv_ss + cg * 4);
+          const float4 vv = *(const float4*)(vb + (long)kk * kv_ss + cg * 4);
           a.x = fmaf(p, vv.x, a.x); a.y = fmaf(p, vv.y, a.y); a.z = fmaf(p, vv.z, a.z); a.w = fmaf(p, vv.w, a.w);
         }
         acc[r] = a;
@@ -258,7 +263,7 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const float* __restri
   }
 }
 
-hipError_t launch_tree_attention_f32(const spec_attn_desc_t& d, const AttnPlan& plan, const float* q,
+hipError_t launch_tree_attention_f32(const spec_attn_desc_t& d, const AttnPlan& plan, const Pages& pg, const float* q,
                                      const float* k_cache, const float* v_cache, const int32_t* parent,
                                      const int32_t* depth, const int32_t* prefix_len, float* out, void* ws,
                                      int32_t* status, hipStream_t s) {
@@ -272,7 +277,7 @@ hipError_t launch_tree_attention_f32(const spec_attn_desc_t& d, const AttnPlan& 
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, q, k_cache, v_cache, parent, depth, prefix_len, out, ws_o, ws_ml,
                      status, d.N, d.H, d.S_cap, d.H / d.H_kv, plan.chunk_keys, plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n,
-                     (long)d.q_stride_h, (long)d.kv_stride_b, (long)d.kv_stride_h, (long)d.kv_stride_s, scale);
+                     (long)d.q_stride_h, (long)d.kv_stride_b, (long)d.kv_stride_h, (long)d.kv_stride_s, scale, pg);
   return hipGetLastError();
 }
 

@@ -257,6 +257,38 @@ def make_attention_inputs(cfg: Config, seed: Optional[int] = None, n_layers: int
     return out
 
 
+def to_paged(caches: Sequence[torch.Tensor], prefix_len, N: int, block_tokens: int, rng: np.random.Generator,
+             spare_blocks: int = 3, max_blocks: Optional[int] = None, unused_entry: int = -1):
+    """Re-lays contiguous caches [B,H_kv,S_cap,D] out as pools of blocks behind one block table (a storage
+    layout only: no arithmetic of the method). Request b gets ceil((prefix_len[b] + N) / block_tokens) blocks,
+    placed at random in the pool among `spare_blocks` unused ones; the pool's other rows hold large finite
+    garbage; table entries of blocks a request does not reach hold `unused_entry`.
+    Returns (pools: list of [n_blocks,H_kv,block_tokens,D], block_table int32 [B,max_blocks])."""
+    B, H, S, D = caches[0].shape
+    bt = block_tokens
+    need_blocks = (S + bt - 1) // bt
+    mb = need_blocks if max_blocks is None else max_blocks
+    used = [min(mb, (int(prefix_len[b]) + N + bt - 1) // bt) for b in range(B)]
+    n_blocks = sum(used) + spare_blocks
+    perm = rng.permutation(n_blocks)
+    table = np.full((B, mb), unused_entry, dtype=np.int32)
+    nxt = 0
+    for b in range(B):
+        for j in range(used[b]):
+            table[b, j] = perm[nxt]
+            nxt += 1
+    pools = []
+    for c in caches:
+        pool = _normal(rng, (n_blocks, H, bt, D), c.dtype, scale=100.0)
+        for b in range(B):
+            for j in range(used[b]):
+                rows = min(bt, S - j * bt)
+                if rows > 0:
+                    pool[int(table[b, j]), :, :rows] = c[b, :, j * bt:j * bt + rows]
+        pools.append(pool)
+    return pools, torch.from_numpy(table)
+
+
 # --------------------------------------------------------------------------------------------------
 # verification-side tensors
 # --------------------------------------------------------------------------------------------------
