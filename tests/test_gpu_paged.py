@@ -10,7 +10,7 @@ import torch
 
 from oracle import spec_oracle as orc
 from paper_2305_09781_amd import workloads as wl
-from test_gpu_parity import DEV, _balanced_wgs, _bits, _check_attention, _chunk_keys, _dev, _f64
+from test_gpu_parity import DEV, _balanced_wgs, _bits, _check_attention, _chunk_keys, _dev, _f64, _oracle_append_attention
 
 pytestmark = pytest.mark.gpu
 
@@ -69,6 +69,34 @@ def test_paged_append_and_attention(spec, case, fused):
     # the whole pool, bit for bit: the appended rows are in place and nothing else moved
     assert np.array_equal(kpd.double().cpu().numpy(), kpo) and np.array_equal(vpd.double().cpu().numpy(), vpo)
     _check_attention(out, ref, inp["q"][0].dtype)
+
+
+@pytest.mark.parametrize("c,bt", [(2, 64), (3, 128), (5, 256)])
+def test_full_size_configs_paged_sampled_heads(spec, c, bt):
+    """The benchmark's shapes with the caches scattered over a pool (fused append + attention); the oracle checks
+    sampled (request, head) pairs completely, on the logical caches the pool stands for."""
+    cfg = wl.CONFIGS[c]
+    inp = wl.make_attention_inputs(cfg)
+    pl = inp["prefix_len"].numpy()
+    pools, table = wl.to_paged([inp["k_cache"][0], inp["v_cache"][0]], pl, cfg.N, bt, np.random.default_rng(c))
+    kpd, vpd = _dev(pools[0]), _dev(pools[1])
+    status = torch.zeros(cfg.B, dtype=torch.int32, device=DEV)
+    out = spec.spec_tree_attention_append_paged(_dev(inp["q"][0]), _dev(inp["k_new"][0]), _dev(inp["v_new"][0]), kpd, vpd,
+                                                _dev(table), _dev(inp["tree_parent"]), _dev(inp["tree_depth"]),
+                                                _dev(inp["prefix_len"]), status=status, max_prefix_len=int(pl.max()))
+    torch.cuda.synchronize()
+    assert (status.cpu().numpy() == 0).all() and torch.isfinite(out.float()).all()
+    rng = np.random.default_rng(c)
+    bsel = sorted(set(int(x) for x in rng.integers(0, cfg.B, size=2)) | {cfg.B - 1})
+    hsel = sorted(set(int(x) for x in rng.integers(0, cfg.H, size=2)) | {0})
+    ref, kco, vco = _oracle_append_attention(inp, bsel=bsel, hsel=hsel)
+    _check_attention(out[bsel][:, :, hsel], ref, torch.bfloat16)
+    kp_host, vp_host, tab = kpd.cpu(), vpd.cpu(), table.numpy()
+    for i, b in enumerate(bsel):                                  # the appended rows, read back through the table
+        for s_ in range(int(pl[b]), int(pl[b]) + cfg.N):
+            e, r = int(tab[b, s_ // bt]), s_ % bt
+            assert np.array_equal(kp_host[e, hsel, r].double().numpy(), kco[i, :, s_])
+            assert np.array_equal(vp_host[e, hsel, r].double().numpy(), vco[i, :, s_])
 
 
 def test_paged_equals_contiguous_on_the_device(spec):
