@@ -71,6 +71,51 @@ def test_paged_append_and_attention(spec, case, fused):
     _check_attention(out, ref, inp["q"][0].dtype)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_randomised_paged_shapes_and_plans(spec, seed):
+    """Random small shapes (grouped heads, head dim, tree size, ragged prefixes down to zero, block sizes) under a
+    random launch plan, fused or not, some requests sharing their prefix blocks: parity, the pool bit for bit."""
+    rng = np.random.default_rng(7000 + seed)
+    dtype = "bf16" if rng.random() < 0.8 else "f32"
+    D = int(rng.choice([64, 128]))
+    H_kv = int(rng.integers(1, 4))
+    N = int(rng.choice([1, 5, 16, 17, 32, 33, 64, 65, 100, 128]))
+    group = int(rng.integers(1, 9)) if rng.random() < 0.3 else int(rng.integers(1, 3))
+    B = int(rng.integers(1, 5))
+    hi = int(rng.choice([0, 40, 130, 400, 700]))
+    lo = int(rng.integers(0, hi + 1))
+    bt = int(rng.choice([64, 128, 512]))
+    tree = str(rng.choice(["random_parent", "random_branching", "expansion"]))
+    cfg, inp, kp, vp, table = _paged_inputs(dtype, B, H_kv * group, H_kv, D, (lo, hi), N, tree, bt, seed=8000 + seed,
+                                            unused_entry=int(rng.choice([-1, 1 << 30, -(1 << 31)])))
+    pl, par = inp["prefix_len"].numpy(), inp["tree_parent"].numpy()
+    plan = int(rng.integers(0, 3))
+    chunk = int(rng.choice([32, 64, 96, 160])) if plan == 1 else 0
+    wgs = int(rng.integers(1, 12)) if plan == 2 and dtype == "bf16" else 0
+    fused = bool(rng.integers(0, 2))
+    kpo, vpo = _f64(kp), _f64(vp)
+    st_ref = orc.kv_append_paged(kpo, vpo, table.numpy(), bt, table.shape[1] * bt, _f64(inp["k_new"][0]),
+                                 _f64(inp["v_new"][0]), pl)
+    ref = orc.tree_attention_paged(_f64(inp["q"][0]), kpo, vpo, table.numpy(), bt, par, pl)
+    assert (st_ref == 0).all()
+    kpd, vpd, tab = _dev(kp), _dev(vp), _dev(table)
+    status = torch.zeros(B, dtype=torch.int32, device=DEV)
+    args = (tab, _dev(inp["tree_parent"]), _dev(inp["tree_depth"]), _dev(inp["prefix_len"]))
+    kn, vn = _dev(inp["k_new"][0]), _dev(inp["v_new"][0])
+    with _chunk_keys(chunk), _balanced_wgs(wgs):
+        if fused:
+            out = spec.spec_tree_attention_append_paged(_dev(inp["q"][0]), kn, vn, kpd, vpd, *args, status=status,
+                                                        max_prefix_len=int(pl.max()))
+        else:
+            spec.spec_kv_append_paged(kn, vn, kpd, vpd, tab, _dev(inp["prefix_len"]), status=status)
+            out = spec.spec_tree_attention_paged(_dev(inp["q"][0]), kpd, vpd, *args, status=status,
+                                                 max_prefix_len=int(pl.max()))
+    torch.cuda.synchronize()
+    assert (status.cpu().numpy() == 0).all()
+    assert np.array_equal(kpd.double().cpu().numpy(), kpo) and np.array_equal(vpd.double().cpu().numpy(), vpo)
+    _check_attention(out, ref, inp["q"][0].dtype)
+
+
 @pytest.mark.parametrize("c,bt", [(2, 64), (3, 128), (5, 256)])
 def test_full_size_configs_paged_sampled_heads(spec, c, bt):
     """The benchmark's shapes with the caches scattered over a pool (fused append + attention); the oracle checks
