@@ -18,6 +18,7 @@ struct AttnPlan {
   int balanced_wgs; // > 0: balanced plan with this many workgroups (see balanced_share), chunk_keys unused
   int balanced_tile;// keys per tile of the balanced deal (the tile of the kernel that runs the plan)
   bool wide;        // bf16: the wide kernel runs the plan (several query tiles per K/V head, or k_new not laid out like q)
+  int heads_per_wg; // wide kernel, whole key ranges: consecutive K/V heads of a request served by one workgroup
   size_t ws_o_off;  // float [B][H][n_splits][N][D]   un-normalised partial outputs
   size_t ws_ml_off; // float [B][H][n_splits][N][2]   running max (log2 domain) and partial sum
   size_t ws_bytes;

@@ -28,6 +28,7 @@
 // being processed as several segments.
 #include <hip/hip_bf16.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "spec_internal.h"
@@ -94,7 +95,7 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     const __hip_bfloat16* __restrict__ k_new, const __hip_bfloat16* __restrict__ v_new,
     const int32_t* __restrict__ parent, const int32_t* __restrict__ depth, const int32_t* __restrict__ prefix_len,
     __hip_bfloat16* __restrict__ out, float* __restrict__ ws_o, float* __restrict__ ws_ml, int32_t* status, int B, int N,
-    int H, int H_v, int n_qg, int hpw, int S_cap, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long n_sb, long n_sn,
+    int H, int H_v, int n_qg, int hpw, int heads_per_wg, int S_cap, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long n_sb, long n_sn,
     long n_sh, long kv_sb, long kv_sh, long kv_ss, float scale_log2, Pages pg) {
   static_assert(KW == 1 || KW == 2, "a 64-key tile is consumed as two 32-key halves");
   static_assert(DEPTH == 2 || DEPTH == 4, "register sets of tiles in flight");
@@ -155,7 +156,12 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
   // One segment: keys [c0, min(c1_cap, prefix_len + N)) of request b, virtual head hv = K/V head h and query
   // group qg (hpw of the H / H_kv query heads that share h). The result is the final output (slot < 0) or
   // float32 partials in slot `slot` of every query head served here.
-  auto segment = [&](const int b, const int hv, const int c0, const int c1_cap, const int slot) {
+  // nh > 1 (only with one query group per K/V head, one key part per wavefront and final outputs): the
+  // workgroup serves the nh consecutive K/V heads h .. h + nh - 1 of the request as ONE stream of nh * n_tiles
+  // tiles. The tree work is done once, the next head's first tiles are requested while the current head's
+  // last ones are computed, and its queries wait in registers (qB_next): a head boundary costs a normalise and
+  // store, not a prologue.
+  auto segment = [&](const int b, const int hv, const int c0, const int c1_cap, const int slot, const int nh) {
     const bool final_out = slot < 0;
     const int h = hv / n_qg, qg = hv % n_qg;
 
@@ -168,10 +174,12 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     const long new_minus_cache_k = APPEND ? (long)(kn - kc) : 0, new_minus_cache_v = APPEND ? (long)(vn - vc) : 0;
 
     // MODE: 1 = clean (no clamp), 2 = tail (clamp, new rows)
-    auto issue = [&](u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT], int k0, auto mode_tag, int Pk, int last_row) {
+    auto issue = [&](u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT], int k0, auto mode_tag, int Pk, int last_row, int hi) {
       constexpr int MODE = decltype(mode_tag)::value;
       bool in_pool;
-      const long shift = PAGED ? page_shift(b, k0, &in_pool) : 0;
+      // head hi of the stream: its cache rows lie hi * kv_sh further, its new rows hi * n_sh
+      const long shift = (PAGED ? page_shift(b, k0, &in_pool) : 0) + (long)hi * kv_sh * 2;
+      const long new_shift = (long)hi * n_sh * 2;
 #pragma unroll
       for (int j = 0; j < NPT; ++j) {
         int row = k0 + ld_row0 + j * ROW_STEP;
@@ -183,8 +191,8 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
           const bool from_new = (MODE == 2) && APPEND && row >= Pk;
           const long in_cache = (long)((unsigned)row * cache_row_bytes) + shift;
           const long in_new = (long)((unsigned)(row - Pk) * new_row_bytes);
-          off_k = from_new ? new_minus_cache_k + in_new : in_cache;
-          off_v = from_new ? new_minus_cache_v + in_new : in_cache;
+          off_k = from_new ? new_minus_cache_k + new_shift + in_new : in_cache;
+          off_v = from_new ? new_minus_cache_v + new_shift + in_new : in_cache;
         }
         Vd[j] = *(const u32x4*)(vc + off_v + ld_col);
         Kd[j] = *(const u32x4*)(kc + off_k + ld_col);
@@ -211,16 +219,20 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
       tile_head[nt] = min(hg, group - 1);
       tile_node[nt] = (tl % tiles_per_head) * 16 + r16;
     }
-    bf16x8 qB[NTW][KS];
+    bf16x8 qB[NTW][KS], qB_next[NTW][KS];
+    auto load_q = [&](bf16x8 (&dst)[NTW][KS], int hi) {
 #pragma unroll
-    for (int nt = 0; nt < NTW; ++nt) {
-      const int n = tile_node[nt], head = h * group + tile_head[nt];
+      for (int nt = 0; nt < NTW; ++nt) {
+        const int n = tile_node[nt], head = (h + hi) * group + tile_head[nt];
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const u32x4 raw = *(const u32x4*)(q + b * q_sb + min(n, N - 1) * q_sn + head * q_sh + ks * 32 + g * 8);
-        qB[nt][ks] = __builtin_bit_cast(bf16x8, raw);
+        for (int ks = 0; ks < KS; ++ks) {
+          const u32x4 raw = *(const u32x4*)(q + b * q_sb + min(n, N - 1) * q_sn + head * q_sh + ks * 32 + g * 8);
+          dst[nt][ks] = __builtin_bit_cast(bf16x8, raw);
+        }
       }
-    }
+    };
+    load_q(qB, 0);
+    if (nh > 1) load_q(qB_next, 1);
     const int my_parent = parent[(long)b * N + min(t, N - 1)];
     const int my_depth = depth[(long)b * N + min(t, N - 1)];
     if (t == 0) s_flag = 0;
@@ -234,10 +246,11 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     const int len = P + N;
     auto zero_outputs = [&](int bit) {
       if (final_out) {
-        for (int i = t; i < hpw * N * D; i += NTHREADS) {   // every query head served here, every node
-          const int hg = qg * hpw + i / (N * D), n = (i / D) % N;
-          if (hg < group) out[b * q_sb + n * q_sn + (h * group + hg) * q_sh + (i % D)] = __float2bfloat16(0.f);
-        }
+        for (int hi = 0; hi < nh; ++hi)
+          for (int i = t; i < hpw * N * D; i += NTHREADS) {   // every query head served here, every node
+            const int hg = qg * hpw + i / (N * D), n = (i / D) % N;
+            if (hg < group) out[b * q_sb + n * q_sn + ((h + hi) * group + hg) * q_sh + (i % D)] = __float2bfloat16(0.f);
+          }
         if (hv == 0 && t == 0) set_status(status, b, bit);
       }
     };
@@ -259,8 +272,14 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     }
 
     // speculative tiles that reach the tree are fetched again from the right sources
-    if (APPEND && n_clean == 0) issue(Kr[0], Vr[0], c0, std::integral_constant<int, 2>{}, P, last_row);
-    if (APPEND && n_clean <= 1 && n_tiles > 1) issue(Kr[1], Vr[1], c0 + KT, std::integral_constant<int, 2>{}, P, last_row);
+    if (APPEND && n_clean == 0) issue(Kr[0], Vr[0], c0, std::integral_constant<int, 2>{}, P, last_row, 0);
+    if (n_tiles > 1) {
+      if (APPEND && n_clean <= 1) issue(Kr[1], Vr[1], c0 + KT, std::integral_constant<int, 2>{}, P, last_row, 0);
+    } else if (nh > 1) {   // the second tile of the stream is the next head's first
+      if (KT <= P) issue(Kr[1], Vr[1], c0, std::integral_constant<int, 1>{}, P, last_row, 1);
+      else issue(Kr[1], Vr[1], c0, std::integral_constant<int, 2>{}, P, last_row, 1);
+    }
+    const int total_tiles = nh * n_tiles;   // tile gt of the stream: head gt / n_tiles, tile gt % n_tiles of that head
 
     // ---- tree: validate, build ancestor-or-self masks (LDS-only barriers: the tile loads stay in flight)
     unsigned long long anc_lo[NTW], anc_hi[NTW];
@@ -296,11 +315,13 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     }
 
     // registers -> LDS stage; masked tiles: rows past the segment end become zeros, appended rows go to the cache
-    auto stage_tile = [&](u32x4 (&Ks_)[NPT], u32x4 (&Vs_)[NPT], int ti, unsigned char* stage) {
+    auto stage_tile = [&](u32x4 (&Ks_)[NPT], u32x4 (&Vs_)[NPT], int gt, unsigned char* stage) {
+      int hi = 0, ti = gt;
+      while (ti >= n_tiles) { ti -= n_tiles; ++hi; }
       const int k0 = c0 + ti * KT;
       const bool masked = ti >= n_clean;
       bool in_pool = true;   // paged cache: rows of a block outside the pool are not written
-      const long shift = (PAGED && APPEND && masked) ? page_shift(b, k0, &in_pool) : 0;
+      const long shift = ((PAGED && APPEND && masked) ? page_shift(b, k0, &in_pool) : 0) + (long)hi * kv_sh * 2;
 #pragma unroll
       for (int j = 0; j < NPT; ++j) {
         const int rit = ld_row0 + j * ROW_STEP;
@@ -318,10 +339,12 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
         *(u32x4*)(stage + MAT_BYTES + rit * ROWB + ld_col) = Vs_[j];
       }
     };
-    auto issue_tile = [&](u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT], int ti) {
+    auto issue_tile = [&](u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT], int gt) {
+      int hi = 0, ti = gt;
+      while (ti >= n_tiles) { ti -= n_tiles; ++hi; }
       const int k0 = c0 + ti * KT;
-      if (k0 + KT <= P) issue(Kd, Vd, k0, std::integral_constant<int, 1>{}, P, last_row);
-      else issue(Kd, Vd, k0, std::integral_constant<int, 2>{}, P, last_row);
+      if (k0 + KT <= P) issue(Kd, Vd, k0, std::integral_constant<int, 1>{}, P, last_row, hi);
+      else issue(Kd, Vd, k0, std::integral_constant<int, 2>{}, P, last_row, hi);
     };
 
     f32x4 O[NTW][DB];
@@ -435,27 +458,65 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     // into that set.
 #pragma unroll
     for (int d = 2; d < DEPTH; ++d)
-      if (d < n_tiles) issue_tile(Kr[d], Vr[d], d);
+      if (d < total_tiles) issue_tile(Kr[d], Vr[d], d);
     stage_tile(Kr[0], Vr[0], 0, lds);
-    if (DEPTH < n_tiles) issue_tile(Kr[0], Vr[0], DEPTH);
-    if (n_tiles > 1) stage_tile(Kr[1], Vr[1], 1, lds + STAGE_BYTES);
-    if (DEPTH + 1 < n_tiles) issue_tile(Kr[1], Vr[1], DEPTH + 1);
+    if (DEPTH < total_tiles) issue_tile(Kr[0], Vr[0], DEPTH);
+    if (total_tiles > 1) stage_tile(Kr[1], Vr[1], 1, lds + STAGE_BYTES);
+    if (DEPTH + 1 < total_tiles) issue_tile(Kr[1], Vr[1], DEPTH + 1);
     lds_barrier();
     WTL(4)
-    auto step = [&](int ti, u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT]) {   // Kd, Vd: the register set of tile ti+2
-      unsigned char* cur = lds + (ti & 1) * STAGE_BYTES;
-      if (ti >= n_clean) compute(ti, cur, std::true_type{});
-      else compute(ti, cur, std::false_type{});
-      lds_barrier();
-      if (ti + 2 < n_tiles) {
-        stage_tile(Kd, Vd, ti + 2, cur);
-        if (ti + 2 + DEPTH < n_tiles) issue_tile(Kd, Vd, ti + 2 + DEPTH);
+    // Normalised output of the query tiles of stream head hi (final outputs only).
+    auto write_out = [&](const float (&l_tot)[NTW], int hi) {
+#pragma unroll
+      for (int nt = 0; nt < NTW; ++nt) {
+        const int n = tile_node[nt], head = (h + hi) * group + tile_head[nt];
+        if (kpart == 0 && tile_live[nt] && n < N) {
+          const float inv = 1.f / l_tot[nt];
+#pragma unroll
+          for (int db = 0; db < DB; ++db) {
+            union { uint2 u; __hip_bfloat16 h4[4]; } pk;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pk.h4[i] = __float2bfloat16(O[nt][db][i] * inv);
+            *(uint2*)(out + b * q_sb + n * q_sn + head * q_sh + db * 16 + 4 * g) = pk.u;
+          }
+        }
       }
     };
-    for (int ti = 0; ti < n_tiles; ti += DEPTH) {
+    int cur_head = 0, cur_ti = 0;   // head and in-head tile of the stream tile being computed
+    auto step = [&](int gt, u32x4 (&Kd)[NPT], u32x4 (&Vd)[NPT]) {   // Kd, Vd: the register set of tile gt+2
+      unsigned char* cur = lds + (gt & 1) * STAGE_BYTES;
+      if (cur_ti >= n_clean) compute(cur_ti, cur, std::true_type{});
+      else compute(cur_ti, cur, std::false_type{});
+      if (++cur_ti == n_tiles && cur_head + 1 < nh) {
+        // Head boundary (KW == 1: a wavefront owns its query tiles' whole state): write this head's outputs,
+        // take the next head's queries from qB_next, request the queries of the head after it.
+        float l_tot[NTW];
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) l_tot[nt] = sum_over_lane_groups(l_run[nt]);
+        write_out(l_tot, cur_head);
+        ++cur_head;
+        cur_ti = 0;
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) {
+          m_run[nt] = -INFINITY;
+          l_run[nt] = 0.f;
+#pragma unroll
+          for (int db = 0; db < DB; ++db) O[nt][db] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) qB[nt][ks] = qB_next[nt][ks];
+        }
+        if (cur_head + 1 < nh) load_q(qB_next, cur_head + 1);
+      }
+      lds_barrier();
+      if (gt + 2 < total_tiles) {
+        stage_tile(Kd, Vd, gt + 2, cur);
+        if (gt + 2 + DEPTH < total_tiles) issue_tile(Kd, Vd, gt + 2 + DEPTH);
+      }
+    };
+    for (int gt = 0; gt < total_tiles; gt += DEPTH) {
 #pragma unroll
       for (int d = 0; d < DEPTH; ++d)
-        if (ti + d < n_tiles) step(ti + d, Kr[(d + 2) % DEPTH], Vr[(d + 2) % DEPTH]);
+        if (gt + d < total_tiles) step(gt + d, Kr[(d + 2) % DEPTH], Vr[(d + 2) % DEPTH]);
     }
     lds_barrier();
     WTL(5)
@@ -498,21 +559,13 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
       }
     }
 
-    // ---- normalise and write (or emit the partial)
+    // ---- normalise and write the (last) head, or emit the partial
+    if (final_out) write_out(l_tot, nh - 1);
 #pragma unroll
     for (int nt = 0; nt < NTW; ++nt) {
       const int n = tile_node[nt], head = h * group + tile_head[nt];
       if (kpart == 0 && tile_live[nt] && n < N) {
-        if (final_out) {
-          const float inv = 1.f / l_tot[nt];
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            union { uint2 u; __hip_bfloat16 h4[4]; } pk;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) pk.h4[i] = __float2bfloat16(O[nt][db][i] * inv);
-            *(uint2*)(out + b * q_sb + n * q_sn + head * q_sh + db * 16 + 4 * g) = pk.u;
-          }
-        } else {
+        if (!final_out) {
           const long base = (((long)b * H + head) * n_splits + slot) * N + n;
 #pragma unroll
           for (int db = 0; db < DB; ++db) *(f32x4*)(ws_o + base * D + db * 16 + 4 * g) = O[nt][db];
@@ -535,7 +588,12 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
       const int r = hv % (8 * n_qg), blk = hv / (8 * n_qg);
       hv = (blk * 8 + r % 8) * n_qg + r / 8;
     }
-    segment(b, hv, split * chunk_keys, split * chunk_keys + chunk_keys, n_splits == 1 ? -1 : split);
+    if (heads_per_wg > 1) {   // several K/V heads per workgroup (host: one query group per head, no key split)
+      hv *= heads_per_wg;
+      segment(b, hv, 0, chunk_keys, -1, min(heads_per_wg, H_v - hv));
+    } else {
+      segment(b, hv, split * chunk_keys, split * chunk_keys + chunk_keys, n_splits == 1 ? -1 : split, 1);
+    }
   } else {
     // Tiles [pos, end) of the flattened (request, head, key tile) order belong to this workgroup.
     // n_splits is the number of partial slots per pair; the workgroups overlapping a pair fill slots
@@ -556,7 +614,7 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
       const int hv = (int)(in_req / tb), tile0 = (int)(in_req % tb);
       const int n_take = (int)min((long)(tb - tile0), end - pos);
       const int slot = (int)blockIdx.x - (int)((req_start + (long)hv * tb) / bs.share);
-      segment(b, hv, tile0 * KT, (tile0 + n_take) * KT, slot);
+      segment(b, hv, tile0 * KT, (tile0 + n_take) * KT, slot, 1);
       pos += n_take;
       lds_barrier();   // LDS (staging tiles, merge area, tree arrays) is reused by the next segment
     }
@@ -584,13 +642,19 @@ hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const Attn
   const NewStrides ns = attn_new_strides(d);
   const bool append = k_new != nullptr;
   const int mode = plan.balanced_wgs == 0 ? wide::PLAN_GRID : wide::PLAN_TILES;
-  const dim3 grid = mode != wide::PLAN_GRID ? dim3(plan.balanced_wgs, 1, 1) : dim3(plan.n_splits, virtual_heads, d.B);
+  // Whole key ranges, one query group per K/V head, a wavefront per query tile: a workgroup may serve several
+  // consecutive K/V heads of a request as one stream (the plan decides how many).
+  const int heads_per_wg = (mode == wide::PLAN_GRID && plan.n_splits == 1 && qgr.n_qgroups == 1 && qw == 8)
+                               ? std::max(1, plan.heads_per_wg) : 1;
+  const dim3 grid = mode != wide::PLAN_GRID
+                        ? dim3(plan.balanced_wgs, 1, 1)
+                        : dim3(plan.n_splits, (virtual_heads + heads_per_wg - 1) / heads_per_wg, d.B);
 #define SPEC_LAUNCH(DD, QQ, NTT, KK, DP, APP, PLAN, PGD)                                                              \
   hipLaunchKernelGGL((wide::tree_attention_bf16_wide_kernel<DD, QQ, NTT, KK, DP, APP, PLAN, PGD>), grid, dim3(QQ * KK * 64), 0, s, \
                      (const __hip_bfloat16*)q, (__hip_bfloat16*)k_cache, (__hip_bfloat16*)v_cache,                    \
                      (const __hip_bfloat16*)k_new, (const __hip_bfloat16*)v_new, parent, depth, prefix_len,           \
                      (__hip_bfloat16*)out, ws_o, ws_ml, status, d.B, d.N, d.H, virtual_heads, qgr.n_qgroups,           \
-                     qgr.heads_per_wg, d.S_cap, plan.chunk_keys,                                                      \
+                     qgr.heads_per_wg, heads_per_wg, d.S_cap, plan.chunk_keys,                                        \
                      plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h, ns.b, ns.n, ns.h,     \
                      (long)d.kv_stride_b, (long)d.kv_stride_h, (long)d.kv_stride_s, scale, pg)
 #define SPEC_SHAPES(DD, APP, PLAN, PGD)                          \

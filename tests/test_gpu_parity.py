@@ -307,6 +307,47 @@ def test_randomised_shapes_and_plans(spec, seed):
     assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco)
 
 
+@pytest.mark.parametrize("case", [
+    # B, H, H_kv, D, (P lo, hi), N, K/V heads per workgroup, fused
+    (2, 5, 5, 128, (100, 300), 128, 2, True),     # uneven: the last workgroup of a request serves one head
+    (2, 6, 6, 128, (100, 300), 97, 3, False),
+    (3, 4, 4, 64, (0, 20), 80, 2, True),          # two tiles per head, both masked
+    (2, 4, 4, 128, (0, 0), 65, 4, True),          # empty prefix
+    (1, 8, 8, 128, (500, 500), 128, 8, True),
+    (2, 3, 3, 128, (64, 200), 100, 7, False),     # more heads per workgroup than heads
+    (3, 24, 3, 128, (0, 48), 16, 2, True),        # grouped heads, 8 tiles per K/V head; one tile per head: the
+    (3, 24, 3, 64, (0, 48), 13, 3, False),        # stream's second tile is the next head's first
+    (2, 32, 4, 128, (30, 200), 16, 4, True),
+], ids=lambda c: f"B{c[0]}H{c[1]}kv{c[2]}D{c[3]}P{c[4][0]}-{c[4][1]}N{c[5]}-nh{c[6]}-{'fused' if c[7] else 'two-calls'}")
+def test_several_heads_per_workgroup(spec, case):
+    """Wide trees on the eight-wavefront shape: a workgroup serves consecutive heads of a request as one stream
+    of tiles. Forced on small inputs; parity, bit-exact append, and the defined results of flagged requests."""
+    B, H, H_kv, D, P, N, nh, fused = case
+    cfg = wl.Config(89, "heads", "bf16", B=B, H=H, D=D, P=P if P[0] != P[1] else P[0], N=N, tree="random_branching",
+                    H_kv=H_kv)
+    inp = wl.make_attention_inputs(cfg, seed=900 + N + nh, S_cap=P[1] + N + 3)
+    ref, kco, vco = _oracle_append_attention(inp)
+    with _plan_env("SPEC_TREE_HEADS_PER_WG", nh):
+        out, kc, vc = _run_append_attention(spec, inp, fused=fused)
+        _check_attention(out, ref, torch.bfloat16)
+        assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco)
+        # a malformed tree and a request that does not fit: zeros for every head, the others served
+        if B >= 2:
+            bad = dict(inp)
+            bad["tree_parent"] = inp["tree_parent"].clone()
+            bad["tree_parent"][0, N - 1] = N - 1
+            bad["prefix_len"] = inp["prefix_len"].clone()
+            bad["prefix_len"][1] = inp["k_cache"][0].shape[2] - N + 1
+            status = torch.zeros(B, dtype=torch.int32, device=DEV)
+            out2, kc2, _ = _run_append_attention(spec, bad, status=status, fused=fused)
+            st = status.cpu().numpy()
+            assert st[0] & orc.ST_BAD_TREE and st[1] & orc.ST_CAPACITY
+            assert (out2[:2].float() == 0).all()
+            assert np.array_equal(_bits(kc2[1]), _bits(inp["k_cache"][0][1]))
+            if B > 2:
+                _check_attention(out2[2:], ref[2:], torch.bfloat16)
+
+
 @pytest.mark.parametrize("N,scale", [(16, 6.0), (40, 6.0), (128, 4.0), (16, 0.01), (64, 0.01)])
 def test_peaked_and_flat_score_distributions(spec, N, scale):
     """Scores far outside the unit range (the running maximum moves by many powers of two between tiles,
