@@ -19,6 +19,10 @@ What each function follows:
   expand_topk, tree_merge     Section 3: one step of expansion-based construction; Definition 3.2
   kv_commit              Algorithm 2 main loop (verified tokens are appended to the sequence), so the
                          K/V rows of the accepted path must become the contiguous prefix
+  lm_head_logits, lm_head_argmax
+                         the LLM's output projection in front of VerifyGreedy (Algorithm 2 takes O(u) from the
+                         LLM's distribution at node u; for greedy decoding only its arg-max is needed): logits =
+                         hidden . W^T, O(u) = argmax, lowest token id on ties. A step adjacent to the path.
   paged_rows, paged_gather, kv_append_paged, tree_attention_paged, kv_commit_paged
                          the same steps on a cache kept as a pool of blocks behind a block table (a
                          storage layout next to the path, not in the paper): logical row s of request b
@@ -33,7 +37,8 @@ Theorem 4.3 and the low-temperature limit against the greedy verifier (naive sam
 overlapping-path cases (append / commit); sequence-set equality by brute force, idempotence, chains
 merging into a trie (tree merge); scalar selection loop and the argmax special case (top-k); identity
 tables against the contiguous functions, invariance under a relabelling of the blocks, shared prefix blocks
-and a hand-derived two-block case (paged caches). No function is unpinned.
+and a hand-derived two-block case (paged caches); scalar triple loop, one-hot weights and a hand-derived case
+(LM head). No function is unpinned.
 
 Readings taken where the paper is silent are listed next to each function.
 """
@@ -582,3 +587,24 @@ def kv_commit_paged(k_pools, v_pools, block_table, block_tokens, S_cap, accepted
                 vc[ed, :, rd, :] = vc[es, :, rs, :]
         out_len[b] = p + n
     return out_len, status
+
+
+# ---------------------------------------------------------------------------------------------
+# LM head in front of the greedy verifier
+# ---------------------------------------------------------------------------------------------
+
+def lm_head_logits(hidden, weight):
+    """logits[m, v] = sum_k hidden[m, k] * weight[v, k] in float64 (hidden [M,K], weight [V,K])."""
+    return np.asarray(hidden, dtype=np.float64) @ np.asarray(weight, dtype=np.float64).T
+
+
+def lm_head_argmax(hidden, weight):
+    """O(u) for every row: (argmax over the vocabulary with the lowest token id on ties, the maximum, and
+    the gap to the runner-up: a row whose gap is within float32 rounding of zero has no unique answer)."""
+    logits = lm_head_logits(hidden, weight)
+    arg = logits.argmax(axis=1).astype(np.int32)          # numpy: first maximum = lowest id
+    top = logits.max(axis=1)
+    rest = logits.copy()
+    rest[np.arange(logits.shape[0]), arg] = -np.inf
+    gap = top - rest.max(axis=1) if logits.shape[1] > 1 else np.full(logits.shape[0], np.inf)
+    return arg, top, gap
