@@ -257,6 +257,30 @@ int spec_kv_commit(const spec_attn_desc_t* desc, int32_t n_layers, void* const* 
                    int32_t* prefix_len_out /*[B]*/, int32_t* status, void* hip_stream);
 
 /*
+ * LM head in front of the greedy verifier (Algorithm 2, VerifyGreedy: O(u) is the arg-max of the LLM's
+ * distribution at node u, so greedy verification needs no logits in memory). For every row m of `hidden`:
+ *     node_argmax[m] = argmax_v  sum_k hidden[m,k] * weight[v,k]    (lowest v among equal maxima),
+ *     node_max[m]    = that maximum (float32; may be NULL),
+ * hidden [M,K] and weight [V,K] bf16, K contiguous (the layout of a linear layer's weight), K a multiple of
+ * 128, both 16-byte aligned; products accumulate in float32 on the matrix cores, so two logits closer than
+ * float32 rounding of the sum may compare either way. Built for the few hundred rows of a verification
+ * pass (M = B*N), where the product is bound by one pass over `weight`; larger M is served in slices of
+ * 128 rows, each streaming `weight` again.
+ * spec_verify_greedy_lm_head = this (M = B*N, row b*N + u is node u of request b) followed by the walk of
+ * spec_verify_greedy; node_argmax [B,N] may be NULL (then it lives in the workspace).
+ * workspace: spec_lm_head_argmax_workspace_bytes(M, V) bytes, 256-byte aligned; contents are scratch.
+ */
+size_t spec_lm_head_argmax_workspace_bytes(int32_t M, int32_t V);
+int spec_lm_head_argmax(int32_t M, int32_t K, int32_t V, const void* hidden, const void* weight,
+                        int32_t* node_argmax /*[M]*/, float* node_max /*[M] or NULL*/, void* workspace,
+                        size_t workspace_bytes, void* hip_stream);
+int spec_verify_greedy_lm_head(int32_t B, int32_t N, int32_t K, int32_t V, const void* hidden /*[B*N,K]*/,
+                               const void* weight /*[V,K]*/, const int32_t* tree_token, const int32_t* tree_parent,
+                               int32_t Lmax, int32_t* accepted_path, int32_t* accepted_len, int32_t* out_tokens,
+                               int32_t* node_argmax /*[B,N] or NULL*/, void* workspace, size_t workspace_bytes,
+                               int32_t* status, void* hip_stream);
+
+/*
  * Paged KV caches (beyond the paper, whose cache is one contiguous region per request; the steps are
  * those of Section 4.2 and Algorithm 2 unchanged, only the place of a cache row differs). Each cache is
  * a pool of n_blocks blocks of block_tokens rows, [n_blocks, H_kv, block_tokens, D]: in the descriptor

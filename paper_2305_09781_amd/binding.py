@@ -28,6 +28,7 @@ EXPORTED = [
     "spec_version",
     "spec_kv_append_paged", "spec_kv_append_rope_paged", "spec_tree_attention_paged", "spec_tree_attention_append_paged",
     "spec_tree_attention_paged_workspace_bytes", "spec_kv_commit_paged",
+    "spec_lm_head_argmax", "spec_lm_head_argmax_workspace_bytes", "spec_verify_greedy_lm_head",
 ]
 
 
@@ -110,6 +111,12 @@ def load():
     lib.spec_tree_attention_paged_workspace_bytes.restype = sz
     lib.spec_kv_commit_paged.argtypes = [dp, pp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i32, vp, vp, vp, vp, vp]
     lib.spec_kv_commit_paged.restype = ctypes.c_int
+    lib.spec_lm_head_argmax_workspace_bytes.argtypes = [i32, i32]
+    lib.spec_lm_head_argmax_workspace_bytes.restype = sz
+    lib.spec_lm_head_argmax.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.spec_lm_head_argmax.restype = ctypes.c_int
+    lib.spec_verify_greedy_lm_head.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp, vp]
+    lib.spec_verify_greedy_lm_head.restype = ctypes.c_int
     lib.spec_probe_read_stream.argtypes = [vp, sz, vp, vp]
     lib.spec_probe_read_stream.restype = ctypes.c_int
     lib.spec_strerror.argtypes = [ctypes.c_int]
@@ -468,6 +475,55 @@ def spec_kv_commit_paged(k_pools: Sequence[torch.Tensor], v_pools: Sequence[torc
                                        accepted_path.shape[1], _ptr(accepted_len), _ptr(prefix_len), _ptr(prefix_len_out),
                                        _ptr(status), _stream(stream)), "spec_kv_commit_paged")
     return prefix_len_out
+
+
+# ------------------------------------------------------------------------------------------------
+# LM head in front of the greedy verifier
+# ------------------------------------------------------------------------------------------------
+
+def spec_lm_head_argmax_workspace_bytes(M: int, V: int) -> int:
+    return int(load().spec_lm_head_argmax_workspace_bytes(M, V))
+
+
+def _lm_head_args(hidden, weight):
+    if hidden.dtype != torch.bfloat16 or weight.dtype != torch.bfloat16 or hidden.dim() != 2 or weight.dim() != 2 or \
+            hidden.shape[1] != weight.shape[1] or not hidden.is_contiguous() or not weight.is_contiguous():
+        raise ValueError("hidden [M,K] and weight [V,K] must be contiguous bf16 with the same K")
+    return hidden.shape[0], hidden.shape[1], weight.shape[0]
+
+
+def spec_lm_head_argmax(hidden, weight, want_max: bool = False, workspace=None, stream=None):
+    """(node_argmax [M] int32, node_max [M] float32 or None) of hidden . weight^T without the logits in memory."""
+    M, K, V = _lm_head_args(hidden, weight)
+    arg = torch.empty(M, dtype=torch.int32, device=hidden.device)
+    mx = torch.empty(M, dtype=torch.float32, device=hidden.device) if want_max else None
+    if workspace is None:
+        workspace = torch.empty(max(spec_lm_head_argmax_workspace_bytes(M, V), 256), dtype=torch.uint8, device=hidden.device)
+    _check(load().spec_lm_head_argmax(M, K, V, _ptr(hidden), _ptr(weight), _ptr(arg), _ptr(mx), _ptr(workspace),
+                                      workspace.numel(), _stream(stream)), "spec_lm_head_argmax")
+    return arg, mx
+
+
+def spec_verify_greedy_lm_head(hidden, weight, tree_token, tree_parent, Lmax: Optional[int] = None, workspace=None,
+                               status=None, stream=None, out=None):
+    """Greedy verification from the LLM's last hidden states [B*N, K] and its output projection [V, K].
+    Returns (accepted_path [B,Lmax], accepted_len [B], out_tokens [B,Lmax], node_argmax [B,N])."""
+    M, K, V = _lm_head_args(hidden, weight)
+    B, N = tree_token.shape
+    if M != B * N:
+        raise ValueError("hidden must have B*N rows")
+    Lmax = N if Lmax is None else Lmax
+    dev = hidden.device
+    if out is None:
+        out = (torch.empty((B, Lmax), dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+               torch.empty((B, Lmax), dtype=torch.int32, device=dev), torch.empty((B, N), dtype=torch.int32, device=dev))
+    if workspace is None:
+        workspace = torch.empty(max(spec_lm_head_argmax_workspace_bytes(M, V), 256), dtype=torch.uint8, device=dev)
+    _check(load().spec_verify_greedy_lm_head(B, N, K, V, _ptr(hidden), _ptr(weight), _ptr(tree_token), _ptr(tree_parent),
+                                             Lmax, _ptr(out[0]), _ptr(out[1]), _ptr(out[2]), _ptr(out[3]),
+                                             _ptr(workspace), workspace.numel(), _ptr(status), _stream(stream)),
+           "spec_verify_greedy_lm_head")
+    return out
 
 
 def spec_probe_read_stream(buf: torch.Tensor, sink: torch.Tensor, stream=None):

@@ -18,7 +18,7 @@ LIB_DIR = os.path.join(PKG_DIR, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libspectree.so")
 
 SOURCES = ["spec_api.hip", "kv_cache.hip", "tree_attention_f32.hip", "tree_attention_bf16.hip",
-           "tree_attention_bf16_wide.hip", "verify.hip", "tree_build.hip", "probe.hip"]
+           "tree_attention_bf16_wide.hip", "verify.hip", "tree_build.hip", "lm_head.hip", "probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=fast",

@@ -410,6 +410,53 @@ int spec_verify_greedy(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, co
   return SPEC_OK;
 }
 
+size_t spec_lm_head_argmax_workspace_bytes(int32_t M, int32_t V) {
+  if (M <= 0 || V <= 0) return 0;
+  // the partials, then room for node_argmax when the caller of spec_verify_greedy_lm_head does not want it
+  return lm_head_partials_bytes(M, V) + round_up((size_t)M * sizeof(int32_t), 256);
+}
+
+static int check_lm_head(int32_t M, int32_t K, int32_t V, const void* hidden, const void* weight, const void* workspace,
+                         size_t workspace_bytes) {
+  if (M <= 0 || K <= 0 || V <= 0) return SPEC_ERR_INVALID_ARG;
+  if (K % 128 != 0) return SPEC_ERR_UNSUPPORTED;
+  if (!hidden || !weight || !aligned16(hidden) || !aligned16(weight)) return SPEC_ERR_INVALID_ARG;
+  if (workspace == nullptr || workspace_bytes < spec_lm_head_argmax_workspace_bytes(M, V)) return SPEC_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return SPEC_ERR_INVALID_ARG;
+  return SPEC_OK;
+}
+
+int spec_lm_head_argmax(int32_t M, int32_t K, int32_t V, const void* hidden, const void* weight, int32_t* node_argmax,
+                        float* node_max, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int rc = check_lm_head(M, K, V, hidden, weight, workspace, workspace_bytes);
+  if (rc != SPEC_OK) return rc;
+  if (!node_argmax) return SPEC_ERR_INVALID_ARG;
+  return launch_lm_head_argmax(M, K, V, hidden, weight, node_argmax, node_max, workspace, (hipStream_t)hip_stream) ==
+                 hipSuccess
+             ? SPEC_OK
+             : SPEC_ERR_HIP;
+}
+
+int spec_verify_greedy_lm_head(int32_t B, int32_t N, int32_t K, int32_t V, const void* hidden, const void* weight,
+                               const int32_t* tree_token, const int32_t* tree_parent, int32_t Lmax,
+                               int32_t* accepted_path, int32_t* accepted_len, int32_t* out_tokens, int32_t* node_argmax,
+                               void* workspace, size_t workspace_bytes, int32_t* status, void* hip_stream) {
+  if (B <= 0 || N <= 0 || Lmax <= 0) return SPEC_ERR_INVALID_ARG;
+  if (N > SPEC_MAX_TREE_NODES) return SPEC_ERR_UNSUPPORTED;
+  if ((long)B * N > 0x7fffffffL) return SPEC_ERR_UNSUPPORTED;
+  const int M = B * N;
+  const int rc = check_lm_head(M, K, V, hidden, weight, workspace, workspace_bytes);
+  if (rc != SPEC_OK) return rc;
+  if (!tree_token || !tree_parent || !accepted_path || !accepted_len || !out_tokens) return SPEC_ERR_INVALID_ARG;
+  if (node_argmax == nullptr) node_argmax = (int32_t*)((char*)workspace + lm_head_partials_bytes(M, V));
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (launch_lm_head_argmax(M, K, V, hidden, weight, node_argmax, nullptr, workspace, s) != hipSuccess) return SPEC_ERR_HIP;
+  if (launch_greedy_walk(B, N, node_argmax, tree_token, tree_parent, Lmax, accepted_path, accepted_len, out_tokens,
+                         status, s) != hipSuccess)
+    return SPEC_ERR_HIP;
+  return SPEC_OK;
+}
+
 size_t spec_verify_naive_workspace_bytes(int32_t B, int32_t N, int32_t V) {
   if (B <= 0 || N <= 0 || V <= 0) return 0;
   // node max, then the sampled tokens when the caller does not want them
