@@ -283,6 +283,10 @@ __global__ void __launch_bounds__(SW_THREADS) stochastic_walk_kernel(
   __shared__ int s_flag;
   __shared__ int s_child[SPEC_MAX_TREE_NODES];
   __shared__ int s_sorted[SPEC_MAX_TREE_NODES];
+  __shared__ int s_cx[SPEC_MAX_TREE_NODES];       // per child in test order: its token,
+  __shared__ float s_cq[SPEC_MAX_TREE_NODES];     // the draft's probability of that token,
+  __shared__ float s_cl[SPEC_MAX_TREE_NODES];     // the LLM's logit of that token at u,
+  __shared__ float s_cr[SPEC_MAX_TREE_NODES];     // and the child's uniform
   __shared__ int s_nchild;
   __shared__ float s_fsum[SW_THREADS / 64];
   __shared__ double s_scan[SW_THREADS / 64];
@@ -345,15 +349,26 @@ __global__ void __launch_bounds__(SW_THREADS) stochastic_walk_kernel(
     bool accepted = false;
     int next_u = -1;
     const long lrow = ((long)b * N + u) * V;
+    // everything a ratio test needs from memory, for all children at once (one round trip instead of one
+    // chain of dependent loads per test)
+    if (t < nchild) {
+      const int s = s_sorted[t];
+      const int x = tok[s];
+      s_cx[t] = x;
+      s_cq[t] = probs_ssm[(long)ssm_row[(long)b * N + s] * V + x];
+      s_cl[t] = load_logit<BF16>(logits, lrow + x);
+      s_cr[t] = u_accept[(long)b * N + s];
+    }
+    __syncthreads();
     for (int j = 0; j < nchild; ++j) {
       const int s = s_sorted[j];
-      const int x = tok[s];
+      const int x = s_cx[j];
       const float* Q = probs_ssm + (long)ssm_row[(long)b * N + s] * V;
-      const float r = u_accept[(long)b * N + s];
+      const float r = s_cr[j];
       float px;
-      if (implicit) px = expf((load_logit<BF16>(logits, lrow + x) - mx) * inv_temp) / se;
+      if (implicit) px = expf((s_cl[j] - mx) * inv_temp) / se;
       else px = resid[x] / Z;
-      if (r * Q[x] <= px) {
+      if (r * s_cq[j] <= px) {
         accepted = true;
         next_u = s;
         if (t == 0) {
