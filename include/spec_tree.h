@@ -262,7 +262,7 @@ int spec_kv_commit(const spec_attn_desc_t* desc, int32_t n_layers, void* const* 
  *     node_argmax[m] = argmax_v  sum_k hidden[m,k] * weight[v,k]    (lowest v among equal maxima),
  *     node_max[m]    = that maximum (float32; may be NULL),
  * hidden [M,K] and weight [V,K] bf16, K contiguous (the layout of a linear layer's weight), K a multiple of
- * 128, both 16-byte aligned; products accumulate in float32 on the matrix cores, so two logits closer than
+ * 256, both 16-byte aligned; products accumulate in float32 on the matrix cores, so two logits closer than
  * float32 rounding of the sum may compare either way. Built for the few hundred rows of a verification
  * pass (M = B*N), where the product is bound by one pass over `weight`; larger M is served in slices of
  * 128 rows, each streaming `weight` again.

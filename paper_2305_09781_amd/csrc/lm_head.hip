@@ -9,7 +9,7 @@
 // wavefront and up to 128 rows of `hidden` (NMT tiles of 16). Every wavefront streams ITS 16 rows of W straight from global
 // memory into the MFMA A-operand layout (lane (r, g) holds W[v0 + r][k0 + 8g .. 8g + 8)), PF chunks of 64 k
 // in flight, independent of the other wavefronts; `hidden` (L2-resident, shared by all wavefronts) is staged
-// through LDS in slices of 128 k, double-buffered, one barrier per slice. The product is taken transposed,
+// through LDS in slices of 256 k, double-buffered, one barrier per slice. The product is taken transposed,
 // C[v, m], so a lane ends up with four vocabulary entries of ONE row m and the arg-max over v is four
 // compares, two cross-lane steps and one pass through LDS over the eight wavefronts. Each workgroup writes its
 // (max, arg-max) per row; lm_head_reduce_kernel merges a row's partials (one per workgroup).
@@ -27,7 +27,8 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 constexpr int KC = 64;                        // k per chunk of W (two MFMA k-steps)
-constexpr int HC = 128;                       // k per LDS slice of hidden (two chunks)
+constexpr int HC = 256;                       // k per LDS slice of hidden (four chunks)
+constexpr int CPS = HC / KC;                  // chunks per slice
 constexpr int PF = 8;                         // chunks of W in flight per wavefront
 constexpr int HROW = HC * 2 + 16;             // LDS bytes per hidden row (+16: 16 rows fall into 16 distinct bank groups)
 
@@ -79,10 +80,11 @@ __global__ void __launch_bounds__(WAVES * 64) lm_head_argmax_kernel(const __hip_
     if (c < NC) issue_w(Wr[c], c);
 
   // hidden slice s: rows m0 .. m0 + MROWS (rows past M repeat the last one), k in [s * HC, s * HC + HC)
-  // Two register sets: a slice is requested two slices before it is staged. Loads return in order, so waiting
-  // for a slice also waits for every older load of W; with a distance of two slices those are loads that had
-  // to be back by then anyway, and the PF chunks of W requested since stay in flight.
-  u32x4 Hr2[2][NPT];
+  // A slice is requested one slice (four chunks) before it is staged. Loads return in order, so waiting for a
+  // slice also waits for every older load of W; at a distance of four chunks those are loads that had to be
+  // back by then anyway, and the chunks of W requested since stay in flight (with slices of two chunks the
+  // compiler's wait counts showed the stream being cut to 2-3 chunks per wavefront at every slice boundary).
+  u32x4 Hreg[NPT];
   auto issue_h = [&](u32x4 (&Hr)[NPT], int s) {
 #pragma unroll
     for (int j = 0; j < NPT; ++j) {
@@ -103,43 +105,48 @@ __global__ void __launch_bounds__(WAVES * 64) lm_head_argmax_kernel(const __hip_
       }
     }
   };
-  issue_h(Hr2[0], 0);
-  if (NS > 1) issue_h(Hr2[1], 1);
-  stage_h(Hr2[0], lds);
-  if (NS > 2) issue_h(Hr2[0], 2);
+  issue_h(Hreg, 0);
+  stage_h(Hreg, lds);
+  if (NS > 1) issue_h(Hreg, 1);
   __syncthreads();
 
   f32x4 acc[NMT];
 #pragma unroll
   for (int mt = 0; mt < NMT; ++mt) acc[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  // chunk c of W (register set c % PF) against the half (c & 1) of hidden slice c / 2
+  // chunk c of W (register set c % PF) against quarter (c % 4) of hidden slice c / 4
   auto chunk = [&](u32x4 (&w)[2], int c) {
-    const unsigned char* hs = lds + ((c >> 1) & 1) * STAGE + r16 * HROW + (c & 1) * (KC * 2) + g * 16;
-    // all B operands of the chunk are requested from LDS before the first product needs one
-    bf16x8 b[2][NMT];
+    const unsigned char* hs = lds + ((c / CPS) & 1) * STAGE + r16 * HROW + (c % CPS) * (KC * 2) + g * 16;
+    // The B operands are requested from LDS ahead of the products that use them (each product then waits for its
+    // own operand only; left to itself the compiler pairs every product with its read): all of the chunk's, or,
+    // with eight tiles of hidden, one k-step's at a time (the register file does not hold both).
+    constexpr int KSB = NMT == 8 ? 1 : 2;   // k-steps per batch of reads
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
+    for (int k0 = 0; k0 < 2; k0 += KSB) {
+      bf16x8 b[KSB][NMT];
 #pragma unroll
-      for (int mt = 0; mt < NMT; ++mt) b[ks][mt] = *(const bf16x8*)(hs + mt * 16 * HROW + ks * 64);
-    __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the products (each product then waits for its own operand only)
+      for (int ks = 0; ks < KSB; ++ks)
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      const bf16x8 a = __builtin_bit_cast(bf16x8, w[ks]);
+        for (int mt = 0; mt < NMT; ++mt) b[ks][mt] = *(const bf16x8*)(hs + mt * 16 * HROW + (k0 + ks) * 64);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int mt = 0; mt < NMT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b[ks][mt], acc[mt], 0, 0, 0);
+      for (int ks = 0; ks < KSB; ++ks) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, w[k0 + ks]);
+#pragma unroll
+        for (int mt = 0; mt < NMT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b[ks][mt], acc[mt], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_barrier(0);
   };
   // End of slice s: the slice after it goes from registers to the other LDS stage (last read during slice
-  // s - 1, before the previous barrier), and the slice three ahead is requested into the registers this frees.
-  // FULL: both exist (no branch).
-  // `odd`: parity of s + 1 (a compile-time constant at every call: blocks start at multiples of PF chunks).
+  // s - 1, before the previous barrier), and the slice two ahead is requested into the registers this frees.
+  // FULL: both exist (no branch). `odd`: parity of s + 1 (a compile-time constant at every call: blocks
+  // start at multiples of PF chunks, i.e. at even slices).
   auto next_slice = [&](int s, auto odd_tag, auto full_tag) {
     constexpr bool FULL = decltype(full_tag)::value;
     constexpr int ODD = decltype(odd_tag)::value;
-    if (FULL || s + 1 < NS) stage_h(Hr2[ODD], lds + ODD * STAGE);
-    if (FULL || s + 3 < NS) issue_h(Hr2[ODD], s + 3);
+    if (FULL || s + 1 < NS) stage_h(Hreg, lds + ODD * STAGE);
+    if (FULL || s + 2 < NS) issue_h(Hreg, s + 2);
     __syncthreads();
   };
   // PF chunks starting at c0. FULL: PF more chunks follow, so every register set is refilled and the block is
@@ -152,12 +159,12 @@ __global__ void __launch_bounds__(WAVES * 64) lm_head_argmax_kernel(const __hip_
       if (FULL || c < NC) {
         chunk(Wr[d], c);
         if (FULL || c + PF < NC) issue_w(Wr[d], c + PF);
-        if constexpr ((d & 1) != 0) next_slice(c >> 1, std::integral_constant<int, ((d >> 1) + 1) & 1>{}, full_tag);
+        if constexpr (d % CPS == CPS - 1) next_slice(c / CPS, std::integral_constant<int, ((d / CPS) + 1) & 1>{}, full_tag);
       }
     });
   };
   int c0 = 0;
-  for (; c0 + 2 * PF <= NC; c0 += PF) block(c0, std::true_type{});   // FULL: slices up to c0 / 2 + 6 exist
+  for (; c0 + 2 * PF <= NC; c0 += PF) block(c0, std::true_type{});   // FULL: slices up to c0 / 4 + 3 exist
   for (; c0 < NC; c0 += PF) block(c0, std::false_type{});
 
   // ---- arg-max over this wavefront's 16 vocabulary rows, per row m: in the lane, then across the four lane groups

@@ -419,7 +419,7 @@ size_t spec_lm_head_argmax_workspace_bytes(int32_t M, int32_t V) {
 static int check_lm_head(int32_t M, int32_t K, int32_t V, const void* hidden, const void* weight, const void* workspace,
                          size_t workspace_bytes) {
   if (M <= 0 || K <= 0 || V <= 0) return SPEC_ERR_INVALID_ARG;
-  if (K % 128 != 0) return SPEC_ERR_UNSUPPORTED;
+  if (K % 256 != 0) return SPEC_ERR_UNSUPPORTED;
   if (!hidden || !weight || !aligned16(hidden) || !aligned16(weight)) return SPEC_ERR_INVALID_ARG;
   if (workspace == nullptr || workspace_bytes < spec_lm_head_argmax_workspace_bytes(M, V)) return SPEC_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return SPEC_ERR_INVALID_ARG;

@@ -38,8 +38,8 @@ def _check_rows(arg_gpu, max_gpu, h, w):
     return arg
 
 
-@pytest.mark.parametrize("M,K,V", [(128, 4096, 32000), (16, 4096, 32000), (1, 512, 1000), (17, 128, 130), (64, 640, 4097),
-                                   (200, 1024, 5000), (33, 384, 127), (128, 2048, 129)])
+@pytest.mark.parametrize("M,K,V", [(128, 4096, 32000), (16, 4096, 32000), (1, 512, 1000), (17, 256, 130), (64, 1280, 4097),
+                                   (200, 1024, 5000), (33, 768, 127), (128, 2048, 129), (48, 2304, 700)])
 def test_lm_head_argmax(spec, M, K, V):
     h, w = _inputs(M, K, V, seed=M + K + V)
     arg, mx = spec.spec_lm_head_argmax(_dev(h), _dev(w), want_max=True)
@@ -107,7 +107,7 @@ def test_lm_head_host_side_errors(spec):
     call = lambda M, K, V, hp, wp, ap, wsp, nb: lib.spec_lm_head_argmax(M, K, V, hp, wp, ap, None, wsp, nb, None)
     assert call(4, 256, 100, hd.data_ptr(), wd.data_ptr(), arg.data_ptr(), ws.data_ptr(), ws.numel()) == 0
     torch.cuda.synchronize()
-    assert call(4, 192, 100, hd.data_ptr(), wd.data_ptr(), arg.data_ptr(), ws.data_ptr(), ws.numel()) == spec.ERR_UNSUPPORTED
+    assert call(4, 128, 100, hd.data_ptr(), wd.data_ptr(), arg.data_ptr(), ws.data_ptr(), ws.numel()) == spec.ERR_UNSUPPORTED
     assert call(0, 256, 100, hd.data_ptr(), wd.data_ptr(), arg.data_ptr(), ws.data_ptr(), ws.numel()) == spec.ERR_INVALID_ARG
     assert call(4, 256, 100, None, wd.data_ptr(), arg.data_ptr(), ws.data_ptr(), ws.numel()) == spec.ERR_INVALID_ARG
     assert call(4, 256, 100, hd.data_ptr(), wd.data_ptr(), None, ws.data_ptr(), ws.numel()) == spec.ERR_INVALID_ARG
