@@ -9,6 +9,7 @@ What each function follows:
                          causal mask: a tree token may see its ancestors and itself, nothing else)
   kv_append              Section 4.2, "depth-first search to update key-value cache": one cache
                          region holds the whole tree, token i at row prefix_len + i
+  rope_queries           the queries of the tree tokens under the same embedding (position prefix_len + depth)
   rope_rotate, kv_append_rope  the same append with the rotary embedding of the paper's LLaMA models
                          applied to the keys at position prefix_len + depth (a step adjacent to the path)
   tree_attention         Definition 4.1 with the attention equations of Section 4.1 (scores scaled by
@@ -158,6 +159,30 @@ def kv_append_rope(k_cache, v_cache, k_new, v_new, prefix_len, tree_depth, rope_
 # ---------------------------------------------------------------------------------------------
 # tree attention  (Definition 4.1, Section 4.1 equations, Section 4.2 mask)
 # ---------------------------------------------------------------------------------------------
+
+def rope_queries(q, prefix_len, tree_depth, rope_cos, rope_sin, S_cap, storage="bf16"):
+    """The queries of the tree tokens under the rotary embedding: row (b, i) of every head rotated by position
+    prefix_len[b] + tree_depth[b,i] and rounded to the storage type. q [B,N,H,D]; returns (rotated copy,
+    status [B]); a request that does not fit S_cap or has a position outside the tables keeps its q
+    (ST_CAPACITY), exactly like kv_append_rope."""
+    import torch
+    q = np.array(q, dtype=np.float64)
+    B, N = q.shape[0], q.shape[1]
+    rope_cos = np.asarray(rope_cos, dtype=np.float64)
+    rope_sin = np.asarray(rope_sin, dtype=np.float64)
+    status = np.zeros(B, dtype=np.int32)
+    dt = torch.bfloat16 if storage == "bf16" else torch.float32
+    for b in range(B):
+        p = int(prefix_len[b])
+        pos = [p + int(tree_depth[b, i]) for i in range(N)]
+        if p < 0 or p + N > S_cap or min(pos) < 0 or max(pos) >= rope_cos.shape[0]:
+            status[b] |= ST_CAPACITY
+            continue
+        for i in range(N):
+            rot = rope_rotate(q[b, i], rope_cos[pos[i]], rope_sin[pos[i]])
+            q[b, i] = torch.from_numpy(rot).to(torch.float32).to(dt).double().numpy()
+    return q, status
+
 
 def tree_attention(q, k_cache, v_cache, tree_parent, prefix_len, softmax_scale=None):
     """Attention output of every tree node over (cached prefix) ++ (its own root-to-node path).

@@ -73,3 +73,64 @@ def test_append_with_rotation_positions_rounding_and_status(storage):
     before = kc.copy()
     st = orc.kv_append_rope(kc, vc, kn, vn, pl, dep, cos[:int(pl.max())], sin[:int(pl.max())], storage)
     assert st[np.argmax(pl)] == orc.ST_CAPACITY and np.array_equal(kc[np.argmax(pl)], before[np.argmax(pl)])
+
+
+@pytest.mark.parametrize("storage", ["bf16", "f32"])
+def test_query_rotation_positions_rounding_and_status(storage):
+    cfg = wl.Config(95, "ropeq", storage, B=3, H=2, D=16, P=(3, 9), N=6, tree="random_parent")
+    inp = wl.make_attention_inputs(cfg, seed=5, S_cap=9 + 6)
+    q = inp["q"][0].double().numpy()
+    pl, dep = inp["prefix_len"].numpy(), inp["tree_depth"].numpy()
+    cos, sin = (t.double().numpy() for t in wl.make_rope_tables(15, cfg.D))
+    same, st = orc.rope_queries(q, pl, dep, np.ones((15, 8)), np.zeros((15, 8)), 15, storage)
+    assert (st == 0).all() and np.array_equal(same, q)                         # angle zero: untouched
+    got, st = orc.rope_queries(q, pl, dep, cos, sin, 15, storage)
+    assert (st == 0).all() and not np.array_equal(got, q)
+    dt = torch.bfloat16 if storage == "bf16" else torch.float32
+    for b in range(cfg.B):
+        for i in range(cfg.N):
+            pos = pl[b] + dep[b, i]                                            # the depth, not the row index
+            z = (q[b, i, :, :8] + 1j * q[b, i, :, 8:]) * np.exp(1j * np.arctan2(sin[pos], cos[pos]))
+            want = np.concatenate([z.real, z.imag], -1)
+            assert np.abs(got[b, i] - want).max() <= (2.0 ** -7 if storage == "bf16" else 2e-6) * np.abs(want).max()
+    assert np.array_equal(torch.from_numpy(got).to(dt).double().numpy(), got)
+    assert np.array_equal(q, inp["q"][0].double().numpy())                     # the input is not modified
+    # tables too short for the longest request, or a tree that does not fit: that request keeps its q
+    short = int(pl.max())
+    got, st = orc.rope_queries(q, pl, dep, cos[:short], sin[:short], 15, storage)
+    worst = int(np.argmax(pl))
+    assert st[worst] == orc.ST_CAPACITY and np.array_equal(got[worst], q[worst])
+    _, st = orc.rope_queries(q, pl, dep, cos, sin, int(pl.max()) + cfg.N - 1, storage)
+    assert st[worst] == orc.ST_CAPACITY
+    # the same flags as the key side
+    kc, vc = inp["k_cache"][0].double().numpy(), inp["v_cache"][0].double().numpy()
+    st_k = orc.kv_append_rope(kc, vc, inp["k_new"][0].double().numpy(), inp["v_new"][0].double().numpy(), pl, dep,
+                              cos[:short], sin[:short], storage)
+    _, st_q = orc.rope_queries(q, pl, dep, cos[:short], sin[:short], 15, storage)
+    assert np.array_equal(st_k, st_q)
+
+
+def test_tree_attention_with_rotated_q_and_k_depends_on_relative_positions_only():
+    """No prefix, queries and keys both rotated: moving every position by the same offset (tables read from row
+    s on) leaves the tree attention output alone, up to the float32 rounding of the rotated operands; rotating
+    only one side does not."""
+    cfg = wl.Config(95, "ropeqa", "f32", B=2, H=2, D=16, P=0, N=7, tree="random_parent")
+    inp = wl.make_attention_inputs(cfg, seed=6, S_cap=8)
+    f64 = lambda t: t.double().numpy()
+    q, kn, vn = f64(inp["q"][0]), f64(inp["k_new"][0]), f64(inp["v_new"][0])
+    pl, dep, par = inp["prefix_len"].numpy(), inp["tree_depth"].numpy(), inp["tree_parent"].numpy()
+    cos, sin = (f64(t) for t in wl.make_rope_tables(40, cfg.D))
+
+    def run(s, rotate_q=True):
+        kc, vc = f64(inp["k_cache"][0]), f64(inp["v_cache"][0])
+        assert (orc.kv_append_rope(kc, vc, kn, vn, pl, dep, cos[s:], sin[s:], "f32") == 0).all()
+        qr = orc.rope_queries(q, pl, dep, cos[s:], sin[s:], 8, "f32")[0] if rotate_q else q
+        return orc.tree_attention(qr, kc, vc, par, pl)
+
+    base = run(0)
+    for s in (1, 5, 30):
+        assert np.abs(run(s) - base).max() < 2e-5
+    assert np.abs(run(5, rotate_q=False) - run(0, rotate_q=False)).max() > 1e-3
+    kc, vc = f64(inp["k_cache"][0]), f64(inp["v_cache"][0])
+    orc.kv_append(kc, vc, kn, vn, pl)
+    assert np.abs(orc.tree_attention(q, kc, vc, par, pl) - base).max() > 1e-3   # the embedding does something
