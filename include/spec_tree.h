@@ -117,6 +117,19 @@ int spec_kv_append_rope(const spec_attn_desc_t* desc, const void* k_new, const v
                         int32_t rope_len, int32_t* status /*[B] or NULL*/, void* hip_stream);
 
 /*
+ * The same append with the queries rotated too, in one launch: q [B,N,H,D] (the descriptor's q strides) is
+ * rotated IN PLACE, row (b, i) of every head by position prefix_len[b] + tree_depth[b,i], same tables, same
+ * pairing, float32 arithmetic rounded to the element type. After this call spec_tree_attention on (q, caches)
+ * is the attention of a model with rotary embeddings. A request that is skipped (see above) keeps its q; in
+ * the paged form a request with SPEC_ST_BAD_BLOCK has its q rotated and the rows of the bad block unwritten.
+ * q == NULL is SPEC_ERR_INVALID_ARG.
+ */
+int spec_qk_rope_append(const spec_attn_desc_t* desc, void* q, const void* k_new, const void* v_new, void* k_cache,
+                        void* v_cache, const int32_t* tree_depth /*[B,N]*/, const int32_t* prefix_len /*[B]*/,
+                        const float* rope_cos, const float* rope_sin, int32_t rope_len, int32_t* status,
+                        void* hip_stream);
+
+/*
  * Tree attention (Definition 4.1; attention equations of Section 4.1; topology-aware causal mask of
  * Section 4.2). For every request b, head h and tree node i:
  *     out[b,i,h,:] = softmax_j( q[b,i,h,:] . k[b,h,j,:] * scale ) . v[b,h,j,:]
@@ -307,6 +320,10 @@ int spec_kv_append_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pa
                          const void* v_new, void* k_cache, void* v_cache, const int32_t* prefix_len,
                          int32_t* status, void* hip_stream);
 int spec_kv_append_rope_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, const void* k_new,
+                              const void* v_new, void* k_cache, void* v_cache, const int32_t* tree_depth,
+                              const int32_t* prefix_len, const float* rope_cos, const float* rope_sin,
+                              int32_t rope_len, int32_t* status, void* hip_stream);
+int spec_qk_rope_append_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, void* q, const void* k_new,
                               const void* v_new, void* k_cache, void* v_cache, const int32_t* tree_depth,
                               const int32_t* prefix_len, const float* rope_cos, const float* rope_sin,
                               int32_t rope_len, int32_t* status, void* hip_stream);

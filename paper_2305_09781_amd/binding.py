@@ -29,6 +29,7 @@ EXPORTED = [
     "spec_kv_append_paged", "spec_kv_append_rope_paged", "spec_tree_attention_paged", "spec_tree_attention_append_paged",
     "spec_tree_attention_paged_workspace_bytes", "spec_kv_commit_paged",
     "spec_lm_head_argmax", "spec_lm_head_argmax_workspace_bytes", "spec_verify_greedy_lm_head",
+    "spec_qk_rope_append", "spec_qk_rope_append_paged",
 ]
 
 
@@ -111,6 +112,10 @@ def load():
     lib.spec_tree_attention_paged_workspace_bytes.restype = sz
     lib.spec_kv_commit_paged.argtypes = [dp, pp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i32, vp, vp, vp, vp, vp]
     lib.spec_kv_commit_paged.restype = ctypes.c_int
+    lib.spec_qk_rope_append.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
+    lib.spec_qk_rope_append.restype = ctypes.c_int
+    lib.spec_qk_rope_append_paged.argtypes = [dp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
+    lib.spec_qk_rope_append_paged.restype = ctypes.c_int
     lib.spec_lm_head_argmax_workspace_bytes.argtypes = [i32, i32]
     lib.spec_lm_head_argmax_workspace_bytes.restype = sz
     lib.spec_lm_head_argmax.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
@@ -200,6 +205,29 @@ def spec_kv_append_rope(k_new, v_new, k_cache, v_cache, tree_depth, prefix_len, 
     _check(load().spec_kv_append_rope(ctypes.byref(d), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
                                       _ptr(tree_depth), _ptr(prefix_len), _ptr(rope_cos), _ptr(rope_sin),
                                       rope_cos.shape[0], _ptr(status), _stream(stream)), "spec_kv_append_rope")
+
+
+def spec_qk_rope_append(q, k_new, v_new, k_cache, v_cache, tree_depth, prefix_len, rope_cos, rope_sin, status=None,
+                        stream=None, block_table=None):
+    """Rotary embedding of q (in place) and of K on its way into the cache, V appended, in one launch. With
+    block_table the caches are pools of blocks (paged)."""
+    _same_layout(k_cache, v_cache, "k_cache and v_cache")
+    _same_layout(k_new, v_new, "k_new and v_new")
+    D = k_new.shape[-1]
+    for tab in (rope_cos, rope_sin):
+        if tab.dtype != torch.float32 or tab.dim() != 2 or tab.shape[1] != D // 2 or not tab.is_contiguous():
+            raise ValueError("rope tables must be contiguous float32 [rope_len, D/2]")
+    if block_table is None:
+        d = make_desc(q, k_cache, k_new=k_new)
+        _check(load().spec_qk_rope_append(ctypes.byref(d), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                          _ptr(tree_depth), _ptr(prefix_len), _ptr(rope_cos), _ptr(rope_sin),
+                                          rope_cos.shape[0], _ptr(status), _stream(stream)), "spec_qk_rope_append")
+    else:
+        d, pg = make_paged_desc(q, k_cache, block_table, k_new=k_new)
+        _check(load().spec_qk_rope_append_paged(ctypes.byref(d), ctypes.byref(pg), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                                _ptr(k_cache), _ptr(v_cache), _ptr(tree_depth), _ptr(prefix_len),
+                                                _ptr(rope_cos), _ptr(rope_sin), rope_cos.shape[0], _ptr(status),
+                                                _stream(stream)), "spec_qk_rope_append_paged")
 
 
 def spec_tree_attention_workspace_bytes(desc: AttnDesc) -> int:

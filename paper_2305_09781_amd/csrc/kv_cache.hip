@@ -40,12 +40,59 @@ __global__ void __launch_bounds__(256) kv_append_kernel(const uint4* __restrict_
   v_cache[dst] = v_new[src];
 }
 
+// Rotation of the two 16-byte pieces of a row that pair up under the half-split rotary embedding (piece c holds
+// dimensions c * EPV .., its partner the same dimensions + D/2), by the angles whose cosines / sines are cs / sn;
+// float32 arithmetic, rounded to the storage type.
+template <bool BF16>
+__device__ __forceinline__ void rope_pair(const uint4 lo, const uint4 hi, const float* __restrict__ cs,
+                                          const float* __restrict__ sn, uint4* olo, uint4* ohi) {
+  constexpr int EPV = BF16 ? 8 : 4;   // elements per 16-byte piece
+  float x1[EPV], x2[EPV];
+  if (BF16) {
+    const unsigned a[4] = {lo.x, lo.y, lo.z, lo.w}, bb[4] = {hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      x1[2 * j] = __uint_as_float(a[j] << 16);
+      x1[2 * j + 1] = __uint_as_float(a[j] & 0xffff0000u);
+      x2[2 * j] = __uint_as_float(bb[j] << 16);
+      x2[2 * j + 1] = __uint_as_float(bb[j] & 0xffff0000u);
+    }
+  } else {
+    x1[0] = __uint_as_float(lo.x); x1[1] = __uint_as_float(lo.y); x1[2] = __uint_as_float(lo.z); x1[3] = __uint_as_float(lo.w);
+    x2[0] = __uint_as_float(hi.x); x2[1] = __uint_as_float(hi.y); x2[2] = __uint_as_float(hi.z); x2[3] = __uint_as_float(hi.w);
+  }
+  float y1[EPV], y2[EPV];
+#pragma unroll
+  for (int j = 0; j < EPV; ++j) {
+    const float co = cs[j], si = sn[j];
+    y1[j] = x1[j] * co - x2[j] * si;
+    y2[j] = x2[j] * co + x1[j] * si;
+  }
+  if (BF16) {
+    unsigned o1[4], o2[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      union { __hip_bfloat16 h; unsigned short u; } a0, a1, b0, b1;
+      a0.h = __float2bfloat16(y1[2 * j]); a1.h = __float2bfloat16(y1[2 * j + 1]);
+      b0.h = __float2bfloat16(y2[2 * j]); b1.h = __float2bfloat16(y2[2 * j + 1]);
+      o1[j] = (unsigned)a0.u | ((unsigned)a1.u << 16);
+      o2[j] = (unsigned)b0.u | ((unsigned)b1.u << 16);
+    }
+    *olo = make_uint4(o1[0], o1[1], o1[2], o1[3]);
+    *ohi = make_uint4(o2[0], o2[1], o2[2], o2[3]);
+  } else {
+    *olo = make_uint4(__float_as_uint(y1[0]), __float_as_uint(y1[1]), __float_as_uint(y1[2]), __float_as_uint(y1[3]));
+    *ohi = make_uint4(__float_as_uint(y2[0]), __float_as_uint(y2[1]), __float_as_uint(y2[2]), __float_as_uint(y2[3]));
+  }
+}
+
 // KV append with the rotary position embedding applied to K on the way in (half-split pairing:
-// dimension i < D/2 rotates with i + D/2). Token i of request b sits at position prefix_len[b] +
-// tree_depth[b,i]; cos / sin come from the caller's tables [rope_len, D/2]. grid = (chunks, B); a
-// block first checks that the request fits the cache and that all its positions lie inside the tables
-// (else it is left untouched and flagged), then every thread moves the two 16-byte pieces of one K row
-// that rotate with each other, and the same two pieces of V unchanged.
+// dimension i < D/2 rotates with i + D/2), and optionally to the queries in place. Token i of request b sits at
+// position prefix_len[b] + tree_depth[b,i]; cos / sin come from the caller's tables [rope_len, D/2]. grid =
+// (chunks, B); a block first checks that the request fits the cache and that all its positions lie inside
+// the tables (else it is left untouched and flagged), then every thread moves the two 16-byte pieces of one K
+// row that rotate with each other and the same two pieces of V unchanged, or (threads past the K/V work,
+// q != nullptr) rotates the two pieces of one query row in place.
 template <bool BF16>
 __global__ void __launch_bounds__(256) kv_append_rope_kernel(const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
                                                              uint4* __restrict__ k_cache, uint4* __restrict__ v_cache,
@@ -55,7 +102,8 @@ __global__ void __launch_bounds__(256) kv_append_rope_kernel(const uint4* __rest
                                                              const float* __restrict__ rope_sin, int rope_len,
                                                              int32_t* status, int N, int H, int D, int S_cap,
                                                              int vec_per_row, long q_sb, long q_sn, long q_sh,
-                                                             long kv_sb, long kv_sh, long kv_ss, Pages pg) {
+                                                             long kv_sb, long kv_sh, long kv_ss, Pages pg, uint4* q,
+                                                             int Hq, long qq_sb, long qq_sn, long qq_sh) {
   constexpr int EPV = BF16 ? 8 : 4;   // elements per 16-byte piece
   __shared__ int s_bad;
   const int b = blockIdx.y, t = threadIdx.x;
@@ -72,9 +120,24 @@ __global__ void __launch_bounds__(256) kv_append_rope_kernel(const uint4* __rest
     return;
   }
   const int half = vec_per_row / 2;
-  const long total = (long)N * H * half;
+  const long kv_items = (long)N * H * half;
   long idx = (long)blockIdx.x * 256 + t;
-  if (idx >= total) return;
+  if (idx >= kv_items) {   // query rows (when asked for)
+    idx -= kv_items;
+    if (q == nullptr || idx >= (long)N * Hq * half) return;
+    const int c = (int)(idx % half);
+    idx /= half;
+    const int h = (int)(idx % Hq);
+    const int i = (int)(idx / Hq);
+    const int pos = p + tree_depth[(long)b * N + i];
+    uint4* row = q + b * qq_sb + i * qq_sn + h * qq_sh + c;
+    uint4 olo, ohi;
+    rope_pair<BF16>(row[0], row[half], rope_cos + (long)pos * (D / 2) + c * EPV, rope_sin + (long)pos * (D / 2) + c * EPV,
+                    &olo, &ohi);
+    row[0] = olo;
+    row[half] = ohi;
+    return;
+  }
   const int c = (int)(idx % half);
   idx /= half;
   const int h = (int)(idx % H);
@@ -87,47 +150,9 @@ __global__ void __launch_bounds__(256) kv_append_rope_kernel(const uint4* __rest
     if (h == 0 && c == 0) set_status(status, b, SPEC_ST_BAD_BLOCK);
     return;
   }
-  const uint4 lo = k_new[src], hi = k_new[src + half];
-  float x1[EPV], x2[EPV];
-  if (BF16) {
-    const unsigned a[4] = {lo.x, lo.y, lo.z, lo.w}, bb[4] = {hi.x, hi.y, hi.z, hi.w};
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      x1[2 * j] = __uint_as_float(a[j] << 16);
-      x1[2 * j + 1] = __uint_as_float(a[j] & 0xffff0000u);
-      x2[2 * j] = __uint_as_float(bb[j] << 16);
-      x2[2 * j + 1] = __uint_as_float(bb[j] & 0xffff0000u);
-    }
-  } else {
-    x1[0] = __uint_as_float(lo.x); x1[1] = __uint_as_float(lo.y); x1[2] = __uint_as_float(lo.z); x1[3] = __uint_as_float(lo.w);
-    x2[0] = __uint_as_float(hi.x); x2[1] = __uint_as_float(hi.y); x2[2] = __uint_as_float(hi.z); x2[3] = __uint_as_float(hi.w);
-  }
-  const float* cs = rope_cos + (long)pos * (D / 2) + c * EPV;
-  const float* sn = rope_sin + (long)pos * (D / 2) + c * EPV;
-  float y1[EPV], y2[EPV];
-#pragma unroll
-  for (int j = 0; j < EPV; ++j) {
-    const float co = cs[j], si = sn[j];
-    y1[j] = x1[j] * co - x2[j] * si;
-    y2[j] = x2[j] * co + x1[j] * si;
-  }
   uint4 olo, ohi;
-  if (BF16) {
-    unsigned o1[4], o2[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      union { __hip_bfloat16 h; unsigned short u; } a0, a1, b0, b1;
-      a0.h = __float2bfloat16(y1[2 * j]); a1.h = __float2bfloat16(y1[2 * j + 1]);
-      b0.h = __float2bfloat16(y2[2 * j]); b1.h = __float2bfloat16(y2[2 * j + 1]);
-      o1[j] = (unsigned)a0.u | ((unsigned)a1.u << 16);
-      o2[j] = (unsigned)b0.u | ((unsigned)b1.u << 16);
-    }
-    olo = make_uint4(o1[0], o1[1], o1[2], o1[3]);
-    ohi = make_uint4(o2[0], o2[1], o2[2], o2[3]);
-  } else {
-    olo = make_uint4(__float_as_uint(y1[0]), __float_as_uint(y1[1]), __float_as_uint(y1[2]), __float_as_uint(y1[3]));
-    ohi = make_uint4(__float_as_uint(y2[0]), __float_as_uint(y2[1]), __float_as_uint(y2[2]), __float_as_uint(y2[3]));
-  }
+  rope_pair<BF16>(k_new[src], k_new[src + half], rope_cos + (long)pos * (D / 2) + c * EPV,
+                  rope_sin + (long)pos * (D / 2) + c * EPV, &olo, &ohi);
   k_cache[dst] = olo;
   k_cache[dst + half] = ohi;
   v_cache[dst] = v_new[src];
@@ -235,18 +260,19 @@ hipError_t launch_kv_append(const spec_attn_desc_t& d, const Pages& pg, const vo
 hipError_t launch_kv_append_rope(const spec_attn_desc_t& d, const Pages& pg, const void* k_new, const void* v_new,
                                  void* k_cache, void* v_cache, const int32_t* tree_depth, const int32_t* prefix_len,
                                  const float* rope_cos, const float* rope_sin, int rope_len, int32_t* status,
-                                 hipStream_t s) {
+                                 hipStream_t s, void* q) {
   const int e = elem_bytes(d.dtype);
   const int per16 = 16 / e;
   const int vec_per_row = d.D / per16;
-  const long per_request = (long)d.N * d.H_kv * (vec_per_row / 2);
+  const long per_request = (long)d.N * (d.H_kv + (q != nullptr ? d.H : 0)) * (vec_per_row / 2);
   const dim3 grid((unsigned)((per_request + 255) / 256), d.B);
   const NewStrides ns = attn_new_strides(d);
 #define SPEC_ROPE(BF)                                                                                                 \
   hipLaunchKernelGGL(kv_append_rope_kernel<BF>, grid, dim3(256), 0, s, (const uint4*)k_new, (const uint4*)v_new,      \
                      (uint4*)k_cache, (uint4*)v_cache, tree_depth, prefix_len, rope_cos, rope_sin, rope_len, status,  \
                      d.N, d.H_kv, d.D, d.S_cap, vec_per_row, ns.b / per16, ns.n / per16, ns.h / per16,                \
-                     d.kv_stride_b / per16, d.kv_stride_h / per16, d.kv_stride_s / per16, pg)
+                     d.kv_stride_b / per16, d.kv_stride_h / per16, d.kv_stride_s / per16, pg, (uint4*)q, d.H,          \
+                     d.q_stride_b / per16, d.q_stride_n / per16, d.q_stride_h / per16)
   if (d.dtype == SPEC_BF16) SPEC_ROPE(true);
   else SPEC_ROPE(false);
 #undef SPEC_ROPE

@@ -233,7 +233,8 @@ int spec_kv_append_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pa
 static int kv_append_rope_impl(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, bool paged, const void* k_new,
                                const void* v_new, void* k_cache, void* v_cache, const int32_t* tree_depth,
                                const int32_t* prefix_len, const float* rope_cos, const float* rope_sin, int32_t rope_len,
-                               int32_t* status, void* hip_stream) {
+                               int32_t* status, void* hip_stream, void* q = nullptr, bool with_q = false) {
+  if (with_q && (q == nullptr || !aligned16(q))) return check_desc(desc) != SPEC_OK ? check_desc(desc) : SPEC_ERR_INVALID_ARG;
   int rc = check_desc(desc);
   if (rc != SPEC_OK) return rc;
   Pages pg = no_pages();
@@ -242,9 +243,24 @@ static int kv_append_rope_impl(const spec_attn_desc_t* desc, const spec_kv_pages
   if (rope_len <= 0 || new_strides_missing(desc)) return SPEC_ERR_INVALID_ARG;
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache)) return SPEC_ERR_INVALID_ARG;
   return launch_kv_append_rope(*desc, pg, k_new, v_new, k_cache, v_cache, tree_depth, prefix_len, rope_cos, rope_sin,
-                               rope_len, status, (hipStream_t)hip_stream) == hipSuccess
+                               rope_len, status, (hipStream_t)hip_stream, q) == hipSuccess
              ? SPEC_OK
              : SPEC_ERR_HIP;
+}
+
+int spec_qk_rope_append(const spec_attn_desc_t* desc, void* q, const void* k_new, const void* v_new, void* k_cache,
+                        void* v_cache, const int32_t* tree_depth, const int32_t* prefix_len, const float* rope_cos,
+                        const float* rope_sin, int32_t rope_len, int32_t* status, void* hip_stream) {
+  return kv_append_rope_impl(desc, nullptr, false, k_new, v_new, k_cache, v_cache, tree_depth, prefix_len, rope_cos,
+                             rope_sin, rope_len, status, hip_stream, q, true);
+}
+
+int spec_qk_rope_append_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, void* q, const void* k_new,
+                              const void* v_new, void* k_cache, void* v_cache, const int32_t* tree_depth,
+                              const int32_t* prefix_len, const float* rope_cos, const float* rope_sin, int32_t rope_len,
+                              int32_t* status, void* hip_stream) {
+  return kv_append_rope_impl(desc, pages, true, k_new, v_new, k_cache, v_cache, tree_depth, prefix_len, rope_cos, rope_sin,
+                             rope_len, status, hip_stream, q, true);
 }
 
 int spec_kv_append_rope(const spec_attn_desc_t* desc, const void* k_new, const void* v_new, void* k_cache, void* v_cache,

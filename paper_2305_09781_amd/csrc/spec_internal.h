@@ -84,7 +84,7 @@ hipError_t launch_kv_append(const spec_attn_desc_t& d, const Pages& pg, const vo
 hipError_t launch_kv_append_rope(const spec_attn_desc_t& d, const Pages& pg, const void* k_new, const void* v_new,
                                  void* k_cache, void* v_cache, const int32_t* tree_depth, const int32_t* prefix_len,
                                  const float* rope_cos, const float* rope_sin, int rope_len, int32_t* status,
-                                 hipStream_t s);
+                                 hipStream_t s, void* q = nullptr);
 hipError_t launch_kv_commit(const spec_attn_desc_t& d, const Pages& pg, int n_layers, void* const* k_caches,
                             void* const* v_caches,
                             const int32_t* path, int Lmax, const int32_t* len, const int32_t* prefix_len,

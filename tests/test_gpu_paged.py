@@ -217,6 +217,39 @@ def test_paged_rope_append(spec):
         assert (np.abs(got_k[b, :, :n] - kco[b, :, :n]) <= 2.0 ** -7 * np.abs(kco[b, :, :n]) + 1e-6).all()
 
 
+def test_paged_q_and_k_rope_append(spec):
+    """The one-launch form on paged caches: the pools as after spec_kv_append_rope_paged bit for bit, q within
+    one unit in the last place of the oracle; a bad table entry among the tree's blocks flags the request."""
+    B, H, H_kv, D, N, bt = 3, 4, 2, 128, 20, 64
+    cfg = wl.Config(91, "pqrope", "bf16", B=B, H=H, H_kv=H_kv, D=D, P=(40, 200), N=N, tree="random_branching")
+    inp = wl.make_attention_inputs(cfg, seed=10, S_cap=256)
+    pl, dep = inp["prefix_len"].numpy(), inp["tree_depth"].numpy()
+    pools, table = wl.to_paged([inp["k_cache"][0], inp["v_cache"][0]], pl, N, bt, np.random.default_rng(3))
+    cos, sin = wl.make_rope_tables(256, D)
+    q_ref, st_ref = orc.rope_queries(_f64(inp["q"][0]), pl, dep, cos.numpy(), sin.numpy(), 256, "bf16")
+    assert (st_ref == 0).all()
+    kp1, vp1 = _dev(pools[0]), _dev(pools[1])
+    spec.spec_kv_append_rope_paged(_dev(inp["k_new"][0]), _dev(inp["v_new"][0]), kp1, vp1, _dev(table),
+                                   _dev(inp["tree_depth"]), _dev(inp["prefix_len"]), _dev(cos), _dev(sin))
+    q, kp, vp = _dev(inp["q"][0]), _dev(pools[0]), _dev(pools[1])
+    status = torch.zeros(B, dtype=torch.int32, device=DEV)
+    spec.spec_qk_rope_append(q, _dev(inp["k_new"][0]), _dev(inp["v_new"][0]), kp, vp, _dev(inp["tree_depth"]),
+                             _dev(inp["prefix_len"]), _dev(cos), _dev(sin), status=status, block_table=_dev(table))
+    torch.cuda.synchronize()
+    assert (status.cpu().numpy() == 0).all()
+    assert np.array_equal(_bits(kp), _bits(kp1)) and np.array_equal(_bits(vp), _bits(vp1))
+    got = q.double().cpu().numpy()
+    assert (np.abs(got - q_ref) <= 2.0 ** -7 * np.abs(q_ref) + 1e-6).all()
+    bad = table.clone()
+    bad[1, int(pl[1]) // bt] = pools[0].shape[0] + 3
+    status.zero_()
+    spec.spec_qk_rope_append(_dev(inp["q"][0]), _dev(inp["k_new"][0]), _dev(inp["v_new"][0]), _dev(pools[0]), _dev(pools[1]),
+                             _dev(inp["tree_depth"]), _dev(inp["prefix_len"]), _dev(cos), _dev(sin), status=status,
+                             block_table=_dev(bad))
+    torch.cuda.synchronize()
+    assert status.cpu().numpy().tolist() == [0, orc.ST_BAD_BLOCK, 0]
+
+
 def test_shared_prefix_blocks(spec):
     """Two requests whose tables name the same physical blocks for a common prefix get the outputs of two
     requests with private copies."""

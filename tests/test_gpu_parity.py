@@ -3,6 +3,7 @@
 Bars: attention max-abs 1e-5 for float32 inputs, |g-o| <= 2e-2 + 1e-2*|o| for bf16 inputs (oracle in
 float64, not rounded); append, commit, verification decisions, paths and tokens bit-exact.
 """
+import ctypes
 import dataclasses
 import os
 
@@ -205,6 +206,77 @@ def test_kv_append_with_rotary_embedding(spec, case):
     assert np.array_equal(status.cpu().numpy(), st2) and (st2 != 0).any()
     for b in np.nonzero(st2)[0]:
         assert np.array_equal(_bits(kc2[b]), _bits(inp["k_cache"][0][b]))
+
+
+@pytest.mark.parametrize("case", [("bf16", 3, 8, 2, 128, (30, 200), 16, "expansion"), ("bf16", 2, 3, 3, 64, (0, 90), 40, "random_branching"),
+                                  ("f32", 2, 4, 2, 64, (5, 60), 9, "random_parent"), ("f32", 1, 2, 2, 128, (100, 100), 128, "random_branching")])
+def test_q_and_k_rotary_embedding_in_one_launch(spec, case):
+    """spec_qk_rope_append: the cache as after spec_kv_append_rope (bit for bit: the same arithmetic), q rotated
+    in place within one unit in the last place of the float64 oracle, skipped requests untouched on both
+    sides, and tree attention on the result within the attention tolerance of the oracle's."""
+    dtype, B, H, H_kv, D, P, N, tree = case
+    cfg = wl.Config(96, "ropeq", dtype, B=B, H=H, H_kv=H_kv, D=D, P=P if P[0] != P[1] else P[0], N=N, tree=tree,
+                    widths=wl.EXPANSION_EVAL * 2)
+    S = P[1] + N + 2
+    inp = wl.make_attention_inputs(cfg, seed=400 + N, S_cap=S)
+    cos, sin = wl.make_rope_tables(S, D)
+    pl, dep, par = inp["prefix_len"].numpy(), inp["tree_depth"].numpy(), inp["tree_parent"].numpy()
+    kco, vco = _f64(inp["k_cache"][0]), _f64(inp["v_cache"][0])
+    orc.kv_append_rope(kco, vco, _f64(inp["k_new"][0]), _f64(inp["v_new"][0]), pl, dep, cos.numpy(), sin.numpy(), dtype)
+    q_ref, st_ref = orc.rope_queries(_f64(inp["q"][0]), pl, dep, cos.numpy(), sin.numpy(), S, dtype)
+    assert (st_ref == 0).all()
+    # the key side alone, for the bit comparison
+    kc1, vc1 = _dev(inp["k_cache"][0]), _dev(inp["v_cache"][0])
+    spec.spec_kv_append_rope(_dev(inp["k_new"][0]), _dev(inp["v_new"][0]), kc1, vc1, _dev(inp["tree_depth"]),
+                             _dev(inp["prefix_len"]), _dev(cos), _dev(sin))
+    q, kc, vc = _dev(inp["q"][0]), _dev(inp["k_cache"][0]), _dev(inp["v_cache"][0])
+    status = torch.zeros(B, dtype=torch.int32, device=DEV)
+    spec.spec_qk_rope_append(q, _dev(inp["k_new"][0]), _dev(inp["v_new"][0]), kc, vc, _dev(inp["tree_depth"]),
+                             _dev(inp["prefix_len"]), _dev(cos), _dev(sin), status=status)
+    torch.cuda.synchronize()
+    assert (status.cpu().numpy() == 0).all()
+    assert np.array_equal(_bits(kc), _bits(kc1)) and np.array_equal(_bits(vc), _bits(vc1))
+    got = q.double().cpu().numpy()
+    ulp = 2.0 ** -7 if dtype == "bf16" else 2.0 ** -21
+    assert (np.abs(got - q_ref) <= ulp * np.abs(q_ref) + 1e-6).all()
+    if dtype == "bf16":
+        assert (got != q_ref).mean() < 0.02
+    # attention on what the launch left behind against the oracle on its own rotated operands
+    out = torch.empty_like(q)
+    spec.spec_tree_attention(q, kc, vc, _dev(inp["tree_parent"]), _dev(inp["tree_depth"]), _dev(inp["prefix_len"]), out)
+    torch.cuda.synchronize()
+    want = orc.tree_attention(q_ref, kco, vco, par, pl)
+    err = np.abs(out.double().cpu().numpy() - want)
+    assert (err <= (3e-2 + 2e-2 * np.abs(want) if dtype == "bf16" else 2e-5)).all(), err.max()
+    # tables too short for one request: its q and its cache rows stay as they were, it is flagged
+    short = int(pl.max())
+    q2, kc2 = _dev(inp["q"][0]), _dev(inp["k_cache"][0])
+    status.zero_()
+    spec.spec_qk_rope_append(q2, _dev(inp["k_new"][0]), _dev(inp["v_new"][0]), kc2, _dev(inp["v_cache"][0]),
+                             _dev(inp["tree_depth"]), _dev(inp["prefix_len"]), _dev(cos[:short].contiguous()),
+                             _dev(sin[:short].contiguous()), status=status)
+    torch.cuda.synchronize()
+    _, st2 = orc.rope_queries(_f64(inp["q"][0]), pl, dep, cos[:short].numpy(), sin[:short].numpy(), S, dtype)
+    assert np.array_equal(status.cpu().numpy(), st2) and (st2 != 0).any()
+    for b in range(B):
+        if st2[b]:
+            assert np.array_equal(_bits(q2[b]), _bits(inp["q"][0][b])) and np.array_equal(_bits(kc2[b]), _bits(inp["k_cache"][0][b]))
+        else:
+            assert np.array_equal(_bits(q2[b]), _bits(q[b]))
+
+
+def test_qk_rope_append_rejects_bad_arguments(spec):
+    cfg = wl.Config(96, "ropeq", "bf16", B=1, H=2, D=64, P=10, N=4, tree="random_parent")
+    inp = wl.make_attention_inputs(cfg, seed=1, S_cap=32)
+    cos, sin = wl.make_rope_tables(32, 64)
+    args = [_dev(inp[k][0]) for k in ("q", "k_new", "v_new", "k_cache", "v_cache")] + [_dev(inp["tree_depth"]), _dev(inp["prefix_len"])]
+    with pytest.raises(ValueError):
+        spec.spec_qk_rope_append(*args, _dev(cos[:, :16].contiguous()), _dev(sin[:, :16].contiguous()))
+    d = spec.make_desc(args[0], args[3], k_new=args[1])
+    ptr = lambda t: ctypes.c_void_p(t.data_ptr())
+    cs, sn = _dev(cos), _dev(sin)
+    rc = spec.load().spec_qk_rope_append(ctypes.byref(d), None, *[ptr(t) for t in args[1:]], ptr(cs), ptr(sn), 32, None, None)
+    assert rc != 0                                                  # q is not optional here
 
 
 GROUPED = [
