@@ -24,9 +24,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy of
 # known size (profiles/tree_attention_bf16_configs2-5_hbm_traffic.txt), per launch of the workload's shape.
-MEASURED_TRAFFIC_BYTES = {2: int((67167.9 * 2.000 + 3148.6) * 1024), 3: int((90357.3 * 2.000 + 49160.9) * 1024),
-                          4: int((549066.6 * 2.000 + 49162.1) * 1024),
-                          5: int(((400853.0 + 7107.0) * 2.000 + 12367.1 + 1024.0) * 1024)}
+MEASURED_TRAFFIC_BYTES = {2: int((67237.9 * 2.000 + 3189.0) * 1024), 3: int((90357.2 * 2.000 + 49164.0) * 1024),
+                          4: int((549066.4 * 2.000 + 49154.8) * 1024),
+                          5: int(((400755.5 + 7107.0) * 2.000 + 12367.2 + 1024.0) * 1024)}
 
 
 def parse():

@@ -345,7 +345,8 @@ int spec_kv_commit_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pa
 
 /*
  * Measurement aid (no passage of the paper): reads `bytes` (a multiple of 16 is used) from buf once with
- * plain 16-byte loads and writes nothing (sink: 16 device bytes that are never written in practice). Timed
+ * non-temporal 16-byte loads, a contiguous piece per workgroup, and writes nothing (sink: 16 device bytes
+ * that are never written in practice). Timed
  * over a buffer much larger than the on-chip caches it gives the read bandwidth this machine sustains,
  * the practical ceiling next to the published HBM peak.
  */

@@ -5,22 +5,30 @@
 
 namespace spec {
 
-__global__ void __launch_bounds__(256) read_stream_kernel(const uint4* __restrict__ p, size_t n, uint4* sink) {
-  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  uint4 acc = {0, 0, 0, 0};
-  for (; i + 3 * stride < n; i += 4 * stride) {   // four independent 16-byte loads in flight per thread
-    const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
-    acc.x ^= a.x ^ b.x ^ c.x ^ d.x; acc.y ^= a.y ^ b.y ^ c.y ^ d.y;
-    acc.z ^= a.z ^ b.z ^ c.z ^ d.z; acc.w ^= a.w ^ b.w ^ c.w ^ d.w;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+// Every workgroup reads one contiguous piece, eight independent non-temporal 16-byte loads in flight per
+// thread: the fastest read-only shape found on this machine (a grid-stride loop of plain loads is 15-25 % slower).
+__global__ void __launch_bounds__(256) read_stream_kernel(const u32x4* __restrict__ p, size_t n, u32x4* sink) {
+  constexpr int INF = 8;
+  const size_t per = (n + gridDim.x - 1) / gridDim.x;
+  const size_t lo = per * blockIdx.x, hi = lo + per < n ? lo + per : n;
+  u32x4 acc = {0, 0, 0, 0};
+  size_t i = lo + threadIdx.x;
+  for (; i + (INF - 1) * 256 < hi; i += INF * 256) {
+    u32x4 v[INF];
+#pragma unroll
+    for (int j = 0; j < INF; ++j) v[j] = __builtin_nontemporal_load(p + i + j * 256);
+#pragma unroll
+    for (int j = 0; j < INF; ++j) acc ^= v[j];
   }
-  for (; i < n; i += stride) { const uint4 a = p[i]; acc.x ^= a.x; acc.y ^= a.y; acc.z ^= a.z; acc.w ^= a.w; }
+  for (; i < hi; i += 256) acc ^= __builtin_nontemporal_load(p + i);
   // the loads must not be optimised away; the condition practically never holds
   if (acc.x == 0x12345678u && acc.y == 0x9abcdef0u && acc.z == 0x0fedcba9u && acc.w == 0x87654321u) sink[0] = acc;
 }
 
 hipError_t launch_read_stream(const void* buf, size_t bytes, void* sink, int workgroups, hipStream_t s) {
-  hipLaunchKernelGGL(read_stream_kernel, dim3(workgroups), dim3(256), 0, s, (const uint4*)buf, bytes / 16, (uint4*)sink);
+  hipLaunchKernelGGL(read_stream_kernel, dim3(workgroups), dim3(256), 0, s, (const u32x4*)buf, bytes / 16, (u32x4*)sink);
   return hipGetLastError();
 }
 

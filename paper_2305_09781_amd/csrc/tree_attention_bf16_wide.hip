@@ -70,6 +70,11 @@ constexpr int KT = SPEC_WIDE_TILE_KEYS;   // keys per workgroup tile
 constexpr int PLAN_GRID = 0, PLAN_TILES = 1;   // how work reaches the workgroups (see the end of the kernel)
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+// 16-byte load of a K/V row piece. Marked non-temporal: the K/V stream is read once per launch, and a plain
+// read of the same bytes is measurably faster with the hint.
+__device__ __forceinline__ u32x4 load_kv(const unsigned char* p) {
+  return __builtin_nontemporal_load((const u32x4*)p);
+}
 __device__ __forceinline__ void store_nt(void* p, u32x4 v) {
   asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(p), "v"(v) : "memory");
 }
@@ -148,8 +153,8 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     for (int j = 0; j < NPT; ++j) {
       const int row = min(k0 + ld_row0 + j * ROW_STEP, S_cap - 1);
       const long off = (long)((unsigned)row * cache_row_bytes) + shift;
-      Vd[j] = *(const u32x4*)(vbase + off + ld_col);
-      Kd[j] = *(const u32x4*)(kbase + off + ld_col);
+      Vd[j] = load_kv(vbase + off + ld_col);
+      Kd[j] = load_kv(kbase + off + ld_col);
     }
   };
 
@@ -194,8 +199,8 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
           off_k = from_new ? new_minus_cache_k + new_shift + in_new : in_cache;
           off_v = from_new ? new_minus_cache_v + new_shift + in_new : in_cache;
         }
-        Vd[j] = *(const u32x4*)(vc + off_v + ld_col);
-        Kd[j] = *(const u32x4*)(kc + off_k + ld_col);
+        Vd[j] = load_kv(vc + off_v + ld_col);
+        Kd[j] = load_kv(kc + off_k + ld_col);
       }
     };
     {
