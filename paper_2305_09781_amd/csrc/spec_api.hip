@@ -97,18 +97,22 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d, bool paged) {
   p.wide = d.dtype == SPEC_BF16 &&
            (tiles > 1 || ns.b != d.q_stride_b || ns.n != d.q_stride_n || ns.h != d.q_stride_h);
   int chunk = env_int("SPEC_TREE_CHUNK_KEYS", 0);
+  // workgroups the device holds at once: four-wavefront shapes of the wide kernel run two per compute unit
+  const long resident = (long)compute_units() * ((p.wide && tiles <= 4) ? 2 : 1);
   if (chunk <= 0 && d.dtype == SPEC_BF16) {
-    // Few (request, head) pairs with long key ranges (long-context serving, ragged lengths): the bf16
-    // kernels deal the key tiles of all pairs to as many workgroups as the device holds at once, in
-    // equal shares, so the stream is balanced whatever the individual lengths are. Used when it gives
-    // more workgroups than pairs, each with at least 8 tiles at the stated maximum length.
+    // Several requests with few (request, head) pairs and long key ranges (long-context serving, ragged
+    // lengths): the bf16 kernels deal the key tiles of all pairs to as many workgroups as the device holds at
+    // once, in equal shares, so the stream is balanced whatever the individual lengths are. A share that
+    // crosses a pair boundary is two segments in a row, each with its own first-load latency and epilogue
+    // (about 6 us, measured against fixed chunks on equal lengths from 1024 to 16384 keys), so the deal is
+    // used only when a share is long enough for that to be small next to what unequal lengths would cost
+    // fixed chunks (a quarter of the stream for lengths uniform in [max/2, max]): at least 2048 keys per
+    // share at the stated maximum length. One request has no lengths to balance: fixed chunks.
     const int tile = p.wide ? SPEC_WIDE_TILE_KEYS : SPEC_SMALL_TILE_KEYS;
-    const int resident_per_cu = (p.wide && tiles <= 4) ? 2 : 1;   // four-wavefront workgroups: two per compute unit
-    const long resident = (long)compute_units() * resident_per_cu;
     int wgs = env_int("SPEC_TREE_BALANCED_WGS", -1);
     if (wgs < 0) {
       const long max_tiles = groups * ((max_len + tile - 1) / tile);
-      long cand = std::min<long>(resident, max_tiles / 8);
+      long cand = (max_tiles * tile / resident >= 2048) ? resident : 0;
       // every workgroup writes (and the combine step reads back) float32 partials for all queries of its
       // pair: keep that traffic under a quarter of the K/V stream (it matters with grouped-query heads,
       // where a pair has many queries and the batch few pairs)
@@ -116,7 +120,7 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d, bool paged) {
       const double partial_bytes_per_wg = 2.0 * (double)qg.heads_per_wg * d.N * (d.D + 2) * 4.0;
       cand = std::min<long>(cand, (long)(0.25 * stream_bytes / partial_bytes_per_wg));
       // every workgroup walks prefix_len[0..B) with scalar loads to find its share: only for small batches
-      wgs = (cand > groups && d.B <= 64) ? (int)cand : 0;
+      wgs = (cand > groups && d.B > 1 && d.B <= 64) ? (int)cand : 0;
     }
     if (wgs > 0) {
       p.balanced_wgs = wgs;
@@ -129,14 +133,13 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d, bool paged) {
     if (chunk <= 0) {
       // One workgroup per (request, head, query group) streams its whole key range when that already
       // gives every compute unit a workgroup: a workgroup's fixed cost (first loads, tree set-up, final
-      // merge, and the extra combine launch) outweighs any gain from more parallel slack. Only batches
-      // with few (request, head) pairs are split, into chunks of at least 512 keys.
-      long splits = 1;
-      if (groups < 256) {
-        splits = (768 + groups - 1) / groups;
-        const long max_splits = max_len / 512 > 0 ? max_len / 512 : 1;
-        if (splits > max_splits) splits = max_splits;
-      }
+      // merge, and the extra combine launch) outweighs any gain from more parallel slack. With fewer pairs
+      // the key range is cut into as many equal chunks as fill the device once, of at least 256 keys
+      // (measured on one to four requests of 32 heads, 1024 to 16384 keys: 13 us instead of 22 for one
+      // request of 1024 keys, 50 instead of 57 for 16384).
+      long splits = std::max<long>(1, resident / std::max<long>(1, groups));
+      const long max_splits = std::max<long>(1, max_len / 256);
+      if (splits > max_splits) splits = max_splits;
       chunk = (int)((max_len + splits - 1) / splits);
       if (chunk < 128) chunk = 128;
     }
@@ -151,7 +154,6 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d, bool paged) {
     // instead of one per head (measured: 3 % on 512 pairs of 640 keys; no gain for the four-wavefront shape,
     // where two workgroups per compute unit already overlap each other's prologues). Chosen to minimise
     // (rounds of workgroups) x (heads in a row + the fixed cost of a workgroup, about a third of a head).
-    const long resident = (long)compute_units();
     int best = 1;
     double best_cost = 1e30;
     for (int nh = 1; nh <= 8 && nh <= d.H_kv; ++nh) {

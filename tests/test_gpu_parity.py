@@ -490,6 +490,26 @@ def test_balanced_plan_attention_and_append(spec, case):
         assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco), fused
 
 
+@pytest.mark.parametrize("case", [(1, 4, 128, (700, 700), 16, "expansion"), (1, 3, 128, (1300, 1300), 40, "random_branching"),
+                                  (2, 2, 128, (300, 1100), 64, "random_branching"), (1, 2, 64, (900, 900), 128, "random_branching"),
+                                  (3, 2, 128, (0, 800), 16, "random_parent")])
+def test_small_batches_take_the_chunked_plan_by_default(spec, case):
+    """With fewer (request, head) pairs than compute units the plan itself (no override) cuts the key range
+    into chunks of at least 256 keys and merges the partial results: the caller must bring a workspace, the
+    result is the oracle's, and requests shorter than the stated maximum leave their trailing chunks empty."""
+    B, H, D, P, N, tree = case
+    cfg = wl.Config(94, "chunked", "bf16", B=B, H=H, D=D, P=P if P[0] != P[1] else P[0], N=N, tree=tree,
+                    widths=wl.EXPANSION_EVAL * 2)
+    inp = wl.make_attention_inputs(cfg, seed=2500 + N + B, S_cap=P[1] + N + 3)
+    desc = spec.make_desc(_dev(inp["q"][0]), _dev(inp["k_cache"][0]), max_prefix_len=int(inp["prefix_len"].max()))
+    assert spec.spec_tree_attention_workspace_bytes(desc) > 0
+    ref, kco, vco = _oracle_append_attention(inp)
+    for fused in (False, True):
+        out, kc, vc = _run_append_attention(spec, inp, fused=fused)
+        _check_attention(out, ref, cfg.torch_dtype)
+        assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco), fused
+
+
 @pytest.mark.parametrize("fused", [False, True])
 def test_config2_bf16_full(spec, fused):
     cfg = wl.CONFIGS[2]
