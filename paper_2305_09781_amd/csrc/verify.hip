@@ -88,6 +88,11 @@ __device__ inline T block_sum(T v, T* scratch) {
 // ---------------------------------------------------------------------------------------------
 constexpr int NS_THREADS = 1024;
 
+// exp(x) for x <= 0 as one v_exp_f32 (1 ulp; results below 2^-126 become 0). The sum over a vocabulary row is
+// bound by this instruction count: the library expf costs about ten instructions per element, and the
+// statistics kernel ran at half the speed of its max-only form with it.
+__device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
+
 template <bool BF16, int VEC>
 __global__ void __launch_bounds__(NS_THREADS) node_stats_kernel(const void* __restrict__ logits, int V, float inv_temp,
                                                                 int32_t* __restrict__ node_argmax,
@@ -122,11 +127,11 @@ __global__ void __launch_bounds__(NS_THREADS) node_stats_kernel(const void* __re
       for (int e = 0; e < VEC; ++e)
         if (x[j][e] > m) { m = x[j][e]; best_i = (g0 + j * NS_THREADS + t) * VEC + e; }   // ascending index: lowest wins ties
     if (want_sum && m > -INFINITY) {
-      sum *= expf((best - m) * inv_temp);     // best = -inf gives 0
+      sum *= fast_exp((best - m) * inv_temp);     // best = -inf gives 0
 #pragma unroll
       for (int j = 0; j < SWEEP_U; ++j)
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) sum += expf((x[j][e] - m) * inv_temp);   // padding: exp(-inf) = 0
+        for (int e = 0; e < VEC; ++e) sum += fast_exp((x[j][e] - m) * inv_temp);   // padding: exp(-inf) = 0
     }
     best = m;
   }
@@ -144,7 +149,7 @@ __global__ void __launch_bounds__(NS_THREADS) node_stats_kernel(const void* __re
     if (s_val[w] > best || (s_val[w] == best && s_idx[w] < best_i)) { best = s_val[w]; best_i = s_idx[w]; }
   if (best_i == 0x7fffffff) best_i = 0;   // all -inf / NaN row
   if (want_sum) {
-    if (my_best > -INFINITY) sum *= expf((my_best - best) * inv_temp); else sum = 0.f;
+    if (my_best > -INFINITY) sum *= fast_exp((my_best - best) * inv_temp); else sum = 0.f;
     sum = block_sum(sum, s_sum);
   }
   if (t == 0) {
