@@ -13,7 +13,8 @@
  * Conventions common to every call
  *   - Every data pointer is a DEVICE pointer unless its comment says "host". The caller owns all
  *     buffers; the library allocates nothing and keeps no state between calls. Scratch memory comes
- *     from a caller-supplied workspace whose size is returned by the matching *_workspace_bytes call.
+ *     from a caller-supplied workspace whose size is returned by the matching *_workspace_bytes call
+ *     (one call, spec_tree_attention_append_static, uses a scratch array of the library instead).
  *   - Every call only enqueues work on `hip_stream` (a hipStream_t passed as void*, NULL = the null
  *     stream) and returns without synchronising. Outputs are valid once the stream reaches that point.
  *   - Return value: SPEC_OK (0) or a negative SPEC_ERR_* code for anything the host can check
@@ -160,6 +161,27 @@ int spec_tree_attention_append(const spec_attn_desc_t* desc, const void* q, cons
                                const int32_t* tree_depth /*[B,N]*/, const int32_t* prefix_len /*[B]*/, void* out,
                                void* workspace, size_t workspace_bytes, int32_t* status /*[B] or NULL*/,
                                void* hip_stream);
+
+/*
+ * spec_tree_attention_append for callers that cannot allocate or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments, results and status bits as
+ * spec_tree_attention_append, without the workspace: the float32 partial results of a split key range live
+ * in a device array of SPEC_STATIC_SCRATCH_BYTES that is part of the library's code object (every GPU the
+ * library runs on holds its own copy until the process ends). The call allocates nothing and calls no
+ * allocating routine; a shape whose launch plan needs more scratch than that is refused with
+ * SPEC_ERR_WORKSPACE (nothing enqueued). The array's device address is looked up once per device, on the
+ * first call made with that device current (do that first call outside graph capture, like any kernel's).
+ * Every call on a GPU shares that GPU's array, which keeps the previous call's contents: nothing in it has
+ * to start at zero (each launch writes every slot it later reads), but two calls whose work overlaps in
+ * time on one GPU (different streams, or threads on different streams) race on it. Calls on one stream are
+ * safe back to back.
+ */
+#define SPEC_STATIC_SCRATCH_BYTES (64u << 20)
+int spec_tree_attention_append_static(const spec_attn_desc_t* desc, const void* q, const void* k_new,
+                                      const void* v_new, void* k_cache, void* v_cache,
+                                      const int32_t* tree_parent /*[B,N]*/, const int32_t* tree_depth /*[B,N]*/,
+                                      const int32_t* prefix_len /*[B]*/, void* out,
+                                      int32_t* status /*[B] or NULL*/, void* hip_stream);
 
 /*
  * Expansion-based token tree construction, one step (Section 3): for every frontier node f of every

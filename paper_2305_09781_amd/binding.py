@@ -29,8 +29,9 @@ EXPORTED = [
     "spec_kv_append_paged", "spec_kv_append_rope_paged", "spec_tree_attention_paged", "spec_tree_attention_append_paged",
     "spec_tree_attention_paged_workspace_bytes", "spec_kv_commit_paged",
     "spec_lm_head_argmax", "spec_lm_head_argmax_workspace_bytes", "spec_verify_greedy_lm_head",
-    "spec_qk_rope_append", "spec_qk_rope_append_paged",
+    "spec_qk_rope_append", "spec_qk_rope_append_paged", "spec_tree_attention_append_static",
 ]
+STATIC_SCRATCH_BYTES = 64 << 20
 
 
 class SpecError(RuntimeError):
@@ -80,6 +81,8 @@ def load():
     lib.spec_tree_attention.restype = ctypes.c_int
     lib.spec_tree_attention_append.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
     lib.spec_tree_attention_append.restype = ctypes.c_int
+    lib.spec_tree_attention_append_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.spec_tree_attention_append_static.restype = ctypes.c_int
     lib.spec_tree_attention_workspace_bytes.argtypes = [dp]
     lib.spec_tree_attention_workspace_bytes.restype = sz
     lib.spec_verify_greedy.argtypes = [i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp, vp]
@@ -269,6 +272,22 @@ def spec_tree_attention_append(q, k_new, v_new, k_cache, v_cache, tree_parent, t
                                              _ptr(v_cache), _ptr(tree_parent), _ptr(tree_depth), _ptr(prefix_len),
                                              _ptr(out), _ptr(workspace), ws_bytes, _ptr(status), _stream(stream)),
            "spec_tree_attention_append")
+    return out
+
+
+def spec_tree_attention_append_static(q, k_new, v_new, k_cache, v_cache, tree_parent, tree_depth, prefix_len, out,
+                                      status=None, max_prefix_len: int = 0, softmax_scale: float = 0.0, stream=None,
+                                      desc=None):
+    """spec_tree_attention_append on the library's own scratch array: no workspace, and nothing is allocated
+    here either (the caller brings `out`)."""
+    _same_layout(k_cache, v_cache, "k_cache and v_cache")
+    _same_layout(k_new, v_new, "k_new and v_new")
+    _same_layout(q, out, "q and out")
+    d = desc if desc is not None else make_desc(q, k_cache, max_prefix_len, softmax_scale, k_new=k_new)
+    _check(load().spec_tree_attention_append_static(ctypes.byref(d), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache),
+                                                    _ptr(v_cache), _ptr(tree_parent), _ptr(tree_depth),
+                                                    _ptr(prefix_len), _ptr(out), _ptr(status), _stream(stream)),
+           "spec_tree_attention_append_static")
     return out
 
 

@@ -5,10 +5,34 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "spec_internal.h"
 
+// Scratch of spec_tree_attention_append_static: the split plans' float32 partial results, for callers that can
+// neither allocate nor bring a workspace. Part of the code object, so every GPU that loads the library holds
+// its own copy at its own address. In host code this name is only a handle for hipGetSymbolAddress; the
+// device address it returns is what kernels and copies take.
+static __device__ __align__(256) unsigned char scratch[SPEC_STATIC_SCRATCH_BYTES];
+
 namespace spec {
+
+// Device address of `scratch` on the current device, looked up once per device.
+static int static_scratch(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SPEC_ERR_HIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return SPEC_ERR_HIP;
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return SPEC_OK;
+}
 
 static inline int elem_bytes(int dtype) { return dtype == SPEC_F32 ? 4 : 2; }
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -360,6 +384,25 @@ int spec_tree_attention_append(const spec_attn_desc_t* desc, const void* q, cons
   if (!k_new || !v_new) return check_desc(desc) != SPEC_OK ? check_desc(desc) : SPEC_ERR_INVALID_ARG;
   return tree_attention_impl(desc, nullptr, false, q, k_new, v_new, k_cache, v_cache, tree_parent, tree_depth,
                              prefix_len, out, workspace, workspace_bytes, status, hip_stream);
+}
+
+int spec_tree_attention_append_static(const spec_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,
+                                      void* k_cache, void* v_cache, const int32_t* tree_parent,
+                                      const int32_t* tree_depth, const int32_t* prefix_len, void* out, int32_t* status,
+                                      void* hip_stream) {
+  const int rc = check_desc(desc);
+  if (rc != SPEC_OK) return rc;
+  if (!k_new || !v_new) return SPEC_ERR_INVALID_ARG;
+  // the plan of the contiguous call decides how much scratch the launch needs
+  const size_t need = make_attn_plan(*desc).ws_bytes;
+  if (need > (size_t)SPEC_STATIC_SCRATCH_BYTES) return SPEC_ERR_WORKSPACE;
+  void* ws = nullptr;
+  if (need > 0) {
+    const int src = static_scratch(&ws);
+    if (src != SPEC_OK) return src;
+  }
+  return tree_attention_impl(desc, nullptr, false, q, k_new, v_new, k_cache, v_cache, tree_parent, tree_depth,
+                             prefix_len, out, ws, need, status, hip_stream);
 }
 
 int spec_tree_attention_append_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, const void* q,

@@ -74,6 +74,22 @@ def test_misaligned_pointers_and_workspace_are_rejected():
     assert lib.spec_tree_attention(ctypes.byref(d), a, a, a, a, a, a, a, a, need - 1, None, None) == binding.ERR_WORKSPACE
 
 
+def test_static_scratch_entry_point_refuses_shapes_beyond_its_array():
+    """The entry point that allocates nothing has a fixed scratch array: a launch plan that needs more is
+    refused on the host (SPEC_ERR_WORKSPACE, nothing enqueued), a small one passes the size check."""
+    lib = binding.load()
+    B, H, D, N, S = 8, 8, 128, 128, 60128
+    d = _desc(B=B, H=H, H_kv=H, D=D, N=N, S_cap=S, dtype=binding.SPEC_BF16, max_prefix_len=60000,
+              q_stride_b=N * H * D, q_stride_n=H * D, q_stride_h=D, kv_stride_b=H * S * D, kv_stride_h=S * D, kv_stride_s=D)
+    assert lib.spec_tree_attention_workspace_bytes(ctypes.byref(d)) > binding.STATIC_SCRATCH_BYTES
+    buf = ctypes.create_string_buffer(4096)
+    a = ctypes.c_void_p((ctypes.addressof(buf) + 255) // 256 * 256)
+    assert lib.spec_tree_attention_append_static(ctypes.byref(d), a, a, a, a, a, a, a, a, a, None, None) == binding.ERR_WORKSPACE
+    assert lib.spec_tree_attention_append_static(ctypes.byref(d), a, None, a, a, a, a, a, a, a, None, None) == binding.ERR_INVALID_ARG
+    bad = _desc(D=96)
+    assert lib.spec_tree_attention_append_static(ctypes.byref(bad), a, a, a, a, a, a, a, a, a, None, None) == binding.ERR_UNSUPPORTED
+
+
 def test_verify_and_commit_reject_bad_arguments():
     lib = binding.load()
     assert lib.spec_verify_greedy(0, 8, 64, 0, None, None, None, 8, None, None, None, None, None, 0, None, None) == binding.ERR_INVALID_ARG
