@@ -82,6 +82,7 @@ def main():
     import torch
 
     from paper_2305_09781_amd import binding as spec
+    from paper_2305_09781_amd import probe_binding as probe
     from paper_2305_09781_amd import workloads as wl
 
     spec.load()
@@ -209,7 +210,7 @@ def main():
     sink = torch.zeros(16, dtype=torch.uint8, device=dev)
     def read_all():
         for pb in probes:
-            spec.spec_probe_read_stream(pb, sink)
+            probe.spec_probe_read_stream(pb, sink)
     read_all()
     torch.cuda.synchronize()
     ev0.record()

@@ -34,6 +34,9 @@
  *     request's sequence, rows [0, prefix_len[b]) are the verified prefix and rows
  *     [prefix_len[b], prefix_len[b] + N) hold the tree in node order after spec_kv_append.
  *     All strides are in ELEMENTS and must be multiples of 16 bytes; base pointers 16-byte aligned.
+ *     The rows of one (request, head) must span less than 4 GiB (S_cap * kv_stride_s * element size
+ *     < 2^32, with S_cap the logical capacity of a request for paged caches; SPEC_ERR_UNSUPPORTED
+ *     otherwise): row offsets inside that span are computed in 32 bits.
  */
 #ifndef SPEC_TREE_H
 #define SPEC_TREE_H
@@ -54,7 +57,7 @@ extern "C" {
 #define SPEC_OK 0
 #define SPEC_ERR_INVALID_ARG (-1) /* null pointer, non-positive size, bad stride or alignment        */
 #define SPEC_ERR_UNSUPPORTED (-2) /* D not in {64,128}, N > SPEC_MAX_TREE_NODES, dtype, H_kv not a   */
-                                  /* divisor of H                                                    */
+                                  /* divisor of H, a (request, head) span of 4 GiB or more           */
 #define SPEC_ERR_CAPACITY (-3)    /* N > S_cap, max_prefix_len + N > S_cap                           */
 #define SPEC_ERR_HIP (-4)         /* a HIP runtime call failed (launch error)                        */
 #define SPEC_ERR_WORKSPACE (-5)   /* workspace NULL or smaller than *_workspace_bytes reports        */
@@ -88,7 +91,16 @@ typedef struct spec_attn_desc {
   int64_t new_stride_b, new_stride_n, new_stride_h; /* k_new, v_new: [B,N,H_kv,D]; all 0 = the q     */
                                                     /* strides (only meaningful when H_kv = H)       */
   float softmax_scale;    /* 0 = 1/sqrt(D)                                                           */
-  int32_t reserved;       /* must be 0                                                               */
+  /* Launch-plan hints of the attention calls, all 0 = the library chooses (by shape and device). They   */
+  /* change how the key range is dealt to workgroups, never what is computed (results agree up to        */
+  /* float32 rounding order); the workspace size follows them. For callers that tune a shape, and for    */
+  /* tests that drive small inputs through every plan.                                                    */
+  int32_t plan_chunk_keys;   /* > 0: fixed chunks of this many keys (rounded up to the kernel's tile), one */
+                             /* workgroup per (request, head, chunk), partials merged by a second launch  */
+  int32_t plan_balanced_wgs; /* > 0: bf16 only, the key tiles of all (request, head) pairs dealt in equal  */
+                             /* shares to this many workgroups; -1: never use that plan                    */
+  int32_t plan_heads_per_wg; /* > 0: trees of 65..128 nodes streamed whole: consecutive K/V heads of a     */
+                             /* request served by one workgroup                                            */
 } spec_attn_desc_t;
 
 /*
@@ -364,15 +376,6 @@ int spec_kv_commit_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pa
                          void* const* k_caches /*host*/, void* const* v_caches /*host*/,
                          const int32_t* accepted_path, int32_t Lmax, const int32_t* accepted_len,
                          const int32_t* prefix_len, int32_t* prefix_len_out, int32_t* status, void* hip_stream);
-
-/*
- * Measurement aid (no passage of the paper): reads `bytes` (a multiple of 16 is used) from buf once with
- * non-temporal 16-byte loads, a contiguous piece per workgroup, and writes nothing (sink: 16 device bytes
- * that are never written in practice). Timed
- * over a buffer much larger than the on-chip caches it gives the read bandwidth this machine sustains,
- * the practical ceiling next to the published HBM peak.
- */
-int spec_probe_read_stream(const void* buf, size_t bytes, void* sink, void* hip_stream);
 
 /* Text for a SPEC_ERR_* code (static storage). Library version as major*10000 + minor*100 + patch. */
 

@@ -24,7 +24,7 @@ EXPORTED = [
     "spec_kv_append", "spec_kv_append_rope", "spec_tree_attention", "spec_tree_attention_append", "spec_tree_attention_workspace_bytes",
     "spec_verify_greedy",
     "spec_verify_stochastic", "spec_verify_stochastic_workspace_bytes", "spec_verify_naive",
-    "spec_verify_naive_workspace_bytes", "spec_tree_expand_topk", "spec_tree_merge", "spec_kv_commit", "spec_probe_read_stream", "spec_strerror",
+    "spec_verify_naive_workspace_bytes", "spec_tree_expand_topk", "spec_tree_merge", "spec_kv_commit", "spec_strerror",
     "spec_version",
     "spec_kv_append_paged", "spec_kv_append_rope_paged", "spec_tree_attention_paged", "spec_tree_attention_append_paged",
     "spec_tree_attention_paged_workspace_bytes", "spec_kv_commit_paged",
@@ -49,7 +49,8 @@ class AttnDesc(ctypes.Structure):
         ("q_stride_b", ctypes.c_int64), ("q_stride_n", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
         ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64), ("kv_stride_s", ctypes.c_int64),
         ("new_stride_b", ctypes.c_int64), ("new_stride_n", ctypes.c_int64), ("new_stride_h", ctypes.c_int64),
-        ("softmax_scale", ctypes.c_float), ("reserved", ctypes.c_int32),
+        ("softmax_scale", ctypes.c_float), ("plan_chunk_keys", ctypes.c_int32), ("plan_balanced_wgs", ctypes.c_int32),
+        ("plan_heads_per_wg", ctypes.c_int32),
     ]
 
 
@@ -125,8 +126,6 @@ def load():
     lib.spec_lm_head_argmax.restype = ctypes.c_int
     lib.spec_verify_greedy_lm_head.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp, vp]
     lib.spec_verify_greedy_lm_head.restype = ctypes.c_int
-    lib.spec_probe_read_stream.argtypes = [vp, sz, vp, vp]
-    lib.spec_probe_read_stream.restype = ctypes.c_int
     lib.spec_strerror.argtypes = [ctypes.c_int]
     lib.spec_strerror.restype = ctypes.c_char_p
     lib.spec_version.restype = ctypes.c_int
@@ -162,9 +161,11 @@ def _check(rc: int, where: str):
 
 
 def make_desc(q_like: torch.Tensor, k_cache: torch.Tensor, max_prefix_len: int = 0,
-              softmax_scale: float = 0.0, k_new: Optional[torch.Tensor] = None) -> AttnDesc:
+              softmax_scale: float = 0.0, k_new: Optional[torch.Tensor] = None,
+              plan: Tuple[int, int, int] = (0, 0, 0)) -> AttnDesc:
     """Descriptor from a [B,N,H,D] tensor (q / out), a [B,H_kv,S_cap,D] cache and, for grouped-query heads,
-    the [B,N,H_kv,D] k_new (its strides; without it k_new / v_new are taken to be laid out like q)."""
+    the [B,N,H_kv,D] k_new (its strides; without it k_new / v_new are taken to be laid out like q).
+    plan = the descriptor's launch-plan hints (plan_chunk_keys, plan_balanced_wgs, plan_heads_per_wg)."""
     B, N, H, D = q_like.shape
     Bc, Hkv, S_cap, Dc = k_cache.shape
     if (Bc, Dc) != (B, D) or q_like.stride(3) != 1 or k_cache.stride(3) != 1:
@@ -176,7 +177,8 @@ def make_desc(q_like: torch.Tensor, k_cache: torch.Tensor, max_prefix_len: int =
         new = (k_new.stride(0), k_new.stride(1), k_new.stride(2))
     return AttnDesc(B, H, Hkv, D, N, S_cap, _dtype_code(q_like.dtype), int(max_prefix_len),
                     q_like.stride(0), q_like.stride(1), q_like.stride(2),
-                    k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), *new, float(softmax_scale), 0)
+                    k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), *new, float(softmax_scale),
+                    int(plan[0]), int(plan[1]), int(plan[2]))
 
 
 def _same_layout(a: torch.Tensor, b: torch.Tensor, what: str):
@@ -238,12 +240,13 @@ def spec_tree_attention_workspace_bytes(desc: AttnDesc) -> int:
 
 
 def spec_tree_attention(q, k_cache, v_cache, tree_parent, tree_depth, prefix_len, out=None, workspace=None,
-                        status=None, max_prefix_len: int = 0, softmax_scale: float = 0.0, stream=None, desc=None):
+                        status=None, max_prefix_len: int = 0, softmax_scale: float = 0.0, stream=None, desc=None,
+                        plan=(0, 0, 0)):
     _same_layout(k_cache, v_cache, "k_cache and v_cache")
     if out is None:
         out = torch.empty_like(q)
     _same_layout(q, out, "q and out")
-    d = desc if desc is not None else make_desc(q, k_cache, max_prefix_len, softmax_scale)
+    d = desc if desc is not None else make_desc(q, k_cache, max_prefix_len, softmax_scale, plan=plan)
     need = spec_tree_attention_workspace_bytes(d)
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
@@ -256,14 +259,14 @@ def spec_tree_attention(q, k_cache, v_cache, tree_parent, tree_depth, prefix_len
 
 def spec_tree_attention_append(q, k_new, v_new, k_cache, v_cache, tree_parent, tree_depth, prefix_len, out=None,
                                workspace=None, status=None, max_prefix_len: int = 0, softmax_scale: float = 0.0,
-                               stream=None, desc=None):
+                               stream=None, desc=None, plan=(0, 0, 0)):
     """KV append of the tree rows fused with the tree attention over them."""
     _same_layout(k_cache, v_cache, "k_cache and v_cache")
     _same_layout(k_new, v_new, "k_new and v_new")
     if out is None:
         out = torch.empty_like(q)
     _same_layout(q, out, "q and out")
-    d = desc if desc is not None else make_desc(q, k_cache, max_prefix_len, softmax_scale, k_new=k_new)
+    d = desc if desc is not None else make_desc(q, k_cache, max_prefix_len, softmax_scale, k_new=k_new, plan=plan)
     need = spec_tree_attention_workspace_bytes(d)
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
@@ -277,13 +280,13 @@ def spec_tree_attention_append(q, k_new, v_new, k_cache, v_cache, tree_parent, t
 
 def spec_tree_attention_append_static(q, k_new, v_new, k_cache, v_cache, tree_parent, tree_depth, prefix_len, out,
                                       status=None, max_prefix_len: int = 0, softmax_scale: float = 0.0, stream=None,
-                                      desc=None):
+                                      desc=None, plan=(0, 0, 0)):
     """spec_tree_attention_append on the library's own scratch array: no workspace, and nothing is allocated
     here either (the caller brings `out`)."""
     _same_layout(k_cache, v_cache, "k_cache and v_cache")
     _same_layout(k_new, v_new, "k_new and v_new")
     _same_layout(q, out, "q and out")
-    d = desc if desc is not None else make_desc(q, k_cache, max_prefix_len, softmax_scale, k_new=k_new)
+    d = desc if desc is not None else make_desc(q, k_cache, max_prefix_len, softmax_scale, k_new=k_new, plan=plan)
     _check(load().spec_tree_attention_append_static(ctypes.byref(d), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache),
                                                     _ptr(v_cache), _ptr(tree_parent), _ptr(tree_depth),
                                                     _ptr(prefix_len), _ptr(out), _ptr(status), _stream(stream)),
@@ -399,7 +402,7 @@ def spec_kv_commit(k_caches: Sequence[torch.Tensor], v_caches: Sequence[torch.Te
         _same_layout(vc, k0, "all layer caches")
     B, H, S_cap, D = k0.shape
     d = AttnDesc(B, H, H, D, N, S_cap, _dtype_code(k0.dtype), 0, N * H * D, H * D, D,
-                 k0.stride(0), k0.stride(1), k0.stride(2), 0, 0, 0, 0.0, 0)
+                 k0.stride(0), k0.stride(1), k0.stride(2), 0, 0, 0, 0.0, 0, 0, 0)
     if prefix_len_out is None:
         prefix_len_out = torch.empty_like(prefix_len)
     arr_t = ctypes.c_void_p * L
@@ -416,7 +419,8 @@ def spec_kv_commit(k_caches: Sequence[torch.Tensor], v_caches: Sequence[torch.Te
 # ------------------------------------------------------------------------------------------------
 
 def make_paged_desc(q_like: torch.Tensor, k_pool: torch.Tensor, block_table: torch.Tensor, max_prefix_len: int = 0,
-                    softmax_scale: float = 0.0, k_new: Optional[torch.Tensor] = None) -> Tuple[AttnDesc, KvPages]:
+                    softmax_scale: float = 0.0, k_new: Optional[torch.Tensor] = None,
+                    plan: Tuple[int, int, int] = (0, 0, 0)) -> Tuple[AttnDesc, KvPages]:
     """Descriptor and page description from a [B,N,H,D] tensor, a pool and the int32 block table (device).
     The logical capacity of a request is max_blocks * block_tokens rows."""
     B, N, H, D = q_like.shape
@@ -434,7 +438,8 @@ def make_paged_desc(q_like: torch.Tensor, k_pool: torch.Tensor, block_table: tor
     max_blocks = block_table.shape[1]
     d = AttnDesc(B, H, Hkv, D, N, max_blocks * bt, _dtype_code(q_like.dtype), int(max_prefix_len),
                  q_like.stride(0), q_like.stride(1), q_like.stride(2),
-                 k_pool.stride(0), k_pool.stride(1), k_pool.stride(2), new[0], new[1], new[2], float(softmax_scale), 0)
+                 k_pool.stride(0), k_pool.stride(1), k_pool.stride(2), new[0], new[1], new[2], float(softmax_scale),
+                 int(plan[0]), int(plan[1]), int(plan[2]))
     return d, KvPages(block_table.data_ptr(), max_blocks, bt, n_blocks)
 
 
@@ -468,13 +473,13 @@ def spec_kv_append_rope_paged(k_new, v_new, k_pool, v_pool, block_table, tree_de
 
 def spec_tree_attention_paged(q, k_pool, v_pool, block_table, tree_parent, tree_depth, prefix_len, out=None,
                               workspace=None, status=None, max_prefix_len: int = 0, softmax_scale: float = 0.0,
-                              stream=None, k_new=None, v_new=None):
+                              stream=None, k_new=None, v_new=None, plan=(0, 0, 0)):
     """Tree attention over paged caches; with k_new / v_new the KV append of the tree rows is fused in."""
     _same_layout(k_pool, v_pool, "k_pool and v_pool")
     if out is None:
         out = torch.empty_like(q)
     _same_layout(q, out, "q and out")
-    d, pg = make_paged_desc(q, k_pool, block_table, max_prefix_len, softmax_scale, k_new=k_new)
+    d, pg = make_paged_desc(q, k_pool, block_table, max_prefix_len, softmax_scale, k_new=k_new, plan=plan)
     need = spec_tree_attention_paged_workspace_bytes(d, pg)
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
@@ -511,7 +516,7 @@ def spec_kv_commit_paged(k_pools: Sequence[torch.Tensor], v_pools: Sequence[torc
     n_blocks, H, bt, D = k0.shape
     B, max_blocks = block_table.shape
     d = AttnDesc(B, H, H, D, N, max_blocks * bt, _dtype_code(k0.dtype), 0, N * H * D, H * D, D,
-                 k0.stride(0), k0.stride(1), k0.stride(2), 0, 0, 0, 0.0, 0)
+                 k0.stride(0), k0.stride(1), k0.stride(2), 0, 0, 0, 0.0, 0, 0, 0)
     pg = KvPages(block_table.data_ptr(), max_blocks, bt, n_blocks)
     if prefix_len_out is None:
         prefix_len_out = torch.empty_like(prefix_len)
@@ -572,8 +577,3 @@ def spec_verify_greedy_lm_head(hidden, weight, tree_token, tree_parent, Lmax: Op
            "spec_verify_greedy_lm_head")
     return out
 
-
-def spec_probe_read_stream(buf: torch.Tensor, sink: torch.Tensor, stream=None):
-    """Measurement aid: one plain read pass over `buf` (device tensor); `sink` holds at least 16 device bytes."""
-    _check(load().spec_probe_read_stream(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream(stream)),
-           "spec_probe_read_stream")

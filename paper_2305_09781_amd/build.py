@@ -1,6 +1,7 @@
-"""Builds libspectree.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree.
+"""Builds libspectree.so (HIP kernels + C ABI) and libspecprobe.so (the read-stream measurement aid the
+benchmark times beside the kernels) for gfx950 with hipcc, in-tree.
 
-    python -m paper_2305_09781_amd.build        # compile every source, link the shared library
+    python -m paper_2305_09781_amd.build        # compile every source, link the shared libraries
 """
 from __future__ import annotations
 
@@ -16,9 +17,11 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 OBJ_DIR = os.path.join(PKG_DIR, "_build")
 LIB_DIR = os.path.join(PKG_DIR, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libspectree.so")
+PROBE_LIB_PATH = os.path.join(LIB_DIR, "libspecprobe.so")
 
 SOURCES = ["spec_api.hip", "kv_cache.hip", "tree_attention_f32.hip", "tree_attention_bf16.hip",
-           "tree_attention_bf16_wide.hip", "verify.hip", "tree_build.hip", "lm_head.hip", "probe.hip"]
+           "tree_attention_bf16_wide.hip", "verify.hip", "tree_build.hip", "lm_head.hip"]
+PROBE_SOURCES = ["probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=fast",
@@ -52,15 +55,17 @@ def build_library(extra_flags=(), verbose: bool = True) -> str:
     hipcc = _hipcc()
     objs = []
     jobs = []
-    for src in SOURCES:
+    probe_objs = []
+    for src in SOURCES + PROBE_SOURCES:
         obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
-        objs.append(obj)
+        (probe_objs if src in PROBE_SOURCES else objs).append(obj)
         jobs.append([hipcc, *HIPCC_FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj])
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(jobs))) as ex:
         list(ex.map(_run, jobs))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs])
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", PROBE_LIB_PATH, *probe_objs])
     if verbose:
-        print("built", LIB_PATH)
+        print("built", LIB_PATH, "and", PROBE_LIB_PATH)
     return LIB_PATH
 
 

@@ -194,17 +194,17 @@ __global__ void __launch_bounds__(256) kv_commit_kernel(LayerPtrs ptrs, const in
     }
   }
   __syncthreads();
-  bool ok = head_ok && s_bad == 0;
+  const bool ok = head_ok && s_bad == 0;
+  __syncthreads();   // every thread has read the path verdict before the flag is used again below
   // paged cache: every block that holds a row of the tree must lie inside the pool, else nothing moves
-  bool blocks_ok = true;
   if (ok && pg.table != nullptr) {
     for (int j = (p >> pg.log2_tokens) + t; j <= ((p + N - 1) >> pg.log2_tokens); j += blockDim.x) {
       const int e = pg.table[(long)b * pg.max_blocks + j];
       if (e < 0 || e >= pg.n_blocks) atomicOr(&s_bad, 2);
     }
-    __syncthreads();
-    blocks_ok = s_bad == 0;
   }
+  __syncthreads();   // reached by every thread: `ok` is uniform, and the barrier is outside the condition
+  const bool blocks_ok = !ok || s_bad == 0;
   if (blockIdx.x == 0 && layer == 0 && t == 0) {
     prefix_len_out[b] = (ok && blocks_ok) ? p + n : p;
     if (!ok) set_status(status, b, cap_ok ? SPEC_ST_BAD_PATH : SPEC_ST_CAPACITY);

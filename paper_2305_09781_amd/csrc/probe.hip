@@ -1,9 +1,12 @@
 // Measurement aid, not part of the method: a plain read stream over a device buffer. Its rate on a buffer
 // far larger than the caches is the practical ceiling any HBM-bound kernel of this library can be held
 // against (the published peak is not reachable by a kernel that only reads).
-#include "spec_internal.h"
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-namespace spec {
+#include "spec_probe.h"
+
+namespace {
 
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
@@ -27,9 +30,17 @@ __global__ void __launch_bounds__(256) read_stream_kernel(const u32x4* __restric
   if (acc.x == 0x12345678u && acc.y == 0x9abcdef0u && acc.z == 0x0fedcba9u && acc.w == 0x87654321u) sink[0] = acc;
 }
 
-hipError_t launch_read_stream(const void* buf, size_t bytes, void* sink, int workgroups, hipStream_t s) {
-  hipLaunchKernelGGL(read_stream_kernel, dim3(workgroups), dim3(256), 0, s, (const u32x4*)buf, bytes / 16, (u32x4*)sink);
-  return hipGetLastError();
-}
+}  // namespace
 
-}  // namespace spec
+extern "C" int spec_probe_read_stream(const void* buf, size_t bytes, void* sink, void* hip_stream) {
+  if (!buf || !sink || bytes < 16 || (reinterpret_cast<uintptr_t>(buf) & 15u) || (reinterpret_cast<uintptr_t>(sink) & 15u))
+    return -1;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    cus = 256;
+  // enough workgroups to fill every compute unit several times over
+  hipLaunchKernelGGL(read_stream_kernel, dim3(cus * 8), dim3(256), 0, (hipStream_t)hip_stream, (const u32x4*)buf,
+                     bytes / 16, (u32x4*)sink);
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}

@@ -3,7 +3,6 @@
 // allocates or synchronises.
 #include <algorithm>
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 #include <mutex>
 
@@ -38,17 +37,11 @@ static inline int elem_bytes(int dtype) { return dtype == SPEC_F32 ? 4 : 2; }
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-static int env_int(const char* name, int dflt) {
-  const char* v = std::getenv(name);
-  if (v == nullptr || *v == 0) return dflt;
-  return std::atoi(v);
-}
-
 // Host-checkable part of the attention descriptor. Returns SPEC_OK or an error code.
 static int check_desc(const spec_attn_desc_t* d) {
   if (d == nullptr) return SPEC_ERR_INVALID_ARG;
   if (d->B <= 0 || d->H <= 0 || d->H_kv <= 0 || d->N <= 0 || d->S_cap <= 0 || d->D <= 0) return SPEC_ERR_INVALID_ARG;
-  if (d->reserved != 0) return SPEC_ERR_INVALID_ARG;
+  if (d->plan_chunk_keys < 0 || d->plan_balanced_wgs < -1 || d->plan_heads_per_wg < 0) return SPEC_ERR_INVALID_ARG;
   if (d->dtype != SPEC_F32 && d->dtype != SPEC_BF16) return SPEC_ERR_UNSUPPORTED;
   if (d->D != 64 && d->D != 128) return SPEC_ERR_UNSUPPORTED;
   if (d->N > SPEC_MAX_TREE_NODES) return SPEC_ERR_UNSUPPORTED;
@@ -68,6 +61,8 @@ static int check_desc(const spec_attn_desc_t* d) {
   for (int64_t s : new_strides)
     if (s % per16 != 0) return SPEC_ERR_INVALID_ARG;
   if (d->q_stride_h < d->D || d->kv_stride_s < d->D) return SPEC_ERR_INVALID_ARG;
+  // the kernels compute row offsets inside one (request, head) span (paged: one block) in 32 bits
+  if ((double)d->S_cap * (double)d->kv_stride_s * elem_bytes(d->dtype) >= 4294967296.0) return SPEC_ERR_UNSUPPORTED;
   return SPEC_OK;
 }
 
@@ -89,18 +84,13 @@ static int check_pages(const spec_attn_desc_t* d, const spec_kv_pages_t* p, Page
 }
 
 // Compute units of the current device (256 when no device can be queried, e.g. sizing a workspace on a
-// machine without a GPU).
+// machine without a GPU). Asked on every call: the answer belongs to the device that is current now.
 static int compute_units() {
-  static int cached = 0;
-  if (cached == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-      cached = n;
-    else
-      cached = 256;
-  }
-  return cached;
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+    return n;
+  return 256;
 }
 
 AttnPlan make_attn_plan(const spec_attn_desc_t& d, bool paged) {
@@ -120,7 +110,7 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d, bool paged) {
   const NewStrides ns = attn_new_strides(d);
   p.wide = d.dtype == SPEC_BF16 &&
            (tiles > 1 || ns.b != d.q_stride_b || ns.n != d.q_stride_n || ns.h != d.q_stride_h);
-  int chunk = env_int("SPEC_TREE_CHUNK_KEYS", 0);
+  int chunk = d.plan_chunk_keys;   // caller's hint; 0 = chosen below
   // workgroups the device holds at once: four-wavefront shapes of the wide kernel run two per compute unit
   const long resident = (long)compute_units() * ((p.wide && tiles <= 4) ? 2 : 1);
   if (chunk <= 0 && d.dtype == SPEC_BF16) {
@@ -133,8 +123,10 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d, bool paged) {
     // fixed chunks (a quarter of the stream for lengths uniform in [max/2, max]): at least 2048 keys per
     // share at the stated maximum length. One request has no lengths to balance: fixed chunks.
     const int tile = p.wide ? SPEC_WIDE_TILE_KEYS : SPEC_SMALL_TILE_KEYS;
-    int wgs = env_int("SPEC_TREE_BALANCED_WGS", -1);
+    int wgs = d.plan_balanced_wgs;   // caller's hint: > 0 that many workgroups, -1 never, 0 = chosen here
     if (wgs < 0) {
+      wgs = 0;
+    } else if (wgs == 0) {
       const long max_tiles = groups * ((max_len + tile - 1) / tile);
       long cand = (max_tiles * tile / resident >= 2048) ? resident : 0;
       // every workgroup writes (and the combine step reads back) float32 partials for all queries of its
@@ -185,7 +177,7 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d, bool paged) {
       const double cost = (double)((wgs + resident - 1) / resident) * (nh + 0.35);
       if (cost < best_cost - 1e-9) { best_cost = cost; best = nh; }
     }
-    p.heads_per_wg = env_int("SPEC_TREE_HEADS_PER_WG", best);
+    p.heads_per_wg = d.plan_heads_per_wg > 0 ? d.plan_heads_per_wg : best;
     if (p.heads_per_wg < 1) p.heads_per_wg = 1;
     if (p.heads_per_wg > d.H_kv) p.heads_per_wg = d.H_kv;
   }
@@ -209,13 +201,6 @@ using namespace spec;
 extern "C" {
 
 int spec_version(void) { return 100; }
-
-int spec_probe_read_stream(const void* buf, size_t bytes, void* sink, void* hip_stream) {
-  if (!buf || !sink || bytes < 16 || !aligned16(buf) || !aligned16(sink)) return SPEC_ERR_INVALID_ARG;
-  // enough workgroups to fill every compute unit several times over
-  return launch_read_stream(buf, bytes, sink, compute_units() * 8, (hipStream_t)hip_stream) == hipSuccess ? SPEC_OK
-                                                                                                             : SPEC_ERR_HIP;
-}
 
 const char* spec_strerror(int code) {
   switch (code) {

@@ -3,7 +3,6 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include <cstdlib>
 
 #include "spec_tree.h"
 
@@ -115,8 +114,6 @@ hipError_t launch_tree_merge(int B, int M, int Nin, const int32_t* in_parent, co
 // LM head + arg-max (lm_head.hip). Workspace: per row one (max, arg-max) pair per vocabulary tile.
 #define SPEC_LM_HEAD_VOCAB_TILE 64   // the smaller of the two workgroup shapes: sizes the partials
 inline int lm_head_waves(int M) {
-  const char* e = getenv("SPEC_LM_HEAD_WAVES");
-  if (e != nullptr && (atoi(e) == 4 || atoi(e) == 8)) return atoi(e);
   return M <= 32 ? 4 : 8;   // few rows: the stream is everything, and two workgroups per CU overlap their starts and ends
 }
 inline size_t lm_head_partials_bytes(int M, int V) {
@@ -125,7 +122,6 @@ inline size_t lm_head_partials_bytes(int M, int V) {
 }
 hipError_t launch_lm_head_argmax(int M, int K, int V, const void* hidden, const void* weight, int32_t* node_argmax,
                                  float* node_max, void* ws, hipStream_t s);
-hipError_t launch_read_stream(const void* buf, size_t bytes, void* sink, int workgroups, hipStream_t s);
 hipError_t launch_node_stats(int B, int N, int V, int logits_dtype, const void* logits, float inv_temp,
                              int32_t* node_argmax, float* node_max, float* node_sumexp, hipStream_t s);
 hipError_t launch_node_sample(int B, int N, int V, int logits_dtype, const void* logits, float inv_temp,

@@ -42,29 +42,6 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 namespace wide {
 
-#ifdef SPEC_WIDE_TIMELINE
-// Development aid: per-wavefront timestamps (100 MHz clock) and placement, written to the workspace.
-#define WTL(slot)                                                                                               \
-  {                                                                                                             \
-    unsigned long long ts_;                                                                                     \
-    asm volatile("s_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(ts_)::"memory");                             \
-    if (lane == 0)                                                                                              \
-      ((unsigned long long*)ws_o)[((blockIdx.x + (long)gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)) * WAVES + wave) * 8 + (slot)] = ts_; \
-  }
-#define WTL_HW()                                                                                                \
-  {                                                                                                             \
-    unsigned hw_, xcc_;                                                                                         \
-    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)\n\ts_getreg_b32 %1, hwreg(HW_REG_XCC_ID)" : "=s"(hw_), "=s"(xcc_)); \
-    if (lane == 0) {                                                                                            \
-      unsigned long long* p_ = (unsigned long long*)ws_o + ((blockIdx.x + (long)gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)) * WAVES + wave) * 8; \
-      p_[2] = hw_; p_[3] = xcc_;                                                                                \
-    }                                                                                                           \
-  }
-#else
-#define WTL(slot)
-#define WTL_HW()
-#endif
-
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int KT = SPEC_WIDE_TILE_KEYS;   // keys per workgroup tile
 constexpr int PLAN_GRID = 0, PLAN_TILES = 1;   // how work reaches the workgroups (see the end of the kernel)
@@ -128,8 +105,6 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
   const int qt = wave % QW, kpart = wave / QW;
   // loader role of this thread: piece j of a tile is row (t + NTHREADS j) / LPR, 16-byte column (t % LPR)
   const int ld_row0 = t / LPR, ld_col = (t % LPR) * 16;
-  WTL(0)
-  WTL_HW()
 
   // DEPTH register sets: the tiles in flight from global memory (tiles ti+2 .. ti+1+DEPTH while tile ti
   // is consumed from LDS and tile ti+1 waits there)
@@ -469,7 +444,6 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     if (total_tiles > 1) stage_tile(Kr[1], Vr[1], 1, lds + STAGE_BYTES);
     if (DEPTH + 1 < total_tiles) issue_tile(Kr[1], Vr[1], DEPTH + 1);
     lds_barrier();
-    WTL(4)
     // Normalised output of the query tiles of stream head hi (final outputs only).
     auto write_out = [&](const float (&l_tot)[NTW], int hi) {
 #pragma unroll
@@ -524,7 +498,6 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
         if (gt + d < total_tiles) step(gt + d, Kr[(d + 2) % DEPTH], Vr[(d + 2) % DEPTH]);
     }
     lds_barrier();
-    WTL(5)
 
     // ---- two key halves per query tile: the wavefront of the second half hands its state over through
     // LDS (layout [query wavefront][tile][register][lane], then m and l), the first merges.
@@ -624,10 +597,6 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
       lds_barrier();   // LDS (staging tiles, merge area, tree arrays) is reused by the next segment
     }
   }
-#ifdef SPEC_WIDE_TIMELINE
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#endif
-  WTL(1)
 }
 
 }  // namespace wide

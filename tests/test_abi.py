@@ -21,6 +21,12 @@ def test_library_exports_every_declared_symbol():
     lib = binding.load()
     names = _declared_functions()
     assert set(names) == set(binding.EXPORTED)
+    # the public header declares the method's calls (and their size queries, error text, version): no
+    # measurement aids, and the library reads no environment variables
+    assert not [n for n in names if "probe" in n or "debug" in n or "test" in n]
+    csrc = os.path.join(ROOT, "paper_2305_09781_amd", "csrc")
+    for f in os.listdir(csrc):
+        assert "getenv" not in open(os.path.join(csrc, f)).read(), f
     for n in names:
         assert getattr(lib, n) is not None
     assert lib.spec_version() >= 100
@@ -31,7 +37,7 @@ def _desc(**kw):
     base = dict(B=1, H=4, H_kv=4, D=64, N=8, S_cap=136, dtype=binding.SPEC_F32, max_prefix_len=0,
                 q_stride_b=8 * 4 * 64, q_stride_n=4 * 64, q_stride_h=64,
                 kv_stride_b=4 * 136 * 64, kv_stride_h=136 * 64, kv_stride_s=64, new_stride_b=0, new_stride_n=0,
-                new_stride_h=0, softmax_scale=0.0, reserved=0)
+                new_stride_h=0, softmax_scale=0.0, plan_chunk_keys=0, plan_balanced_wgs=0, plan_heads_per_wg=0)
     base.update(kw)
     return binding.AttnDesc(**base)
 
@@ -48,7 +54,10 @@ def _desc(**kw):
     (dict(q_stride_h=66), binding.ERR_INVALID_ARG),
     (dict(kv_stride_s=32), binding.ERR_INVALID_ARG),
     (dict(B=0), binding.ERR_INVALID_ARG),
-    (dict(reserved=1), binding.ERR_INVALID_ARG),
+    (dict(plan_chunk_keys=-1), binding.ERR_INVALID_ARG),
+    (dict(plan_balanced_wgs=-2), binding.ERR_INVALID_ARG),
+    (dict(plan_heads_per_wg=-1), binding.ERR_INVALID_ARG),
+    (dict(S_cap=1 << 23, kv_stride_s=128, kv_stride_h=(1 << 23) * 128, kv_stride_b=4 * (1 << 23) * 128), binding.ERR_UNSUPPORTED),   # 4 GiB span
     (dict(softmax_scale=-1.0), binding.ERR_INVALID_ARG),
 ])
 def test_attention_and_append_reject_bad_descriptors(kw, code):
