@@ -6,13 +6,17 @@ One step = one verification pass of a whole model over one batch of token trees:
                               per-layer caches)
     spec_verify_greedy, spec_verify_stochastic                        (once per pass)
     spec_kv_commit of the greedy path over all L layers
-Inputs are resident in HBM before the timed region. Prints ONE JSON line.
+Inputs are resident in HBM before the timed region. Prints ONE JSON line: the headline workload (config 4, the
+largest single-GPU configuration) measured in full, and a `per_config` list with the same measurement of the
+other bf16 workloads (configs 2, 3, 5) on fewer timed steps.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-graph] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-per-config] [--no-graph] [--no-cpu-baseline]
 """
 import argparse
+import gc
 import json
 import os
+import re
 import sys
 import time
 
@@ -21,21 +25,18 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-
-# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy of
-# known size (profiles/tree_attention_bf16_configs2-5_hbm_traffic.txt), per launch of the workload's shape.
-MEASURED_TRAFFIC_BYTES = {2: int((67237.9 * 2.000 + 3189.0) * 1024), 3: int((90357.2 * 2.000 + 49164.0) * 1024),
-                          4: int((549066.4 * 2.000 + 49154.8) * 1024),
-                          5: int(((400755.5 + 7107.0) * 2.000 + 12367.2 + 1024.0) * 1024)}
+HEADLINE_CONFIG = 4
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "tree_attention_bf16_hbm_traffic.txt")
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="workload (BASELINE config number, 2..5)")
-    ap.add_argument("--layers", type=int, default=0, help="layers per pass (0 = as many of the model's layers as fit)")
+    ap.add_argument("--config", type=int, default=HEADLINE_CONFIG, help="headline workload (BASELINE config number, 2..5)")
+    ap.add_argument("--layers", type=int, default=0, help="layers per pass (0 = every layer of the model the shape comes from)")
+    ap.add_argument("--no-per-config", action="store_true", help="measure the headline workload only")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-only", action="store_true", help="time only the attention launches (profiling aid)")
@@ -43,6 +44,20 @@ def parse():
                     help="also run three plain 256 MiB device copies, the known-size reference for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings")
     return ap.parse_args()
+
+
+def counter_traffic_bytes(cfg_id):
+    """HBM bytes per attention launch of this workload as rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE counted them
+    (a committed summary under profiles/, which also records the commit it was taken at); None when that file
+    is not next to this script."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            m = re.match(r"\s*config\s+(\d+)\s*:.*\btotal_bytes=(\d+)", line)
+            if m and int(m.group(1)) == cfg_id:
+                return int(m.group(2))
+    except OSError:
+        pass
+    return None
 
 
 def build_workload(cfg, n_layers, dev):
@@ -59,12 +74,7 @@ def build_workload(cfg, n_layers, dev):
          "tree_depth": inp["tree_depth"].to(dev), "q": [], "k_new": [], "v_new": [], "k_cache": [], "v_cache": [],
          "out": [], "host": inp}
     for l in range(n_layers):
-        for name in ("q", "k_new", "v_new"):
-            if l == 0:
-                W[name].append(inp[name][0].to(dev))
-            else:
-                W[name].append(torch.randn(inp[name][0].shape, generator=g, device=dev, dtype=torch.float32).to(dt))
-        for name in ("k_cache", "v_cache"):
+        for name in ("q", "k_new", "v_new", "k_cache", "v_cache"):
             if l == 0:
                 W[name].append(inp[name][0].to(dev))
             else:
@@ -73,31 +83,22 @@ def build_workload(cfg, n_layers, dev):
     return W
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
-    import numpy as np
+def measure(cfg_id, args, steps, warmup, want_cpu_baseline, want_read_probe):
+    """One workload, measured in full: the whole pass (graph replay, wall clock around `steps` replays), the
+    dominant kernel (events on the launch stream around back-to-back attention launches), the once-per-pass
+    steps on their own."""
     import torch
 
     from paper_2305_09781_amd import binding as spec
     from paper_2305_09781_amd import probe_binding as probe
     from paper_2305_09781_amd import workloads as wl
 
-    spec.load()
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
     dev = "cuda:0"
-    torch.cuda.set_device(0)
-    cfg = wl.CONFIGS[args.config]
+    cfg = wl.CONFIGS[cfg_id]
     e = 2 if cfg.dtype == "bf16" else 4
     per_layer_cache = 2 * cfg.B * cfg.H * cfg.S_cap * cfg.D * e
     L = args.layers or cfg.layers
-    L = max(1, min(L, int(200e9 // per_layer_cache)))
-    if cfg.cfg == 4 and not args.layers:
-        L = 16          # 65B shape: 16 of the 80 layers (17.7 GB of caches) keep set-up time bounded
+    L = max(1, min(L, int(200e9 // per_layer_cache), 128))
     W = build_workload(cfg, L, dev)
     B, N, H, D = cfg.B, cfg.N, cfg.H, cfg.D
     pl, par, dep = W["prefix_len"], W["tree_parent"], W["tree_depth"]
@@ -108,7 +109,7 @@ def main():
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
     status = torch.zeros(B, dtype=torch.int32, device=dev)
 
-    # verification inputs (vocabulary of the 7B model also for the 65B-shaped config, which names none)
+    # verification inputs (the 65B-shaped config names no vocabulary: LLaMA's 32000, as in the 7B shapes)
     vcfg = cfg if cfg.V else wl.Config(cfg.cfg, cfg.name, cfg.dtype, B=B, H=H, D=D, P=cfg.P, N=N, tree=cfg.tree,
                                        widths=cfg.widths, V=32000)
     par_np = W["host"]["tree_parent"].numpy()
@@ -129,15 +130,22 @@ def main():
             spec.spec_tree_attention_append(W["q"][l], W["k_new"][l], W["v_new"][l], W["k_cache"][l], W["v_cache"][l], par,
                                             dep, pl, out=W["out"][l], workspace=ws, status=status, desc=desc)
 
-    def one_pass():
-        for l in range(L):
-            spec.spec_tree_attention_append(W["q"][l], W["k_new"][l], W["v_new"][l], W["k_cache"][l], W["v_cache"][l], par,
-                                            dep, pl, out=W["out"][l], workspace=ws, status=status, desc=desc)
+    def greedy():
         spec.spec_verify_greedy(g_logits, g_tok, par, Lmax=Lmax, status=status, out=g_out)
+
+    def stochastic():
         spec.spec_verify_stochastic(s_dev["logits"], s_dev["probs_ssm"], s_dev["ssm_row"], s_dev["tree_token"], par,
                                     s_dev["u_accept"], s_dev["u_order"], s_dev["u_final"], Lmax=Lmax, workspace=s_ws,
                                     status=status, out=s_out)
+
+    def commit():
         spec.spec_kv_commit(W["k_cache"], W["v_cache"], g_out[0], g_out[1], pl, N, prefix_len_out=pl_out, status=status)
+
+    def one_pass():
+        attention_layers()
+        greedy()
+        stochastic()
+        commit()
 
     work = attention_layers if args.attn_only else one_pass
 
@@ -152,40 +160,22 @@ def main():
         return graph.replay
 
     run = make_runner(work)
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         run()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms_per_step = dt * 1e3 / args.steps
+    ms_per_step = dt * 1e3 / steps
     assert int(status.abs().sum().item()) == 0, "a request was flagged malformed during the benchmark"
 
     # ---- dominant kernel: tree attention, timed live with events on the launch stream
-    run_attn = make_runner(attention_layers) if not args.attn_only else run
-    for _ in range(3):
-        run_attn()
-    reps = max(5, min(args.steps, 50))
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    ev0.record()
-    for _ in range(reps):
-        run_attn()
-    ev1.record()
-    torch.cuda.synchronize()
-    attn_us = ev0.elapsed_time(ev1) * 1e3 / (reps * L)
-    sum_p = int(W["host"]["prefix_len"].sum())
-    # fused append + attention: prefix K,V read (2P), new K,V read (2N) and written to the cache (2N), Q in, O out
-    attn_bytes = e * H * D * (2 * sum_p + 6 * B * N)
-    achieved = attn_bytes / (attn_us * 1e-6) / 1e9
-    layer_bytes = attn_bytes
 
-    # the once-per-pass steps, each timed on its own (graph replay, events): verified tree tokens per second of
-    # verification time, as the metric's per-verifier figure
-    def time_us(fn, reps=20):
-        r = make_runner(fn)
+    def time_us(fn, reps, per=1):
+        r = run if fn is work else make_runner(fn)
         for _ in range(3):
             r()
         torch.cuda.synchronize()
@@ -194,76 +184,139 @@ def main():
             r()
         ev1.record()
         torch.cuda.synchronize()
-        return ev0.elapsed_time(ev1) * 1e3 / reps
-    greedy_us = time_us(lambda: spec.spec_verify_greedy(g_logits, g_tok, par, Lmax=Lmax, status=status, out=g_out))
-    stoch_us = time_us(lambda: spec.spec_verify_stochastic(
-        s_dev["logits"], s_dev["probs_ssm"], s_dev["ssm_row"], s_dev["tree_token"], par, s_dev["u_accept"], s_dev["u_order"],
-        s_dev["u_final"], Lmax=Lmax, workspace=s_ws, status=status, out=s_out))
-    commit_us = time_us(lambda: spec.spec_kv_commit(W["k_cache"], W["v_cache"], g_out[0], g_out[1], pl, N,
-                                                    prefix_len_out=pl_out, status=status))
+        return ev0.elapsed_time(ev1) * 1e3 / (reps * per)
 
-    # practical ceiling on this machine for a launch of this size: a plain read kernel, one launch per buffer,
-    # over distinct buffers of the attention launch's byte count (>= 2 GB in total, far beyond the 256 MB
-    # Infinity Cache), timed the same way
-    n_probe = max(2, int(2e9 // attn_bytes) + 1)
-    probes = [torch.empty(attn_bytes // 16 * 16, dtype=torch.uint8, device=dev).fill_(l + 1) for l in range(n_probe)]
-    sink = torch.zeros(16, dtype=torch.uint8, device=dev)
-    def read_all():
-        for pb in probes:
-            probe.spec_probe_read_stream(pb, sink)
-    read_all()
-    torch.cuda.synchronize()
-    ev0.record()
-    for _ in range(3):
+    attn_us = time_us(attention_layers, max(5, min(steps, 50)), per=L)
+    sum_p = int(W["host"]["prefix_len"].sum())
+    # fused append + attention: prefix K,V read (2P), new K,V read (2N) and written to the cache (2N), Q in, O out
+    attn_bytes = e * H * D * (2 * sum_p + 6 * B * N)
+    achieved = attn_bytes / (attn_us * 1e-6) / 1e9
+    # the once-per-pass steps, each replayed on its own
+    greedy_us, stoch_us, commit_us = time_us(greedy, 20), time_us(stochastic, 20), time_us(commit, 20)
+
+    read_stream_gbs = None
+    if want_read_probe:
+        # practical ceiling on this machine for a launch of this size: a plain read kernel, one launch per buffer,
+        # over distinct buffers of the attention launch's byte count (>= 2 GB in total, far beyond the 256 MB
+        # Infinity Cache), timed the same way
+        n_probe = max(2, int(2e9 // attn_bytes) + 1)
+        probes = [torch.empty(attn_bytes // 16 * 16, dtype=torch.uint8, device=dev).fill_(l + 1) for l in range(n_probe)]
+        sink = torch.zeros(16, dtype=torch.uint8, device=dev)
+
+        def read_all():
+            for pb in probes:
+                probe.spec_probe_read_stream(pb, sink)
         read_all()
-    ev1.record()
-    torch.cuda.synchronize()
-    read_stream_gbs = 3 * n_probe * (attn_bytes // 16 * 16) / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
-    del probes
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(3):
+            read_all()
+        ev1.record()
+        torch.cuda.synchronize()
+        read_stream_gbs = 3 * n_probe * (attn_bytes // 16 * 16) / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+        del probes
 
     dense_flops = 4.0 * H * D * N * float(W["host"]["prefix_len"].double().add(N).sum())
-    result = {
-        "metric": "verified tree tokens/sec (whole verification pass: L layers of KV append + tree attention, "
-                  "greedy + stochastic verification, KV commit) + achieved HBM GB/s",
-        "value": B * N / (ms_per_step * 1e-3), "unit": "tree tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"config {cfg.cfg}: {cfg.name} B={B} H={H} D={D} prefix={cfg.P} tree N={N} "
-                               f"vocab={vcfg.V} layers/pass={L}" + (" (attention only)" if args.attn_only else ""),
-                   "launch": "eager" if args.no_graph else "hip-graph replay",
-                   "layer_tree_tokens_per_s": B * N / (attn_us * 1e-6),
-                   "attention_us_per_layer": attn_us, "layer_algorithmic_bytes": layer_bytes,
-                   "greedy_verify_us": greedy_us, "greedy_verify_tree_tokens_per_s": B * N / (greedy_us * 1e-6),
-                   "stochastic_verify_us": stoch_us, "stochastic_verify_tree_tokens_per_s": B * N / (stoch_us * 1e-6),
-                   "commit_all_layers_us": commit_us},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.cfg),
-                     "kernel": ("tree_attention_bf16_kernel" if N <= 16 else "tree_attention_bf16_wide_kernel")
-                               + " (KV append fused; + attn_combine_kernel when the key range is split)",
-                     "bytes_per_launch": attn_bytes,
-                     "us_per_launch": attn_us,
-                     "measured_read_stream_gbs": read_stream_gbs, "frac_of_measured_read_stream": achieved / read_stream_gbs,
-                     # the two products as dense contractions over all N x (prefix + N) pairs, against the bf16
-                     # MFMA peak: what the matrix cores would be charged with if this were the bound (it is not)
-                     "dense_equivalent_tflops": dense_flops / (attn_us * 1e-6) / 1e12,
-                     "frac_of_bf16_mfma_peak": dense_flops / (attn_us * 1e-6) / 2.5e15},
+    wide = N > 16
+    res = {
+        "cfg": cfg.cfg,
+        "workload": f"config {cfg.cfg}: {cfg.name} B={B} H={H} D={D} prefix={cfg.P} tree N={N} vocab={vcfg.V} "
+                    f"layers/pass={L}" + (" (attention only)" if args.attn_only else ""),
+        "ms_per_step": ms_per_step, "value": B * N / (ms_per_step * 1e-3), "steps": steps,
+        "attn_us": attn_us, "attn_bytes": attn_bytes, "achieved": achieved,
+        "greedy_us": greedy_us, "stoch_us": stoch_us, "commit_us": commit_us, "L": L,
+        "kernel": ("tree_attention_bf16_wide_kernel" if wide else "tree_attention_bf16_kernel")
+                  + " (KV append fused; + attn_combine_kernel when the key range is split)",
+        "read_stream_gbs": read_stream_gbs, "dense_flops": dense_flops, "dtype": cfg.dtype,
+        "traffic": counter_traffic_bytes(cfg.cfg),
     }
-
     if args.pmc_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, vcfg, W["host"], gi, si, L)
+    if want_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cfg, W["host"], gi, si, L)
+    del W, s_dev, g_logits, ws, s_ws, run
+    gc.collect()
+    torch.cuda.empty_cache()
+    return res
+
+
+def roofline_of(r):
+    d = {"bound": "hbm", "achieved": r["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+         "frac": r["achieved"] / HBM_PEAK_GBS,
+         # counter-measured HBM bytes per launch of this shape, read from the committed rocprofv3 --pmc summary
+         # (which names the commit it was taken at): not measured in this run; null when the summary is not
+         # next to this script
+         "traffic": r["traffic"],
+         "traffic_source": "profiles/tree_attention_bf16_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, offline)",
+         "kernel": r["kernel"], "bytes_per_launch": r["attn_bytes"], "us_per_launch": r["attn_us"],
+         # the two products as dense contractions over all N x (prefix + N) pairs, against the bf16 MFMA
+         # peak: what the matrix cores would be charged with if this were the bound (it is not)
+         "dense_equivalent_tflops": r["dense_flops"] / (r["attn_us"] * 1e-6) / 1e12,
+         "frac_of_bf16_mfma_peak": r["dense_flops"] / (r["attn_us"] * 1e-6) / 2.5e15}
+    if r["read_stream_gbs"]:
+        d["measured_read_stream_gbs"] = r["read_stream_gbs"]
+        d["frac_of_measured_read_stream"] = r["achieved"] / r["read_stream_gbs"]
+    return d
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2305_09781_amd import binding as spec
+
+    spec.load()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    head = measure(args.config, args, args.steps, args.warmup, not args.no_cpu_baseline, True)
+    tokens = head["value"] * head["ms_per_step"] * 1e-3          # tree tokens per pass (B * N)
+    result = {
+        "metric": "verified tree tokens/sec (whole verification pass: L layers of KV append + tree attention, "
+                  "greedy + stochastic verification, KV commit) + achieved HBM GB/s",
+        "value": head["value"], "unit": "tree tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic",
+        "config": {"workload": head["workload"],
+                   "launch": "eager" if args.no_graph else "hip-graph replay",
+                   "layer_tree_tokens_per_s": tokens / (head["attn_us"] * 1e-6),
+                   "attention_us_per_layer": head["attn_us"], "layer_algorithmic_bytes": head["attn_bytes"],
+                   "greedy_verify_us": head["greedy_us"], "greedy_verify_tree_tokens_per_s": tokens / (head["greedy_us"] * 1e-6),
+                   "stochastic_verify_us": head["stoch_us"],
+                   "stochastic_verify_tree_tokens_per_s": tokens / (head["stoch_us"] * 1e-6),
+                   "commit_all_layers_us": head["commit_us"]},
+        "roofline": roofline_of(head),
+    }
+    if "cpu_baseline" in head:
+        result["cpu_baseline"] = head["cpu_baseline"]
+    if not args.no_per_config and not args.attn_only:
+        per = []
+        for c in (2, 3, 4, 5):
+            if c == args.config:
+                continue
+            r = measure(c, args, max(3, min(args.steps, 10)), min(args.warmup, 3), False, False)
+            per.append({"workload": r["workload"], "tree_tokens_per_s": r["value"], "ms_per_step": r["ms_per_step"],
+                        "steps": r["steps"], "us_per_launch": r["attn_us"], "bytes_per_launch": r["attn_bytes"],
+                        "roofline": {"bound": "hbm", "achieved": r["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                     "frac": r["achieved"] / HBM_PEAK_GBS, "traffic": r["traffic"]},
+                        "greedy_verify_us": r["greedy_us"], "stochastic_verify_us": r["stoch_us"],
+                        "commit_all_layers_us": r["commit_us"]})
+        result["per_config"] = per
     print(json.dumps(result))
 
 
-def cpu_baseline(cfg, vcfg, host, gi, si, L):
+def cpu_baseline(cfg, host, gi, si, L):
     """The CPU oracle, as it stands, on a bounded sample of the same workload."""
-    import numpy as np
+    import torch
     from oracle import spec_oracle as orc
     try:
         from threadpoolctl import threadpool_info
@@ -295,7 +348,7 @@ def cpu_baseline(cfg, vcfg, host, gi, si, L):
                           par, si["u_accept"].numpy(), si["u_order"].numpy(), si["u_final"].numpy())
     t_verify = time.perf_counter() - t0
     t0 = time.perf_counter()
-    kc = host["k_cache"][0].view(dtype=__import__("torch").int16 if cfg.dtype == "bf16" else __import__("torch").int32).numpy().copy()
+    kc = host["k_cache"][0].view(dtype=torch.int16 if cfg.dtype == "bf16" else torch.int32).numpy().copy()
     orc.kv_commit([kc], [kc.copy()], gp, gl, pl, N=N)
     t_commit = time.perf_counter() - t0
     t_pass = L * (t_layer + t_commit) + t_verify
