@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(LIB_DIR, "libspectree.so")
 PROBE_LIB_PATH = os.path.join(LIB_DIR, "libspecprobe.so")
 
 SOURCES = ["spec_api.hip", "kv_cache.hip", "tree_attention_f32.hip", "tree_attention_bf16.hip",
-           "tree_attention_bf16_wide.hip", "verify.hip", "tree_build.hip", "lm_head.hip"]
+           "tree_attention_bf16_wide.hip", "tree_attention_bf16_wide32.hip", "verify.hip", "tree_build.hip", "lm_head.hip"]
 PROBE_SOURCES = ["probe.hip"]
 
 HIPCC_FLAGS = [

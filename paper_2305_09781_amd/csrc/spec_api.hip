@@ -98,6 +98,7 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d, bool paged) {
   p.balanced_wgs = 0;
   p.balanced_tile = 0;
   p.heads_per_wg = 1;
+  p.m32 = false;
   const int max_prefix = d.max_prefix_len > 0 ? d.max_prefix_len : d.S_cap - d.N;
   const int max_len = max_prefix + d.N;
   // bf16: one workgroup serves all query heads of a K/V head; float32: one per query head
@@ -111,8 +112,11 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d, bool paged) {
   p.wide = d.dtype == SPEC_BF16 &&
            (tiles > 1 || ns.b != d.q_stride_b || ns.n != d.q_stride_n || ns.h != d.q_stride_h);
   int chunk = d.plan_chunk_keys;   // caller's hint; 0 = chosen below
+  // Five to eight query tiles: four wavefronts of 32 queries unless the caller asks for several heads per
+  // workgroup, which only the eight-wavefront shape serves.
+  p.m32 = p.wide && tiles > 4 && d.D == 128 && d.plan_heads_per_wg == 0;
   // workgroups the device holds at once: four-wavefront shapes of the wide kernel run two per compute unit
-  const long resident = (long)compute_units() * ((p.wide && tiles <= 4) ? 2 : 1);
+  const long resident = (long)compute_units() * ((p.wide && (tiles <= 4 || p.m32)) ? 2 : 1);
   if (chunk <= 0 && d.dtype == SPEC_BF16) {
     // Several requests with few (request, head) pairs and long key ranges (long-context serving, ragged
     // lengths): the bf16 kernels deal the key tiles of all pairs to as many workgroups as the device holds at
@@ -164,7 +168,7 @@ AttnPlan make_attn_plan(const spec_attn_desc_t& d, bool paged) {
     p.chunk_keys = chunk;
     p.n_splits = (max_len + chunk - 1) / chunk;
   }
-  if (p.wide && p.n_splits <= 1 && p.balanced_wgs == 0 && qg.n_qgroups == 1 && tiles > 4) {
+  if (p.wide && p.n_splits <= 1 && p.balanced_wgs == 0 && qg.n_qgroups == 1 && tiles > 4 && !p.m32) {
     // Eight-wavefront workgroups (one per compute unit) and more (request, head) pairs than compute units: a
     // workgroup then serves several heads of a request in a row, which costs one prologue and one tree set-up
     // instead of one per head (measured: 3 % on 512 pairs of 640 keys; no gain for the four-wavefront shape,

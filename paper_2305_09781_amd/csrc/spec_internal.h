@@ -19,6 +19,8 @@ struct AttnPlan {
   int balanced_tile;// keys per tile of the balanced deal (the tile of the kernel that runs the plan)
   bool wide;        // bf16: the wide kernel runs the plan (several query tiles per K/V head, or k_new not laid out like q)
   int heads_per_wg; // wide kernel, whole key ranges: consecutive K/V heads of a request served by one workgroup
+  bool m32;         // 5..8 query tiles, D = 128: the kernel of tree_attention_bf16_wide32.hip (four wavefronts of 32
+                    // queries, two workgroups per compute unit) instead of the wide kernel's eight wavefronts of 16
   size_t ws_o_off;  // float [B][H][n_splits][N][D]   un-normalised partial outputs
   size_t ws_ml_off; // float [B][H][n_splits][N][2]   running max (log2 domain) and partial sum
   size_t ws_bytes;
@@ -102,6 +104,11 @@ hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const Attn
                                            void* v_cache, const void* k_new, const void* v_new, const int32_t* parent,
                                            const int32_t* depth, const int32_t* prefix_len, void* out, void* ws,
                                            int32_t* status, hipStream_t s);
+// Five to eight query tiles per K/V head, D = 128: 32-query MFMA tiles, K/V loaded straight into an LDS ring.
+hipError_t launch_tree_attention_bf16_wide32(const spec_attn_desc_t& d, const AttnPlan& plan, const Pages& pg, const void* q,
+                                             void* k_cache, void* v_cache, const void* k_new, const void* v_new,
+                                             const int32_t* parent, const int32_t* depth, const int32_t* prefix_len,
+                                             void* out, void* ws, int32_t* status, hipStream_t s);
 hipError_t launch_attn_combine(const spec_attn_desc_t& d, const AttnPlan& plan, const int32_t* parent,
                                const int32_t* depth, const int32_t* prefix_len, const void* ws, void* out,
                                int32_t* status, hipStream_t s);

@@ -79,7 +79,9 @@ __device__ __forceinline__ u32x4 load_kv(const unsigned char* p) {
 // 16-byte store of an appended cache row. Marked non-temporal: the rows are not read again by this
 // kernel, and dirty lines left in the L2 lengthen the write-back at the end of the kernel.
 __device__ __forceinline__ void store_cache_row(void* p, u32x4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(p), "v"(v) : "memory");
+  // (the builtin, not inline assembly: the compiler then keeps the store's data registers untouched for the wait
+  // states a 16-byte store needs after issue)
+  __builtin_nontemporal_store(v, (u32x4*)p);
 }
 
 // Orders LDS accesses of the lanes of one wavefront (they execute in lockstep; this stops the

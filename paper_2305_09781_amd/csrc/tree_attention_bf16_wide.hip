@@ -53,7 +53,9 @@ __device__ __forceinline__ u32x4 load_kv(const unsigned char* p) {
   return __builtin_nontemporal_load((const u32x4*)p);
 }
 __device__ __forceinline__ void store_nt(void* p, u32x4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(p), "v"(v) : "memory");
+  // (the builtin, not inline assembly: the compiler then keeps the store's data registers untouched for the wait
+  // states a 16-byte store needs after issue)
+  __builtin_nontemporal_store(v, (u32x4*)p);
 }
 __device__ inline float max_over_lane_groups(float v) {
   v = fmaxf(v, __shfl_xor(v, 16));
@@ -613,6 +615,9 @@ hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const Attn
   const int tiles = qgr.tiles_per_wg;   // (query heads per workgroup) x ceil(N / 16)
   const int virtual_heads = d.H_kv * qgr.n_qgroups;
   const int qw = tiles <= 2 ? 2 : tiles <= 4 ? 4 : 8;
+  if (plan.m32)   // five to eight query tiles, head dimension 128: four wavefronts of 32 queries, K/V straight to LDS
+    return launch_tree_attention_bf16_wide32(d, plan, pg, q, k_cache, v_cache, k_new, v_new, parent, depth, prefix_len, out,
+                                             ws, status, s);
   const NewStrides ns = attn_new_strides(d);
   const bool append = k_new != nullptr;
   const int mode = plan.balanced_wgs == 0 ? wide::PLAN_GRID : wide::PLAN_TILES;
