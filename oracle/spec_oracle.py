@@ -20,7 +20,7 @@ What each function follows:
   expand_topk, tree_merge     Section 3: one step of expansion-based construction; Definition 3.2
   kv_commit              Algorithm 2 main loop (verified tokens are appended to the sequence), so the
                          K/V rows of the accepted path must become the contiguous prefix
-  lm_head_logits, lm_head_argmax
+  lm_head_logits, lm_head_argmax, softmax_stats
                          the LLM's output projection in front of VerifyGreedy (Algorithm 2 takes O(u) from the
                          LLM's distribution at node u; for greedy decoding only its arg-max is needed): logits =
                          hidden . W^T, O(u) = argmax, lowest token id on ties. A step adjacent to the path.
@@ -633,3 +633,14 @@ def lm_head_argmax(hidden, weight):
     rest[np.arange(logits.shape[0]), arg] = -np.inf
     gap = top - rest.max(axis=1) if logits.shape[1] > 1 else np.full(logits.shape[0], np.inf)
     return arg, top, gap
+
+
+def softmax_stats(logits, temperature=1.0):
+    """What VerifyStochastic needs of the LLM's distribution at a node before any rejection (Algorithm 2:
+    P(x | u) = softmax(logits[u] / T)[x]) without the whole row: per row (arg-max with the lowest token id on
+    ties, the maximum m, Z = sum_x exp((logits[x] - m) / T)), so that P(x) = exp((logits[x] - m) / T) / Z.
+    logits [..., V] (the values as stored, e.g. already rounded to bf16); float64."""
+    x = np.asarray(logits, dtype=np.float64)
+    m = x.max(axis=-1)
+    z = np.exp((x - m[..., None]) / float(temperature)).sum(axis=-1)
+    return x.argmax(axis=-1).astype(np.int32), m, z

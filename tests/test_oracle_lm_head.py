@@ -63,3 +63,44 @@ def test_greedy_verifier_on_the_materialised_logits():
     path, ln, out, node_arg = orc.verify_greedy(logits, tok, par)
     assert np.array_equal(node_arg.reshape(-1), arg)
     assert (ln >= 1).all() and ln.max() > 1
+
+
+def test_softmax_stats_closed_form_ties_and_the_verifier_it_feeds():
+    """softmax_stats: hand-derived values, the tie rule, P(x) rebuilt from (m, Z) against a library softmax, and
+    the use it is made for: the first ratio test of VerifyStochastic at a node needs P(x) only, so a walk that
+    meets no rejection is decided by the statistics alone."""
+    import scipy.special
+    # logits (0, ln 2, ln 2): max ln 2 at token 1 (lowest id of the tie), Z = 1/2 + 1 + 1
+    arg, m, z = orc.softmax_stats(np.array([[0.0, np.log(2.0), np.log(2.0)]]))
+    assert arg[0] == 1 and abs(m[0] - np.log(2.0)) < 1e-15 and abs(z[0] - 2.5) < 1e-12
+    # temperature 1/2 squares the ratios: Z = 1/4 + 1 + 1
+    _, _, z2 = orc.softmax_stats(np.array([[0.0, np.log(2.0), np.log(2.0)]]), temperature=0.5)
+    assert abs(z2[0] - 2.25) < 1e-12
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((5, 7, 33)) * 3
+    for T in (1.0, 0.7, 1.9):
+        arg, m, z = orc.softmax_stats(x, T)
+        p = np.exp((x - m[..., None]) / T) / z[..., None]
+        assert np.allclose(p, scipy.special.softmax(x / T, axis=-1), rtol=1e-12, atol=0)
+        assert np.array_equal(arg, x.argmax(-1)) and np.array_equal(m, x.max(-1))
+    # a chain tree whose every child is accepted (draft = LLM, so r * Q(x) <= P(x) always): the path is the chain,
+    # and every acceptance test r * Q(x) <= P(x) can be re-evaluated from the statistics
+    B, N, V = 2, 6, 17
+    par = np.tile(np.arange(-1, N - 1, dtype=np.int32), (B, 1))
+    logits = rng.standard_normal((B, N, V)) * 2
+    arg, m, z = orc.softmax_stats(logits)
+    probs = scipy.special.softmax(logits, axis=-1).reshape(B * N, V).astype(np.float32)
+    tok = rng.integers(0, V, size=(B, N)).astype(np.int32)
+    row = np.zeros((B, N), dtype=np.int32)
+    for b in range(B):
+        for v in range(1, N):
+            row[b, v] = b * N + par[b, v]
+    ua = rng.random((B, N), dtype=np.float32) * 0.99
+    path, ln, out, st = orc.verify_stochastic(logits, probs, row, tok, par, ua, rng.random((B, N), dtype=np.float32),
+                                              rng.random(B, dtype=np.float32))
+    assert (ln == N).all() and (st == 0).all()
+    for b in range(B):
+        for v in range(1, N):
+            u, xx = par[b, v], tok[b, v]
+            p_stats = np.exp(logits[b, u, xx] - m[b, u]) / z[b, u]
+            assert np.float32(ua[b, v]) * probs[row[b, v], xx] <= np.float32(p_stats) * (1 + 1e-6)
