@@ -287,6 +287,24 @@ int spec_verify_stochastic(int32_t B, int32_t N, int32_t V, int32_t logits_dtype
 size_t spec_verify_stochastic_workspace_bytes(int32_t B, int32_t N, int32_t V);
 
 /*
+ * Stochastic verification from statistics the caller already has (Algorithm 2, VerifyStochastic: before any
+ * rejection at a node the walk needs P(x | u) for single tokens only, i.e. the row's maximum and its sum of
+ * exponentials). Exactly spec_verify_stochastic without its first pass over the logits: node_max[b,u] = max_x
+ * logits_llm[b,u,x] and node_sumexp[b,u] = sum_x exp((logits_llm[b,u,x] - node_max[b,u]) / temperature), float32
+ * [B,N], computed from the logits AS STORED (spec_lm_head_logits_stats produces all three in one pass over the
+ * LLM's output projection). The logits themselves are still read for the tokens tested, after a rejection and
+ * for the final draw. workspace: spec_verify_stochastic_stats_workspace_bytes(B, V) bytes, 256-byte aligned.
+ */
+size_t spec_verify_stochastic_stats_workspace_bytes(int32_t B, int32_t V);
+int spec_verify_stochastic_stats(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, const void* logits_llm,
+                                 const float* node_max /*[B,N]*/, const float* node_sumexp /*[B,N]*/,
+                                 const float* probs_ssm /*[R,V]*/, int32_t R, const int32_t* ssm_row /*[B,N]*/,
+                                 const int32_t* tree_token, const int32_t* tree_parent, const float* u_accept,
+                                 const float* u_order, const float* u_final, float temperature, int32_t Lmax,
+                                 int32_t* accepted_path, int32_t* accepted_len, int32_t* out_tokens, void* workspace,
+                                 size_t workspace_bytes, int32_t* status, void* hip_stream);
+
+/*
  * KV commit (Algorithm 2 main loop: every verified token is appended to the sequence, so the accepted
  * path's K/V must become the contiguous continuation of the prefix). For every layer l, request b,
  * head h and k in [0, accepted_len[b]):
@@ -326,6 +344,22 @@ int spec_verify_greedy_lm_head(int32_t B, int32_t N, int32_t K, int32_t V, const
                                int32_t Lmax, int32_t* accepted_path, int32_t* accepted_len, int32_t* out_tokens,
                                int32_t* node_argmax /*[B,N] or NULL*/, void* workspace, size_t workspace_bytes,
                                int32_t* status, void* hip_stream);
+
+/*
+ * LM head in front of the stochastic verifiers (Algorithm 2, VerifyStochastic: P(x | u, LLM) = softmax of the
+ * LLM's logits at node u). One pass over `weight` that writes the logits, rounded to bf16, and the per-row
+ * statistics of the ROUNDED values that spec_verify_stochastic_stats starts from:
+ *     logits[m,v]    = bf16( sum_k hidden[m,k] * weight[v,k] )            [M,V] contiguous
+ *     node_max[m]    = max_v logits[m,v],  node_argmax[m] = its lowest v (may be NULL)
+ *     node_sumexp[m] = sum_v exp((logits[m,v] - node_max[m]) / temperature)          (float32)
+ * Shapes, alignment and accumulation as for spec_lm_head_argmax. temperature > 0.
+ * workspace: spec_lm_head_logits_stats_workspace_bytes(M, V) bytes, 256-byte aligned; contents are scratch.
+ */
+size_t spec_lm_head_logits_stats_workspace_bytes(int32_t M, int32_t V);
+int spec_lm_head_logits_stats(int32_t M, int32_t K, int32_t V, const void* hidden, const void* weight,
+                              float temperature, void* logits /*[M,V] bf16*/, int32_t* node_argmax /*[M] or NULL*/,
+                              float* node_max /*[M]*/, float* node_sumexp /*[M]*/, void* workspace,
+                              size_t workspace_bytes, void* hip_stream);
 
 /*
  * Paged KV caches (beyond the paper, whose cache is one contiguous region per request; the steps are

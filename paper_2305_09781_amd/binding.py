@@ -30,6 +30,8 @@ EXPORTED = [
     "spec_tree_attention_paged_workspace_bytes", "spec_kv_commit_paged",
     "spec_lm_head_argmax", "spec_lm_head_argmax_workspace_bytes", "spec_verify_greedy_lm_head",
     "spec_qk_rope_append", "spec_qk_rope_append_paged", "spec_tree_attention_append_static",
+    "spec_lm_head_logits_stats", "spec_lm_head_logits_stats_workspace_bytes", "spec_verify_stochastic_stats",
+    "spec_verify_stochastic_stats_workspace_bytes",
 ]
 STATIC_SCRATCH_BYTES = 64 << 20
 
@@ -126,6 +128,15 @@ def load():
     lib.spec_lm_head_argmax.restype = ctypes.c_int
     lib.spec_verify_greedy_lm_head.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp, vp]
     lib.spec_verify_greedy_lm_head.restype = ctypes.c_int
+    lib.spec_lm_head_logits_stats_workspace_bytes.argtypes = [i32, i32]
+    lib.spec_lm_head_logits_stats_workspace_bytes.restype = sz
+    lib.spec_lm_head_logits_stats.argtypes = [i32, i32, i32, vp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
+    lib.spec_lm_head_logits_stats.restype = ctypes.c_int
+    lib.spec_verify_stochastic_stats_workspace_bytes.argtypes = [i32, i32]
+    lib.spec_verify_stochastic_stats_workspace_bytes.restype = sz
+    lib.spec_verify_stochastic_stats.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, f32, i32,
+                                                 vp, vp, vp, vp, sz, vp, vp]
+    lib.spec_verify_stochastic_stats.restype = ctypes.c_int
     lib.spec_strerror.argtypes = [ctypes.c_int]
     lib.spec_strerror.restype = ctypes.c_char_p
     lib.spec_version.restype = ctypes.c_int
@@ -577,3 +588,47 @@ def spec_verify_greedy_lm_head(hidden, weight, tree_token, tree_parent, Lmax: Op
            "spec_verify_greedy_lm_head")
     return out
 
+
+def spec_lm_head_logits_stats(hidden, weight, temperature: float = 1.0, workspace=None, stream=None):
+    """One pass over the output projection: (logits [M,V] bf16, node_argmax [M] int32, node_max [M], node_sumexp [M]
+    float32), the statistics being those of the rounded logits."""
+    M, K, V = _lm_head_args(hidden, weight)
+    dev = hidden.device
+    logits = torch.empty((M, V), dtype=torch.bfloat16, device=dev)
+    arg = torch.empty(M, dtype=torch.int32, device=dev)
+    mx, se = torch.empty(M, dtype=torch.float32, device=dev), torch.empty(M, dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(int(load().spec_lm_head_logits_stats_workspace_bytes(M, V)), 256), dtype=torch.uint8,
+                                device=dev)
+    _check(load().spec_lm_head_logits_stats(M, K, V, _ptr(hidden), _ptr(weight), float(temperature), _ptr(logits), _ptr(arg),
+                                            _ptr(mx), _ptr(se), _ptr(workspace), workspace.numel(), _stream(stream)),
+           "spec_lm_head_logits_stats")
+    return logits, arg, mx, se
+
+
+def spec_verify_stochastic_stats(logits, node_max, node_sumexp, probs_ssm, ssm_row, tree_token, tree_parent, u_accept,
+                                 u_order, u_final, temperature: float = 1.0, Lmax: Optional[int] = None, workspace=None,
+                                 status=None, stream=None, out: Optional[Tuple[torch.Tensor, ...]] = None):
+    """spec_verify_stochastic from per-node (max, sum of exponentials) the caller already has.
+    Returns (accepted_path [B,Lmax], accepted_len [B], out_tokens [B,Lmax])."""
+    B, N, V = logits.shape
+    Lmax = N if Lmax is None else Lmax
+    dev = logits.device
+    if probs_ssm.dtype != torch.float32 or (probs_ssm.numel() and probs_ssm.shape[1] != V) or not probs_ssm.is_contiguous():
+        raise ValueError("probs_ssm must be contiguous float32 [R,V]")
+    for t_ in (node_max, node_sumexp):
+        if t_.dtype != torch.float32 or t_.numel() != B * N or not t_.is_contiguous():
+            raise ValueError("node_max / node_sumexp must be contiguous float32 with B*N entries")
+    if workspace is None:
+        workspace = torch.empty(int(load().spec_verify_stochastic_stats_workspace_bytes(B, V)), dtype=torch.uint8, device=dev)
+    if out is None:
+        out = (torch.empty((B, Lmax), dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+               torch.empty((B, Lmax), dtype=torch.int32, device=dev))
+    path, ln, toks = out
+    _check(load().spec_verify_stochastic_stats(B, N, V, _dtype_code(logits.dtype), _ptr(logits), _ptr(node_max),
+                                               _ptr(node_sumexp), _ptr(probs_ssm), probs_ssm.shape[0], _ptr(ssm_row),
+                                               _ptr(tree_token), _ptr(tree_parent), _ptr(u_accept), _ptr(u_order),
+                                               _ptr(u_final), float(temperature), Lmax, _ptr(path), _ptr(ln), _ptr(toks),
+                                               _ptr(workspace), workspace.numel(), _ptr(status), _stream(stream)),
+           "spec_verify_stochastic_stats")
+    return path, ln, toks

@@ -46,10 +46,15 @@ __device__ __forceinline__ bool beats(float v2, int i2, float v1, int i1) { retu
 
 // WAVES wavefronts of 16 vocabulary rows each: eight (128 rows, one workgroup per CU) or four (64 rows, two
 // workgroups per CU, so that one's start and end overlap the other's stream).
-template <int NMT, int WAVES>
+// STATS: the logits are also written out, rounded to bf16, and every partial carries the sum of
+// exp((x - max) / T) over the workgroup's vocabulary rows - of the ROUNDED values, which are what a verifier
+// reading those logits will see (maximum and arg-max are then those of the rounded values too).
+template <int NMT, int WAVES, bool STATS>
 __global__ void __launch_bounds__(WAVES * 64) lm_head_argmax_kernel(const __hip_bfloat16* __restrict__ hidden,
                                                                   const __hip_bfloat16* __restrict__ weight,
                                                                   float* __restrict__ part_val, int32_t* __restrict__ part_idx,
+                                                                  float* __restrict__ part_sum,
+                                                                  __hip_bfloat16* __restrict__ logits_out, float inv_temp_log2,
                                                                   int M, int K, int V, int n_vtiles) {
   constexpr int NTHREADS = WAVES * 64, VT = WAVES * 16;
   constexpr int MROWS = NMT * 16;
@@ -59,6 +64,7 @@ __global__ void __launch_bounds__(WAVES * 64) lm_head_argmax_kernel(const __hip_
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE];
   __shared__ float s_val[WAVES][MROWS];
   __shared__ int s_idx[WAVES][MROWS];
+  __shared__ float s_sum[STATS ? WAVES : 1][MROWS];
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -172,20 +178,58 @@ __global__ void __launch_bounds__(WAVES * 64) lm_head_argmax_kernel(const __hip_
   // ---- arg-max over this wavefront's 16 vocabulary rows, per row m: in the lane, then across the four lane groups
 #pragma unroll
   for (int mt = 0; mt < NMT; ++mt) {
+    float x[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x[i] = acc[mt][i];
+    if (STATS) {   // round to the stored type first: statistics and arg-max are those of the stored logits
+      union { uint2 u; __hip_bfloat16 h4[4]; } pk;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        pk.h4[i] = __float2bfloat16(x[i]);
+        x[i] = __bfloat162float(pk.h4[i]);
+      }
+      const int m = m0 + mt * 16 + r16, v = v0 + 4 * g;
+      if (m < M) {
+        __hip_bfloat16* dst = logits_out + (long)m * V + v;
+        if (v + 3 < V && (((long)m * V + v) & 3) == 0) {
+          *(uint2*)dst = pk.u;
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (v + i < V) dst[i] = pk.h4[i];
+        }
+      }
+    }
     float best = -INFINITY;
     int best_i = 0x7fffffff;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int v = v0 + 4 * g + i;
-      if (v < V && acc[mt][i] > best) { best = acc[mt][i]; best_i = v; }   // ascending v: the lowest wins ties
+      if (v < V && x[i] > best) { best = x[i]; best_i = v; }   // ascending v: the lowest wins ties
     }
+    const float lane_best = best;
 #pragma unroll
     for (int o = 16; o <= 32; o <<= 1) {
       const float ov = __shfl_xor(best, o);
       const int oi = __shfl_xor(best_i, o);
       if (beats(ov, oi, best, best_i)) { best = ov; best_i = oi; }
     }
-    if (g == 0) { s_val[wave][mt * 16 + r16] = best; s_idx[wave][mt * 16 + r16] = best_i; }
+    float sum = 0.f;
+    if (STATS) {   // sum of exp((x - best) / T) over the wavefront's 16 vocabulary rows (best: the wavefront's maximum)
+      if (best > -INFINITY) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (v0 + 4 * g + i < V) sum += __builtin_amdgcn_exp2f((x[i] - best) * inv_temp_log2);
+      }
+      sum += __shfl_xor(sum, 16);
+      sum += __shfl_xor(sum, 32);
+      (void)lane_best;
+    }
+    if (g == 0) {
+      s_val[wave][mt * 16 + r16] = best;
+      s_idx[wave][mt * 16 + r16] = best_i;
+      if (STATS) s_sum[wave][mt * 16 + r16] = sum;
+    }
   }
   __syncthreads();
   if (t < MROWS && m0 + t < M) {
@@ -196,15 +240,26 @@ __global__ void __launch_bounds__(WAVES * 64) lm_head_argmax_kernel(const __hip_
       if (beats(s_val[w][t], s_idx[w][t], best, best_i)) { best = s_val[w][t]; best_i = s_idx[w][t]; }
     part_val[(long)(m0 + t) * n_vtiles + blockIdx.x] = best;
     part_idx[(long)(m0 + t) * n_vtiles + blockIdx.x] = best_i;
+    if (STATS) {
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w)
+        if (s_val[w][t] > -INFINITY) sum += s_sum[w][t] * __builtin_amdgcn_exp2f((s_val[w][t] - best) * inv_temp_log2);
+      part_sum[(long)(m0 + t) * n_vtiles + blockIdx.x] = sum;
+    }
   }
 }
 
-// One workgroup per row: merges the row's n_vtiles partials.
+// One workgroup per row: merges the row's n_vtiles partials (part_sum != nullptr: also the sums, rescaled to
+// the row's maximum).
 __global__ void __launch_bounds__(256) lm_head_reduce_kernel(const float* __restrict__ part_val,
-                                                             const int32_t* __restrict__ part_idx, int n_vtiles,
-                                                             int32_t* __restrict__ node_argmax, float* __restrict__ node_max) {
+                                                             const int32_t* __restrict__ part_idx,
+                                                             const float* __restrict__ part_sum, float inv_temp_log2,
+                                                             int n_vtiles, int32_t* __restrict__ node_argmax,
+                                                             float* __restrict__ node_max, float* __restrict__ node_sumexp) {
   __shared__ float s_val[4];
   __shared__ int s_idx[4];
+  __shared__ float s_sum[4];
   const int m = blockIdx.x, t = threadIdx.x;
   float best = -INFINITY;
   int best_i = 0x7fffffff;
@@ -220,44 +275,68 @@ __global__ void __launch_bounds__(256) lm_head_reduce_kernel(const float* __rest
   }
   if ((t & 63) == 0) { s_val[t >> 6] = best; s_idx[t >> 6] = best_i; }
   __syncthreads();
+  best = s_val[0]; best_i = s_idx[0];
+  for (int w = 1; w < 4; ++w)
+    if (beats(s_val[w], s_idx[w], best, best_i)) { best = s_val[w]; best_i = s_idx[w]; }
+  if (part_sum != nullptr) {
+    float sum = 0.f;
+    for (int j = t; j < n_vtiles; j += 256) {
+      const float v = part_val[(long)m * n_vtiles + j];
+      if (v > -INFINITY) sum += part_sum[(long)m * n_vtiles + j] * __builtin_amdgcn_exp2f((v - best) * inv_temp_log2);
+    }
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    if ((t & 63) == 0) s_sum[t >> 6] = sum;
+    __syncthreads();
+    if (t == 0 && node_sumexp != nullptr) node_sumexp[m] = (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]);
+  }
   if (t == 0) {
-    for (int w = 1; w < 4; ++w)
-      if (beats(s_val[w], s_idx[w], best, best_i)) { best = s_val[w]; best_i = s_idx[w]; }
-    node_argmax[m] = best_i == 0x7fffffff ? 0 : best_i;   // a row of NaN / -inf logits
+    if (node_argmax != nullptr) node_argmax[m] = best_i == 0x7fffffff ? 0 : best_i;   // a row of NaN / -inf logits
     if (node_max != nullptr) node_max[m] = best;
   }
 }
 
 }  // namespace lmh
 
-hipError_t launch_lm_head_argmax(int M, int K, int V, const void* hidden, const void* weight, int32_t* node_argmax,
-                                 float* node_max, void* ws, hipStream_t s) {
+// logits_out != nullptr: the kernel also writes the bf16 logits [M, V] and the softmax statistics of the rounded
+// values (node_sumexp; inv_temp = 1 / temperature); the workspace then holds a third partial array.
+hipError_t launch_lm_head(int M, int K, int V, const void* hidden, const void* weight, void* logits_out, float inv_temp,
+                          int32_t* node_argmax, float* node_max, float* node_sumexp, void* ws, hipStream_t s) {
+  const bool stats = logits_out != nullptr;
+  const size_t arr = lm_head_partials_bytes(M, V) / 2;
   float* part_val = (float*)ws;
-  int32_t* part_idx = (int32_t*)((char*)ws + lm_head_partials_bytes(M, V) / 2);
+  int32_t* part_idx = (int32_t*)((char*)ws + arr);
+  float* part_sum = stats ? (float*)((char*)ws + 2 * arr) : nullptr;
+  const float itl2 = inv_temp * 1.4426950408889634f;
   const int nmt = M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : 8;
   const int waves = lm_head_waves(M);
   const int n_vtiles = (V + waves * 16 - 1) / (waves * 16);
   const dim3 grid(n_vtiles, (M + nmt * 16 - 1) / (nmt * 16));
-#define SPEC_LMH(NMT, WV)                                                                                              \
-  hipLaunchKernelGGL((lmh::lm_head_argmax_kernel<NMT, WV>), grid, dim3(WV * 64), 0, s, (const __hip_bfloat16*)hidden, \
-                     (const __hip_bfloat16*)weight, part_val, part_idx, M, K, V, n_vtiles)
+#define SPEC_LMH(NMT, WV, ST)                                                                                              \
+  hipLaunchKernelGGL((lmh::lm_head_argmax_kernel<NMT, WV, ST>), grid, dim3(WV * 64), 0, s, (const __hip_bfloat16*)hidden, \
+                     (const __hip_bfloat16*)weight, part_val, part_idx, part_sum, (__hip_bfloat16*)logits_out, itl2, M, K, \
+                     V, n_vtiles)
+#define SPEC_LMH_T(WV, ST)                  \
+  if (nmt == 1) SPEC_LMH(1, WV, ST);        \
+  else if (nmt == 2) SPEC_LMH(2, WV, ST);   \
+  else if (nmt == 4) SPEC_LMH(4, WV, ST);   \
+  else SPEC_LMH(8, WV, ST)
   if (waves == 4) {
-    if (nmt == 1) SPEC_LMH(1, 4);
-    else if (nmt == 2) SPEC_LMH(2, 4);
-    else if (nmt == 4) SPEC_LMH(4, 4);
-    else SPEC_LMH(8, 4);
+    if (stats) { SPEC_LMH_T(4, true); } else { SPEC_LMH_T(4, false); }
   } else {
-    if (nmt == 1) SPEC_LMH(1, 8);
-    else if (nmt == 2) SPEC_LMH(2, 8);
-    else if (nmt == 4) SPEC_LMH(4, 8);
-    else SPEC_LMH(8, 8);
+    if (stats) { SPEC_LMH_T(8, true); } else { SPEC_LMH_T(8, false); }
   }
+#undef SPEC_LMH_T
 #undef SPEC_LMH
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(lmh::lm_head_reduce_kernel, dim3(M), dim3(256), 0, s, part_val, part_idx, n_vtiles, node_argmax,
-                     node_max);
+  hipLaunchKernelGGL(lmh::lm_head_reduce_kernel, dim3(M), dim3(256), 0, s, part_val, part_idx, part_sum, itl2, n_vtiles,
+                     node_argmax, node_max, node_sumexp);
   return hipGetLastError();
+}
+
+hipError_t launch_lm_head_argmax(int M, int K, int V, const void* hidden, const void* weight, int32_t* node_argmax,
+                                 float* node_max, void* ws, hipStream_t s) {
+  return launch_lm_head(M, K, V, hidden, weight, nullptr, 1.f, node_argmax, node_max, nullptr, ws, s);
 }
 
 }  // namespace spec

@@ -574,6 +574,53 @@ int spec_verify_stochastic(int32_t B, int32_t N, int32_t V, int32_t logits_dtype
   return SPEC_OK;
 }
 
+size_t spec_lm_head_logits_stats_workspace_bytes(int32_t M, int32_t V) {
+  if (M <= 0 || V <= 0) return 0;
+  return 3 * (lm_head_partials_bytes(M, V) / 2);   // (max, arg-max, sum) per row and vocabulary tile
+}
+
+int spec_lm_head_logits_stats(int32_t M, int32_t K, int32_t V, const void* hidden, const void* weight, float temperature,
+                              void* logits, int32_t* node_argmax, float* node_max, float* node_sumexp, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  if (M <= 0 || K <= 0 || V <= 0) return SPEC_ERR_INVALID_ARG;
+  if (K % 256 != 0) return SPEC_ERR_UNSUPPORTED;
+  if (!hidden || !weight || !aligned16(hidden) || !aligned16(weight)) return SPEC_ERR_INVALID_ARG;
+  if (!logits || !node_max || !node_sumexp || (reinterpret_cast<uintptr_t>(logits) & 7u)) return SPEC_ERR_INVALID_ARG;
+  if (!(temperature > 0.f) || std::isinf(temperature)) return SPEC_ERR_INVALID_ARG;
+  if (workspace == nullptr || workspace_bytes < spec_lm_head_logits_stats_workspace_bytes(M, V)) return SPEC_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return SPEC_ERR_INVALID_ARG;
+  return launch_lm_head(M, K, V, hidden, weight, logits, 1.0f / temperature, node_argmax, node_max, node_sumexp, workspace,
+                        (hipStream_t)hip_stream) == hipSuccess
+             ? SPEC_OK
+             : SPEC_ERR_HIP;
+}
+
+size_t spec_verify_stochastic_stats_workspace_bytes(int32_t B, int32_t V) {
+  if (B <= 0 || V <= 0) return 0;
+  return round_up((size_t)2 * B * V * sizeof(float), 256);   // two residual buffers of V floats per request
+}
+
+int spec_verify_stochastic_stats(int32_t B, int32_t N, int32_t V, int32_t logits_dtype, const void* logits_llm,
+                                 const float* node_max, const float* node_sumexp, const float* probs_ssm, int32_t R,
+                                 const int32_t* ssm_row, const int32_t* tree_token, const int32_t* tree_parent,
+                                 const float* u_accept, const float* u_order, const float* u_final, float temperature,
+                                 int32_t Lmax, int32_t* accepted_path, int32_t* accepted_len, int32_t* out_tokens,
+                                 void* workspace, size_t workspace_bytes, int32_t* status, void* hip_stream) {
+  const int rc = check_verify_common(B, N, V, logits_dtype, logits_llm, tree_token, tree_parent, Lmax, accepted_path,
+                                     accepted_len, out_tokens);
+  if (rc != SPEC_OK) return rc;
+  if (!ssm_row || !u_accept || !u_order || !u_final || !node_max || !node_sumexp) return SPEC_ERR_INVALID_ARG;
+  if (R < 0 || (R > 0 && probs_ssm == nullptr)) return SPEC_ERR_INVALID_ARG;
+  if (!(temperature > 0.f) || std::isinf(temperature)) return SPEC_ERR_INVALID_ARG;
+  if (workspace == nullptr || workspace_bytes < spec_verify_stochastic_stats_workspace_bytes(B, V)) return SPEC_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return SPEC_ERR_INVALID_ARG;
+  return launch_stochastic_walk(B, N, V, logits_dtype, logits_llm, probs_ssm, R, ssm_row, tree_token, tree_parent, u_accept,
+                                u_order, u_final, 1.0f / temperature, node_max, node_sumexp, (float*)workspace, Lmax,
+                                accepted_path, accepted_len, out_tokens, status, (hipStream_t)hip_stream) == hipSuccess
+             ? SPEC_OK
+             : SPEC_ERR_HIP;
+}
+
 static int kv_commit_impl(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, bool paged, int32_t n_layers,
                           void* const* k_caches, void* const* v_caches, const int32_t* accepted_path, int32_t Lmax,
                           const int32_t* accepted_len, const int32_t* prefix_len, int32_t* prefix_len_out, int32_t* status,

@@ -129,6 +129,10 @@ inline size_t lm_head_partials_bytes(int M, int V) {
 }
 hipError_t launch_lm_head_argmax(int M, int K, int V, const void* hidden, const void* weight, int32_t* node_argmax,
                                  float* node_max, void* ws, hipStream_t s);
+// The same pass over the weights that also writes bf16 logits and their softmax statistics; the workspace holds
+// three partial arrays (lm_head_partials_bytes(M, V) / 2 each).
+hipError_t launch_lm_head(int M, int K, int V, const void* hidden, const void* weight, void* logits_out, float inv_temp,
+                          int32_t* node_argmax, float* node_max, float* node_sumexp, void* ws, hipStream_t s);
 hipError_t launch_node_stats(int B, int N, int V, int logits_dtype, const void* logits, float inv_temp,
                              int32_t* node_argmax, float* node_max, float* node_sumexp, hipStream_t s);
 hipError_t launch_node_sample(int B, int N, int V, int logits_dtype, const void* logits, float inv_temp,

@@ -114,3 +114,77 @@ def test_lm_head_host_side_errors(spec):
     assert call(4, 256, 100, hd.data_ptr(), wd.data_ptr(), arg.data_ptr(), ws.data_ptr(), 16) == spec.ERR_WORKSPACE
     assert call(4, 256, 100, hd.data_ptr(), wd.data_ptr(), arg.data_ptr(), None, 0) == spec.ERR_WORKSPACE
     assert spec.spec_lm_head_argmax_workspace_bytes(0, 5) == 0
+
+
+# ------------------------------------------------------------------------------------------------
+# LM head in front of the stochastic verifier: bf16 logits + per-row softmax statistics in one pass
+# ------------------------------------------------------------------------------------------------
+
+def _stats_case(spec, M, K, V, temperature, seed):
+    """Logits against the float64 product (within one unit in the last place of bf16 plus the float32 accumulation
+    bound); maximum, arg-max and sum of exponentials against the oracle's statistics OF THE LOGITS THE KERNEL
+    STORED (they are defined on the stored values)."""
+    from oracle import spec_oracle as orc
+    h, w = _inputs(M, K, V, seed=seed)
+    logits, arg, mx, se = spec.spec_lm_head_logits_stats(_dev(h), _dev(w), temperature=temperature)
+    torch.cuda.synchronize()
+    hd, wd = h.double().numpy(), w.double().numpy()
+    want = orc.lm_head_logits(hd, wd)
+    got = logits.double().cpu().numpy()
+    bound = hd.shape[1] * 2.0 ** -24 * (np.abs(hd) @ np.abs(wd).T)
+    assert (np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + bound + 1e-30).all()
+    ra, rm, rz = orc.softmax_stats(got, temperature)
+    assert np.array_equal(arg.cpu().numpy(), ra)
+    assert np.array_equal(mx.double().cpu().numpy(), rm)
+    assert np.allclose(se.double().cpu().numpy(), rz, rtol=2e-5, atol=0)
+    return logits, mx, se
+
+
+@pytest.mark.parametrize("M,K,V,T", [(128, 4096, 32000, 1.0), (16, 4096, 32000, 0.7), (1, 512, 1000, 1.0), (17, 256, 130, 1.6),
+                                     (64, 1280, 4097, 1.0), (200, 1024, 5001, 0.9), (33, 768, 127, 1.0)])
+def test_lm_head_logits_and_softmax_statistics(spec, M, K, V, T):
+    _stats_case(spec, M, K, V, T, seed=M + K + V)
+
+
+@pytest.mark.parametrize("temperature", [1.0, 0.8])
+def test_stochastic_verification_from_the_lm_head_statistics(spec, temperature):
+    """hidden states -> spec_lm_head_logits_stats -> spec_verify_stochastic_stats: the same accepted path and tokens
+    as spec_verify_stochastic on the stored logits (the statistics replace its first pass, nothing else), and as
+    the oracle's VerifyStochastic on those logits with uniforms vetted against them."""
+    from oracle import spec_oracle as orc
+    from oracle import vetting
+    cfg = wl.Config(2, "lmh-stoch", "bf16", B=8, H=1, D=64, P=1, N=16, tree="expansion", widths=wl.EXPANSION_EVAL, V=4000)
+    K = 512
+    par_np = wl.make_trees(cfg, np.random.default_rng(3))
+    h, w = _inputs(cfg.B * cfg.N, K, cfg.V, seed=77, scale=1.5)
+    logits2d, _, mx, se = spec.spec_lm_head_logits_stats(_dev(h), _dev(w), temperature=temperature)
+    torch.cuda.synchronize()
+    logits = logits2d.view(cfg.B, cfg.N, cfg.V)
+    lg = logits.float().cpu()
+    # drafts near the LLM and children sampled from them, built on the logits the kernel stored
+    rng = np.random.default_rng(5)
+    probs_t, ssm_row, tok = wl.make_ssm(cfg, rng, lg, par_np, tau=1.2)
+    probs = probs_t.numpy()
+    ua, uo, uf = wl.make_uniforms(rng, cfg.B, cfg.N)
+    args = (lg.numpy(), probs, ssm_row, tok, par_np)
+    ua, uf, _ = vetting.vet_uniforms(*args, ua, uo, uf, rng, temperature=temperature)
+    rp, rl, rt, rs = orc.verify_stochastic(*args, ua, uo, uf, temperature=temperature)
+    dev_args = (_dev(probs), _dev(ssm_row), _dev(tok), _dev(par_np), _dev(ua), _dev(uo), _dev(uf))
+    status = torch.zeros(cfg.B, dtype=torch.int32, device=DEV)
+    p1, l1, t1 = spec.spec_verify_stochastic_stats(logits, mx, se, *dev_args, temperature=temperature, status=status)
+    p2, l2, t2 = spec.spec_verify_stochastic(logits, *dev_args, temperature=temperature)
+    torch.cuda.synchronize()
+    assert np.array_equal(p1.cpu().numpy(), rp) and np.array_equal(l1.cpu().numpy(), rl) and np.array_equal(t1.cpu().numpy(), rt)
+    assert np.array_equal(status.cpu().numpy(), rs)
+    assert torch.equal(p1, p2) and torch.equal(l1, l2) and torch.equal(t1, t2)
+    assert rl.max() > 1
+
+
+def test_lm_head_stats_reject_bad_arguments(spec):
+    h, w = _inputs(4, 256, 100, seed=1)
+    with pytest.raises(spec.SpecError) as e:
+        spec.spec_lm_head_logits_stats(_dev(h), _dev(w), temperature=0.0)
+    assert e.value.code == spec.ERR_INVALID_ARG
+    with pytest.raises(spec.SpecError) as e:
+        spec.spec_lm_head_logits_stats(_dev(h), _dev(w), workspace=torch.empty(256, dtype=torch.uint8, device=DEV)[:8])
+    assert e.value.code == spec.ERR_WORKSPACE
