@@ -130,6 +130,14 @@ def measure(cfg_id, args, steps, warmup, want_cpu_baseline, want_read_probe):
             spec.spec_tree_attention_append(W["q"][l], W["k_new"][l], W["v_new"][l], W["k_cache"][l], W["v_cache"][l], par,
                                             dep, pl, out=W["out"][l], workspace=ws, status=status, desc=desc)
 
+    rope_cos, rope_sin = (t.to(dev) for t in wl.make_rope_tables(cfg.S_cap, D))
+
+    def attention_layers_rope():   # the same launches with the rotary embedding of q and the new K rows fused in
+        for l in range(L):
+            spec.spec_tree_attention_append_rope(W["q"][l], W["k_new"][l], W["v_new"][l], W["k_cache"][l], W["v_cache"][l],
+                                                 par, dep, pl, rope_cos, rope_sin, out=W["out"][l], workspace=ws,
+                                                 status=status, max_prefix_len=max_prefix)
+
     def greedy():
         spec.spec_verify_greedy(g_logits, g_tok, par, Lmax=Lmax, status=status, out=g_out)
 
@@ -187,6 +195,7 @@ def measure(cfg_id, args, steps, warmup, want_cpu_baseline, want_read_probe):
         return ev0.elapsed_time(ev1) * 1e3 / (reps * per)
 
     attn_us = time_us(attention_layers, max(5, min(steps, 50)), per=L)
+    attn_rope_us = time_us(attention_layers_rope, max(5, min(steps, 20)), per=L) if cfg.dtype == "bf16" else None
     sum_p = int(W["host"]["prefix_len"].sum())
     # fused append + attention: prefix K,V read (2P), new K,V read (2N) and written to the cache (2N), Q in, O out
     attn_bytes = e * H * D * (2 * sum_p + 6 * B * N)
@@ -223,9 +232,10 @@ def measure(cfg_id, args, steps, warmup, want_cpu_baseline, want_read_probe):
         "workload": f"config {cfg.cfg}: {cfg.name} B={B} H={H} D={D} prefix={cfg.P} tree N={N} vocab={vcfg.V} "
                     f"layers/pass={L}" + (" (attention only)" if args.attn_only else ""),
         "ms_per_step": ms_per_step, "value": B * N / (ms_per_step * 1e-3), "steps": steps,
-        "attn_us": attn_us, "attn_bytes": attn_bytes, "achieved": achieved,
+        "attn_us": attn_us, "attn_rope_us": attn_rope_us, "attn_bytes": attn_bytes, "achieved": achieved,
         "greedy_us": greedy_us, "stoch_us": stoch_us, "commit_us": commit_us, "L": L,
-        "kernel": ("tree_attention_bf16_wide_kernel" if wide else "tree_attention_bf16_kernel")
+        "kernel": ("tree_attention_bf16_wide32_kernel" if N > 64 and D == 128 else
+                   "tree_attention_bf16_wide_kernel" if wide else "tree_attention_bf16_kernel")
                   + " (KV append fused; + attn_combine_kernel when the key range is split)",
         "read_stream_gbs": read_stream_gbs, "dense_flops": dense_flops, "dtype": cfg.dtype,
         "traffic": counter_traffic_bytes(cfg.cfg),
@@ -290,6 +300,8 @@ def main():
                    "launch": "eager" if args.no_graph else "hip-graph replay",
                    "layer_tree_tokens_per_s": tokens / (head["attn_us"] * 1e-6),
                    "attention_us_per_layer": head["attn_us"], "layer_algorithmic_bytes": head["attn_bytes"],
+                   # the same launch with the rotary embedding of q and of the new K rows fused in
+                   "attention_with_rotary_us_per_layer": head["attn_rope_us"],
                    "greedy_verify_us": head["greedy_us"], "greedy_verify_tree_tokens_per_s": tokens / (head["greedy_us"] * 1e-6),
                    "stochastic_verify_us": head["stoch_us"],
                    "stochastic_verify_tree_tokens_per_s": tokens / (head["stoch_us"] * 1e-6),
@@ -305,7 +317,8 @@ def main():
                 continue
             r = measure(c, args, max(3, min(args.steps, 10)), min(args.warmup, 3), False, False)
             per.append({"workload": r["workload"], "tree_tokens_per_s": r["value"], "ms_per_step": r["ms_per_step"],
-                        "steps": r["steps"], "us_per_launch": r["attn_us"], "bytes_per_launch": r["attn_bytes"],
+                        "steps": r["steps"], "us_per_launch": r["attn_us"], "us_per_launch_with_rotary": r["attn_rope_us"],
+                        "bytes_per_launch": r["attn_bytes"],
                         "roofline": {"bound": "hbm", "achieved": r["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                      "frac": r["achieved"] / HBM_PEAK_GBS, "traffic": r["traffic"]},
                         "greedy_verify_us": r["greedy_us"], "stochastic_verify_us": r["stoch_us"],

@@ -175,6 +175,25 @@ int spec_tree_attention_append(const spec_attn_desc_t* desc, const void* q, cons
                                void* hip_stream);
 
 /*
+ * The fused call for a model with rotary embeddings (the paper's LLaMA models; Sections 4.1-4.2 for the
+ * attention and the cache, the rotation as in spec_kv_append_rope): spec_qk_rope_append followed by
+ * spec_tree_attention in ONE launch. The queries are rotated in registers (q itself is NOT modified), the new K
+ * rows are rotated before they are used by the attention and written to the cache, V is copied; positions,
+ * pairing, tables and arithmetic are those of spec_kv_append_rope, and the cache rows and `out` come out
+ * bit-identical to the two calls made one after the other. bf16 only (other dtypes: SPEC_ERR_UNSUPPORTED).
+ * Capacity rule: the tables must cover every position a tree of N nodes can take, so a request with
+ * prefix_len[b] + N > min(S_cap, rope_len) is neither appended nor attended and is flagged SPEC_ST_CAPACITY
+ * (the two-launch form checks each node's own position instead). Workspace: spec_tree_attention_workspace_bytes
+ * (paged form: spec_tree_attention_paged_workspace_bytes). NULL tables or rope_len <= 0: SPEC_ERR_INVALID_ARG.
+ */
+int spec_tree_attention_append_rope(const spec_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,
+                                    void* k_cache, void* v_cache, const int32_t* tree_parent /*[B,N]*/,
+                                    const int32_t* tree_depth /*[B,N]*/, const int32_t* prefix_len /*[B]*/,
+                                    const float* rope_cos /*[rope_len, D/2]*/, const float* rope_sin /*[rope_len, D/2]*/,
+                                    int32_t rope_len, void* out, void* workspace, size_t workspace_bytes,
+                                    int32_t* status /*[B] or NULL*/, void* hip_stream);
+
+/*
  * spec_tree_attention_append for callers that cannot allocate or bring a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments, results and status bits as
  * spec_tree_attention_append, without the workspace: the float32 partial results of a split key range live
@@ -404,7 +423,13 @@ int spec_tree_attention_append_paged(const spec_attn_desc_t* desc, const spec_kv
                                      const int32_t* tree_parent, const int32_t* tree_depth,
                                      const int32_t* prefix_len, void* out, void* workspace, size_t workspace_bytes,
                                      int32_t* status, void* hip_stream);
-/* workspace of the two paged attention calls (the launch plan of a paged call may differ) */
+int spec_tree_attention_append_rope_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, const void* q,
+                                          const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                                          const int32_t* tree_parent, const int32_t* tree_depth,
+                                          const int32_t* prefix_len, const float* rope_cos, const float* rope_sin,
+                                          int32_t rope_len, void* out, void* workspace, size_t workspace_bytes,
+                                          int32_t* status, void* hip_stream);
+/* workspace of the paged attention calls (the launch plan of a paged call may differ) */
 size_t spec_tree_attention_paged_workspace_bytes(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages);
 int spec_kv_commit_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, int32_t n_layers,
                          void* const* k_caches /*host*/, void* const* v_caches /*host*/,

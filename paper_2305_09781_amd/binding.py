@@ -32,6 +32,7 @@ EXPORTED = [
     "spec_qk_rope_append", "spec_qk_rope_append_paged", "spec_tree_attention_append_static",
     "spec_lm_head_logits_stats", "spec_lm_head_logits_stats_workspace_bytes", "spec_verify_stochastic_stats",
     "spec_verify_stochastic_stats_workspace_bytes",
+    "spec_tree_attention_append_rope", "spec_tree_attention_append_rope_paged",
 ]
 STATIC_SCRATCH_BYTES = 64 << 20
 
@@ -86,6 +87,8 @@ def load():
     lib.spec_tree_attention_append.restype = ctypes.c_int
     lib.spec_tree_attention_append_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.spec_tree_attention_append_static.restype = ctypes.c_int
+    lib.spec_tree_attention_append_rope.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp, vp]
+    lib.spec_tree_attention_append_rope.restype = ctypes.c_int
     lib.spec_tree_attention_workspace_bytes.argtypes = [dp]
     lib.spec_tree_attention_workspace_bytes.restype = sz
     lib.spec_verify_greedy.argtypes = [i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp, vp]
@@ -114,6 +117,9 @@ def load():
     lib.spec_tree_attention_paged.restype = ctypes.c_int
     lib.spec_tree_attention_append_paged.argtypes = [dp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
     lib.spec_tree_attention_append_paged.restype = ctypes.c_int
+    lib.spec_tree_attention_append_rope_paged.argtypes = [dp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz,
+                                                          vp, vp]
+    lib.spec_tree_attention_append_rope_paged.restype = ctypes.c_int
     lib.spec_tree_attention_paged_workspace_bytes.argtypes = [dp, pp]
     lib.spec_tree_attention_paged_workspace_bytes.restype = sz
     lib.spec_kv_commit_paged.argtypes = [dp, pp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i32, vp, vp, vp, vp, vp]
@@ -286,6 +292,45 @@ def spec_tree_attention_append(q, k_new, v_new, k_cache, v_cache, tree_parent, t
                                              _ptr(v_cache), _ptr(tree_parent), _ptr(tree_depth), _ptr(prefix_len),
                                              _ptr(out), _ptr(workspace), ws_bytes, _ptr(status), _stream(stream)),
            "spec_tree_attention_append")
+    return out
+
+
+def spec_tree_attention_append_rope(q, k_new, v_new, k_cache, v_cache, tree_parent, tree_depth, prefix_len, rope_cos,
+                                    rope_sin, out=None, workspace=None, status=None, max_prefix_len: int = 0,
+                                    softmax_scale: float = 0.0, stream=None, plan=(0, 0, 0), block_table=None):
+    """Rotary embedding of q (in registers: q is not modified) and of the new K rows, KV append and tree attention
+    in one launch. With block_table the caches are pools of blocks (paged)."""
+    _same_layout(k_cache, v_cache, "k_cache and v_cache")
+    _same_layout(k_new, v_new, "k_new and v_new")
+    D = k_new.shape[-1]
+    for tab in (rope_cos, rope_sin):
+        if tab.dtype != torch.float32 or tab.dim() != 2 or tab.shape[1] != D // 2 or not tab.is_contiguous():
+            raise ValueError("rope tables must be contiguous float32 [rope_len, D/2]")
+    if out is None:
+        out = torch.empty_like(q)
+    _same_layout(q, out, "q and out")
+    if block_table is None:
+        d = make_desc(q, k_cache, max_prefix_len, softmax_scale, k_new=k_new, plan=plan)
+        need = spec_tree_attention_workspace_bytes(d)
+    else:
+        d, pg = make_paged_desc(q, k_cache, block_table, max_prefix_len, softmax_scale, k_new=k_new, plan=plan)
+        need = spec_tree_attention_paged_workspace_bytes(d, pg)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    if block_table is None:
+        _check(load().spec_tree_attention_append_rope(ctypes.byref(d), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache),
+                                                      _ptr(v_cache), _ptr(tree_parent), _ptr(tree_depth),
+                                                      _ptr(prefix_len), _ptr(rope_cos), _ptr(rope_sin), rope_cos.shape[0],
+                                                      _ptr(out), _ptr(workspace), ws_bytes, _ptr(status),
+                                                      _stream(stream)), "spec_tree_attention_append_rope")
+    else:
+        _check(load().spec_tree_attention_append_rope_paged(ctypes.byref(d), ctypes.byref(pg), _ptr(q), _ptr(k_new),
+                                                            _ptr(v_new), _ptr(k_cache), _ptr(v_cache), _ptr(tree_parent),
+                                                            _ptr(tree_depth), _ptr(prefix_len), _ptr(rope_cos),
+                                                            _ptr(rope_sin), rope_cos.shape[0], _ptr(out), _ptr(workspace),
+                                                            ws_bytes, _ptr(status), _stream(stream)),
+               "spec_tree_attention_append_rope_paged")
     return out
 
 

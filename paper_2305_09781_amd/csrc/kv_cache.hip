@@ -40,52 +40,6 @@ __global__ void __launch_bounds__(256) kv_append_kernel(const uint4* __restrict_
   v_cache[dst] = v_new[src];
 }
 
-// Rotation of the two 16-byte pieces of a row that pair up under the half-split rotary embedding (piece c holds
-// dimensions c * EPV .., its partner the same dimensions + D/2), by the angles whose cosines / sines are cs / sn;
-// float32 arithmetic, rounded to the storage type.
-template <bool BF16>
-__device__ __forceinline__ void rope_pair(const uint4 lo, const uint4 hi, const float* __restrict__ cs,
-                                          const float* __restrict__ sn, uint4* olo, uint4* ohi) {
-  constexpr int EPV = BF16 ? 8 : 4;   // elements per 16-byte piece
-  float x1[EPV], x2[EPV];
-  if (BF16) {
-    const unsigned a[4] = {lo.x, lo.y, lo.z, lo.w}, bb[4] = {hi.x, hi.y, hi.z, hi.w};
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      x1[2 * j] = __uint_as_float(a[j] << 16);
-      x1[2 * j + 1] = __uint_as_float(a[j] & 0xffff0000u);
-      x2[2 * j] = __uint_as_float(bb[j] << 16);
-      x2[2 * j + 1] = __uint_as_float(bb[j] & 0xffff0000u);
-    }
-  } else {
-    x1[0] = __uint_as_float(lo.x); x1[1] = __uint_as_float(lo.y); x1[2] = __uint_as_float(lo.z); x1[3] = __uint_as_float(lo.w);
-    x2[0] = __uint_as_float(hi.x); x2[1] = __uint_as_float(hi.y); x2[2] = __uint_as_float(hi.z); x2[3] = __uint_as_float(hi.w);
-  }
-  float y1[EPV], y2[EPV];
-#pragma unroll
-  for (int j = 0; j < EPV; ++j) {
-    const float co = cs[j], si = sn[j];
-    y1[j] = x1[j] * co - x2[j] * si;
-    y2[j] = x2[j] * co + x1[j] * si;
-  }
-  if (BF16) {
-    unsigned o1[4], o2[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      union { __hip_bfloat16 h; unsigned short u; } a0, a1, b0, b1;
-      a0.h = __float2bfloat16(y1[2 * j]); a1.h = __float2bfloat16(y1[2 * j + 1]);
-      b0.h = __float2bfloat16(y2[2 * j]); b1.h = __float2bfloat16(y2[2 * j + 1]);
-      o1[j] = (unsigned)a0.u | ((unsigned)a1.u << 16);
-      o2[j] = (unsigned)b0.u | ((unsigned)b1.u << 16);
-    }
-    *olo = make_uint4(o1[0], o1[1], o1[2], o1[3]);
-    *ohi = make_uint4(o2[0], o2[1], o2[2], o2[3]);
-  } else {
-    *olo = make_uint4(__float_as_uint(y1[0]), __float_as_uint(y1[1]), __float_as_uint(y1[2]), __float_as_uint(y1[3]));
-    *ohi = make_uint4(__float_as_uint(y2[0]), __float_as_uint(y2[1]), __float_as_uint(y2[2]), __float_as_uint(y2[3]));
-  }
-}
-
 // KV append with the rotary position embedding applied to K on the way in (half-split pairing:
 // dimension i < D/2 rotates with i + D/2), and optionally to the queries in place. Token i of request b sits at
 // position prefix_len[b] + tree_depth[b,i]; cos / sin come from the caller's tables [rope_len, D/2]. grid =

@@ -308,7 +308,8 @@ size_t spec_tree_attention_paged_workspace_bytes(const spec_attn_desc_t* desc, c
 static int tree_attention_impl(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, bool paged, const void* q,
                                const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                                const int32_t* tree_parent, const int32_t* tree_depth, const int32_t* prefix_len, void* out,
-                               void* workspace, size_t workspace_bytes, int32_t* status, void* hip_stream) {
+                               void* workspace, size_t workspace_bytes, int32_t* status, void* hip_stream,
+                               const Rope& rope = no_rope()) {
   int rc = check_desc(desc);
   if (rc != SPEC_OK) return rc;
   Pages pg = no_pages();
@@ -328,11 +329,13 @@ static int tree_attention_impl(const spec_attn_desc_t* desc, const spec_kv_pages
   // capacity, so such a request is flagged SPEC_ST_CAPACITY like one that does not fit the cache.
   spec_attn_desc_t d = *desc;
   if (d.max_prefix_len > 0) d.S_cap = d.max_prefix_len + d.N;   // <= S_cap (checked above); strides are unchanged
+  // Rotary tables: they must cover every position of a tree of N nodes, so their length bounds the capacity too.
+  if (rope.cos != nullptr && rope.len < d.S_cap) d.S_cap = rope.len;
   hipStream_t s = (hipStream_t)hip_stream;
   hipError_t e;
   if (d.dtype == SPEC_BF16) {
     e = launch_tree_attention_bf16(d, plan, pg, q, k_cache, v_cache, k_new, v_new, tree_parent, tree_depth, prefix_len, out,
-                                   workspace, status, s);
+                                   workspace, status, s, rope);
   } else {
     if (append) {
       e = launch_kv_append(d, pg, k_new, v_new, k_cache, v_cache, prefix_len, status, s);
@@ -373,6 +376,39 @@ int spec_tree_attention_append(const spec_attn_desc_t* desc, const void* q, cons
   if (!k_new || !v_new) return check_desc(desc) != SPEC_OK ? check_desc(desc) : SPEC_ERR_INVALID_ARG;
   return tree_attention_impl(desc, nullptr, false, q, k_new, v_new, k_cache, v_cache, tree_parent, tree_depth,
                              prefix_len, out, workspace, workspace_bytes, status, hip_stream);
+}
+
+static int rope_args(const spec_attn_desc_t* desc, const void* k_new, const void* v_new, const float* rope_cos,
+                     const float* rope_sin, int32_t rope_len) {
+  const int rc = check_desc(desc);
+  if (rc != SPEC_OK) return rc;
+  if (!k_new || !v_new || !rope_cos || !rope_sin || rope_len <= 0) return SPEC_ERR_INVALID_ARG;
+  if (desc->dtype != SPEC_BF16) return SPEC_ERR_UNSUPPORTED;
+  return SPEC_OK;
+}
+
+int spec_tree_attention_append_rope(const spec_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,
+                                    void* k_cache, void* v_cache, const int32_t* tree_parent, const int32_t* tree_depth,
+                                    const int32_t* prefix_len, const float* rope_cos, const float* rope_sin,
+                                    int32_t rope_len, void* out, void* workspace, size_t workspace_bytes,
+                                    int32_t* status, void* hip_stream) {
+  const int rc = rope_args(desc, k_new, v_new, rope_cos, rope_sin, rope_len);
+  if (rc != SPEC_OK) return rc;
+  return tree_attention_impl(desc, nullptr, false, q, k_new, v_new, k_cache, v_cache, tree_parent, tree_depth,
+                             prefix_len, out, workspace, workspace_bytes, status, hip_stream,
+                             Rope{rope_cos, rope_sin, rope_len});
+}
+
+int spec_tree_attention_append_rope_paged(const spec_attn_desc_t* desc, const spec_kv_pages_t* pages, const void* q,
+                                          const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                                          const int32_t* tree_parent, const int32_t* tree_depth,
+                                          const int32_t* prefix_len, const float* rope_cos, const float* rope_sin,
+                                          int32_t rope_len, void* out, void* workspace, size_t workspace_bytes,
+                                          int32_t* status, void* hip_stream) {
+  const int rc = rope_args(desc, k_new, v_new, rope_cos, rope_sin, rope_len);
+  if (rc != SPEC_OK) return rc;
+  return tree_attention_impl(desc, pages, true, q, k_new, v_new, k_cache, v_cache, tree_parent, tree_depth, prefix_len,
+                             out, workspace, workspace_bytes, status, hip_stream, Rope{rope_cos, rope_sin, rope_len});
 }
 
 int spec_tree_attention_append_static(const spec_attn_desc_t* desc, const void* q, const void* k_new, const void* v_new,

@@ -2,6 +2,9 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#ifdef __HIPCC__
+#include <hip/hip_bf16.h>
+#endif
 #include <stdint.h>
 
 #include "spec_tree.h"
@@ -36,6 +39,15 @@ struct Pages {
   int n_blocks;
 };
 inline Pages no_pages() { return Pages{nullptr, 0, 0, 0}; }
+
+// Rotary position embedding applied inside the fused append + attention call (cos == nullptr: none): the caller's
+// float32 device tables [len, D/2]. Token i of request b sits at position prefix_len[b] + tree_depth[b, i].
+struct Rope {
+  const float* cos;
+  const float* sin;
+  int len;
+};
+inline Rope no_rope() { return Rope{nullptr, nullptr, 0}; }
 
 AttnPlan make_attn_plan(const spec_attn_desc_t& d, bool paged = false);
 
@@ -95,20 +107,23 @@ hipError_t launch_tree_attention_f32(const spec_attn_desc_t& d, const AttnPlan& 
                                      const int32_t* depth, const int32_t* prefix_len, float* out, void* ws,
                                      int32_t* status, hipStream_t s);
 // k_new / v_new non-null: the kernel also appends the tree rows to the cache (fused KV append).
+// rope.cos non-null (with k_new / v_new): the queries (in registers) and the new K rows (before they are used and
+// stored) are rotated by their positions' angles.
 hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan& plan, const Pages& pg, const void* q, void* k_cache,
                                       void* v_cache, const void* k_new, const void* v_new, const int32_t* parent,
                                       const int32_t* depth, const int32_t* prefix_len, void* out, void* ws,
-                                      int32_t* status, hipStream_t s);
+                                      int32_t* status, hipStream_t s, const Rope& rope = no_rope());
 // Wide trees (N > 32): the workgroup's wavefronts split the queries and share the K/V stream through LDS.
 hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const AttnPlan& plan, const Pages& pg, const void* q, void* k_cache,
                                            void* v_cache, const void* k_new, const void* v_new, const int32_t* parent,
                                            const int32_t* depth, const int32_t* prefix_len, void* out, void* ws,
-                                           int32_t* status, hipStream_t s);
+                                           int32_t* status, hipStream_t s, const Rope& rope = no_rope());
 // Five to eight query tiles per K/V head, D = 128: 32-query MFMA tiles, K/V loaded straight into an LDS ring.
 hipError_t launch_tree_attention_bf16_wide32(const spec_attn_desc_t& d, const AttnPlan& plan, const Pages& pg, const void* q,
                                              void* k_cache, void* v_cache, const void* k_new, const void* v_new,
                                              const int32_t* parent, const int32_t* depth, const int32_t* prefix_len,
-                                             void* out, void* ws, int32_t* status, hipStream_t s);
+                                             void* out, void* ws, int32_t* status, hipStream_t s,
+                                             const Rope& rope = no_rope());
 hipError_t launch_attn_combine(const spec_attn_desc_t& d, const AttnPlan& plan, const int32_t* parent,
                                const int32_t* depth, const int32_t* prefix_len, const void* ws, void* out,
                                int32_t* status, hipStream_t s);
@@ -193,6 +208,56 @@ __device__ inline BalancedShare balanced_share(const int32_t* __restrict__ prefi
   r.share = (r.total + n_wg - 1) / n_wg;
   if (r.share < 1) r.share = 1;
   return r;
+}
+
+// Rotation of the two 16-byte pieces of a row that pair up under the half-split rotary embedding (piece `lo`
+// holds dimensions c .. c + EPV, `hi` the same dimensions + D/2), by the angles whose cosines / sines are cs / sn.
+// float32 arithmetic in one fixed order (product, then fused multiply-add: the product is kept out of the
+// compiler's contraction so that every kernel that rotates a row produces the same bits), rounded to the storage
+// type.
+template <bool BF16>
+__device__ __forceinline__ void rope_pair(const uint4 lo, const uint4 hi, const float* __restrict__ cs,
+                                          const float* __restrict__ sn, uint4* olo, uint4* ohi) {
+  constexpr int EPV = BF16 ? 8 : 4;   // elements per 16-byte piece
+  float x1[EPV], x2[EPV];
+  if (BF16) {
+    const unsigned a[4] = {lo.x, lo.y, lo.z, lo.w}, bb[4] = {hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      x1[2 * j] = __uint_as_float(a[j] << 16);
+      x1[2 * j + 1] = __uint_as_float(a[j] & 0xffff0000u);
+      x2[2 * j] = __uint_as_float(bb[j] << 16);
+      x2[2 * j + 1] = __uint_as_float(bb[j] & 0xffff0000u);
+    }
+  } else {
+    x1[0] = __uint_as_float(lo.x); x1[1] = __uint_as_float(lo.y); x1[2] = __uint_as_float(lo.z); x1[3] = __uint_as_float(lo.w);
+    x2[0] = __uint_as_float(hi.x); x2[1] = __uint_as_float(hi.y); x2[2] = __uint_as_float(hi.z); x2[3] = __uint_as_float(hi.w);
+  }
+  float y1[EPV], y2[EPV];
+#pragma unroll
+  for (int j = 0; j < EPV; ++j) {
+    const float co = cs[j], si = sn[j];
+    float p1 = x2[j] * si, p2 = x1[j] * si;
+    asm("" : "+v"(p1), "+v"(p2));
+    y1[j] = fmaf(x1[j], co, -p1);
+    y2[j] = fmaf(x2[j], co, p2);
+  }
+  if (BF16) {
+    unsigned o1[4], o2[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      union { __hip_bfloat16 h; unsigned short u; } a0, a1, b0, b1;
+      a0.h = __float2bfloat16(y1[2 * j]); a1.h = __float2bfloat16(y1[2 * j + 1]);
+      b0.h = __float2bfloat16(y2[2 * j]); b1.h = __float2bfloat16(y2[2 * j + 1]);
+      o1[j] = (unsigned)a0.u | ((unsigned)a1.u << 16);
+      o2[j] = (unsigned)b0.u | ((unsigned)b1.u << 16);
+    }
+    *olo = make_uint4(o1[0], o1[1], o1[2], o1[3]);
+    *ohi = make_uint4(o2[0], o2[1], o2[2], o2[3]);
+  } else {
+    *olo = make_uint4(__float_as_uint(y1[0]), __float_as_uint(y1[1]), __float_as_uint(y1[2]), __float_as_uint(y1[3]));
+    *ohi = make_uint4(__float_as_uint(y2[0]), __float_as_uint(y2[1]), __float_as_uint(y2[2]), __float_as_uint(y2[3]));
+  }
 }
 
 __device__ inline void set_status(int32_t* status, int b, int bit) {

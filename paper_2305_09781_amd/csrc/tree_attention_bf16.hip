@@ -181,7 +181,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
     const int32_t* __restrict__ parent, const int32_t* __restrict__ depth, const int32_t* __restrict__ prefix_len,
     __hip_bfloat16* __restrict__ out, float* __restrict__ ws_o, float* __restrict__ ws_ml, int32_t* status, int B, int N,
     int H, int S_cap, int n_qgroups, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long kv_sb,
-    long kv_sh, long kv_ss, float scale_log2, Pages pg) {
+    long kv_sh, long kv_ss, float scale_log2, Pages pg, Rope rope) {
   using T = AttnTraits<D, NT>;
   constexpr int KS = T::KS, DB = T::DB, LPR = T::LPR, RPI = T::RPI, NVL = T::NVL, VROW = T::VROW, NQ = T::NQ,
                 MROW = T::MROW;
@@ -267,6 +267,24 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
   const int last_row = len - 1;
   const bool is_tail = wave == TAIL;
 
+  // Rotary embedding: a lane's pieces of a query or key row pair up within the lane (k-step ks holds dimensions
+  // 32 ks + 8 g .., its partner ks + KS/2 the same dimensions + D/2), so a row is rotated in registers.
+  auto rotate_row = [&](auto& lo, auto& hi, int pos, int ks) {
+    const long at = (long)min(max(pos, 0), rope.len - 1) * (D / 2) + ks * 32 + g * 8;
+    uint4 olo, ohi;
+    rope_pair<true>(__builtin_bit_cast(uint4, lo), __builtin_bit_cast(uint4, hi), rope.cos + at, rope.sin + at, &olo, &ohi);
+    lo = __builtin_bit_cast(std::remove_reference_t<decltype(lo)>, olo);
+    hi = __builtin_bit_cast(std::remove_reference_t<decltype(hi)>, ohi);
+  };
+  if (APPEND && rope.cos != nullptr) {   // the queries, at their nodes' positions
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int pos = P + depth[(long)b * N + min(q0 + nt * 16 + r16, N - 1)];
+#pragma unroll
+      for (int ks = 0; ks < KS / 2; ++ks) rotate_row(qB[nt][ks], qB[nt][ks + KS / 2], pos, ks);
+    }
+  }
+
   // tiles of this wavefront: first, stride, count
   const int ti_first = is_tail ? n_clean : wave;
   const int ti_stride = is_tail ? 1 : SWAVES;
@@ -349,6 +367,17 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
 #pragma unroll
       for (int j = 0; j < NVL; ++j)
         if (k0 + j * RPI + lane / LPR >= c1) VA[j] = (u32x4){0u, 0u, 0u, 0u};
+      if (APPEND && rope.cos != nullptr) {   // new K rows are rotated before they are used and stored
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+          const int row = k0 + hf * 16 + r16;
+          if (row >= P && row < c1) {
+            const int pos = P + s_depth[row - P];
+#pragma unroll
+            for (int ks = 0; ks < KS / 2; ++ks) rotate_row(KA[hf][ks], KA[hf][ks + KS / 2], pos, ks);
+          }
+        }
+      }
       if (APPEND && qg == 0) {   // this tile carries tree rows taken from k_new / v_new: put them in the cache
         bool dst_ok = true;      // paged cache: rows of a block outside the pool are not written
         const long dst_shift = PAGED ? page_shift(b, k0, &dst_ok) : 0;
@@ -571,12 +600,12 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
 hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan& plan, const Pages& pg, const void* q, void* k_cache,
                                       void* v_cache, const void* k_new, const void* v_new, const int32_t* parent,
                                       const int32_t* depth, const int32_t* prefix_len, void* out, void* ws,
-                                      int32_t* status, hipStream_t s) {
+                                      int32_t* status, hipStream_t s, const Rope& rope) {
   // This kernel: one 16-query tile per K/V head, k_new / v_new laid out like q. Larger trees, grouped-query
   // heads and separately laid out k_new go to the wide kernel (the plan decides).
   if (plan.wide)
     return launch_tree_attention_bf16_wide(d, plan, pg, q, k_cache, v_cache, k_new, v_new, parent, depth, prefix_len, out, ws,
-                                           status, s);
+                                           status, s, rope);
   const float scale = (d.softmax_scale != 0.f ? d.softmax_scale : 1.0f / sqrtf((float)d.D)) * kLog2eB;
   float* ws_o = ws ? (float*)((char*)ws + plan.ws_o_off) : nullptr;
   float* ws_ml = ws ? (float*)((char*)ws + plan.ws_ml_off) : nullptr;
@@ -590,7 +619,7 @@ hipError_t launch_tree_attention_bf16(const spec_attn_desc_t& d, const AttnPlan&
                      (const __hip_bfloat16*)k_new, (const __hip_bfloat16*)v_new, parent, depth, prefix_len,      \
                      (__hip_bfloat16*)out, ws_o, ws_ml, status, d.B, d.N, d.H, d.S_cap, n_qgroups,               \
                      plan.chunk_keys, plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h, \
-                     (long)d.kv_stride_b, (long)d.kv_stride_h, (long)d.kv_stride_s, scale, pg)
+                     (long)d.kv_stride_b, (long)d.kv_stride_h, (long)d.kv_stride_s, scale, pg, rope)
 #define SPEC_DIMS(APP, BAL, PGD)                      \
   if (d.D == 128) SPEC_LAUNCH(128, 1, APP, BAL, PGD); \
   else SPEC_LAUNCH(64, 1, APP, BAL, PGD)

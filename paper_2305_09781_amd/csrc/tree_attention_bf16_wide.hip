@@ -80,7 +80,7 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
     const int32_t* __restrict__ parent, const int32_t* __restrict__ depth, const int32_t* __restrict__ prefix_len,
     __hip_bfloat16* __restrict__ out, float* __restrict__ ws_o, float* __restrict__ ws_ml, int32_t* status, int B, int N,
     int H, int H_v, int n_qg, int hpw, int heads_per_wg, int S_cap, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh, long n_sb, long n_sn,
-    long n_sh, long kv_sb, long kv_sh, long kv_ss, float scale_log2, Pages pg) {
+    long n_sh, long kv_sb, long kv_sh, long kv_ss, float scale_log2, Pages pg, Rope rope) {
   static_assert(KW == 1 || KW == 2, "a 64-key tile is consumed as two 32-key halves");
   static_assert(DEPTH == 2 || DEPTH == 4, "register sets of tiles in flight");
   constexpr int WAVES = QW * KW;
@@ -223,6 +223,25 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
       s_depth[t] = my_depth;
     }
     lds_barrier();
+    // Rotary embedding of the queries, in registers: k-step ks of a lane holds dimensions 32 ks + 8 g .., its
+    // partner ks + KS/2 the same dimensions + D/2. A position is clamped into the tables (a malformed tree is
+    // found only later, and its outputs are zeros).
+    auto rotate_q = [&](bf16x8 (&dst)[NTW][KS]) {
+#pragma unroll
+      for (int nt = 0; nt < NTW; ++nt) {
+        const int pos = min(max(P + s_depth[min(tile_node[nt], N - 1)], 0), rope.len - 1);
+#pragma unroll
+        for (int ks = 0; ks < KS / 2; ++ks) {
+          const long at = (long)pos * (D / 2) + ks * 32 + g * 8;
+          uint4 olo, ohi;
+          rope_pair<true>(__builtin_bit_cast(uint4, dst[nt][ks]), __builtin_bit_cast(uint4, dst[nt][ks + KS / 2]),
+                          rope.cos + at, rope.sin + at, &olo, &ohi);
+          dst[nt][ks] = __builtin_bit_cast(bf16x8, olo);
+          dst[nt][ks + KS / 2] = __builtin_bit_cast(bf16x8, ohi);
+        }
+      }
+    };
+    if (APPEND && rope.cos != nullptr) rotate_q(qB);
 
     const bool cap_ok = (P >= 0) && (P <= S_cap - N);
     const int len = P + N;
@@ -304,6 +323,27 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
       const bool masked = ti >= n_clean;
       bool in_pool = true;   // paged cache: rows of a block outside the pool are not written
       const long shift = ((PAGED && APPEND && masked) ? page_shift(b, k0, &in_pool) : 0) + (long)hi * kv_sh * 2;
+      if (APPEND && masked && rope.cos != nullptr) {
+        // New K rows are rotated before they are stored and used. A thread holds one 16-byte piece of a row; the
+        // piece it rotates with (the same dimensions -+ D/2) is held LPR/2 lanes away in the same wavefront.
+#pragma unroll
+        for (int j = 0; j < NPT; ++j) {
+          u32x4 other;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) other[e] = __shfl_xor(Ks_[j][e], LPR / 2);
+          const int row = k0 + ld_row0 + j * ROW_STEP;
+          if (row >= P && row < c1) {
+            const int piece = t % LPR;
+            const bool low = piece < LPR / 2;
+            const int pos = min(max(P + s_depth[row - P], 0), rope.len - 1);
+            const long at = (long)pos * (D / 2) + (piece % (LPR / 2)) * 8;
+            uint4 olo, ohi;
+            rope_pair<true>(__builtin_bit_cast(uint4, low ? Ks_[j] : other), __builtin_bit_cast(uint4, low ? other : Ks_[j]),
+                            rope.cos + at, rope.sin + at, &olo, &ohi);
+            Ks_[j] = __builtin_bit_cast(u32x4, low ? olo : ohi);
+          }
+        }
+      }
 #pragma unroll
       for (int j = 0; j < NPT; ++j) {
         const int rit = ld_row0 + j * ROW_STEP;
@@ -486,6 +526,7 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
 #pragma unroll
           for (int ks = 0; ks < KS; ++ks) qB[nt][ks] = qB_next[nt][ks];
         }
+        if (APPEND && rope.cos != nullptr) rotate_q(qB);
         if (cur_head + 1 < nh) load_q(qB_next, cur_head + 1);
       }
       lds_barrier();
@@ -606,7 +647,7 @@ __global__ void __launch_bounds__(QW * KW * 64, 2) tree_attention_bf16_wide_kern
 hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const AttnPlan& plan, const Pages& pg, const void* q, void* k_cache,
                                            void* v_cache, const void* k_new, const void* v_new, const int32_t* parent,
                                            const int32_t* depth, const int32_t* prefix_len, void* out, void* ws,
-                                           int32_t* status, hipStream_t s) {
+                                           int32_t* status, hipStream_t s, const Rope& rope) {
   const float scale = (d.softmax_scale != 0.f ? d.softmax_scale : 1.0f / sqrtf((float)d.D)) * wide::kLog2e;
   float* ws_o = ws ? (float*)((char*)ws + plan.ws_o_off) : nullptr;
   float* ws_ml = ws ? (float*)((char*)ws + plan.ws_ml_off) : nullptr;
@@ -617,7 +658,7 @@ hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const Attn
   const int qw = tiles <= 2 ? 2 : tiles <= 4 ? 4 : 8;
   if (plan.m32)   // five to eight query tiles, head dimension 128: four wavefronts of 32 queries, K/V straight to LDS
     return launch_tree_attention_bf16_wide32(d, plan, pg, q, k_cache, v_cache, k_new, v_new, parent, depth, prefix_len, out,
-                                             ws, status, s);
+                                             ws, status, s, rope);
   const NewStrides ns = attn_new_strides(d);
   const bool append = k_new != nullptr;
   const int mode = plan.balanced_wgs == 0 ? wide::PLAN_GRID : wide::PLAN_TILES;
@@ -635,7 +676,7 @@ hipError_t launch_tree_attention_bf16_wide(const spec_attn_desc_t& d, const Attn
                      (__hip_bfloat16*)out, ws_o, ws_ml, status, d.B, d.N, d.H, virtual_heads, qgr.n_qgroups,           \
                      qgr.heads_per_wg, heads_per_wg, d.S_cap, plan.chunk_keys,                                        \
                      plan.n_splits, (long)d.q_stride_b, (long)d.q_stride_n, (long)d.q_stride_h, ns.b, ns.n, ns.h,     \
-                     (long)d.kv_stride_b, (long)d.kv_stride_h, (long)d.kv_stride_s, scale, pg)
+                     (long)d.kv_stride_b, (long)d.kv_stride_h, (long)d.kv_stride_s, scale, pg, rope)
 #define SPEC_SHAPES(DD, APP, PLAN, PGD)                          \
   if (qw == 2) SPEC_LAUNCH(DD, 2, 1, 2, 2, APP, PLAN, PGD);      \
   else if (qw == 4) SPEC_LAUNCH(DD, 4, 1, 1, 2, APP, PLAN, PGD); \

@@ -95,14 +95,14 @@ __device__ __forceinline__ int opaque(int v) {
   return v;
 }
 
-template <bool APPEND, int PLAN, bool PAGED>
+template <bool APPEND, int PLAN, bool PAGED, bool ROPE>
 __global__ void __launch_bounds__(NTHREADS, 2) tree_attention_bf16_wide32_kernel(
     const __hip_bfloat16* __restrict__ q, __hip_bfloat16* k_cache, __hip_bfloat16* v_cache,
     const __hip_bfloat16* __restrict__ k_new, const __hip_bfloat16* __restrict__ v_new,
     const int32_t* __restrict__ parent, const int32_t* __restrict__ depth, const int32_t* __restrict__ prefix_len,
     __hip_bfloat16* __restrict__ out, float* __restrict__ ws_o, float* __restrict__ ws_ml, int32_t* status, int B, int N,
     int H, int H_v, int n_qg, int hpw, int S_cap, int chunk_keys, int n_splits, long q_sb, long q_sn, long q_sh,
-    long n_sb, long n_sn, long n_sh, long kv_sb, long kv_sh, long kv_ss, float scale_log2, Pages pg) {
+    long n_sb, long n_sn, long n_sh, long kv_sb, long kv_sh, long kv_ss, float scale_log2, Pages pg, Rope rope) {
   __shared__ __attribute__((aligned(1024))) unsigned char ring[NST * STAGE];
   __shared__ unsigned long long s_anc[SPEC_MAX_TREE_NODES][2];
   __shared__ int s_parent[SPEC_MAX_TREE_NODES];
@@ -202,6 +202,21 @@ __global__ void __launch_bounds__(NTHREADS, 2) tree_attention_bf16_wide32_kernel
       s_depth[t] = my_depth;
     }
     lds_barrier();
+    if (APPEND && ROPE) {
+      // Rotary embedding of the queries, in registers: k-step ks of a lane holds dimensions 16 ks + 8 hh .., its
+      // partner ks + KSQ/2 the same dimensions + D/2. The position is clamped into the tables (a malformed tree is
+      // found only later, and its outputs are zeros).
+      const int pos = min(max(P + s_depth[min(node, N - 1)], 0), rope.len - 1);
+#pragma unroll
+      for (int ks = 0; ks < KSQ / 2; ++ks) {
+        const long at = (long)pos * (D / 2) + ks * 16 + hh * 8;
+        uint4 olo, ohi;
+        rope_pair<true>(__builtin_bit_cast(uint4, qB[ks]), __builtin_bit_cast(uint4, qB[ks + KSQ / 2]), rope.cos + at,
+                        rope.sin + at, &olo, &ohi);
+        qB[ks] = __builtin_bit_cast(bf16x8, olo);
+        qB[ks + KSQ / 2] = __builtin_bit_cast(bf16x8, ohi);
+      }
+    }
 
     const bool cap_ok = (P >= 0) && (P <= S_cap - N);
     const int len = P + N;
@@ -406,6 +421,26 @@ __global__ void __launch_bounds__(NTHREADS, 2) tree_attention_bf16_wide32_kernel
       else wait_loads_but<0>();
       lds_barrier();   // stage st has landed for every lane
       const bool masked = st >= n_clean;
+      if (APPEND && ROPE && masked) {
+        // New K rows are rotated where they landed, before they are stored and used: a thread takes the two
+        // pieces of one row that rotate with each other (piece c and c + 8 of row t / 8, at their swizzled slots).
+        const int tt = opaque(t);
+        const int rr = tt >> 3, c = tt & 7;
+        const int row = c0 + st * SK + rr;
+        if (row >= P && row < c1) {
+          unsigned char* at_row = ring + rs * STAGE + rr * ROWB;
+          u32x4* lo = (u32x4*)(at_row + ((c ^ swizzle(rr & 15)) << 4));
+          u32x4* hi = (u32x4*)(at_row + (((c + 8) ^ swizzle(rr & 15)) << 4));
+          const int pos = min(max(P + s_depth[row - P], 0), rope.len - 1);
+          const long at = (long)pos * (D / 2) + c * 8;
+          uint4 olo, ohi;
+          rope_pair<true>(__builtin_bit_cast(uint4, *lo), __builtin_bit_cast(uint4, *hi), rope.cos + at, rope.sin + at, &olo,
+                          &ohi);
+          *lo = __builtin_bit_cast(u32x4, olo);
+          *hi = __builtin_bit_cast(u32x4, ohi);
+        }
+        lds_barrier();
+      }
       if (APPEND && masked && qg == 0) {   // the pair's first query group writes the appended rows to the cache
         const int k0 = c0 + st * SK;
         bool in_pool = true;               // paged cache: rows of a block outside the pool are not written
@@ -506,7 +541,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) tree_attention_bf16_wide32_kernel
 hipError_t launch_tree_attention_bf16_wide32(const spec_attn_desc_t& d, const AttnPlan& plan, const Pages& pg, const void* q,
                                              void* k_cache, void* v_cache, const void* k_new, const void* v_new,
                                              const int32_t* parent, const int32_t* depth, const int32_t* prefix_len,
-                                             void* out, void* ws, int32_t* status, hipStream_t s) {
+                                             void* out, void* ws, int32_t* status, hipStream_t s, const Rope& rope) {
   const float scale = (d.softmax_scale != 0.f ? d.softmax_scale : 1.0f / sqrtf((float)d.D)) * wide32::kLog2e;
   float* ws_o = ws ? (float*)((char*)ws + plan.ws_o_off) : nullptr;
   float* ws_ml = ws ? (float*)((char*)ws + plan.ws_ml_off) : nullptr;
@@ -516,21 +551,25 @@ hipError_t launch_tree_attention_bf16_wide32(const spec_attn_desc_t& d, const At
   const bool append = k_new != nullptr;
   const bool tiles_plan = plan.balanced_wgs > 0;
   const dim3 grid = tiles_plan ? dim3(plan.balanced_wgs, 1, 1) : dim3(plan.n_splits, virtual_heads, d.B);
-#define SPEC_LAUNCH(APP, PLAN, PGD)                                                                                  \
-  hipLaunchKernelGGL((wide32::tree_attention_bf16_wide32_kernel<APP, PLAN, PGD>), grid, dim3(wide32::NTHREADS), 0, s, \
+#define SPEC_LAUNCH(APP, PLAN, PGD, RP)                                                                                  \
+  hipLaunchKernelGGL((wide32::tree_attention_bf16_wide32_kernel<APP, PLAN, PGD, RP>), grid, dim3(wide32::NTHREADS), 0, s, \
                      (const __hip_bfloat16*)q, (__hip_bfloat16*)k_cache, (__hip_bfloat16*)v_cache,                   \
                      (const __hip_bfloat16*)k_new, (const __hip_bfloat16*)v_new, parent, depth, prefix_len,          \
                      (__hip_bfloat16*)out, ws_o, ws_ml, status, d.B, d.N, d.H, virtual_heads, qgr.n_qgroups,          \
                      qgr.heads_per_wg, d.S_cap, plan.chunk_keys, plan.n_splits, (long)d.q_stride_b,                  \
                      (long)d.q_stride_n, (long)d.q_stride_h, ns.b, ns.n, ns.h, (long)d.kv_stride_b,                  \
-                     (long)d.kv_stride_h, (long)d.kv_stride_s, scale, pg)
-#define SPEC_PLANS(APP, PGD)                                          \
-  if (tiles_plan) SPEC_LAUNCH(APP, wide32::PLAN_TILES, PGD);          \
-  else SPEC_LAUNCH(APP, wide32::PLAN_GRID, PGD)
-#define SPEC_DISPATCH(APP)                              \
-  if (pg.table != nullptr) { SPEC_PLANS(APP, true); }   \
-  else { SPEC_PLANS(APP, false); }
-  if (append) { SPEC_DISPATCH(true); } else { SPEC_DISPATCH(false); }
+                     (long)d.kv_stride_h, (long)d.kv_stride_s, scale, pg, rope)
+#define SPEC_PLANS(APP, PGD, RP)                                          \
+  if (tiles_plan) SPEC_LAUNCH(APP, wide32::PLAN_TILES, PGD, RP);          \
+  else SPEC_LAUNCH(APP, wide32::PLAN_GRID, PGD, RP)
+#define SPEC_DISPATCH(APP, RP)                              \
+  if (pg.table != nullptr) { SPEC_PLANS(APP, true, RP); }   \
+  else { SPEC_PLANS(APP, false, RP); }
+  // (the rotary embedding is a template parameter here, not a run-time branch as in the other kernels: this kernel
+  // uses every register it may, and the extra live values of a branch that is never taken cost it 7 % of its speed)
+  if (append && rope.cos != nullptr) { SPEC_DISPATCH(true, true); }
+  else if (append) { SPEC_DISPATCH(true, false); }
+  else { SPEC_DISPATCH(false, false); }
 #undef SPEC_DISPATCH
 #undef SPEC_PLANS
 #undef SPEC_LAUNCH
