@@ -471,19 +471,36 @@ __global__ void __launch_bounds__(NTHREADS, 2) tree_attention_bf16_wide32_kernel
 
     // ---- normalise and write, or emit the partial
     const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (live && node < N) {
-      if (final_out) {
-        const float inv = 1.f / l_tot;
+    if (final_out) {
+      // A lane holds 8-byte pieces of its query's output row, 16 of them spread over the row: written as they are,
+      // a store touches 64 rows for 8 bytes each. The wavefront's 32 rows go through its quarter of the first ring
+      // slots instead (16-byte piece p of row r at slot p ^ (r & 15): the 16 lanes of a row meet no bank twice) and
+      // leave as whole 256-byte rows, four rows per store.
+      lds_barrier();   // every wavefront is done with the ring
+      unsigned char* stg = ring + wave * (32 * ROWB);
+      const float inv = 1.f / l_tot;
 #pragma unroll
-        for (int db = 0; db < DB32; ++db)
+      for (int db = 0; db < DB32; ++db)
 #pragma unroll
-          for (int c4 = 0; c4 < 4; ++c4) {
-            union { uint2 u; __hip_bfloat16 h4[4]; } pk;
+        for (int c4 = 0; c4 < 4; ++c4) {
+          union { uint2 u; __hip_bfloat16 h4[4]; } pk;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) pk.h4[i] = __float2bfloat16(O[db][c4 * 4 + i] * inv);
-            *(uint2*)(out + b * q_sb + node * q_sn + q_head * q_sh + db * 32 + c4 * 8 + 4 * hh) = pk.u;
-          }
-      } else {
+          for (int i = 0; i < 4; ++i) pk.h4[i] = __float2bfloat16(O[db][c4 * 4 + i] * inv);
+          *(uint2*)(stg + n32 * ROWB + (((db * 4 + c4) ^ (n32 & 15)) << 4) + hh * 8) = pk.u;
+        }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the wavefront's own writes have landed
+      const int tt = opaque(lane);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int r = 4 * j + (tt >> 4), piece = tt & 15;
+        const int tl_r = 2 * wave + (r >> 4);
+        const int hg_r = qg * hpw + tl_r / tiles_per_head, node_r = (tl_r % tiles_per_head) * 16 + (r & 15);
+        if (tl_r / tiles_per_head < hpw && hg_r < group && node_r < N)
+          store_nt((unsigned char*)(out + b * q_sb + node_r * q_sn + (h * group + hg_r) * q_sh) + piece * 16,
+                   *(const u32x4*)(stg + r * ROWB + ((piece ^ (r & 15)) << 4)));
+      }
+    } else if (live && node < N) {
+      {
         const long base = (((long)b * H + q_head) * n_splits + slot) * N + node;
 #pragma unroll
         for (int db = 0; db < DB32; ++db)

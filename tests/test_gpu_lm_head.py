@@ -39,7 +39,9 @@ def _check_rows(arg_gpu, max_gpu, h, w):
 
 
 @pytest.mark.parametrize("M,K,V", [(128, 4096, 32000), (16, 4096, 32000), (1, 512, 1000), (17, 256, 130), (64, 1280, 4097),
-                                   (200, 1024, 5000), (33, 768, 127), (128, 2048, 129), (48, 2304, 700)])
+                                   (200, 1024, 5000), (33, 768, 127), (128, 2048, 129), (48, 2304, 700),
+                                   (65, 512, 200), (96, 1024, 1000), (97, 1536, 4097), (129, 512, 128), (300, 1024, 999),
+                                   (128, 768, 300)])
 def test_lm_head_argmax(spec, M, K, V):
     h, w = _inputs(M, K, V, seed=M + K + V)
     arg, mx = spec.spec_lm_head_argmax(_dev(h), _dev(w), want_max=True)
@@ -141,7 +143,8 @@ def _stats_case(spec, M, K, V, temperature, seed):
 
 
 @pytest.mark.parametrize("M,K,V,T", [(128, 4096, 32000, 1.0), (16, 4096, 32000, 0.7), (1, 512, 1000, 1.0), (17, 256, 130, 1.6),
-                                     (64, 1280, 4097, 1.0), (200, 1024, 5001, 0.9), (33, 768, 127, 1.0)])
+                                     (64, 1280, 4097, 1.0), (200, 1024, 5001, 0.9), (33, 768, 127, 1.0),
+                                     (65, 512, 200, 1.0), (96, 1024, 1002, 0.8), (129, 1536, 4097, 1.3)])
 def test_lm_head_logits_and_softmax_statistics(spec, M, K, V, T):
     _stats_case(spec, M, K, V, T, seed=M + K + V)
 
