@@ -128,6 +128,16 @@ def rope_rotate(x, cos, sin):
     return np.concatenate([x1 * cos - x2 * sin, x2 * cos + x1 * sin], axis=-1)
 
 
+def round_to_storage(x, storage):
+    """float64 values rounded ONCE, to nearest with ties to even, to the storage type: "bf16" (8 significant
+    bits; values in bfloat16's normal range, which rotated activations are) or "f32". Returned as float64."""
+    x = np.asarray(x, dtype=np.float64)
+    if storage != "bf16":
+        return x.astype(np.float32).astype(np.float64)
+    m, e = np.frexp(x)                       # x = m * 2**e, 0.5 <= |m| < 1
+    return np.ldexp(np.rint(m * 256.0) / 256.0, e)   # np.rint rounds halves to even
+
+
 def kv_append_rope(k_cache, v_cache, k_new, v_new, prefix_len, tree_depth, rope_cos, rope_sin, storage="bf16"):
     """KV append with the rotary embedding applied to the keys on the way in: tree token i of request b
     sits at sequence position prefix_len[b] + tree_depth[b,i] (its depth below the last verified token,
@@ -135,7 +145,6 @@ def kv_append_rope(k_cache, v_cache, k_new, v_new, prefix_len, tree_depth, rope_
     storage type ("bf16" or "f32"); V is copied. rope_cos, rope_sin: [rope_len, D/2] tables supplied by
     the caller (float32 values). Returns status [B]: ST_CAPACITY if the tree does not fit the cache or a
     position lies outside the tables (request untouched)."""
-    import torch
     B, N = k_new.shape[0], k_new.shape[1]
     S_cap = k_cache.shape[2]
     rope_cos = np.asarray(rope_cos, dtype=np.float64)
@@ -149,9 +158,7 @@ def kv_append_rope(k_cache, v_cache, k_new, v_new, prefix_len, tree_depth, rope_
             continue
         for i in range(N):
             rot = rope_rotate(k_new[b, i], rope_cos[pos[i]], rope_sin[pos[i]])          # [H, D]
-            t = torch.from_numpy(rot)
-            t = t.to(torch.bfloat16) if storage == "bf16" else t.to(torch.float32)
-            k_cache[b, :, p + i, :] = t.double().numpy()
+            k_cache[b, :, p + i, :] = round_to_storage(rot, storage)
             v_cache[b, :, p + i, :] = v_new[b, i, :, :]
     return status
 
@@ -165,13 +172,11 @@ def rope_queries(q, prefix_len, tree_depth, rope_cos, rope_sin, S_cap, storage="
     prefix_len[b] + tree_depth[b,i] and rounded to the storage type. q [B,N,H,D]; returns (rotated copy,
     status [B]); a request that does not fit S_cap or has a position outside the tables keeps its q
     (ST_CAPACITY), exactly like kv_append_rope."""
-    import torch
     q = np.array(q, dtype=np.float64)
     B, N = q.shape[0], q.shape[1]
     rope_cos = np.asarray(rope_cos, dtype=np.float64)
     rope_sin = np.asarray(rope_sin, dtype=np.float64)
     status = np.zeros(B, dtype=np.int32)
-    dt = torch.bfloat16 if storage == "bf16" else torch.float32
     for b in range(B):
         p = int(prefix_len[b])
         pos = [p + int(tree_depth[b, i]) for i in range(N)]
@@ -180,7 +185,7 @@ def rope_queries(q, prefix_len, tree_depth, rope_cos, rope_sin, S_cap, storage="
             continue
         for i in range(N):
             rot = rope_rotate(q[b, i], rope_cos[pos[i]], rope_sin[pos[i]])
-            q[b, i] = torch.from_numpy(rot).to(torch.float32).to(dt).double().numpy()
+            q[b, i] = round_to_storage(rot, storage)
     return q, status
 
 

@@ -24,6 +24,26 @@ def test_rotation_is_complex_multiplication_and_preserves_norms():
     assert np.allclose(back, x, atol=1e-13)
 
 
+def test_rounding_to_the_storage_type_is_one_rounding_to_nearest_even():
+    """bfloat16 keeps 8 significant bits: hand-derived cases, among them a value that rounding through float32
+    first would get wrong, and agreement with a library conversion of values that float32 holds exactly."""
+    r = lambda x: float(orc.round_to_storage(np.array([x]), "bf16")[0])
+    assert r(1.0) == 1.0 and r(-0.15625) == -0.15625 and r(0.0) == 0.0
+    assert r(1.0 + 2.0 ** -8) == 1.0                       # a tie: to the even neighbour (down)
+    assert r(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6       # a tie: to the even neighbour (up)
+    assert r(1.0 + 2.0 ** -8 + 2.0 ** -30) == 1.0 + 2.0 ** -7   # just above the tie
+    assert r(-(3.0 + 2.0 ** -7)) == -3.0 and r(-(3.0 + 3 * 2.0 ** -7)) == -(3.0 + 2.0 ** -5)   # spacing 2^-6 in [2, 4)
+    # 1 + 2^-8 + 2^-40 lies above the tie; float32 first rounds it onto the tie, which then goes down: double rounding
+    x = 1.0 + 2.0 ** -8 + 2.0 ** -40
+    assert r(x) == 1.0 + 2.0 ** -7
+    assert float(torch.tensor([x], dtype=torch.float64).to(torch.float32).to(torch.bfloat16).double()[0]) == 1.0
+    rng = np.random.default_rng(3)
+    v = rng.standard_normal(4000).astype(np.float32) * np.float32(10.0) ** rng.integers(-3, 4, 4000).astype(np.float32)
+    assert np.array_equal(orc.round_to_storage(v.astype(np.float64), "bf16"), torch.from_numpy(v).to(torch.bfloat16).double().numpy())
+    w = rng.standard_normal(100)
+    assert np.array_equal(orc.round_to_storage(w, "f32"), w.astype(np.float32).astype(np.float64))
+
+
 def test_scores_depend_only_on_relative_position():
     """The property rotary embeddings exist for: <R(m) q, R(n) k> is a function of m - n."""
     rng = np.random.default_rng(1)
