@@ -121,6 +121,36 @@ def test_rotary_embedding_inside_the_fused_launch_paged(spec, case):
     _check_attention(out, want, torch.bfloat16)
 
 
+@pytest.mark.parametrize("c", [2, 3, 4, 5])
+def test_full_size_configs_with_the_rotation_fused_in(spec, c):
+    """The benchmark's shapes at full size, in the plan the library chooses: caches and outputs of the one-launch call
+    equal, bit for bit, those of spec_qk_rope_append followed by the attention launch (every request, head, node and
+    the whole cache); the last request's last head is also held to the oracle on the rotated bits."""
+    cfg = wl.CONFIGS[c]
+    inp = wl.make_attention_inputs(cfg)
+    S = inp["k_cache"][0].shape[2]
+    cos, sin = wl.make_rope_tables(S, cfg.D)
+    pl, par = inp["prefix_len"].numpy(), inp["tree_parent"].numpy()
+    mp = int(pl.max())
+    q, kn, vn = (_dev(inp[k][0]) for k in ("q", "k_new", "v_new"))
+    tree_args = (_dev(inp["tree_parent"]), _dev(inp["tree_depth"]), _dev(inp["prefix_len"]))
+    cs, sn = _dev(cos), _dev(sin)
+    q2, kc2, vc2 = q.clone(), _dev(inp["k_cache"][0]), _dev(inp["v_cache"][0])
+    spec.spec_qk_rope_append(q2, kn, vn, kc2, vc2, tree_args[1], tree_args[2], cs, sn)
+    out2 = spec.spec_tree_attention(q2, kc2, vc2, *tree_args, max_prefix_len=mp)
+    kc, vc = _dev(inp["k_cache"][0]), _dev(inp["v_cache"][0])
+    status = torch.zeros(cfg.B, dtype=torch.int32, device=DEV)
+    out = spec.spec_tree_attention_append_rope(q, kn, vn, kc, vc, *tree_args, cs, sn, status=status, max_prefix_len=mp)
+    torch.cuda.synchronize()
+    assert (status.cpu().numpy() == 0).all()
+    assert torch.equal(kc.view(torch.int16), kc2.view(torch.int16)) and torch.equal(vc.view(torch.int16), vc2.view(torch.int16))
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+    b, h = cfg.B - 1, cfg.H - 1
+    want = orc.tree_attention(q2[b:b + 1, :, h:h + 1].double().cpu().numpy(), kc[b:b + 1, h:h + 1].double().cpu().numpy(),
+                              vc[b:b + 1, h:h + 1].double().cpu().numpy(), par[b:b + 1], pl[b:b + 1])
+    _check_attention(out[b:b + 1, :, h:h + 1], want, torch.bfloat16)
+
+
 @pytest.mark.parametrize("N,D", [(16, 128), (48, 64), (128, 128)])
 def test_tables_shorter_than_a_request_needs(spec, N, D):
     """prefix_len + N beyond the tables: that request is neither appended nor attended (zeros, SPEC_ST_CAPACITY),
