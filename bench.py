@@ -11,6 +11,9 @@ largest single-GPU configuration) measured in full, and a `per_config` list with
 other bf16 workloads (configs 2, 3, 5) on fewer timed steps.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-per-config] [--no-graph] [--no-cpu-baseline]
+
+`--lm-head` measures something else and prints its own JSON line: verification from hidden states (the LM head fused
+with the arg-max, or with the logits' softmax statistics) next to a library GEMM followed by the verifier on its logits.
 """
 import argparse
 import gc
@@ -43,6 +46,9 @@ def parse():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 256 MiB device copies, the known-size reference for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings")
+    ap.add_argument("--lm-head", action="store_true",
+                    help="instead of the verification pass: the LM-head entry points against a library GEMM + verifier, "
+                         "at 16 .. 256 tree nodes per pass (hidden 4096, vocabulary 32000)")
     return ap.parse_args()
 
 
@@ -254,6 +260,78 @@ def measure(cfg_id, args, steps, warmup, want_cpu_baseline, want_read_probe):
     return res
 
 
+def lm_head_comparison(args):
+    """Greedy / stochastic verification from hidden states: spec_verify_greedy_lm_head and spec_lm_head_logits_stats
+    next to torch.matmul (the library GEMM) writing bf16 logits followed by spec_verify_greedy on them. HIP-graph
+    replay over several distinct weight matrices (a 32000 x 4096 head is 262 MB, more than the Infinity Cache)."""
+    import numpy as np
+    import torch
+
+    from paper_2305_09781_amd import binding as spec
+    from paper_2305_09781_amd import workloads as wl
+
+    dev = "cuda:0"
+    K, V, N = 4096, 32000, 16
+    Ws = [torch.randn((V, K), device=dev, dtype=torch.float32).mul_(0.05).to(torch.bfloat16) for _ in range(6)]
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def time_us(fn, reps=10):
+        fn()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            fn()
+        for _ in range(2):
+            graph.replay()
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(reps):
+            graph.replay()
+        ev1.record()
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) * 1e3 / (reps * len(Ws))
+
+    rows = []
+    for B in (1, 2, 4, 6, 8, 16):
+        M = B * N
+        h = torch.randn((M, K), device=dev, dtype=torch.bfloat16)
+        par = torch.from_numpy(np.stack([wl.tree_expansion(wl.EXPANSION_EVAL * 16, N) for _ in range(B)]).astype(np.int32)).to(dev)
+        tok = torch.randint(0, V, (B, N), device=dev, dtype=torch.int32)
+        ws = torch.empty(spec.spec_lm_head_argmax_workspace_bytes(M, V), dtype=torch.uint8, device=dev)
+        ws2 = torch.empty(int(spec.load().spec_lm_head_logits_stats_workspace_bytes(M, V)), dtype=torch.uint8, device=dev)
+        logits = torch.empty((B, N, V), device=dev, dtype=torch.bfloat16)
+
+        def fused():
+            for W in Ws:
+                spec.spec_verify_greedy_lm_head(h, W, tok, par, workspace=ws)
+
+        def gemm_then_verify():
+            for W in Ws:
+                torch.matmul(h, W.t(), out=logits.view(M, V))
+                spec.spec_verify_greedy(logits, tok, par)
+
+        def gemm_only():
+            for W in Ws:
+                torch.matmul(h, W.t(), out=logits.view(M, V))
+
+        def head_only():
+            for W in Ws:
+                spec.spec_lm_head_argmax(h, W, workspace=ws)
+
+        def logits_and_stats():
+            for W in Ws:
+                spec.spec_lm_head_logits_stats(h, W, 1.0, workspace=ws2)
+
+        us = {"fused_greedy_verify_us": time_us(fused), "library_gemm_plus_greedy_verify_us": time_us(gemm_then_verify),
+              "lm_head_argmax_us": time_us(head_only), "lm_head_logits_and_stats_us": time_us(logits_and_stats),
+              "library_gemm_us": time_us(gemm_only)}
+        weight_bytes = V * K * 2 + M * K * 2
+        rows.append({"rows": M, **{k: round(v, 2) for k, v in us.items()},
+                     "lm_head_argmax_frac_of_hbm_peak": round(weight_bytes / us["lm_head_argmax_us"] / 1e3 / HBM_PEAK_GBS, 3)})
+    print(json.dumps({"metric": "verification from hidden states, microseconds per pass (hidden 4096, vocabulary 32000, "
+                                "trees of 16 nodes)", "n_gpus": 1, "dtype": "bf16", "data": "synthetic", "rows": rows}))
+
+
 def roofline_of(r):
     d = {"bound": "hbm", "achieved": r["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
          "frac": r["achieved"] / HBM_PEAK_GBS,
@@ -287,6 +365,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.lm_head:
+        lm_head_comparison(args)
+        return
 
     head = measure(args.config, args, args.steps, args.warmup, not args.no_cpu_baseline, True)
     tokens = head["value"] * head["ms_per_step"] * 1e-3          # tree tokens per pass (B * N)
