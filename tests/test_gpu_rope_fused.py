@@ -121,6 +121,92 @@ def test_rotary_embedding_inside_the_fused_launch_paged(spec, case):
     _check_attention(out, want, torch.bfloat16)
 
 
+@pytest.mark.parametrize("seed", range(20))
+def test_randomised_shapes_and_plans_with_the_rotation_fused_in(spec, seed):
+    """Random small shapes (grouped heads, head dim, tree size from one node to 128, ragged prefixes down to zero)
+    under a random launch plan, contiguous or paged: the one-launch call against the oracle's rotation (one unit in
+    the last place) and the oracle's attention on the rotated bits, the caches bit-equal to spec_qk_rope_append's."""
+    rng = np.random.default_rng(9100 + seed)
+    D = int(rng.choice([64, 128]))
+    H_kv = int(rng.integers(1, 4))
+    N = int(rng.choice([1, 5, 16, 17, 32, 33, 64, 65, 100, 128]))
+    group = int(rng.integers(1, 9)) if rng.random() < 0.3 else int(rng.integers(1, 3))
+    B = int(rng.integers(1, 5))
+    hi = int(rng.choice([0, 40, 130, 400, 700]))
+    lo = int(rng.integers(0, hi + 1))
+    tree = str(rng.choice(["random_parent", "random_branching", "expansion"]))
+    bt = int(rng.choice([0, 0, 64, 128]))                        # 0: contiguous cache
+    S = hi + N + 3 if bt == 0 else ((hi + N + bt - 1) // bt) * bt
+    cfg, inp, _ = _inputs(B, H_kv * group, H_kv, D, (lo, hi), N, tree, seed=9200 + seed, S=S)
+    plan = int(rng.integers(0, 3))
+    chunk = int(rng.choice([32, 64, 96, 160])) if plan == 1 else 0
+    wgs = int(rng.integers(1, 12)) if plan == 2 else 0
+    cos, sin = wl.make_rope_tables(S + int(rng.integers(0, 5)), D)
+    pl, dep, par = inp["prefix_len"].numpy(), inp["tree_depth"].numpy(), inp["tree_parent"].numpy()
+    q, kn, vn = (_dev(inp[k][0]) for k in ("q", "k_new", "v_new"))
+    tree_args = (_dev(inp["tree_parent"]), _dev(inp["tree_depth"]), _dev(inp["prefix_len"]))
+    cs, sn = _dev(cos), _dev(sin)
+    caches, tab = [inp["k_cache"][0], inp["v_cache"][0]], None
+    if bt:
+        caches, table = wl.to_paged(caches, pl, N, bt, np.random.default_rng(seed))
+        tab = _dev(table)
+    q2, kc2, vc2 = q.clone(), _dev(caches[0]), _dev(caches[1])
+    spec.spec_qk_rope_append(q2, kn, vn, kc2, vc2, tree_args[1], tree_args[2], cs, sn, block_table=tab)
+    kc, vc = _dev(caches[0]), _dev(caches[1])
+    status = torch.zeros(B, dtype=torch.int32, device=DEV)
+    with _chunk_keys(chunk), _balanced_wgs(wgs):
+        out = spec.spec_tree_attention_append_rope(q, kn, vn, kc, vc, *tree_args, cs, sn, status=status, max_prefix_len=int(pl.max()),
+                                                   plan=_plan(), block_table=tab)
+    torch.cuda.synchronize()
+    assert (status.cpu().numpy() == 0).all()
+    assert np.array_equal(_bits(q), _bits(inp["q"][0]))
+    assert np.array_equal(_bits(kc), _bits(kc2)) and np.array_equal(_bits(vc), _bits(vc2))
+    q_ref, _ = orc.rope_queries(_f64(inp["q"][0]), pl, dep, cos.numpy(), sin.numpy(), S, "bf16")
+    got_q = q2.double().cpu().numpy()
+    assert (np.abs(got_q - q_ref) <= 2.0 ** -7 * np.abs(q_ref) + 1e-6).all()
+    kco, vco = _f64(inp["k_cache"][0]), _f64(inp["v_cache"][0])       # the logical caches, rotated rows appended
+    orc.kv_append_rope(kco, vco, _f64(inp["k_new"][0]), _f64(inp["v_new"][0]), pl, dep, cos.numpy(), sin.numpy(), "bf16")
+    if bt:
+        got = orc.tree_attention_paged(got_q, kc.double().cpu().numpy(), vc.double().cpu().numpy(), table.numpy(), bt, par, pl)
+        # the pool's appended rows against the oracle's, read through the table
+        for b in range(B):
+            rows = np.arange(pl[b], pl[b] + N)
+            blk, off = table.numpy()[b, rows // bt], rows % bt
+            gk = kc.double().cpu().numpy()[blk, :, off]              # [N, H_kv, D]
+            want_k = kco[b][:, rows].transpose(1, 0, 2)
+            assert (np.abs(gk - want_k) <= 2.0 ** -7 * np.abs(want_k) + 1e-6).all()
+    else:
+        got_k = kc.double().cpu().numpy()
+        assert (np.abs(got_k - kco) <= 2.0 ** -7 * np.abs(kco) + 1e-6).all()
+        assert np.array_equal(vc.double().cpu().numpy(), vco)
+        got = orc.tree_attention(got_q, got_k, vc.double().cpu().numpy(), par, pl)
+    _check_attention(out, got, torch.bfloat16)
+
+
+def test_outputs_depend_on_relative_positions_only(spec):
+    """What the rotary embedding is for, through the whole launch: with every position shifted by the same amount
+    (tables that start s rows later) the scores, and so the outputs, stay the same up to the rounding of the
+    rotated operands. The prefix rows are rotated on the host by the oracle, the tree rows by the launch."""
+    B, H, D, N, P = 2, 2, 128, 24, 90
+    cfg, inp, S = _inputs(B, H, H, D, (P, P), N, "random_branching", seed=31)
+    cos, sin = wl.make_rope_tables(S + 64, D)
+    pl, par = inp["prefix_len"].numpy(), inp["tree_parent"].numpy()
+    outs = []
+    for shift in (0, 37):
+        c, s_ = cos[shift:].contiguous(), sin[shift:].contiguous()
+        kc = _f64(inp["k_cache"][0])
+        for b in range(B):                                            # prefix row j sits at position j (+ shift)
+            for j in range(P):
+                kc[b, :, j] = orc.round_to_storage(orc.rope_rotate(kc[b, :, j], c[j].double().numpy(), s_[j].double().numpy()), "bf16")
+        kcd, vcd = _dev(torch.from_numpy(kc).to(torch.bfloat16)), _dev(inp["v_cache"][0])
+        outs.append(spec.spec_tree_attention_append_rope(_dev(inp["q"][0]), _dev(inp["k_new"][0]), _dev(inp["v_new"][0]), kcd, vcd,
+                                                         _dev(inp["tree_parent"]), _dev(inp["tree_depth"]), _dev(inp["prefix_len"]),
+                                                         _dev(c), _dev(s_)).double().cpu().numpy())
+    # two bf16 roundings of differently rotated operands: the bf16 attention bar, not bit equality
+    assert (np.abs(outs[0] - outs[1]) <= 2e-2 + 1e-2 * np.abs(outs[0])).all()
+    assert np.abs(outs[0]).max() > 0.05                                # and not trivially: the outputs are not zeros
+
+
 @pytest.mark.parametrize("c", [2, 3, 4, 5])
 def test_full_size_configs_with_the_rotation_fused_in(spec, c):
     """The benchmark's shapes at full size, in the plan the library chooses: caches and outputs of the one-launch call
