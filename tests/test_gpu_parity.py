@@ -285,6 +285,27 @@ def test_qk_rope_append_rejects_bad_arguments(spec):
     assert rc != 0                                                  # q is not optional here
 
 
+@pytest.mark.parametrize("case", [(1, 2, 128, 131072, 16, "expansion"), (1, 1, 128, 200000, 100, "random_branching"),
+                                  (2, 1, 64, (70000, 90001), 40, "random_branching"), (1, 2, 128, 131072, 128, "random_branching")],
+                         ids=lambda c: f"B{c[0]}H{c[1]}D{c[2]}P{c[3]}N{c[4]}")
+def test_very_long_prefixes(spec, case):
+    """Prefixes of a hundred thousand keys and more (key ranges cut into hundreds of chunks, float32 partials and
+    the combine step; row offsets near the 32-bit range for one head): every output against the oracle, the
+    appended rows bit for bit."""
+    B, H, D, P, N, tree = case
+    cfg = wl.Config(89, "long", "bf16", B=B, H=H, D=D, P=P, N=N, tree=tree, widths=wl.EXPANSION_EVAL * 16)
+    inp = wl.make_attention_inputs(cfg, seed=5 + N)
+    ref, kco, vco = _oracle_append_attention(inp)
+    for fused in (True, False):
+        out, kc, vc = _run_append_attention(spec, inp, fused=fused)
+        _check_attention(out, ref, torch.bfloat16)
+        pl = inp["prefix_len"].numpy()
+        for b in range(B):
+            rows = slice(int(pl[b]), int(pl[b]) + N)
+            assert np.array_equal(kc[b, :, rows].double().cpu().numpy(), kco[b, :, rows])
+            assert np.array_equal(vc[b, :, rows].double().cpu().numpy(), vco[b, :, rows])
+
+
 GROUPED = [
     # dtype, B, H, H_kv, D, (P lo, hi), N, tree, forced chunk, balanced workgroups
     ("bf16", 2, 4, 2, 128, (70, 300), 16, "expansion", 0, 0),        # 2 query tiles per K/V head
