@@ -634,14 +634,17 @@ def spec_verify_greedy_lm_head(hidden, weight, tree_token, tree_parent, Lmax: Op
     return out
 
 
-def spec_lm_head_logits_stats(hidden, weight, temperature: float = 1.0, workspace=None, stream=None):
+def spec_lm_head_logits_stats(hidden, weight, temperature: float = 1.0, workspace=None, stream=None, out=None):
     """One pass over the output projection: (logits [M,V] bf16, node_argmax [M] int32, node_max [M], node_sumexp [M]
-    float32), the statistics being those of the rounded logits."""
+    float32), the statistics being those of the rounded logits. `out`: those four tensors, brought by the caller."""
     M, K, V = _lm_head_args(hidden, weight)
     dev = hidden.device
-    logits = torch.empty((M, V), dtype=torch.bfloat16, device=dev)
-    arg = torch.empty(M, dtype=torch.int32, device=dev)
-    mx, se = torch.empty(M, dtype=torch.float32, device=dev), torch.empty(M, dtype=torch.float32, device=dev)
+    if out is not None:
+        logits, arg, mx, se = out
+    else:
+        logits = torch.empty((M, V), dtype=torch.bfloat16, device=dev)
+        arg = torch.empty(M, dtype=torch.int32, device=dev)
+        mx, se = torch.empty(M, dtype=torch.float32, device=dev), torch.empty(M, dtype=torch.float32, device=dev)
     if workspace is None:
         workspace = torch.empty(max(int(load().spec_lm_head_logits_stats_workspace_bytes(M, V)), 256), dtype=torch.uint8,
                                 device=dev)
