@@ -7,7 +7,6 @@ from __future__ import annotations
 
 import concurrent.futures
 import os
-import re
 import shutil
 import subprocess
 import sys
@@ -68,51 +67,6 @@ def build_library(extra_flags=(), verbose: bool = True) -> str:
     if verbose:
         print("built", LIB_PATH, "and", PROBE_LIB_PATH)
     return LIB_PATH
-
-
-def compile_to_assembly(src: str, out_path: str, extra_flags=()) -> str:
-    """Device assembly of one source of csrc/ (what the checks below read); returns its text."""
-    _run([_hipcc(), *HIPCC_FLAGS, *extra_flags, "-S", "--cuda-device-only", os.path.join(CSRC, src), "-o", out_path])
-    with open(out_path) as f:
-        return f.read()
-
-
-def check_hidden_loads(asm_text: str):
-    """tree_attention_bf16_wide32.hip requests a workgroup's queries and tree words with loads written in inline
-    assembly, whose destination registers are valid only behind the wait that follows the first ring requests
-    (the compiler is not told, so that it does not wait for the ring too). That is sound as long as the compiler
-    neither reads nor overwrites those registers, and in particular copies none of them, between a load and that
-    wait. Verified here on the assembly of every instantiation; returns [(kernel, loads, violations)]."""
-    def regs_of(tok):
-        m = re.match(r"v\[(\d+):(\d+)\]", tok)
-        return set(range(int(m.group(1)), int(m.group(2)) + 1)) if m else {int(tok[1:])}
-
-    def touched(line):
-        out = set()
-        for a, b in re.findall(r"v\[(\d+):(\d+)\]", line):
-            out.update(range(int(a), int(b) + 1))
-        for a in re.findall(r"\bv(\d+)\b", line):
-            out.add(int(a))
-        return out
-
-    report = []
-    for body in re.split(r"\n(?=_ZN4spec6wide32\w+: )", asm_text):
-        m = re.match(r"(_ZN4spec6wide32\w+): ", body)
-        if not m:
-            continue
-        lines = body.split("\n")
-        first_direct = next(i for i, l in enumerate(lines) if "global_load_lds" in l)
-        hidden = [i for i, l in enumerate(lines[:first_direct])
-                  if re.search(r"\tglobal_load_dword(x4)? ", l) and "ASMSTART" in lines[i - 1]]
-        wait = next(i for i, l in enumerate(lines) if i > first_direct and "ASMSTART" in lines[i - 1] and "s_waitcnt vmcnt(" in l)
-        violations = []
-        for h in hidden:
-            mine = regs_of(lines[h].split()[1].rstrip(","))
-            for i in range(h + 1, wait):
-                if lines[i].startswith("\t") and not lines[i].strip().startswith(";") and touched(lines[i]) & mine:
-                    violations.append(lines[i].strip())
-        report.append((m.group(1), len(hidden), violations))
-    return report
 
 
 if __name__ == "__main__":

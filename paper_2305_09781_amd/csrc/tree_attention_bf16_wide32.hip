@@ -19,11 +19,6 @@
 //     other vector memory operation in flight (queries, appended-row stores): loads return in order, so extra
 //     operations can only make a wait longer, never too short. Every exit path drains the loads first: a
 //     workgroup's LDS must not be written after it has ended.
-//   * A segment starts by requesting, in the order of need, its queries and tree words (into registers, also from
-//     inline assembly) and then the first three ring stages, and waits for the former with a count that leaves the
-//     stages in flight: the ring fills while the tree is checked and the masks are built. The registers of those
-//     loads are valid only behind that wait; build.check_hidden_loads verifies on the compiled code that nothing
-//     touches them before it (tests/test_build_checks.py).
 //
 //   iteration t:  barrier (everybody finished stage t-1); request stage t+3 into the slot stage t-1 used, so that
 //                 up to four stages are in flight while stage t is awaited; wait for this lane's loads of stage t;
@@ -84,24 +79,6 @@ __device__ __forceinline__ const unsigned char* uniform_ptr(const unsigned char*
   const unsigned long long v = (unsigned long long)p;
   const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
   return (const unsigned char*)(((unsigned long long)hi << 32) | lo);
-}
-// Loads whose return the compiler does not wait for (it would wait with a count that knows nothing of the direct
-// loads in flight, i.e. for all of them): the registers are valid only behind await_queries below, which the
-// values pass through.
-__device__ __forceinline__ void load_hidden(u32x4& dst, const void* p) {
-  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
-}
-__device__ __forceinline__ void load_hidden(int& dst, const void* p) {
-  asm volatile("global_load_dword %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
-}
-// Waits until at most YOUNGER vector memory operations of this lane are in flight (they return in order: the eight
-// query pieces and the two tree words requested before them have landed).
-template <int YOUNGER>
-__device__ __forceinline__ void await_queries(u32x4 (&q)[8], int& a, int& b) {
-  asm volatile("s_waitcnt vmcnt(%10)"
-               : "+v"(q[0]), "+v"(q[1]), "+v"(q[2]), "+v"(q[3]), "+v"(q[4]), "+v"(q[5]), "+v"(q[6]), "+v"(q[7]), "+v"(a), "+v"(b)
-               : "n"(YOUNGER)
-               : "memory");
 }
 __device__ __forceinline__ void store_nt(void* p, u32x4 v) {
   // (the builtin, not inline assembly: the compiler then keeps the store's data registers untouched for the wait
@@ -200,6 +177,9 @@ __global__ void __launch_bounds__(NTHREADS, 2) tree_attention_bf16_wide32_kernel
         }
       }
     };
+#pragma unroll
+    for (int s = 0; s < AHEAD; ++s) request(s, c0 + s * SK, std::integral_constant<int, 0>{}, 0, 0);
+
     // The query of this lane: 16-query tile tl of the workgroup (head qg * hpw + tl / tiles_per_head of the group,
     // nodes (tl % tiles_per_head) * 16 ..), node r16 of it. Tiles past the workgroup's heads idle.
     const int group = H / (H_v / n_qg), tiles_per_head = (N + 15) / 16;
@@ -208,24 +188,14 @@ __global__ void __launch_bounds__(NTHREADS, 2) tree_attention_bf16_wide32_kernel
     const bool live = tl / tiles_per_head < hpw && hg < group;
     const int q_head = h * group + min(hg, group - 1);
     const int node = (tl % tiles_per_head) * 16 + r16;
-    // Requests in the order of need: the queries and this thread's tree node first, then the first ring stages
-    // (speculative: cache rows clamped to the capacity, prefix_len not needed). The former are waited for with a
-    // count that leaves the stages in flight, so the ring is already filling while the tree is checked and the
-    // masks are built.
-    u32x4 q_raw[KSQ];
-    int my_parent, my_depth;
-    static_assert(KSQ == 8, "await_queries takes eight pieces");
-#pragma unroll
-    for (int ks = 0; ks < KSQ; ++ks)
-      load_hidden(q_raw[ks], q + b * q_sb + min(node, N - 1) * q_sn + q_head * q_sh + ks * 16 + hh * 8);
-    load_hidden(my_parent, parent + (long)b * N + min(t, N - 1));
-    load_hidden(my_depth, depth + (long)b * N + min(t, N - 1));
-#pragma unroll
-    for (int s = 0; s < AHEAD; ++s) request(s, c0 + s * SK, std::integral_constant<int, 0>{}, 0, 0);
-    await_queries<AHEAD * LPS>(q_raw, my_parent, my_depth);
     bf16x8 qB[KSQ];   // Q^T as the B operand: lane (n32, hh) holds d = 16 ks + 8 hh .. + 8 of its query
 #pragma unroll
-    for (int ks = 0; ks < KSQ; ++ks) qB[ks] = __builtin_bit_cast(bf16x8, q_raw[ks]);
+    for (int ks = 0; ks < KSQ; ++ks) {
+      const u32x4 raw = *(const u32x4*)(q + b * q_sb + min(node, N - 1) * q_sn + q_head * q_sh + ks * 16 + hh * 8);
+      qB[ks] = __builtin_bit_cast(bf16x8, raw);
+    }
+    const int my_parent = parent[(long)b * N + min(t, N - 1)];
+    const int my_depth = depth[(long)b * N + min(t, N - 1)];
     if (t == 0) s_flag = 0;
     if (t < N) {
       s_parent[t] = my_parent;
