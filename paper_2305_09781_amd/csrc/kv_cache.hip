@@ -149,7 +149,7 @@ __global__ void __launch_bounds__(256) kv_commit_kernel(LayerPtrs ptrs, const in
   }
   __syncthreads();
   const bool ok = head_ok && s_bad == 0;
-  __syncthreads();   // every thread has read the path verdict before the flag is used again below
+  __syncthreads();   // every thread has read the result of the path check before the flag is used again below
   // paged cache: every block that holds a row of the tree must lie inside the pool, else nothing moves
   if (ok && pg.table != nullptr) {
     for (int j = (p >> pg.log2_tokens) + t; j <= ((p + N - 1) >> pg.log2_tokens); j += blockDim.x) {
