@@ -184,6 +184,9 @@ __global__ void __launch_bounds__(NTHREADS, 2) tree_attention_bf16_wide32_kernel
     // nodes (tl % tiles_per_head) * 16 ..), node r16 of it. Tiles past the workgroup's heads idle.
     const int group = H / (H_v / n_qg), tiles_per_head = (N + 15) / 16;
     const int tl = 2 * wave + (g & 1);
+    // the last node among this wavefront's queries: a tree stage whose keys all come after it is skipped (a node
+    // sees no later node; the skipped arithmetic would have added exact zeros)
+    const int wave_last_node = max((2 * wave) % tiles_per_head, (2 * wave + 1) % tiles_per_head) * 16 + 15;
     const int hg = qg * hpw + tl / tiles_per_head;
     const bool live = tl / tiles_per_head < hpw && hg < group;
     const int q_head = h * group + min(hg, group - 1);
@@ -297,8 +300,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) tree_attention_bf16_wide32_kernel
     // One stage of 32 keys from ring slot rs. S^T = K Q^T on eight 32x32x16 products: register i of lane (n32, hh)
     // is key 8 (i / 4) + 4 hh + i % 4 of the stage for query n32: the B-operand layout of P^T for two k = 16
     // products per d block (registers 0..7 and 8..15), with V^T read transposed from LDS in the same key order.
-    auto compute = [&](const int st, auto rs_tag, auto masked_tag) {
-      constexpr bool MASKED = decltype(masked_tag)::value;
+    auto compute = [&](const int st, auto rs_tag, const bool masked) {
       constexpr int rs = decltype(rs_tag)::value;   // compile-time slot: stage offsets fold into the LDS instructions
       const unsigned char* Ks = ring + rs * STAGE;
       const unsigned char* Vs = Ks + MAT;
@@ -316,7 +318,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) tree_attention_bf16_wide32_kernel
       __builtin_amdgcn_sched_group_barrier(0x100, KSQ, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, KSQ, 0);
       __builtin_amdgcn_sched_barrier(0);
-      if (MASKED) {
+      if (masked) {   // (a branch inside one body: two bodies per slot made the compiler copy O between them)
         const int nd = opaque(node);   // the ancestor mask is read back from LDS rather than held across clean stages
         const unsigned long long anc_lo = nd < N ? s_anc[nd][0] : 0ull, anc_hi = nd < N ? s_anc[nd][1] : 0ull;
         // visibility of the stage's 32 keys for this lane's query as one word: bit j = key kb + j is inside the
@@ -458,8 +460,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) tree_attention_bf16_wide32_kernel
           }
         }
       }
-      if (masked) compute(st, rs_tag, std::true_type{});
-      else compute(st, rs_tag, std::false_type{});
+      if (!masked || c0 + st * SK - P <= wave_last_node) compute(st, rs_tag, masked);   // else: every key is a later node
     };
 #pragma nounroll
     for (int st0 = 0; st0 < n_st; st0 += NST) {
