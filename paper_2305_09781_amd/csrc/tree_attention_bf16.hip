@@ -23,8 +23,8 @@
 //                 P^T needs for the second product, so probabilities never leave registers.
 //   mask          tail wavefront only: bit (key - prefix_len) of the query's 128-bit ancestor-or-self
 //                 mask (built from the parent array by walking up the parent chain in LDS).
-//   softmax       online, in the exp2 domain; row max over the tile = 8 in-lane values + 2 cross-lane
-//                 exchanges; the rescale factor of a query is lane-local for its O^T fragment.
+//   softmax       online, in the exp2 domain, with a lazy running maximum (refreshed, with two cross-lane
+//                 exchanges and a rescale of the lane-local O^T fragment, only when a score outgrows it).
 //   O^T += V^T P^T  A = V^T needs 8 keys x 1 d per lane, the transpose of how V lies in memory: V is
 //                 loaded fully coalesced (four 256-byte rows per instruction), staged in a
 //                 wavefront-private LDS tile and read back with ds_read_b64_tr_b16.
@@ -400,18 +400,16 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
     }
 #pragma unroll
     for (int j = 0; j < NVL; ++j) *(u32x4*)(vst + (j * RPI + lane / LPR) * VROW + (lane % LPR) * 16) = VA[j];
-    // Refill: V's registers are free once staged. K's are free after the S^T products; with one query
-    // tile there is room to copy K aside and request the next K at once, with two there is not.
+    // Refill in place: V's registers are free once staged, K's once the S^T products have read them. The
+    // scheduling fences keep the compiler from moving the requests above those uses: it would then need a second
+    // set of registers for the rows in flight and copy it into the first on every tile, after the rows have arrived
+    // and before the next request, which is time with nothing in flight.
     const int kn0 = c0 + ti_refill * TILE;
     bool refill_ok;
     const long refill_shift = (PAGED && ti_refill >= 0) ? page_shift(b, kn0, &refill_ok) : 0;
+    __builtin_amdgcn_sched_barrier(0);
     if (ti_refill >= 0) issue_v_loads<D, NT, APPEND, !MASKED>(src, kn0, P, last_row, lane, VA, refill_shift);
-    bf16x8 Kc[2][KS];
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) Kc[hf][ks] = __builtin_bit_cast(bf16x8, KA[hf][ks]);
-    if (NT == 1 && ti_refill >= 0) issue_k_loads<D, NT, APPEND, !MASKED>(src, kn0, P, last_row, r16, KA, refill_shift);
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- S^T = K Q^T : sc[nt][hf][v] = score of query nt*16+r16 and key k0 + hf*16 + 4g + v
     f32x4 sc[NT][2];
@@ -422,14 +420,12 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Kc[hf][ks], qB[nt][ks], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, KA[hf][ks]), qB[nt][ks], acc, 0, 0, 0);
         sc[nt][hf] = acc;
       }
-    if (NT != 1 && ti_refill >= 0) {
-      // the products above must have read K before the loads below overwrite it
-      asm volatile("" : "+v"(sc[0][0]), "+v"(sc[NT - 1][1]));
-      issue_k_loads<D, NT, APPEND, !MASKED>(src, kn0, P, last_row, r16, KA, refill_shift);
-    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (ti_refill >= 0) issue_k_loads<D, NT, APPEND, !MASKED>(src, kn0, P, last_row, r16, KA, refill_shift);
+    __builtin_amdgcn_sched_barrier(0);
 
     bf16x8 pB[NT];
 #pragma unroll
@@ -454,24 +450,32 @@ __global__ void __launch_bounds__(WAVES * 64, 2) tree_attention_bf16_kernel(
             if (!vis) s[hf * 4 + v] = -INFINITY;
           }
       }
-      float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-      mx = wave_max_over_lane_groups(mx);
-      const float m_new = fmaxf(m_run[nt], mx);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_use);
-      m_run[nt] = m_new;
+      // Lazy running maximum. m_run (exp2 domain, identical in the four lanes of a query) only has to be close to
+      // the true maximum: probabilities are exp2(score - m_run) and everything is normalised by the same sum at the
+      // end. It is refreshed, with the exact cross-lane maximum and the usual rescaling of l and O, only when some
+      // score of the wavefront exceeds it by more than 2^16 (or it is still -inf); otherwise a tile costs no
+      // cross-lane exchange and no pass over the accumulators, which a lone wavefront on its SIMD cannot hide.
+      const float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+      if (__any(mx > m_run[nt] + 16.f)) {
+        const float m_new = fmaxf(m_run[nt], wave_max_over_lane_groups(mx));
+        const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_ref);
+        m_run[nt] = m_new;
+        l_run[nt] *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) O[nt][db] *= alpha;
+      }
+      const float neg_m = (m_run[nt] == -INFINITY) ? 0.f : -m_run[nt];
       float psum = 0.f;
       bf16x8 pb;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const float p = __builtin_amdgcn_exp2f(s[i] - m_use);
+        const float p = __builtin_amdgcn_exp2f(s[i] + neg_m);
         psum += p;
         pb[i] = (__bf16)p;
       }
       pB[nt] = pb;
-      l_run[nt] = l_run[nt] * alpha + psum;
-#pragma unroll
-      for (int db = 0; db < DB; ++db) O[nt][db] *= alpha;
+      l_run[nt] += psum;
     }
 
     // ---- O^T += V^T P^T : A operand = V^T through the transposing LDS read
