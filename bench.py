@@ -50,6 +50,9 @@ def parse():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 256 MiB device copies, the known-size reference for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="instead of the verification pass: the attention launch of --config (2, 3 or 4: equal prefix "
+                         "lengths, 128 elements per row) next to a kernel that issues only its memory requests")
     ap.add_argument("--lm-head", action="store_true",
                     help="instead of the verification pass: the LM-head entry points against a library GEMM + verifier, "
                          "at 16 .. 256 tree nodes per pass (hidden 4096, vocabulary 32000)")
@@ -380,6 +383,10 @@ def main():
         need_gpu()
         lm_head_comparison(args)
         return
+    if args.traffic_probe:
+        need_gpu()
+        traffic_probe(args)
+        return
 
     if args.per_config_entry:   # child of a default run: one workload, printed as an entry of `per_config`
         need_gpu()
@@ -446,6 +453,80 @@ def per_config_entry(r):
                          "frac": r["achieved"] / HBM_PEAK_GBS, "traffic": r["traffic"]},
             "greedy_verify_us": r["greedy_us"], "stochastic_verify_us": r["stoch_us"],
             "commit_all_layers_us": r["commit_us"]}
+
+
+def traffic_probe(args):
+    """The attention launch of one workload next to spec_probe_attention_traffic: the same memory requests (K/V
+    stream through an LDS ring, queries, new rows, appended rows, outputs) with no arithmetic. One JSON line."""
+    import torch
+
+    from paper_2305_09781_amd import binding as spec
+    from paper_2305_09781_amd import probe_binding as probe
+    from paper_2305_09781_amd import workloads as wl
+
+    dev = "cuda:0"
+    cfg = wl.CONFIGS[args.config]
+    prefix = cfg.P if isinstance(cfg.P, int) else None
+    if cfg.dtype != "bf16" or cfg.D != 128 or prefix is None:
+        print("bench.py --traffic-probe: config %d has no equal prefix lengths / 128-element bf16 rows" % args.config,
+              file=sys.stderr)
+        sys.exit(2)
+    L = args.layers or min(cfg.layers, 32)
+    W = build_workload(cfg, L, dev)
+    pl, par, dep = W["prefix_len"], W["tree_parent"], W["tree_depth"]
+    desc = spec.make_desc(W["q"][0], W["k_cache"][0], max_prefix_len=prefix)
+    ws = torch.empty(max(spec.spec_tree_attention_workspace_bytes(desc), 256), dtype=torch.uint8, device=dev)
+    status = torch.zeros(cfg.B, dtype=torch.int32, device=dev)
+
+    def attention():
+        for l in range(L):
+            spec.spec_tree_attention_append(W["q"][l], W["k_new"][l], W["v_new"][l], W["k_cache"][l], W["v_cache"][l], par,
+                                            dep, pl, out=W["out"][l], workspace=ws, status=status, desc=desc)
+
+    def requests(flags):
+        def run():
+            for l in range(L):
+                probe.spec_probe_attention_traffic(W["k_cache"][l], W["v_cache"][l], W["q"][l], W["k_new"][l], W["v_new"][l],
+                                                   W["out"][l], prefix, flags)
+        return run
+
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def time_us(fn, reps=10, repeats=5):
+        fn()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            fn()
+        for _ in range(3):
+            graph.replay()
+        batches = []
+        for _ in range(repeats):
+            torch.cuda.synchronize()
+            ev0.record()
+            for _ in range(reps):
+                graph.replay()
+            ev1.record()
+            torch.cuda.synchronize()
+            batches.append(ev0.elapsed_time(ev1) * 1e3 / (reps * L))
+        return sorted(batches)[len(batches) // 2]
+
+    Q, NEW, APP, OUT = probe.TRAFFIC_QUERIES, probe.TRAFFIC_NEW_ROWS, probe.TRAFFIC_APPEND, probe.TRAFFIC_OUTPUTS
+    attn_us = time_us(attention)
+    sets = [("kv_stream", 0), ("kv_stream+queries", Q), ("kv_stream+new_rows", NEW), ("kv_stream+new_rows+appended_rows", NEW | APP),
+            ("kv_stream+outputs", OUT), ("everything", Q | NEW | APP | OUT)]
+    req = {name: time_us(requests(flags)) for name, flags in sets}
+    attn_us_again = time_us(attention)
+    e = 2
+    attn_bytes = e * cfg.H * cfg.D * cfg.B * (2 * prefix + 6 * cfg.N)
+    print(json.dumps({
+        "mode": "traffic-probe", "workload": "config %d: %s B=%d H=%d D=%d prefix=%d tree N=%d" % (
+            cfg.cfg, cfg.name, cfg.B, cfg.H, cfg.D, prefix, cfg.N),
+        "layers": L, "bytes_per_launch": attn_bytes,
+        "attention_us_per_launch": [attn_us, attn_us_again],
+        "memory_requests_only_us_per_launch": req,
+        "memory_requests_only_gbs": attn_bytes / (req["everything"] * 1e-6) / 1e9,
+        "attention_over_memory_requests_only": min(attn_us, attn_us_again) / req["everything"]}))
 
 
 def cpu_baseline(cfg, host, gi, si, L):

@@ -153,3 +153,26 @@ def test_header_is_plain_c_and_links_from_c(tmp_path):
                     "-lspectree", "-Wl,-rpath," + lib_dir], check=True)
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
     assert out.startswith("ok ") and int(out.split()[1]) == ctypes.sizeof(binding.AttnDesc)
+
+
+def test_probe_library_exports_what_its_header_declares_and_checks_arguments():
+    """libspecprobe (measurement aids, a library of its own): symbols of include/spec_probe.h, host-side checks."""
+    from paper_2305_09781_amd import probe_binding
+    text = open(os.path.join(ROOT, "include", "spec_probe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(spec_probe_[a-z_]+)\s*\(", text)))
+    assert names == ["spec_probe_attention_traffic", "spec_probe_read_stream"]
+    lib = probe_binding.load()
+    for n in names:
+        assert getattr(lib, n) is not None
+    buf = ctypes.create_string_buffer(4096)
+    a = ctypes.c_void_p((ctypes.addressof(buf) + 255) // 256 * 256)
+    mis = ctypes.c_void_p(a.value + 4)
+    f = lib.spec_probe_attention_traffic
+    assert f(1, 1, 16, 16, 16, a, a, a, a, a, a, 15, None) == -1        # prefix + tree beyond the capacity
+    assert f(1, 1, 129, 0, 256, a, a, a, a, a, a, 15, None) == -1       # more than 128 nodes
+    assert f(1, 1, 16, 0, 32, a, mis, a, a, a, a, 15, None) == -1       # misaligned pointer
+    assert f(1, 1, 16, 0, 32, a, a, None, a, a, a, 15, None) == -1      # null pointer
+    assert f(1, 1, 16, 0, 32, a, a, a, a, a, a, 16, None) == -1         # unknown flag
+    assert f(0, 1, 16, 0, 32, a, a, a, a, a, a, 15, None) == -1
+    assert lib.spec_probe_read_stream(None, 64, a, None) == -1
