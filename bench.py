@@ -412,9 +412,12 @@ def main():
             child = subprocess.run(cmd, capture_output=True, text=True)
             lines = [ln for ln in child.stdout.splitlines() if ln.startswith("{")]
             if child.returncode != 0 or not lines:
+                # said loudly, and the headline measurement still runs: its line is what the caller came for
                 sys.stderr.write(child.stderr[-2000:])
-                raise RuntimeError("bench.py: measuring config %d in a child process failed (exit %d)" % (c, child.returncode))
-            per.append(json.loads(lines[-1]))
+                sys.stderr.write("bench.py: measuring config %d in a child process failed (exit %d)\n" % (c, child.returncode))
+                per.append({"workload": "config %d" % c, "error": "child process exited with %d" % child.returncode})
+            else:
+                per.append(json.loads(lines[-1]))
             time.sleep(SETTLE_SECONDS)
         time.sleep(SETTLE_SECONDS)
     need_gpu()
