@@ -400,6 +400,7 @@ def main():
     if not args.no_per_config and not args.attn_only:
         import subprocess
         per = []
+        time.sleep(SETTLE_SECONDS)   # whatever ran on the machine before this may have just freed its memory
         for c in (2, 3, 4, 5):
             if c == args.config:
                 continue
