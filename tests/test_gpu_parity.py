@@ -172,6 +172,33 @@ def test_small_shapes_attention_and_append(spec, case):
         assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco), fused
 
 
+def _shaped_tree(kind, N):
+    """Extremes of the topology-aware mask (Section 4.2): a chain (every node sees all nodes before it), a star
+    (a node sees the root and itself), and a comb (a chain of every 8th node, seven leaves hanging off each)."""
+    par = np.full(N, -1, dtype=np.int32)
+    for i in range(1, N):
+        par[i] = {"chain": i - 1, "star": 0, "comb": (i - 8 if i % 8 == 0 else i - i % 8)}[kind]
+    par[0] = -1
+    return par
+
+
+@pytest.mark.parametrize("kind", ["chain", "star", "comb"])
+@pytest.mark.parametrize("N,P", [(16, 45), (48, 0), (64, 97), (96, 64), (128, 33), (128, 160), (65, 31)])
+def test_extreme_tree_shapes(spec, kind, N, P):
+    """Chains, stars and combs on every bf16 kernel, with prefixes that end inside a key stage: the masks of whole
+    stages are all-visible, all-hidden or mixed, and the wavefronts that may skip a stage must skip exactly those."""
+    cfg = wl.Config(91, "shaped", "bf16", B=2, H=2, D=128, P=P, N=N, tree="random_parent")
+    inp = wl.make_attention_inputs(cfg, seed=77 + N + P, S_cap=P + N + 3)
+    par = _shaped_tree(kind, N)
+    inp["tree_parent"] = torch.from_numpy(np.stack([par, par]))
+    inp["tree_depth"] = torch.from_numpy(np.stack([wl.depth_of(par), wl.depth_of(par)]).astype(np.int32))
+    ref, kco, vco = _oracle_append_attention(inp)
+    for fused in (False, True):
+        out, kc, vc = _run_append_attention(spec, inp, fused=fused)
+        _check_attention(out, ref, cfg.torch_dtype)
+        assert np.array_equal(kc.double().cpu().numpy(), kco) and np.array_equal(vc.double().cpu().numpy(), vco), fused
+
+
 @pytest.mark.parametrize("case", [("bf16", 3, 4, 128, (30, 200), 16, "expansion"), ("bf16", 2, 3, 64, (0, 90), 40, "random_branching"),
                                   ("f32", 2, 2, 64, (5, 60), 9, "random_parent"), ("f32", 1, 2, 128, (100, 100), 128, "random_branching")])
 def test_kv_append_with_rotary_embedding(spec, case):
